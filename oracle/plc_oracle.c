@@ -1,0 +1,433 @@
+/*
+ * plc_oracle.c -- CPU oracle for predictive delta coding of a KV cache.
+ *
+ * TEST INFRASTRUCTURE ONLY (see plc_oracle.h).  Plain scalar C, one symbol at
+ * a time, in the order the format is defined in; nothing here is blocked,
+ * fused or reordered.  Build with -ffp-contract=off so that the compiler never
+ * fuses a multiply and an add the text below keeps apart.
+ */
+#include "plc_oracle.h"
+
+#include <math.h>
+#include <stddef.h>
+#include <string.h>
+
+#define RANS_LANES 32
+#define RANS_SCALE_BITS 12
+#define RANS_SCALE (1u << RANS_SCALE_BITS) /* frequencies sum to this      */
+#define RANS_LOW (1u << 16)                /* lower end of the state range */
+#define ESCAPE 255
+#define ZERO_SYMBOL 127                    /* symbol of q = 0              */
+
+/* ------------------------------------------------------------------------- */
+/* IEEE binary16                                                             */
+/* ------------------------------------------------------------------------- */
+
+double plco_half_to_double(uint16_t h) {
+  int sign = (h >> 15) & 1;
+  int ex = (h >> 10) & 31;
+  int man = h & 1023;
+  double v;
+  if (ex == 0) {
+    v = ldexp((double)man, -24); /* zero and subnormals: man * 2^-24 */
+  } else if (ex == 31) {
+    v = man ? NAN : INFINITY;
+  } else {
+    v = ldexp((double)(1024 + man), ex - 25); /* (1 + man/1024) * 2^(ex-15) */
+  }
+  return sign ? -v : v;
+}
+
+uint16_t plco_double_to_half(double x) {
+  uint16_t sign = signbit(x) ? 0x8000u : 0u;
+  double a = fabs(x);
+  if (isnan(x)) return (uint16_t)(sign | 0x7e00u);
+  if (a >= 65520.0) return (uint16_t)(sign | 0x7c00u); /* rounds past the largest finite value */
+  if (a < ldexp(1.0, -14)) {
+    /* subnormal range: multiples of 2^-24; nearbyint rounds half to even.
+     * A result of 1024 is the smallest normal number, and its bit pattern
+     * 0x0400 is what the plain integer gives. */
+    double m = nearbyint(ldexp(a, 24));
+    return (uint16_t)(sign | (uint16_t)m);
+  }
+  int e;
+  (void)frexp(a, &e); /* a = f * 2^e, f in [0.5, 1) */
+  int E = e - 1;      /* a = 1.xxx * 2^E            */
+  double m = nearbyint(ldexp(a, 10 - E)); /* in [1024, 2048] */
+  if (m >= 2048.0) {
+    m = 1024.0;
+    E += 1;
+  }
+  if (E + 15 >= 31) return (uint16_t)(sign | 0x7c00u);
+  return (uint16_t)(sign | (uint16_t)((E + 15) << 10) | (uint16_t)((int)m - 1024));
+}
+
+/* ------------------------------------------------------------------------- */
+/* Sec. 7.1: renormalised top-k weights                                      */
+/* ------------------------------------------------------------------------- */
+
+int plco_weights(const float *p, int k, int mode, double *w) {
+  int j;
+  if (k < 1) return PLCO_ERR_INVALID;
+  for (j = 0; j < k; ++j) {
+    if (isnan(p[j]) || p[j] < 0.0f) return PLCO_ERR_INVALID;
+  }
+  if (mode == PLCO_F32) {
+    float Z = 0.0f;
+    for (j = 0; j < k; ++j) Z = Z + p[j];
+    if (!(Z > 0.0f) || !isfinite(Z)) return PLCO_ERR_INVALID;
+    for (j = 0; j < k; ++j) {
+      float wj = p[j] / Z;
+      w[j] = (double)wj;
+    }
+  } else {
+    double Z = 0.0;
+    for (j = 0; j < k; ++j) Z = Z + (double)p[j];
+    if (!(Z > 0.0) || !isfinite(Z)) return PLCO_ERR_INVALID;
+    for (j = 0; j < k; ++j) w[j] = (double)p[j] / Z;
+  }
+  return PLCO_OK;
+}
+
+/* Weighted mean of the k candidates for one component (Sec. 7.1), j ascending. */
+static double predict_one(const double *w, const uint16_t *cand, int64_t stride_j,
+                          int k, int mode) {
+  int j;
+  if (mode == PLCO_F32) {
+    float acc = 0.0f;
+    for (j = 0; j < k; ++j) {
+      float c = (float)plco_half_to_double(cand[(int64_t)j * stride_j]);
+      acc = fmaf((float)w[j], c, acc);
+    }
+    return (double)acc;
+  } else {
+    double acc = 0.0;
+    for (j = 0; j < k; ++j) {
+      double c = plco_half_to_double(cand[(int64_t)j * stride_j]);
+      acc = acc + w[j] * c;
+    }
+    return acc;
+  }
+}
+
+static int check_dims(const plco_dims *dm) {
+  if (!dm) return PLCO_ERR_INVALID;
+  if (dm->S < 1 || dm->L < 1 || dm->H < 1 || dm->n < 1 || dm->d < 1) return PLCO_ERR_INVALID;
+  if (dm->k < 1) return PLCO_ERR_INVALID;
+  if (!(dm->delta > 0.0f) || !isfinite(dm->delta)) return PLCO_ERR_INVALID;
+  if (dm->qmax < 1 || dm->qmax > 127) return PLCO_ERR_INVALID;
+  return PLCO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Encode side: predict, subtract, quantise (Sec. 7.2, integration point 1)  */
+/* ------------------------------------------------------------------------- */
+
+int plco_predict_residual(const plco_dims *dm, int mode,
+                          const uint16_t *cand_k, const uint16_t *cand_v,
+                          const float *probs,
+                          const uint16_t *act_k, const uint16_t *act_v,
+                          uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                          uint32_t *esc_cnt, uint64_t *esc_off,
+                          double *pred_out, double *u_out) {
+  int rc = check_dims(dm);
+  if (rc) return rc;
+  const int S = dm->S, L = dm->L, H = dm->H, n = dm->n, k = dm->k, d = dm->d;
+  double w[64];
+  if (k > 64) return PLCO_ERR_INVALID;
+  uint64_t n_esc = 0; /* running length of the escape list over all streams */
+  int64_t out = 0;    /* running index into symbols / pred_out / u_out      */
+
+  for (int s = 0; s < S; ++s)
+    for (int l = 0; l < L; ++l)
+      for (int h = 0; h < H; ++h) {
+        int64_t stream = ((int64_t)s * L + l) * H + h;
+        esc_off[stream] = n_esc;
+        uint32_t cnt = 0;
+        for (int i = 0; i < n; ++i) {
+          rc = plco_weights(probs + ((int64_t)s * n + i) * k, k, mode, w);
+          if (rc) return rc;
+          for (int c = 0; c < 2; ++c) {
+            const uint16_t *cand = c ? cand_v : cand_k;
+            const uint16_t *act = c ? act_v : act_k;
+            int64_t cbase = s * dm->cand_stride[0] + l * dm->cand_stride[1] +
+                            h * dm->cand_stride[2] + i * dm->cand_stride[3];
+            int64_t abase = s * dm->act_stride[0] + l * dm->act_stride[1] +
+                            h * dm->act_stride[2] + i * dm->act_stride[3];
+            for (int e = 0; e < d; ++e, ++out) {
+              double pred = predict_one(w, cand + cbase + e, dm->cand_stride[4], k, mode);
+              uint16_t raw = act[abase + e];
+              double a = plco_half_to_double(raw);
+              double u, q;
+              if (mode == PLCO_F32) {
+                float r = (float)a - (float)pred; /* Def. KV residual */
+                float uf = r / dm->delta;
+                u = (double)uf;
+                q = (double)rintf(uf); /* round half to even */
+              } else {
+                double r = a - pred;
+                u = r / (double)dm->delta;
+                q = nearbyint(u);
+              }
+              if (pred_out) pred_out[out] = pred;
+              if (u_out) u_out[out] = u;
+              if (!isfinite(u) || fabs(q) > (double)dm->qmax) {
+                symbols[out] = ESCAPE;
+                if (n_esc >= esc_cap) return PLCO_ERR_CAPACITY;
+                esc_vals[n_esc++] = raw;
+                ++cnt;
+              } else {
+                symbols[out] = (uint8_t)((int)q + ZERO_SYMBOL);
+              }
+            }
+          }
+        }
+        esc_cnt[stream] = cnt;
+      }
+  return PLCO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Symbol statistics                                                         */
+/* ------------------------------------------------------------------------- */
+
+int plco_histogram(const uint8_t *symbols, int64_t n_streams,
+                   int64_t syms_per_stream, uint32_t *counts) {
+  if (n_streams < 0 || syms_per_stream < 0) return PLCO_ERR_INVALID;
+  for (int64_t st = 0; st < n_streams; ++st) {
+    uint32_t *c = counts + st * 256;
+    memset(c, 0, 256 * sizeof(uint32_t));
+    for (int64_t t = 0; t < syms_per_stream; ++t) c[symbols[st * syms_per_stream + t]] += 1;
+  }
+  return PLCO_OK;
+}
+
+/* Frequencies on the 2^12 scale.  The cumulative counts are scaled and
+ * floored, so differences sum to 4096 by construction; a symbol that occurs
+ * but was scaled to zero then takes one unit from the currently largest
+ * frequency (lowest symbol on ties), in ascending symbol order. */
+int plco_build_freq(const uint32_t *counts, int64_t n_streams,
+                    uint16_t *freq, uint16_t *cum) {
+  for (int64_t st = 0; st < n_streams; ++st) {
+    const uint32_t *cnt = counts + st * 256;
+    uint32_t f[256];
+    uint64_t T = 0, C = 0, prev = 0;
+    int s;
+    for (s = 0; s < 256; ++s) T += cnt[s];
+    if (T == 0) return PLCO_ERR_INVALID;
+    for (s = 0; s < 256; ++s) {
+      C += cnt[s];
+      uint64_t scaled = (C * RANS_SCALE) / T; /* floor(C[s+1] * 4096 / T) */
+      f[s] = (uint32_t)(scaled - prev);
+      prev = scaled;
+    }
+    for (s = 0; s < 256; ++s) {
+      if (cnt[s] > 0 && f[s] == 0) {
+        int donor = 0, m;
+        for (m = 1; m < 256; ++m)
+          if (f[m] > f[donor]) donor = m;
+        f[donor] -= 1;
+        f[s] = 1;
+      }
+    }
+    uint32_t acc = 0;
+    for (s = 0; s < 256; ++s) {
+      freq[st * 256 + s] = (uint16_t)f[s];
+      if (cum) cum[st * 257 + s] = (uint16_t)acc;
+      acc += f[s];
+    }
+    if (cum) cum[st * 257 + 256] = (uint16_t)acc;
+    if (acc != RANS_SCALE) return PLCO_ERR_INVALID;
+  }
+  return PLCO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* 32-lane interleaved rANS                                                  */
+/* ------------------------------------------------------------------------- */
+
+int64_t plco_units_per_stream(int64_t syms_per_stream, int32_t chunk_syms) {
+  if (chunk_syms <= 0) return 1;
+  return (syms_per_stream + chunk_syms - 1) / chunk_syms;
+}
+
+/* Encode one unit.  Symbol t sits in lane t mod 32.  The encoder walks the
+ * symbols from the last to the first so that the decoder meets them first to
+ * last; words are appended in the order they are produced. */
+static int rans_encode_unit(const uint8_t *sym, int64_t N, const uint16_t *f,
+                            const uint32_t *cum, uint32_t *state_out,
+                            uint16_t *words, uint64_t cap, uint32_t *n_words_out) {
+  uint32_t x[RANS_LANES];
+  uint64_t nw = 0;
+  for (int lane = 0; lane < RANS_LANES; ++lane) x[lane] = RANS_LOW;
+  for (int64_t t = N - 1; t >= 0; --t) { /* group descending, lane descending */
+    int lane = (int)(t % RANS_LANES);
+    uint32_t fs = f[sym[t]];
+    uint32_t cs = cum[sym[t]];
+    if (fs == 0) return PLCO_ERR_INVALID; /* symbol absent from the table */
+    /* renormalise: keep the coding step's result below 2^32.  x >= fs * 2^20
+     * is tested on the high bits because fs * 2^20 does not fit 32 bits for
+     * fs = 4096.  One word always suffices. */
+    if ((x[lane] >> 20) >= fs) {
+      if (nw >= cap) return PLCO_ERR_CAPACITY;
+      words[nw++] = (uint16_t)(x[lane] & 0xffffu);
+      x[lane] >>= 16;
+    }
+    x[lane] = (x[lane] / fs) * RANS_SCALE + (x[lane] % fs) + cs;
+  }
+  for (int lane = 0; lane < RANS_LANES; ++lane) state_out[lane] = x[lane];
+  if (nw > 0xffffffffull) return PLCO_ERR_CAPACITY;
+  *n_words_out = (uint32_t)nw;
+  return PLCO_OK;
+}
+
+/* Decode one unit: the exact inverse, symbols first to last, words consumed
+ * from the end of the unit's word list backwards. */
+static int rans_decode_unit(const uint16_t *f, const uint32_t *cum,
+                            const uint8_t *slot_to_sym, const uint32_t *state_in,
+                            const uint16_t *words, uint32_t n_words, int64_t N,
+                            uint8_t *sym) {
+  uint32_t x[RANS_LANES];
+  uint64_t ptr = n_words;
+  for (int lane = 0; lane < RANS_LANES; ++lane) x[lane] = state_in[lane];
+  for (int64_t t = 0; t < N; ++t) { /* group ascending, lane ascending */
+    int lane = (int)(t % RANS_LANES);
+    uint32_t slot = x[lane] & (RANS_SCALE - 1);
+    uint8_t s = slot_to_sym[slot];
+    sym[t] = s;
+    x[lane] = (uint32_t)f[s] * (x[lane] >> RANS_SCALE_BITS) + slot - cum[s];
+    if (x[lane] < RANS_LOW) {
+      if (ptr == 0) return PLCO_ERR_CORRUPT;
+      x[lane] = (x[lane] << 16) | words[--ptr];
+    }
+  }
+  /* integrity: every word used, every lane back at its initial state */
+  if (ptr != 0) return PLCO_ERR_CORRUPT;
+  for (int lane = 0; lane < RANS_LANES; ++lane)
+    if (x[lane] != RANS_LOW) return PLCO_ERR_CORRUPT;
+  return PLCO_OK;
+}
+
+static int check_rans_args(int64_t n_streams, int64_t N, int32_t chunk_syms) {
+  if (n_streams < 0 || N < 1) return PLCO_ERR_INVALID;
+  if (chunk_syms < 0 || (chunk_syms % RANS_LANES) != 0) return PLCO_ERR_INVALID;
+  return PLCO_OK;
+}
+
+int plco_rans_encode(const uint8_t *symbols, int64_t n_streams,
+                     int64_t syms_per_stream, int32_t chunk_syms,
+                     const uint16_t *freq, uint32_t *states, uint16_t *words,
+                     const uint64_t *word_off, uint64_t word_cap_per_unit,
+                     uint32_t *n_words) {
+  int rc = check_rans_args(n_streams, syms_per_stream, chunk_syms);
+  if (rc) return rc;
+  const int64_t N = syms_per_stream;
+  const int64_t U = plco_units_per_stream(N, chunk_syms);
+  const int64_t C = chunk_syms > 0 ? chunk_syms : N;
+  for (int64_t st = 0; st < n_streams; ++st) {
+    const uint16_t *f = freq + st * 256;
+    uint32_t cum[257];
+    cum[0] = 0;
+    for (int s = 0; s < 256; ++s) cum[s + 1] = cum[s] + f[s];
+    if (cum[256] != RANS_SCALE) return PLCO_ERR_INVALID;
+    for (int64_t u = 0; u < U; ++u) {
+      int64_t unit = st * U + u;
+      int64_t begin = u * C;
+      int64_t len = (begin + C <= N) ? C : (N - begin);
+      rc = rans_encode_unit(symbols + st * N + begin, len, f, cum,
+                            states + unit * RANS_LANES, words + word_off[unit],
+                            word_cap_per_unit, n_words + unit);
+      if (rc) return rc;
+    }
+  }
+  return PLCO_OK;
+}
+
+int plco_rans_decode(const uint16_t *freq, const uint32_t *states,
+                     const uint16_t *words, const uint64_t *word_off,
+                     const uint32_t *n_words, int64_t n_streams,
+                     int64_t syms_per_stream, int32_t chunk_syms,
+                     uint8_t *symbols) {
+  int rc = check_rans_args(n_streams, syms_per_stream, chunk_syms);
+  if (rc) return rc;
+  const int64_t N = syms_per_stream;
+  const int64_t U = plco_units_per_stream(N, chunk_syms);
+  const int64_t C = chunk_syms > 0 ? chunk_syms : N;
+  for (int64_t st = 0; st < n_streams; ++st) {
+    const uint16_t *f = freq + st * 256;
+    uint32_t cum[257];
+    uint8_t slot_to_sym[RANS_SCALE];
+    cum[0] = 0;
+    for (int s = 0; s < 256; ++s) cum[s + 1] = cum[s] + f[s];
+    if (cum[256] != RANS_SCALE) return PLCO_ERR_CORRUPT;
+    /* the symbol s with cum[s] <= slot < cum[s+1], tabulated for every slot */
+    for (int s = 0; s < 256; ++s)
+      for (uint32_t slot = cum[s]; slot < cum[s + 1]; ++slot) slot_to_sym[slot] = (uint8_t)s;
+    for (int64_t u = 0; u < U; ++u) {
+      int64_t unit = st * U + u;
+      int64_t begin = u * C;
+      int64_t len = (begin + C <= N) ? C : (N - begin);
+      rc = rans_decode_unit(f, cum, slot_to_sym, states + unit * RANS_LANES,
+                            words + word_off[unit], n_words[unit], len,
+                            symbols + st * N + begin);
+      if (rc) return rc;
+    }
+  }
+  return PLCO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Decode side: dequantise, add the prediction back (Sec. 7.2, point 2)      */
+/* ------------------------------------------------------------------------- */
+
+int plco_reconstruct(const plco_dims *dm, int mode,
+                     const uint16_t *cand_k, const uint16_t *cand_v,
+                     const float *probs, const uint8_t *symbols,
+                     const uint16_t *esc_vals, const uint64_t *esc_off,
+                     uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
+  int rc = check_dims(dm);
+  if (rc) return rc;
+  const int S = dm->S, L = dm->L, H = dm->H, n = dm->n, k = dm->k, d = dm->d;
+  double w[64];
+  if (k > 64) return PLCO_ERR_INVALID;
+  int64_t in = 0;
+
+  for (int s = 0; s < S; ++s)
+    for (int l = 0; l < L; ++l)
+      for (int h = 0; h < H; ++h) {
+        int64_t stream = ((int64_t)s * L + l) * H + h;
+        uint64_t next_esc = esc_off[stream];
+        for (int i = 0; i < n; ++i) {
+          rc = plco_weights(probs + ((int64_t)s * n + i) * k, k, mode, w);
+          if (rc) return rc;
+          for (int c = 0; c < 2; ++c) {
+            const uint16_t *cand = c ? cand_v : cand_k;
+            uint16_t *out = c ? out_v : out_k;
+            int64_t cbase = s * dm->cand_stride[0] + l * dm->cand_stride[1] +
+                            h * dm->cand_stride[2] + i * dm->cand_stride[3];
+            int64_t abase = s * dm->act_stride[0] + l * dm->act_stride[1] +
+                            h * dm->act_stride[2] + i * dm->act_stride[3];
+            for (int e = 0; e < d; ++e, ++in) {
+              uint8_t sym = symbols[in];
+              if (sym == ESCAPE) {
+                uint16_t raw = esc_vals[next_esc++];
+                out[abase + e] = raw;
+                if (pre_round_out) pre_round_out[in] = plco_half_to_double(raw);
+                continue;
+              }
+              double pred = predict_one(w, cand + cbase + e, dm->cand_stride[4], k, mode);
+              int q = (int)sym - ZERO_SYMBOL;
+              double xhat;
+              if (mode == PLCO_F32) {
+                xhat = (double)fmaf((float)q, dm->delta, (float)pred);
+              } else {
+                xhat = pred + (double)q * (double)dm->delta;
+              }
+              if (pre_round_out) pre_round_out[in] = xhat;
+              out[abase + e] = plco_double_to_half(xhat);
+            }
+          }
+        }
+      }
+  return PLCO_OK;
+}
