@@ -1,0 +1,203 @@
+/*
+ * plc.h -- predictive delta coding of a transformer KV cache on AMD MI355X
+ * (gfx950): the C boundary of libplc.so.
+ *
+ * The method (paper "Sequential KV Cache Compression via Probabilistic
+ * Language Tries", Layer 2): before a KV vector is written to the cache, the
+ * model's own next-token distribution predicts it; only the residual is
+ * quantised and entropy coded.  Before it is read, the residual is decoded
+ * and the identically recomputed prediction is added back (Sec. 7.2,
+ * "Integration with the inference loop").
+ *
+ * Conventions for every entry point
+ *   - Plain C ABI.  All data pointers are DEVICE pointers unless a parameter is
+ *     marked "host".  `stream` is a hipStream_t passed as void* (NULL = the
+ *     default stream).  Calls only enqueue kernels on `stream` and return; they
+ *     never synchronise, allocate or free.
+ *   - The caller owns every buffer.  `const` inputs are never written.
+ *     Scratch comes from a caller-provided workspace (plc_workspace_bytes).
+ *   - Return value: PLC_OK, or an error detected on the host before anything
+ *     was enqueued (PLC_ERR_INVALID), or a HIP launch failure (PLC_ERR_HIP).
+ *   - Errors that depend on the data are reported through `status`, a device
+ *     uint32_t the caller zeroes beforehand and reads after synchronising:
+ *     kernels raise it (atomic max) to one of the PLC_ERR_* codes.  Outputs of
+ *     a call whose status is non-zero are unspecified but every access stays
+ *     inside the buffers described here.
+ *   - Calls on different streams are independent as long as their buffers
+ *     (including workspace and status) are distinct.
+ *
+ * Data layout
+ *   stream   one per (session s, layer l, KV head h): id = (s*L + l)*H + h.
+ *   symbol   one byte per KV component.  Inside a stream, component e of
+ *            position i sits at t = (i*2 + c)*d + e with c = 0 for K and 1 for
+ *            V, so a stream has N = 2*n*d symbols and `symbols` is the
+ *            contiguous array u8 [S,L,H,n,2,d].  Symbol q+127 stands for the
+ *            quantised residual q in [-qmax, qmax]; 255 is the escape symbol.
+ *   escapes  raw fp16 bit patterns of the escaped components, stream after
+ *            stream, in symbol order inside each stream.
+ *   table    256 x u16 frequencies per stream summing to 4096.
+ *   rANS     32 interleaved lanes per coded unit; symbol t belongs to lane
+ *            t mod 32; 32-bit states in [2^16, 2^32); 16-bit words.  The
+ *            encoder walks symbols last to first and appends words as they are
+ *            produced; the decoder walks first to last and consumes the word
+ *            list from its end.  A unit is a whole stream (chunk_syms = 0) or a
+ *            run of chunk_syms symbols of it (chunk_syms a multiple of 32);
+ *            unit id = stream * units_per_stream + chunk.
+ */
+#ifndef PLC_H
+#define PLC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PLC_OK 0
+#define PLC_ERR_INVALID 1  /* bad argument, or an invalid probability row / empty histogram  */
+#define PLC_ERR_CAPACITY 2 /* an output list (escapes, rANS words) was too small             */
+#define PLC_ERR_CORRUPT 3  /* decoder integrity check failed                                 */
+#define PLC_ERR_HIP 4      /* the HIP runtime refused a launch                               */
+
+#define PLC_ESCAPE 255     /* escape symbol                                                  */
+#define PLC_RANS_LANES 32
+#define PLC_RANS_SCALE 4096
+
+typedef struct plc_dims {
+  int32_t S, L, H, n, k, d; /* sessions, layers, KV heads, positions, candidates (1..32), head dim (multiple of 8) */
+  int64_t cand_stride[5];   /* element strides of the candidate tensors for (s, l, h, i, j); component e is
+                               contiguous.  Every stride must be a multiple of 8 (16-byte rows).             */
+  int64_t act_stride[4];    /* element strides of actual / reconstructed KV for (s, l, h, i); multiples of 8 */
+  float delta;              /* quantiser step, > 0.  The step IS this fp32 value.                            */
+  int32_t qmax;             /* largest |q| with a symbol of its own, 1..127                                  */
+} plc_dims;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int plc_version(void);
+
+/* Static text for a PLC_* code (host pointer, never NULL). */
+const char *plc_strerror(int code);
+
+/* Bytes of device workspace plc_predict_residual / plc_reconstruct need for
+ * these dimensions (0 if dims are invalid).  Host call. */
+size_t plc_workspace_bytes(const plc_dims *dims /* host */);
+
+/* Number of rANS units per stream for a chunk length (1 when chunk_syms = 0). Host call. */
+int64_t plc_units_per_stream(int64_t syms_per_stream, int32_t chunk_syms);
+
+/*
+ * Encode side, floating-point part.  For every (s,l,h,i) and for K and V:
+ *   weights     w_j = p_j / sum_m p_m over the k candidates (Sec. 7.1, "Top-k
+ *               approximation": the prediction is renormalised over the top k);
+ *   prediction  pred = sum_j w_j * cand_j, accumulated in fp32 with fused
+ *               multiply-add, j ascending from 0 (Def. "Predicted KV vector"
+ *               restricted to the top k);
+ *   residual    r = act - pred (Def. "KV residual");
+ *   quantise    q = round-half-even(r / delta) (Sec. 7.2, point 1: "quantize
+ *               and write R_i"); symbol q+127 if |q| <= qmax and r/delta is
+ *               finite, else 255 with the raw fp16 of `act` appended to the
+ *               stream's escape list.
+ * One probability row serves every layer, head, K and V of a position.
+ *
+ *   dims      host; validated (PLC_ERR_INVALID).
+ *   cand_k/v  fp16, logical [S,L,H,n,k,d] addressed through dims->cand_stride; 16-byte aligned.
+ *   probs     fp32 [S,n,k] contiguous, raw top-k probabilities.  A row with a negative or NaN
+ *             entry, or whose sum is not positive and finite, raises status PLC_ERR_INVALID.
+ *   act_k/v   fp16, logical [S,L,H,n,d] through dims->act_stride; 16-byte aligned.
+ *   symbols   out, u8 [S,L,H,n,2,d] contiguous; 8-byte aligned.
+ *   esc_vals  out, u16[esc_cap].  If the escapes do not fit, status PLC_ERR_CAPACITY is raised
+ *             and only the first esc_cap entries are written.
+ *   esc_cnt   out, u32 [S*L*H]: escapes per stream.
+ *   esc_off   out, u64 [S*L*H]: start of each stream's list in esc_vals (exclusive prefix sum).
+ *   pred_out  out, nullable: fp32 [S,L,H,n,2,d], the prediction (for inspection and tests).
+ *   ws        workspace of at least plc_workspace_bytes(dims) bytes, 256-byte aligned.
+ *   status    device u32, see above.
+ */
+int plc_predict_residual(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                         const float *probs, const void *act_k, const void *act_v,
+                         uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                         uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
+                         void *ws, size_t ws_bytes, uint32_t *status, void *stream);
+
+/*
+ * Per-stream symbol statistics for the entropy coder ("standard source
+ * coding" of the residuals, proof of Prop. "Layer orthogonality", Sec. 6.1).
+ *   symbols  u8 [n_streams, syms_per_stream] contiguous.
+ *   counts   out, u32 [n_streams, 256]; overwritten.  syms_per_stream < 2^32.
+ */
+int plc_histogram(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                  uint32_t *counts, void *stream);
+
+/*
+ * Counts -> integer frequency table on the 2^12 scale, integer arithmetic
+ * only.  With C the inclusive running count and T the total,
+ *   f[s] = floor(C[s] * 4096 / T) - floor(C[s-1] * 4096 / T);
+ * then, for s ascending, every symbol that occurs but got f[s] = 0 takes one
+ * unit from the currently largest frequency (lowest symbol on ties).
+ *   counts  u32 [n_streams, 256].  A stream with T = 0 raises status PLC_ERR_INVALID.
+ *   freq    out, u16 [n_streams, 256]  (a single-symbol stream has f = 4096).
+ *   cum     out, nullable: u16 [n_streams, 257], exclusive prefix sums of freq.
+ */
+int plc_build_freq(const uint32_t *counts, int64_t n_streams, uint16_t *freq, uint16_t *cum,
+                   uint32_t *status, void *stream);
+
+/*
+ * rANS encoder.  For each unit, with x = 2^16 in all 32 lanes initially and
+ * for t from the unit's last symbol down to its first (lane = t mod 32):
+ *   if (x >> 20) >= f[sym]:  append (x & 0xffff) to the unit's words, x >>= 16
+ *   x = (x / f[sym]) * 4096 + (x % f[sym]) + cum[sym]
+ *   symbols   u8 [n_streams, syms_per_stream].
+ *   freq      u16 [n_streams, 256] summing to 4096 with f > 0 for every symbol that occurs;
+ *             a symbol with f = 0 in the data raises status PLC_ERR_INVALID.
+ *   states    out, u32 [n_units, 32]: final lane states.
+ *   words     out, u16: unit u writes words[word_off[u] .. word_off[u] + n_words[u]).
+ *   word_off  u64 [n_units], chosen by the caller; word_cap_per_unit entries are reserved for
+ *             each unit.  A unit never needs more words than it has symbols.  If the
+ *             reservation is too small, status PLC_ERR_CAPACITY is raised and nothing is
+ *             written past it.
+ *   n_words   out, u32 [n_units].
+ */
+int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                    int32_t chunk_syms, const uint16_t *freq, uint32_t *states,
+                    uint16_t *words, const uint64_t *word_off, uint64_t word_cap_per_unit,
+                    uint32_t *n_words, uint32_t *status, void *stream);
+
+/*
+ * rANS decoder, the exact inverse.  For each unit, x = states, ptr = n_words,
+ * and for t from the unit's first symbol to its last (lane = t mod 32):
+ *   slot = x & 4095;  sym = the s with cum[s] <= slot < cum[s+1]
+ *   x = f[sym] * (x >> 12) + slot - cum[sym]
+ *   if x < 2^16:  x = (x << 16) | words[--ptr]
+ * At the end ptr must be 0 and every lane state 2^16, otherwise status
+ * PLC_ERR_CORRUPT is raised.  Reads stay inside words[0 .. words_len) and
+ * inside each unit's [word_off, word_off + n_words) whatever the data holds.
+ *   symbols   out, u8 [n_streams, syms_per_stream].
+ */
+int plc_rans_decode(const uint16_t *freq, const uint32_t *states, const uint16_t *words,
+                    uint64_t words_len, const uint64_t *word_off, const uint32_t *n_words,
+                    int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms,
+                    uint8_t *symbols, uint32_t *status, void *stream);
+
+/*
+ * Decode side, floating-point part (Sec. 7.2, point 2: "dequantize R_i; add
+ * back the prediction, recomputed identically"; Prop. "Three-layer
+ * composition", correctness: the error of the recovered KV is the quantiser's
+ * error on the residual).  The prediction is computed exactly as in
+ * plc_predict_residual; then x = fma((float)(sym - 127), delta, pred), rounded
+ * to fp16 (nearest even).  An escape symbol takes the next raw fp16 of its
+ * stream's escape list instead.
+ *   symbols   u8 [S,L,H,n,2,d].
+ *   esc_vals  u16[esc_len]; esc_off u64 [S*L*H] as produced by plc_predict_residual.  An escape
+ *             whose list index falls outside esc_len raises status PLC_ERR_CORRUPT.
+ *   out_k/v   out, fp16 logical [S,L,H,n,d] through dims->act_stride; 16-byte aligned.
+ */
+int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                    const float *probs, const uint8_t *symbols, const uint16_t *esc_vals,
+                    uint64_t esc_len, const uint64_t *esc_off, void *out_k, void *out_v,
+                    void *ws, size_t ws_bytes, uint32_t *status, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLC_H */

@@ -1,0 +1,117 @@
+"""Buffer management around the six libplc calls: allocate once, then encode
+and decode a KV cache of fixed shape any number of times.  Every step of the
+coding path runs inside libplc; this class only owns torch tensors and calls
+the entry points in order."""
+from __future__ import annotations
+
+import dataclasses
+
+import torch
+
+from . import plc
+
+
+@dataclasses.dataclass
+class Coded:
+    """What an encode leaves in device memory (views into the codec's buffers)."""
+    symbols: torch.Tensor    # u8  [streams, N]
+    esc_vals: torch.Tensor   # i16 [esc_cap] raw fp16 bit patterns, stream after stream
+    esc_cnt: torch.Tensor    # i32 [streams]
+    esc_off: torch.Tensor    # i64 [streams]
+    counts: torch.Tensor     # i32 [streams, 256]
+    freq: torch.Tensor       # i16 [streams, 256]
+    cum: torch.Tensor        # i16 [streams, 257]
+    states: torch.Tensor     # i32 [units, 32]
+    words: torch.Tensor      # i16 [units * word_cap]
+    word_off: torch.Tensor   # i64 [units]
+    n_words: torch.Tensor    # i32 [units]
+
+
+class KVDeltaCodec:
+    def __init__(self, S, L, H, n, k, d, delta, qmax=127, chunk_syms=0, device="cuda",
+                 cand_stride=None, act_stride=None, esc_frac=1.0 / 16, word_frac=1.0,
+                 want_pred=False):
+        self.device = torch.device(device)
+        self.dims = plc.make_dims(S, L, H, n, k, d, delta, qmax, cand_stride, act_stride)
+        self.S, self.L, self.H, self.n, self.k, self.d = S, L, H, n, k, d
+        self.n_streams = S * L * H
+        self.N = 2 * n * d
+        self.chunk_syms = int(chunk_syms)
+        self.units_per_stream = plc.plc_units_per_stream(self.N, self.chunk_syms)
+        self.n_units = self.n_streams * self.units_per_stream
+        unit_syms = self.chunk_syms if self.chunk_syms else self.N
+        # words per unit: never more than one per symbol; rounded up to 16 bytes
+        self.word_cap = (max(8, int(unit_syms * word_frac)) + 7) // 8 * 8
+        E = self.n_streams * self.N
+        esc_cap = max(64, int(E * esc_frac))
+        dev = self.device
+        ws_bytes = plc.plc_workspace_bytes(self.dims)
+        if ws_bytes == 0:
+            raise plc.PlcError(plc.PLC_ERR_INVALID, "plc_workspace_bytes")
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        self.status = torch.zeros(1, dtype=torch.int32, device=dev)
+        self.symbols = torch.empty((self.n_streams, self.N), dtype=torch.uint8, device=dev)
+        self.esc_vals = torch.empty(esc_cap, dtype=torch.int16, device=dev)
+        self.esc_cnt = torch.empty(self.n_streams, dtype=torch.int32, device=dev)
+        self.esc_off = torch.empty(self.n_streams, dtype=torch.int64, device=dev)
+        self.counts = torch.empty((self.n_streams, 256), dtype=torch.int32, device=dev)
+        self.freq = torch.empty((self.n_streams, 256), dtype=torch.int16, device=dev)
+        self.cum = torch.empty((self.n_streams, 257), dtype=torch.int16, device=dev)
+        self.states = torch.empty((self.n_units, 32), dtype=torch.int32, device=dev)
+        self.words = torch.empty(self.n_units * self.word_cap, dtype=torch.int16, device=dev)
+        self.word_off = torch.arange(self.n_units, dtype=torch.int64, device=dev) * self.word_cap
+        self.n_words = torch.empty(self.n_units, dtype=torch.int32, device=dev)
+        self.pred = (torch.empty((self.n_streams, self.N), dtype=torch.float32, device=dev)
+                     if want_pred else None)
+        self.dec_symbols = torch.empty_like(self.symbols)
+
+    # -- single steps -------------------------------------------------------------------
+    def predict_residual(self, cand_k, cand_v, probs, act_k, act_v):
+        plc.plc_predict_residual(self.dims, cand_k, cand_v, probs, act_k, act_v, self.symbols,
+                                 self.esc_vals, self.esc_cnt, self.esc_off, self.ws, self.status,
+                                 pred_out=self.pred)
+
+    def histogram(self, symbols=None):
+        plc.plc_histogram(self.symbols if symbols is None else symbols, self.n_streams, self.N, self.counts)
+
+    def build_freq(self):
+        plc.plc_build_freq(self.counts, self.n_streams, self.freq, self.cum, self.status)
+
+    def rans_encode(self, symbols=None):
+        plc.plc_rans_encode(self.symbols if symbols is None else symbols, self.n_streams, self.N,
+                            self.chunk_syms, self.freq, self.states, self.words, self.word_off,
+                            self.word_cap, self.n_words, self.status)
+
+    def rans_decode(self, out=None):
+        out = self.dec_symbols if out is None else out
+        plc.plc_rans_decode(self.freq, self.states, self.words, self.word_off, self.n_words,
+                            self.n_streams, self.N, self.chunk_syms, out, self.status)
+        return out
+
+    def reconstruct(self, cand_k, cand_v, probs, out_k, out_v, symbols=None):
+        plc.plc_reconstruct(self.dims, cand_k, cand_v, probs,
+                            self.dec_symbols if symbols is None else symbols,
+                            self.esc_vals, self.esc_off, out_k, out_v, self.ws, self.status)
+
+    # -- whole directions ---------------------------------------------------------------
+    def encode(self, cand_k, cand_v, probs, act_k, act_v) -> Coded:
+        self.predict_residual(cand_k, cand_v, probs, act_k, act_v)
+        self.histogram()
+        self.build_freq()
+        self.rans_encode()
+        return self.coded()
+
+    def decode(self, cand_k, cand_v, probs, out_k, out_v):
+        self.rans_decode()
+        self.reconstruct(cand_k, cand_v, probs, out_k, out_v)
+
+    def coded(self) -> Coded:
+        return Coded(self.symbols, self.esc_vals, self.esc_cnt, self.esc_off, self.counts, self.freq,
+                     self.cum, self.states, self.words, self.word_off, self.n_words)
+
+    def check_status(self, where="plc"):
+        """Synchronises and raises if a kernel reported a data-dependent error."""
+        code = int(self.status.item())
+        if code != plc.PLC_OK:
+            self.status.zero_()
+            raise plc.PlcError(code, where)

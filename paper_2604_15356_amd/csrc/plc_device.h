@@ -1,0 +1,64 @@
+// Internal helpers shared by the device sources of libplc (not part of the C boundary).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plc.h"
+
+namespace plc {
+
+// One tile = the 2048 consecutive symbols of a stream that one 256-thread
+// workgroup handles: each thread owns one 16-byte chunk of 8 fp16 components.
+constexpr int kBlock = 256;
+constexpr int kChunk = 8;
+constexpr int kTileSyms = kBlock * kChunk;
+
+constexpr uint32_t kZeroSymbol = 127;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// 16-byte load of data that is read once: keep it from displacing cache lines that are reused.
+__device__ __forceinline__ uint4 load16_stream(const void *p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? PLC_OK : PLC_ERR_HIP; }
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+__device__ __forceinline__ void raise(uint32_t *status, uint32_t code) {
+  if (status) atomicMax(status, code);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wavefront.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    uint32_t up = __shfl_up(v, off, 64);
+    if (lane >= off) v += up;
+  }
+  return v;
+}
+
+// Exclusive prefix sum of one value per thread over a 256-thread workgroup.
+// `smem` needs 5 words.  Returns the exclusive prefix; *total gets the block sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t *smem, uint32_t *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t inc = wave_inclusive_scan(v);
+  __syncthreads();  // protect smem against a previous use
+  if (lane == 63) smem[wave] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+#pragma unroll
+  for (int w = 0; w < kBlock / 64; ++w) {
+    uint32_t s = smem[w];
+    if (w < wave) base += s;
+  }
+  *total = smem[0] + smem[1] + smem[2] + smem[3];
+  return base + inc - v;
+}
+
+}  // namespace plc

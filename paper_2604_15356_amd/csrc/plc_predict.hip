@@ -1,0 +1,469 @@
+// Floating-point half of the codec: top-k prediction, residual, quantiser
+// (encode) and dequantise / add-back (decode).  See include/plc.h for the
+// definition of every step; the paper passages are Sec. 7.1 ("Top-k
+// approximation"), Def. "KV residual" and Sec. 7.2 (the two integration
+// points of the inference loop).
+//
+// Both directions are HBM streams: per KV component they read 2k bytes of
+// candidates and touch 3 more bytes, with about 2k + 20 fp32 operations in
+// between.  There is no data reuse and no contraction, so the kernels are
+// organised purely around wide coalesced accesses: one thread owns one
+// 16-byte chunk (8 components) of one K or V row, and issues all of its
+// k + 1 loads before the first use.
+#include "plc_device.h"
+
+namespace plc {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+struct CodecArgs {
+  const uint16_t *cand_k, *cand_v;
+  const uint16_t *act_k, *act_v;  // encode only
+  uint16_t *out_k, *out_v;        // decode only
+  const float *weights;           // [S, n, k] renormalised weights
+  uint8_t *symbols;               // encode: out, decode: in
+  const uint16_t *esc_in;         // decode
+  uint64_t esc_len;               // decode
+  const uint64_t *esc_off;        // decode
+  float *pred_out;                // encode, nullable
+  uint32_t *tile_cnt;             // [n_streams * tiles_per_stream] escapes per tile
+  const uint32_t *tile_off;       // decode: exclusive prefix of tile_cnt inside a stream
+  uint32_t *status;
+  int32_t L, H, n, k, d8;
+  uint32_t tiles_per_stream, chunks_per_stream;
+  int64_t cs[5], as[4];
+  int64_t syms_per_stream;
+  float delta, qmax;
+};
+
+// Where a thread's chunk lives.  All threads of a workgroup share (s, l, h).
+struct Coord {
+  bool valid;
+  int64_t cand;  // element offset of candidate 0, component 0 of the chunk
+  int64_t act;   // element offset in act / out
+  int64_t w;     // offset of the weight row
+  int64_t sym;   // offset in symbols / pred_out
+  int c;         // 0 = K, 1 = V
+  uint32_t stream, tile;
+};
+
+__device__ __forceinline__ Coord locate(const CodecArgs &a) {
+  Coord q;
+  q.stream = blockIdx.x / a.tiles_per_stream;
+  q.tile = blockIdx.x - q.stream * a.tiles_per_stream;
+  const uint32_t lh = a.L * a.H;
+  const uint32_t s = q.stream / lh;
+  const uint32_t r = q.stream - s * lh;
+  const uint32_t l = r / a.H;
+  const uint32_t h = r - l * a.H;
+  const uint32_t chunk = q.tile * kBlock + threadIdx.x;
+  q.valid = chunk < a.chunks_per_stream;
+  const uint32_t row = chunk / (uint32_t)a.d8;  // row = i * 2 + c
+  const uint32_t e8 = chunk - row * a.d8;
+  const uint32_t i = row >> 1;
+  q.c = row & 1;
+  q.cand = s * a.cs[0] + l * a.cs[1] + h * a.cs[2] + (int64_t)i * a.cs[3] + e8 * kChunk;
+  q.act = s * a.as[0] + l * a.as[1] + h * a.as[2] + (int64_t)i * a.as[3] + e8 * kChunk;
+  q.w = ((int64_t)s * a.n + i) * a.k;
+  q.sym = (int64_t)q.stream * a.syms_per_stream + (int64_t)chunk * kChunk;
+  return q;
+}
+
+// pred[e] = sum_j w[j] * cand_j[e], fp32 fused multiply-add, j ascending from 0.
+template <int K>
+__device__ __forceinline__ void predict8(const uint16_t *cand, int64_t sj, const float *w, int k,
+                                         float pred[kChunk]) {
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) pred[e] = 0.0f;
+  if constexpr (K > 0) {
+    uint4 cv[K];
+    float wv[K];
+#pragma unroll
+    for (int j = 0; j < K; ++j) cv[j] = load16_stream(cand + j * sj);
+#pragma unroll
+    for (int j = 0; j < K; ++j) wv[j] = w[j];
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      const half8 c = __builtin_bit_cast(half8, cv[j]);
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) pred[e] = __builtin_fmaf(wv[j], (float)c[e], pred[e]);
+    }
+  } else {
+#pragma unroll 4
+    for (int j = 0; j < k; ++j) {
+      const half8 c = __builtin_bit_cast(half8, load16_stream(cand + j * sj));
+      const float wj = w[j];
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) pred[e] = __builtin_fmaf(wj, (float)c[e], pred[e]);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// w[s,i,j] = p[s,i,j] / sum_m p[s,i,m]   (one thread per probability row)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void weights_kernel(const float *__restrict__ probs, float *__restrict__ w,
+                                                         int64_t rows, int k, uint32_t *status) {
+  const int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (row >= rows) return;
+  const float *p = probs + row * k;
+  float Z = 0.0f;
+  bool bad = false;
+  for (int j = 0; j < k; ++j) {
+    const float pj = p[j];
+    if (!(pj >= 0.0f)) bad = true;  // negative or NaN
+    Z = Z + pj;
+  }
+  if (!(Z > 0.0f) || __builtin_isinf(Z)) bad = true;
+  for (int j = 0; j < k; ++j) w[row * k + j] = bad ? 0.0f : p[j] / Z;
+  if (bad) raise(status, PLC_ERR_INVALID);
+}
+
+// ---------------------------------------------------------------------------
+// Encode: symbols and per-tile escape counts
+// ---------------------------------------------------------------------------
+template <int K>
+__global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArgs a) {
+  __shared__ uint32_t wave_cnt[kBlock / 64];
+  const Coord q = locate(a);
+  uint32_t n_esc = 0;
+  if (q.valid) {
+    const uint16_t *cand = (q.c ? a.cand_v : a.cand_k) + q.cand;
+    const uint16_t *act = (q.c ? a.act_v : a.act_k) + q.act;
+    const uint4 av = load16_stream(act);
+    float pred[kChunk];
+    predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
+    const half8 x = __builtin_bit_cast(half8, av);
+    uint32_t packed[2] = {0u, 0u};
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) {
+      const float r = (float)x[e] - pred[e];
+      const float u = r / a.delta;
+      const float qf = __builtin_rintf(u);  // round half to even
+      uint32_t sym;
+      if (__builtin_fabsf(qf) <= a.qmax) {  // false for NaN and infinities
+        sym = (uint32_t)((int)qf + (int)kZeroSymbol);
+      } else {
+        sym = PLC_ESCAPE;
+        ++n_esc;
+      }
+      packed[e >> 2] |= sym << (8 * (e & 3));
+    }
+    *reinterpret_cast<uint2 *>(a.symbols + q.sym) = make_uint2(packed[0], packed[1]);
+    if (a.pred_out) {
+      float4 *po = reinterpret_cast<float4 *>(a.pred_out + q.sym);
+      po[0] = make_float4(pred[0], pred[1], pred[2], pred[3]);
+      po[1] = make_float4(pred[4], pred[5], pred[6], pred[7]);
+    }
+  }
+  // escapes in this tile (their values are gathered by a second, sparse pass)
+  uint32_t wsum = n_esc;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) wsum += __shfl_xor(wsum, off, 64);
+  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = wsum;
+  __syncthreads();
+  if (threadIdx.x == 0) a.tile_cnt[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+}
+
+// Count the escape symbols of each tile (decode side).
+__global__ __launch_bounds__(kBlock) void count_escapes_kernel(const CodecArgs a) {
+  __shared__ uint32_t wave_cnt[kBlock / 64];
+  const Coord q = locate(a);
+  uint32_t n_esc = 0;
+  if (q.valid) {
+    const uint2 sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) n_esc += (((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE;
+  }
+  uint32_t wsum = n_esc;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) wsum += __shfl_xor(wsum, off, 64);
+  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = wsum;
+  __syncthreads();
+  if (threadIdx.x == 0) a.tile_cnt[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+}
+
+// Exclusive prefix sum of the tile counts inside each stream; one workgroup per stream.
+__global__ __launch_bounds__(kBlock) void scan_tiles_kernel(const uint32_t *__restrict__ tile_cnt,
+                                                            uint32_t *__restrict__ tile_off,
+                                                            uint32_t tiles_per_stream,
+                                                            uint32_t *__restrict__ esc_cnt) {
+  __shared__ uint32_t smem[8];
+  const int64_t base = (int64_t)blockIdx.x * tiles_per_stream;
+  uint32_t carry = 0;
+  for (uint32_t t0 = 0; t0 < tiles_per_stream; t0 += kBlock) {
+    const uint32_t t = t0 + threadIdx.x;
+    const uint32_t v = t < tiles_per_stream ? tile_cnt[base + t] : 0u;
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan(v, smem, &total);
+    if (t < tiles_per_stream) tile_off[base + t] = carry + ex;
+    carry += total;
+  }
+  if (esc_cnt && threadIdx.x == 0) esc_cnt[blockIdx.x] = carry;
+}
+
+// esc_off = exclusive prefix sum of esc_cnt over all streams (one workgroup).
+__global__ __launch_bounds__(kBlock) void scan_streams_kernel(const uint32_t *__restrict__ esc_cnt,
+                                                              uint64_t *__restrict__ esc_off, int64_t n_streams,
+                                                              uint64_t esc_cap, uint32_t *status) {
+  __shared__ uint32_t smem[8];
+  uint64_t carry = 0;
+  for (int64_t s0 = 0; s0 < n_streams; s0 += kBlock) {
+    const int64_t s = s0 + threadIdx.x;
+    const uint32_t v = s < n_streams ? esc_cnt[s] : 0u;  // a block of 256 streams holds < 2^32 escapes
+    uint32_t total;
+    const uint32_t ex = block_exclusive_scan(v, smem, &total);
+    if (s < n_streams) esc_off[s] = carry + ex;
+    carry += total;
+  }
+  if (threadIdx.x == 0 && carry > esc_cap) raise(status, PLC_ERR_CAPACITY);
+}
+
+// Write the raw fp16 of every escaped component to its place in the stream's list.
+__global__ __launch_bounds__(kBlock) void gather_escapes_kernel(const CodecArgs a, uint16_t *__restrict__ esc_vals,
+                                                                uint64_t esc_cap,
+                                                                const uint64_t *__restrict__ esc_off) {
+  __shared__ uint32_t smem[8];
+  if (a.tile_cnt[blockIdx.x] == 0) return;  // uniform
+  const Coord q = locate(a);
+  uint2 sv = make_uint2(0u, 0u);
+  uint32_t n_esc = 0;
+  if (q.valid) {
+    sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) n_esc += (((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE;
+  }
+  uint32_t total;
+  uint32_t rank = block_exclusive_scan(n_esc, smem, &total);
+  if (n_esc == 0) return;
+  const uint16_t *act = (q.c ? a.act_v : a.act_k) + q.act;
+  uint64_t dst = esc_off[q.stream] + a.tile_off[blockIdx.x] + rank;
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) {
+    if ((((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE) {
+      if (dst < esc_cap) esc_vals[dst] = act[e];
+      ++dst;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Decode: prediction again, plus the dequantised residual
+// ---------------------------------------------------------------------------
+template <int K>
+__global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) {
+  __shared__ uint32_t smem[8];
+  const Coord q = locate(a);
+  const bool tile_has_escapes = a.tile_cnt[blockIdx.x] != 0;  // uniform
+  uint2 sv = make_uint2(0u, 0u);
+  half8 out;
+  uint32_t n_esc = 0;
+  if (q.valid) {
+    const uint16_t *cand = (q.c ? a.cand_v : a.cand_k) + q.cand;
+    sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
+    float pred[kChunk];
+    predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) {
+      const uint32_t sym = ((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u;
+      n_esc += sym == PLC_ESCAPE;
+      const float qf = (float)((int)sym - (int)kZeroSymbol);
+      out[e] = (_Float16)__builtin_fmaf(qf, a.delta, pred[e]);  // fp32 -> fp16, nearest even
+    }
+  }
+  if (tile_has_escapes) {
+    uint32_t total;
+    const uint32_t rank = block_exclusive_scan(n_esc, smem, &total);
+    if (n_esc) {
+      uint64_t src = a.esc_off[q.stream] + a.tile_off[blockIdx.x] + rank;
+      uint16_t raw[kChunk];
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) {
+        raw[e] = 0;
+        if ((((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE) {
+          if (src < a.esc_len) {
+            raw[e] = a.esc_in[src];
+          } else {
+            raise(a.status, PLC_ERR_CORRUPT);
+          }
+          ++src;
+          out[e] = __builtin_bit_cast(_Float16, raw[e]);
+        }
+      }
+    }
+  }
+  if (q.valid) {
+    uint16_t *dst = (q.c ? a.out_v : a.out_k) + q.act;
+    *reinterpret_cast<uint4 *>(dst) = __builtin_bit_cast(uint4, out);
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+struct Plan {
+  int64_t n_streams, syms_per_stream, chunks_per_stream, tiles_per_stream, n_tiles, rows;
+  size_t off_weights, off_tile_cnt, off_tile_off, total;
+};
+
+bool make_plan(const plc_dims *dm, Plan *p) {
+  if (!dm) return false;
+  if (dm->S < 1 || dm->L < 1 || dm->H < 1 || dm->n < 1) return false;
+  if (dm->k < 1 || dm->k > 32) return false;
+  if (dm->d < kChunk || dm->d % kChunk) return false;
+  if (!(dm->delta > 0.0f) || !(dm->delta < 3.0e38f)) return false;
+  if (dm->qmax < 1 || dm->qmax > 127) return false;
+  for (int a = 0; a < 5; ++a)
+    if (dm->cand_stride[a] < 0 || dm->cand_stride[a] % kChunk) return false;
+  for (int a = 0; a < 4; ++a)
+    if (dm->act_stride[a] < 0 || dm->act_stride[a] % kChunk) return false;
+  p->n_streams = (int64_t)dm->S * dm->L * dm->H;
+  p->syms_per_stream = 2ll * dm->n * dm->d;
+  p->chunks_per_stream = p->syms_per_stream / kChunk;
+  p->tiles_per_stream = (p->chunks_per_stream + kBlock - 1) / kBlock;
+  p->n_tiles = p->n_streams * p->tiles_per_stream;
+  p->rows = (int64_t)dm->S * dm->n;
+  if (p->syms_per_stream >= (1ll << 32)) return false;  // u32 counts per stream
+  if (p->n_tiles >= (1ll << 31) || p->n_streams >= (1ll << 31)) return false;
+  p->off_weights = 0;
+  p->off_tile_cnt = align_up((size_t)p->rows * dm->k * sizeof(float), 256);
+  p->off_tile_off = p->off_tile_cnt + align_up((size_t)p->n_tiles * sizeof(uint32_t), 256);
+  p->total = p->off_tile_off + align_up((size_t)p->n_tiles * sizeof(uint32_t), 256);
+  return true;
+}
+
+bool aligned(const void *p, size_t a) { return p && (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+void fill_args(const plc_dims *dm, const Plan &p, void *ws, CodecArgs *a) {
+  char *w = static_cast<char *>(ws);
+  a->weights = reinterpret_cast<const float *>(w + p.off_weights);
+  a->tile_cnt = reinterpret_cast<uint32_t *>(w + p.off_tile_cnt);
+  a->tile_off = reinterpret_cast<const uint32_t *>(w + p.off_tile_off);
+  a->L = dm->L;
+  a->H = dm->H;
+  a->n = dm->n;
+  a->k = dm->k;
+  a->d8 = dm->d / kChunk;
+  a->tiles_per_stream = (uint32_t)p.tiles_per_stream;
+  a->chunks_per_stream = (uint32_t)p.chunks_per_stream;
+  for (int i = 0; i < 5; ++i) a->cs[i] = dm->cand_stride[i];
+  for (int i = 0; i < 4; ++i) a->as[i] = dm->act_stride[i];
+  a->syms_per_stream = p.syms_per_stream;
+  a->delta = dm->delta;
+  a->qmax = (float)dm->qmax;
+}
+
+template <template <int> class Launcher>
+void dispatch_k(int k, const CodecArgs &a, unsigned grid, hipStream_t st) {
+  switch (k) {
+#define PLC_CASE(K) \
+  case K:           \
+    Launcher<K>::run(a, grid, st); \
+    break;
+    PLC_CASE(1) PLC_CASE(2) PLC_CASE(3) PLC_CASE(4) PLC_CASE(5) PLC_CASE(6) PLC_CASE(7) PLC_CASE(8)
+    PLC_CASE(12) PLC_CASE(16) PLC_CASE(20)
+#undef PLC_CASE
+    default:
+      Launcher<0>::run(a, grid, st);
+  }
+}
+
+template <int K>
+struct LaunchPredict {
+  static void run(const CodecArgs &a, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL(predict_residual_kernel<K>, dim3(grid), dim3(kBlock), 0, st, a);
+  }
+};
+template <int K>
+struct LaunchReconstruct {
+  static void run(const CodecArgs &a, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL(reconstruct_kernel<K>, dim3(grid), dim3(kBlock), 0, st, a);
+  }
+};
+
+}  // namespace
+}  // namespace plc
+
+using namespace plc;
+
+extern "C" size_t plc_workspace_bytes(const plc_dims *dims) {
+  Plan p;
+  return make_plan(dims, &p) ? p.total : 0;
+}
+
+extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                    const float *probs, const void *act_k, const void *act_v,
+                                    uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                                    uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out, void *ws,
+                                    size_t ws_bytes, uint32_t *status, void *stream) {
+  Plan p;
+  if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(act_k, 16) || !aligned(act_v, 16))
+    return PLC_ERR_INVALID;
+  if (!aligned(symbols, 8) || !aligned(probs, 4) || !aligned(esc_cnt, 4) || !aligned(esc_off, 8))
+    return PLC_ERR_INVALID;
+  if (!aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total) return PLC_ERR_INVALID;
+  if (pred_out && !aligned(pred_out, 16)) return PLC_ERR_INVALID;
+  if (esc_cap > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  CodecArgs a = {};
+  fill_args(dims, p, ws, &a);
+  a.cand_k = static_cast<const uint16_t *>(cand_k);
+  a.cand_v = static_cast<const uint16_t *>(cand_v);
+  a.act_k = static_cast<const uint16_t *>(act_k);
+  a.act_v = static_cast<const uint16_t *>(act_v);
+  a.symbols = symbols;
+  a.pred_out = pred_out;
+  a.status = status;
+  float *weights = const_cast<float *>(a.weights);
+  uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
+
+  hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
+                     weights, p.rows, dims->k, status);
+  dispatch_k<LaunchPredict>(dims->k, a, (unsigned)p.n_tiles, st);
+  hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
+                     (uint32_t)p.tiles_per_stream, esc_cnt);
+  hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
+                     status);
+  hipLaunchKernelGGL(gather_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a, esc_vals, esc_cap,
+                     esc_off);
+  return launch_status();
+}
+
+extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
+                               const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
+                               const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
+                               uint32_t *status, void *stream) {
+  Plan p;
+  if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(out_k, 16) || !aligned(out_v, 16))
+    return PLC_ERR_INVALID;
+  if (!aligned(symbols, 8) || !aligned(probs, 4) || !aligned(esc_off, 8)) return PLC_ERR_INVALID;
+  if (!aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total) return PLC_ERR_INVALID;
+  if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  CodecArgs a = {};
+  fill_args(dims, p, ws, &a);
+  a.cand_k = static_cast<const uint16_t *>(cand_k);
+  a.cand_v = static_cast<const uint16_t *>(cand_v);
+  a.out_k = static_cast<uint16_t *>(out_k);
+  a.out_v = static_cast<uint16_t *>(out_v);
+  a.symbols = const_cast<uint8_t *>(symbols);
+  a.esc_in = esc_vals;
+  a.esc_len = esc_len;
+  a.esc_off = esc_off;
+  a.status = status;
+  float *weights = const_cast<float *>(a.weights);
+  uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
+
+  hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
+                     weights, p.rows, dims->k, status);
+  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
+  hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
+                     (uint32_t)p.tiles_per_stream, (uint32_t *)nullptr);
+  dispatch_k<LaunchReconstruct>(dims->k, a, (unsigned)p.n_tiles, st);
+  return launch_status();
+}

@@ -1,0 +1,178 @@
+"""Thin ctypes binding over libplc.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their
+device pointers and the current HIP stream to the C entry point of the same
+name (see include/plc.h), and returns.  No step of the coding path runs in
+Python or in torch; torch only owns the memory and the stream.  If the library
+has not been built, loading fails with an error -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libplc.so")
+
+PLC_OK, PLC_ERR_INVALID, PLC_ERR_CAPACITY, PLC_ERR_CORRUPT, PLC_ERR_HIP = 0, 1, 2, 3, 4
+PLC_ESCAPE = 255
+
+EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_stream",
+           "plc_predict_residual", "plc_histogram", "plc_build_freq", "plc_rans_encode",
+           "plc_rans_decode", "plc_reconstruct")
+
+
+class PlcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+class plc_dims(C.Structure):
+    _fields_ = [("S", C.c_int32), ("L", C.c_int32), ("H", C.c_int32), ("n", C.c_int32),
+                ("k", C.c_int32), ("d", C.c_int32),
+                ("cand_stride", C.c_int64 * 5), ("act_stride", C.c_int64 * 4),
+                ("delta", C.c_float), ("qmax", C.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first "
+                               "(python -m paper_2604_15356_amd.build); there is no fallback path")
+        L = C.CDLL(LIB_PATH)
+        p, u64, i64, i32, sz = C.c_void_p, C.c_uint64, C.c_int64, C.c_int32, C.c_size_t
+        dp = C.POINTER(plc_dims)
+        L.plc_version.restype = C.c_int
+        L.plc_strerror.restype = C.c_char_p
+        L.plc_strerror.argtypes = [C.c_int]
+        L.plc_workspace_bytes.restype = sz
+        L.plc_workspace_bytes.argtypes = [dp]
+        L.plc_units_per_stream.restype = i64
+        L.plc_units_per_stream.argtypes = [i64, i32]
+        L.plc_predict_residual.argtypes = [dp, p, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_histogram.argtypes = [p, i64, i64, p, p]
+        L.plc_build_freq.argtypes = [p, i64, p, p, p, p]
+        L.plc_rans_encode.argtypes = [p, i64, i64, i32, p, p, p, p, u64, p, p, p]
+        L.plc_rans_decode.argtypes = [p, p, p, u64, p, p, i64, i64, i32, p, p, p]
+        L.plc_reconstruct.argtypes = [dp, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().plc_strerror(int(code)).decode()
+
+
+def plc_version() -> int:
+    return int(lib().plc_version())
+
+
+def make_dims(S, L, H, n, k, d, delta, qmax=127, cand_stride=None, act_stride=None) -> plc_dims:
+    if cand_stride is None:
+        cand_stride = (L * H * n * k * d, H * n * k * d, n * k * d, k * d, d)
+    if act_stride is None:
+        act_stride = (L * H * n * d, H * n * d, n * d, d)
+    dm = plc_dims()
+    dm.S, dm.L, dm.H, dm.n, dm.k, dm.d = S, L, H, n, k, d
+    dm.cand_stride = (C.c_int64 * 5)(*[int(x) for x in cand_stride])
+    dm.act_stride = (C.c_int64 * 4)(*[int(x) for x in act_stride])
+    dm.delta = float(delta)
+    dm.qmax = int(qmax)
+    return dm
+
+
+def plc_workspace_bytes(dims: plc_dims) -> int:
+    return int(lib().plc_workspace_bytes(C.byref(dims)))
+
+
+def plc_units_per_stream(syms_per_stream: int, chunk_syms: int) -> int:
+    return int(lib().plc_units_per_stream(int(syms_per_stream), int(chunk_syms)))
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("plc takes device tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _contig(t, dtype):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return _ptr(t, dtype)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, where):
+    if rc != PLC_OK:
+        raise PlcError(rc, where)
+
+
+def plc_predict_residual(dims, cand_k, cand_v, probs, act_k, act_v, symbols, esc_vals, esc_cnt,
+                         esc_off, ws, status, pred_out=None):
+    """cand_*/act_* fp16 (strides in dims); probs fp32 [S,n,k]; symbols u8 out; esc_vals int16/uint16
+    out (its numel is the capacity); esc_cnt int32 out; esc_off int64 out; ws uint8; status int32[1]."""
+    rc = lib().plc_predict_residual(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _ptr(act_k, torch.float16), _ptr(act_v, torch.float16),
+        _contig(symbols, torch.uint8), _contig(esc_vals, None), esc_vals.numel(),
+        _contig(esc_cnt, torch.int32), _contig(esc_off, torch.int64), _contig(pred_out, torch.float32),
+        _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_predict_residual")
+
+
+def plc_histogram(symbols, n_streams, syms_per_stream, counts):
+    rc = lib().plc_histogram(_contig(symbols, torch.uint8), n_streams, syms_per_stream,
+                             _contig(counts, torch.int32), _stream())
+    _check(rc, "plc_histogram")
+
+
+def plc_build_freq(counts, n_streams, freq, cum, status):
+    rc = lib().plc_build_freq(_contig(counts, torch.int32), n_streams, _contig(freq, torch.int16),
+                              _contig(cum, torch.int16), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_build_freq")
+
+
+def plc_rans_encode(symbols, n_streams, syms_per_stream, chunk_syms, freq, states, words, word_off,
+                    word_cap_per_unit, n_words, status):
+    rc = lib().plc_rans_encode(_contig(symbols, torch.uint8), n_streams, syms_per_stream, chunk_syms,
+                               _contig(freq, torch.int16), _contig(states, torch.int32),
+                               _contig(words, torch.int16), _contig(word_off, torch.int64),
+                               int(word_cap_per_unit), _contig(n_words, torch.int32),
+                               _contig(status, torch.int32), _stream())
+    _check(rc, "plc_rans_encode")
+
+
+def plc_rans_decode(freq, states, words, word_off, n_words, n_streams, syms_per_stream, chunk_syms,
+                    symbols, status):
+    rc = lib().plc_rans_decode(_contig(freq, torch.int16), _contig(states, torch.int32),
+                               _contig(words, torch.int16), words.numel(),
+                               _contig(word_off, torch.int64), _contig(n_words, torch.int32),
+                               n_streams, syms_per_stream, chunk_syms, _contig(symbols, torch.uint8),
+                               _contig(status, torch.int32), _stream())
+    _check(rc, "plc_rans_decode")
+
+
+def plc_reconstruct(dims, cand_k, cand_v, probs, symbols, esc_vals, esc_off, out_k, out_v, ws, status):
+    rc = lib().plc_reconstruct(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _contig(symbols, torch.uint8), _contig(esc_vals, None),
+        esc_vals.numel(), _contig(esc_off, torch.int64), _ptr(out_k, torch.float16),
+        _ptr(out_v, torch.float16), _contig(ws, torch.uint8), ws.numel(),
+        _contig(status, torch.int32), _stream())
+    _check(rc, "plc_reconstruct")

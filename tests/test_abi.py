@@ -1,0 +1,83 @@
+"""The C boundary: libplc.so loads without a GPU, exports every symbol that
+include/plc.h declares, and rejects bad arguments on the host before anything
+is enqueued.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2604_15356_amd import plc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "plc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(plc_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = _declared()
+    assert set(names) == set(plc.EXPORTS)
+    lib = plc.lib()
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_host_only_calls():
+    assert plc.plc_version() >= 100
+    assert plc.strerror(plc.PLC_OK) == "ok"
+    for code in (1, 2, 3, 4, 99):
+        assert plc.strerror(code)
+    assert plc.plc_units_per_stream(1000, 0) == 1
+    assert plc.plc_units_per_stream(1000, 32) == 32
+    assert plc.plc_units_per_stream(1024, 512) == 2
+    dm = plc.make_dims(1, 32, 8, 4096, 8, 128, 0.02)
+    ws = plc.plc_workspace_bytes(dm)
+    tiles = 32 * 8 * (2 * 4096 * 128 // 2048)
+    assert ws >= 4096 * 8 * 4 + 2 * 4 * tiles and ws % 256 == 0
+
+
+@pytest.mark.parametrize("field,value", [("k", 0), ("k", 33), ("d", 12), ("d", 0), ("n", 0), ("S", 0),
+                                         ("delta", 0.0), ("delta", -1.0), ("delta", float("nan")),
+                                         ("qmax", 0), ("qmax", 128)])
+def test_invalid_dims_are_rejected(field, value):
+    dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
+    setattr(dm, field, value)
+    assert plc.plc_workspace_bytes(dm) == 0
+    p = C.c_void_p(4096)
+    rc = plc.lib().plc_predict_residual(C.byref(dm), p, p, p, p, p, p, p, 0, p, p, None, p, 1 << 20, p, None)
+    assert rc == plc.PLC_ERR_INVALID
+    rc = plc.lib().plc_reconstruct(C.byref(dm), p, p, p, p, p, 0, p, p, p, p, 1 << 20, p, None)
+    assert rc == plc.PLC_ERR_INVALID
+
+
+def test_bad_strides_pointers_and_sizes_are_rejected():
+    L = plc.lib()
+    p = C.c_void_p(4096)
+    dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
+    dm.cand_stride[3] = 4 * 64 + 4          # rows not 16-byte aligned
+    assert L.plc_predict_residual(C.byref(dm), p, p, p, p, p, p, p, 0, p, p, None, p, 1 << 20, p, None) == 1
+    dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
+    odd = C.c_void_p(4098)
+    assert L.plc_predict_residual(C.byref(dm), odd, p, p, p, p, p, p, 0, p, p, None, p, 1 << 20, p, None) == 1
+    assert L.plc_predict_residual(C.byref(dm), p, p, p, p, p, p, p, 0, p, p, None, p, 16, p, None) == 1   # ws too small
+    assert L.plc_predict_residual(C.byref(dm), None, p, p, p, p, p, p, 0, p, p, None, p, 1 << 20, p, None) == 1
+    # byte-stream calls
+    assert L.plc_histogram(p, 0, 10, p, None) == 1
+    assert L.plc_histogram(p, 1, 0, p, None) == 1
+    assert L.plc_histogram(None, 1, 10, p, None) == 1
+    assert L.plc_build_freq(p, 0, p, p, p, None) == 1
+    assert L.plc_rans_encode(p, 1, 100, 48, p, p, p, p, 100, p, p, None) == 1      # chunk not a multiple of 32
+    assert L.plc_rans_encode(p, 1, 100, -32, p, p, p, p, 100, p, p, None) == 1
+    assert L.plc_rans_decode(p, p, p, 10, p, p, 1, 0, 0, p, p, None) == 1
+    assert L.plc_rans_decode(p, p, p, 10, p, p, 1, 1 << 31, 0, p, p, None) == 1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(plc, "_lib", None)
+    monkeypatch.setattr(plc, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        plc.lib()

@@ -1,0 +1,312 @@
+"""Parity of the HIP path (through the C ABI of libplc.so) against the CPU
+oracle, element by element, on the same seeded inputs.
+
+Bars: symbols, escape lists, histograms, tables, rANS states and words are
+bit-exact against the oracle evaluated in the kernel's precision (strict
+fp32); against the fp64 oracle, predictions agree to 1e-3 relative (in fact
+~1e-6) and symbols may differ only at rounding near-ties, which are counted.
+Streams written by either side decode on the other.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_15356_amd.workloads import make_workload, random_bytes
+from tests.gpu_util import (codec_for, near_tie_report, oracle_dims, storage_np, u8, u16, u32, u64)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def dev():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2604_15356_amd import plc
+    plc.lib()            # raises if libplc.so is missing: there is no fallback
+    return torch.device("cuda:0")
+
+
+CASES = {
+    # name: (config, overrides, layout, random probability rows)
+    "tiny": ("tiny", None, "lhnkd", False),
+    "tiny_heads_inner": ("tiny", None, "lnkhd", True),
+    "ragged_k5_d24": ("tiny", dict(S=2, L=2, H=3, n=37, k=5, d=24, seed=11), "lhnkd", True),
+    "ragged_k5_d24_heads_inner": ("tiny", dict(S=2, L=2, H=3, n=37, k=5, d=24, seed=12), "lnkhd", True),
+    "k1": ("tiny", dict(k=1, n=100, seed=13), "lhnkd", False),
+    "k8_d128": ("llama8b", dict(L=2, H=2, n=300, seed=14), "lhnkd", True),
+    "k11_runtime_loop": ("tiny", dict(k=11, n=129, d=40, seed=15), "lhnkd", True),
+    "k20": ("tiny", dict(k=20, L=1, H=2, n=65, d=128, seed=16), "lhnkd", True),
+    "one_position": ("tiny", dict(L=1, H=1, n=1, d=8, seed=17), "lhnkd", False),
+}
+
+
+def _oracle_encode(O, w, mode, **kw):
+    return O.predict_residual(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v),
+                              w.probs.cpu().numpy(), storage_np(w.act_k), storage_np(w.act_v),
+                              mode=mode, **kw)
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_encode_decode_matches_oracle(oracle, dev, case):
+    O = oracle
+    name, overrides, layout, random_rows = CASES[case]
+    w = make_workload(name, device=dev, layout=layout, overrides=overrides, random_rows=random_rows)
+    codec = codec_for(w, want_pred=True, esc_frac=1.0)
+    print(f"case {case}: S{w.S} L{w.L} H{w.H} n{w.n} k{w.k} d{w.d} layout {layout}", flush=True)
+    coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    codec.check_status("encode")
+
+    # ---- floating-point part
+    ref32 = _oracle_encode(O, w, O.F32)
+    ref64 = _oracle_encode(O, w, O.F64, want_pred=True, want_u=True)
+    sym = u8(coded.symbols)
+    assert np.array_equal(sym, ref32["symbols"]), "symbols differ from the strict-fp32 oracle"
+    pred = codec.pred.cpu().numpy().astype(np.float64)
+    scale = np.maximum(np.abs(ref64["pred"]), 1e-2)
+    assert (np.abs(pred - ref64["pred"]) / scale).max() < 1e-3
+    tau = 64 * 2.0 ** -24 * 8.0 / float(np.float32(w.delta))
+    n_diff, n_ok = near_tie_report(sym, ref64["symbols"], ref64["u"], tau)
+    print(f"  near-ties vs fp64 oracle: {n_diff} of {sym.size} ({n_diff / sym.size:.2e})", flush=True)
+    assert n_diff == n_ok and n_diff <= max(3, 1e-4 * sym.size)
+    total = int(ref32["esc_cnt"].sum())
+    assert np.array_equal(u32(coded.esc_cnt), ref32["esc_cnt"])
+    assert np.array_equal(u64(coded.esc_off), ref32["esc_off"])
+    assert np.array_equal(u16(coded.esc_vals)[:total], ref32["esc_vals"])
+
+    # ---- integer part, bit-exact given identical symbols
+    counts = O.histogram(sym)
+    freq, cum = O.build_freq(counts)
+    enc = O.rans_encode(sym, freq, word_cap_per_unit=codec.word_cap)
+    assert np.array_equal(u32(coded.counts), counts)
+    assert np.array_equal(u16(coded.freq), freq)
+    assert np.array_equal(u16(coded.cum), cum)
+    assert np.array_equal(u32(coded.n_words), enc["n_words"])
+    assert np.array_equal(u32(coded.states), enc["states"])
+    words = u16(coded.words)
+    for unit in range(codec.n_units):
+        off, nw = unit * codec.word_cap, int(enc["n_words"][unit])
+        assert np.array_equal(words[off:off + nw], enc["words"][off:off + nw]), f"unit {unit}"
+    # the oracle decodes the GPU's stream
+    dec = O.rans_decode(u16(coded.freq), u32(coded.states), words, u64(coded.word_off),
+                        u32(coded.n_words), codec.n_streams, codec.N)
+    assert np.array_equal(dec, sym)
+
+    # ---- decode direction on the GPU
+    out_k = torch.zeros_like(w.act_k)
+    out_v = torch.zeros_like(w.act_v)
+    codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+    codec.check_status("decode")
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    rk32, rv32 = O.reconstruct(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v),
+                               w.probs.cpu().numpy(), sym, ref32["esc_vals"], ref32["esc_off"], mode=O.F32)
+    assert np.array_equal(u16(out_k).ravel(), rk32) and np.array_equal(u16(out_v).ravel(), rv32)
+    rk64, rv64 = O.reconstruct(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v),
+                               w.probs.cpu().numpy(), sym, ref32["esc_vals"], ref32["esc_off"], mode=O.F64)
+    for got, want in ((u16(out_k).ravel(), rk64), (u16(out_v).ravel(), rv64)):
+        d = np.abs(got.astype(np.int32) - want.astype(np.int32))      # fp16 neighbours differ by 1
+        assert d.max() <= 1 and (d != 0).mean() < 2e-3
+    # recovery error is the quantiser's: |act - out| <= Delta/2 (+ half an fp16 ulp of the output)
+    esc = sym.reshape(codec.n_streams, w.n, 2, w.d) == 255
+    for c, (act, out) in enumerate(((w.act_k, out_k), (w.act_v, out_v))):
+        a = act.double().cpu().numpy().reshape(codec.n_streams, w.n, w.d)
+        o = out.double().cpu().numpy().reshape(codec.n_streams, w.n, w.d)
+        ulp = np.spacing(np.abs(o).astype(np.float16)).astype(np.float64)
+        e = esc[:, :, c, :]
+        bound = float(np.float32(w.delta)) / 2 + ulp / 2 + 1e-6
+        assert (np.abs(a - o)[~e] <= bound[~e]).all()
+        assert np.array_equal(u16(act).reshape(e.shape)[e], u16(out).reshape(e.shape)[e])
+
+
+def test_one_hot_rows_give_a_single_symbol(oracle, dev):
+    """One-hot prediction without noise: zero residuals everywhere, a histogram that is a
+    single spike, no rANS words, bit-exact reconstruction."""
+    w = make_workload("tiny", device=dev, one_hot=True, overrides=dict(n=256))
+    codec = codec_for(w)
+    coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    codec.check_status()
+    assert (coded.symbols == 127).all() and int(coded.esc_cnt.sum()) == 0
+    assert (u16(coded.freq)[:, 127] == 4096).all()
+    assert (u32(coded.n_words) == 0).all() and (u32(coded.states) == 65536).all()
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+    codec.check_status()
+    assert torch.equal(out_k.view(torch.int16), w.act_k.view(torch.int16))
+    assert torch.equal(out_v.view(torch.int16), w.act_v.view(torch.int16))
+
+
+def test_special_values_escape_bit_exactly(oracle, dev):
+    """Infinities, NaNs, fp16 subnormals and out-of-range residuals."""
+    O = oracle
+    w = make_workload("tiny", device=dev, overrides=dict(L=1, H=2, n=40, seed=21))
+    ak = w.act_k.clone()
+    flat = ak.view(-1)
+    flat[5] = float("inf")
+    flat[6] = float("-inf")
+    flat[7] = float("nan")
+    flat[70] = 6.0e-8           # fp16 subnormal
+    flat[71] = 30000.0
+    w.cand_k.view(-1)[1000] = float("inf")     # non-finite prediction
+    w.cand_v.view(-1)[2000] = 2.0 ** -24       # subnormal candidate
+    w.act_k = ak
+    codec = codec_for(w, esc_frac=1.0)
+    coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    codec.check_status()
+    ref = _oracle_encode(O, w, O.F32)
+    assert np.array_equal(u8(coded.symbols), ref["symbols"])
+    total = int(ref["esc_cnt"].sum())
+    assert np.array_equal(u16(coded.esc_vals)[:total], ref["esc_vals"])
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+    codec.check_status()
+    rk, rv = O.reconstruct(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v),
+                           w.probs.cpu().numpy(), ref["symbols"], ref["esc_vals"], ref["esc_off"], mode=O.F32)
+    assert np.array_equal(u16(out_k).ravel(), rk) and np.array_equal(u16(out_v).ravel(), rv)
+
+
+# --------------------------------------------------------------------------- byte-stream calls on their own
+
+BYTE_CASES = [(1, 1, "gauss"), (3, 5, "gauss"), (2, 33, "uniform"), (5, 1000, "gauss"), (2, 4097, "two"),
+              (3, 70001, "gauss"), (2, 200000, "constant"), (4, 131072, "uniform"), (1, 262144 + 17, "gauss")]
+
+
+@pytest.mark.parametrize("n_streams,N,kind", BYTE_CASES)
+@pytest.mark.parametrize("chunk", [0, 4096])
+def test_histogram_table_rans_bit_exact(oracle, dev, n_streams, N, kind, chunk):
+    from paper_2604_15356_amd import plc
+    O = oracle
+    print(f"bytes {n_streams}x{N} {kind} chunk {chunk}", flush=True)
+    sym_t = random_bytes(n_streams, N, seed=N % 1000 + n_streams, kind=kind, device=dev)
+    sym = sym_t.cpu().numpy()
+    U = plc.plc_units_per_stream(N, chunk)
+    n_units = n_streams * U
+    cap = ((chunk if chunk else N) + 7) // 8 * 8
+    i32, i16 = torch.int32, torch.int16
+    counts = torch.empty((n_streams, 256), dtype=i32, device=dev)
+    freq = torch.empty((n_streams, 256), dtype=i16, device=dev)
+    cum = torch.empty((n_streams, 257), dtype=i16, device=dev)
+    states = torch.empty((n_units, 32), dtype=i32, device=dev)
+    words = torch.zeros(n_units * cap, dtype=i16, device=dev)
+    word_off = torch.arange(n_units, dtype=torch.int64, device=dev) * cap
+    n_words = torch.empty(n_units, dtype=i32, device=dev)
+    status = torch.zeros(1, dtype=i32, device=dev)
+    plc.plc_histogram(sym_t, n_streams, N, counts)
+    plc.plc_build_freq(counts, n_streams, freq, cum, status)
+    plc.plc_rans_encode(sym_t, n_streams, N, chunk, freq, states, words, word_off, cap, n_words, status)
+    assert int(status.item()) == 0
+
+    ref_counts = O.histogram(sym)
+    ref_freq, ref_cum = O.build_freq(ref_counts)
+    enc = O.rans_encode(sym, ref_freq, chunk_syms=chunk, word_cap_per_unit=cap)
+    assert np.array_equal(u32(counts), ref_counts)
+    assert np.array_equal(u16(freq), ref_freq) and np.array_equal(u16(cum), ref_cum)
+    assert np.array_equal(u32(n_words), enc["n_words"])
+    assert np.array_equal(u32(states), enc["states"])
+    got_words = u16(words)
+    for unit in range(n_units):
+        nw = int(enc["n_words"][unit])
+        assert np.array_equal(got_words[unit * cap:unit * cap + nw], enc["words"][unit * cap:unit * cap + nw])
+
+    # GPU decodes the oracle's stream (cross-decode in the other direction)
+    o_words = torch.from_numpy(enc["words"].view(np.int16)).to(dev)
+    o_states = torch.from_numpy(enc["states"].view(np.int32)).to(dev)
+    o_nw = torch.from_numpy(enc["n_words"].view(np.int32)).to(dev)
+    dec = torch.zeros_like(sym_t)
+    plc.plc_rans_decode(freq, o_states, o_words, word_off, o_nw, n_streams, N, chunk, dec, status)
+    assert int(status.item()) == 0
+    assert torch.equal(dec, sym_t)
+
+
+def test_word_list_at_odd_addresses(oracle, dev):
+    """Units whose word lists start at arbitrary 2-byte offsets decode correctly."""
+    from paper_2604_15356_amd import plc
+    O = oracle
+    n_streams, N = 5, 50000
+    sym_t = random_bytes(n_streams, N, seed=77, kind="gauss", device=dev)
+    sym = sym_t.cpu().numpy()
+    freq_np, _ = O.build_freq(O.histogram(sym))
+    enc = O.rans_encode(sym, freq_np)
+    nw = enc["n_words"].astype(np.int64)
+    # pack the lists back to back with odd gaps
+    offs = np.zeros(n_streams, dtype=np.int64)
+    pos = 3
+    for s in range(n_streams):
+        offs[s] = pos
+        pos += int(nw[s]) + 1 + 2 * s
+    packed = np.zeros(pos + 5, dtype=np.uint16)
+    for s in range(n_streams):
+        o = int(enc["word_off"][s])
+        packed[offs[s]:offs[s] + nw[s]] = enc["words"][o:o + nw[s]]
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    dec = torch.zeros_like(sym_t)
+    big = torch.from_numpy(packed.view(np.int16)).to(dev)
+    plc.plc_rans_decode(torch.from_numpy(freq_np.view(np.int16)).to(dev),
+                        torch.from_numpy(enc["states"].view(np.int32)).to(dev), big[1:],      # odd base too
+                        torch.from_numpy(offs - 1).to(dev), torch.from_numpy(enc["n_words"].view(np.int32)).to(dev),
+                        n_streams, N, 0, dec, status)
+    assert int(status.item()) == 0 and torch.equal(dec, sym_t)
+
+
+def test_data_dependent_errors_are_reported_not_fatal(oracle, dev):
+    from paper_2604_15356_amd import plc
+    O = oracle
+    w = make_workload("tiny", device=dev, overrides=dict(L=1, H=2, n=128, seed=31))
+    # invalid probability row -> status INVALID
+    codec = codec_for(w)
+    probs = w.probs.clone()
+    probs[0, 7, :] = 0.0
+    codec.predict_residual(w.cand_k, w.cand_v, probs, w.act_k, w.act_v)
+    with pytest.raises(plc.PlcError) as e:
+        codec.check_status()
+    assert e.value.code == plc.PLC_ERR_INVALID
+    # escape list too small -> CAPACITY, nothing written past the end
+    codec = codec_for(w, esc_frac=0.0)          # 64 entries
+    guard = codec.esc_vals.clone()
+    coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    n_esc = int(coded.esc_cnt.sum())
+    if n_esc > codec.esc_vals.numel():
+        with pytest.raises(plc.PlcError) as e:
+            codec.check_status()
+        assert e.value.code == plc.PLC_ERR_CAPACITY
+    del guard
+    # word list too small -> CAPACITY
+    codec = codec_for(w, word_frac=0.25)
+    codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    with pytest.raises(plc.PlcError) as e:
+        codec.check_status()
+    assert e.value.code == plc.PLC_ERR_CAPACITY
+    # damaged stream -> CORRUPT (or different symbols), never a fault
+    codec = codec_for(w)
+    coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    codec.check_status()
+    good = coded.symbols.clone()
+    codec.words[100] ^= 0x40
+    codec.n_words[1] -= 1
+    codec.rans_decode()
+    with pytest.raises(plc.PlcError) as e:
+        codec.check_status()
+    assert e.value.code == plc.PLC_ERR_CORRUPT
+    # a word count that points outside the buffer is refused
+    codec.n_words[1] = 2 ** 31 - 1
+    codec.rans_decode()
+    with pytest.raises(plc.PlcError) as e:
+        codec.check_status()
+    assert e.value.code == plc.PLC_ERR_CORRUPT
+    del good
+
+
+def test_runs_are_deterministic(oracle, dev):
+    w = make_workload("tiny", device=dev)
+    codec = codec_for(w)
+    codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    codec.check_status()
+    first = [t.clone() for t in (codec.symbols, codec.counts, codec.freq, codec.states, codec.n_words)]
+    nw = u32(codec.n_words)
+    words1 = codec.words.clone()
+    codec.words.zero_()
+    codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    codec.check_status()
+    for a, b in zip(first, (codec.symbols, codec.counts, codec.freq, codec.states, codec.n_words)):
+        assert torch.equal(a, b)
+    for unit in range(codec.n_units):
+        o = unit * codec.word_cap
+        assert torch.equal(words1[o:o + int(nw[unit])], codec.words[o:o + int(nw[unit])])
