@@ -197,6 +197,21 @@ int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v
                     uint64_t esc_len, const uint64_t *esc_off, void *out_k, void *out_v,
                     void *ws, size_t ws_bytes, uint32_t *status, void *stream);
 
+/*
+ * Instrumentation for benchmarks (not part of the coding path; process-wide,
+ * not thread-safe).  While a pair of hipEvent_t (passed as void*) is set for
+ * a kernel id, each later call records `start` immediately before and `stop`
+ * immediately after that call's main kernel on the call's stream, so that the
+ * kernel alone can be timed from outside.  Pass NULLs to clear.  Host call.
+ */
+#define PLC_TRACE_PREDICT 0     /* main kernel of plc_predict_residual */
+#define PLC_TRACE_RECONSTRUCT 1 /* main kernel of plc_reconstruct      */
+#define PLC_TRACE_HISTOGRAM 2
+#define PLC_TRACE_RANS_ENCODE 3
+#define PLC_TRACE_RANS_DECODE 4
+#define PLC_TRACE_COUNT 5
+int plc_trace_kernel_events(int kernel_id, void *start, void *stop);
+
 #ifdef __cplusplus
 }
 #endif

@@ -13,3 +13,15 @@ extern "C" const char *plc_strerror(int code) {
     default: return "unknown plc status";
   }
 }
+
+namespace plc {
+TraceEvents g_trace[PLC_TRACE_COUNT] = {};
+}
+
+extern "C" int plc_trace_kernel_events(int kernel_id, void *start, void *stop) {
+  if (kernel_id < 0 || kernel_id >= PLC_TRACE_COUNT) return PLC_ERR_INVALID;
+  if ((start == nullptr) != (stop == nullptr)) return PLC_ERR_INVALID;
+  plc::g_trace[kernel_id].start = static_cast<hipEvent_t>(start);
+  plc::g_trace[kernel_id].stop = static_cast<hipEvent_t>(stop);
+  return PLC_OK;
+}

@@ -24,6 +24,23 @@ __device__ __forceinline__ uint4 load16_stream(const void *p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Optional event pairs around the main kernel of each call (plc_trace_kernel_events).
+struct TraceEvents {
+  hipEvent_t start, stop;
+};
+extern TraceEvents g_trace[PLC_TRACE_COUNT];
+
+struct TraceScope {
+  int id;
+  hipStream_t st;
+  TraceScope(int id_, hipStream_t st_) : id(id_), st(st_) {
+    if (g_trace[id].start) (void)hipEventRecord(g_trace[id].start, st);
+  }
+  ~TraceScope() {
+    if (g_trace[id].stop) (void)hipEventRecord(g_trace[id].stop, st);
+  }
+};
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? PLC_OK : PLC_ERR_HIP; }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

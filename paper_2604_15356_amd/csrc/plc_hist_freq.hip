@@ -163,8 +163,11 @@ extern "C" int plc_histogram(const uint8_t *symbols, int64_t n_streams, int64_t 
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int64_t n = n_streams * 256;
   hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, counts, n);
-  hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)(n_streams * segs)), dim3(kBlock), 0, st, symbols,
-                     syms_per_stream, (uint32_t)segs, counts);
+  {
+    TraceScope trace(PLC_TRACE_HISTOGRAM, st);
+    hipLaunchKernelGGL(histogram_kernel, dim3((unsigned)(n_streams * segs)), dim3(kBlock), 0, st, symbols,
+                       syms_per_stream, (uint32_t)segs, counts);
+  }
   return launch_status();
 }
 

@@ -422,7 +422,10 @@ extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, co
 
   hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
                      weights, p.rows, dims->k, status);
-  dispatch_k<LaunchPredict>(dims->k, a, (unsigned)p.n_tiles, st);
+  {
+    TraceScope trace(PLC_TRACE_PREDICT, st);
+    dispatch_k<LaunchPredict>(dims->k, a, (unsigned)p.n_tiles, st);
+  }
   hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
                      (uint32_t)p.tiles_per_stream, esc_cnt);
   hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
@@ -464,6 +467,9 @@ extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const v
   hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
   hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
                      (uint32_t)p.tiles_per_stream, (uint32_t *)nullptr);
-  dispatch_k<LaunchReconstruct>(dims->k, a, (unsigned)p.n_tiles, st);
+  {
+    TraceScope trace(PLC_TRACE_RECONSTRUCT, st);
+    dispatch_k<LaunchReconstruct>(dims->k, a, (unsigned)p.n_tiles, st);
+  }
   return launch_status();
 }

@@ -357,8 +357,11 @@ extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_
   a.word_cap = word_cap_per_unit;
   a.n_words_out = n_words;
   a.status = status;
-  hipLaunchKernelGGL(rans_encode_kernel, dim3((unsigned)((a.n_units + 1) / 2)), dim3(64), 0,
-                     static_cast<hipStream_t>(stream), a);
+  {
+    TraceScope trace(PLC_TRACE_RANS_ENCODE, static_cast<hipStream_t>(stream));
+    hipLaunchKernelGGL(rans_encode_kernel, dim3((unsigned)((a.n_units + 1) / 2)), dim3(64), 0,
+                       static_cast<hipStream_t>(stream), a);
+  }
   return launch_status();
 }
 
@@ -380,7 +383,10 @@ extern "C" int plc_rans_decode(const uint16_t *freq, const uint32_t *states, con
   a.word_off = word_off;
   a.n_words_in = n_words;
   a.status = status;
-  hipLaunchKernelGGL(rans_decode_kernel, dim3((unsigned)((a.n_units + 1) / 2)), dim3(64), 0,
-                     static_cast<hipStream_t>(stream), a);
+  {
+    TraceScope trace(PLC_TRACE_RANS_DECODE, static_cast<hipStream_t>(stream));
+    hipLaunchKernelGGL(rans_decode_kernel, dim3((unsigned)((a.n_units + 1) / 2)), dim3(64), 0,
+                       static_cast<hipStream_t>(stream), a);
+  }
   return launch_status();
 }

@@ -21,7 +21,9 @@ PLC_ESCAPE = 255
 
 EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_stream",
            "plc_predict_residual", "plc_histogram", "plc_build_freq", "plc_rans_encode",
-           "plc_rans_decode", "plc_reconstruct")
+           "plc_rans_decode", "plc_reconstruct", "plc_trace_kernel_events")
+
+TRACE_PREDICT, TRACE_RECONSTRUCT, TRACE_HISTOGRAM, TRACE_RANS_ENCODE, TRACE_RANS_DECODE = range(5)
 
 
 class PlcError(RuntimeError):
@@ -62,6 +64,7 @@ def lib() -> C.CDLL:
         L.plc_rans_encode.argtypes = [p, i64, i64, i32, p, p, p, p, u64, p, p, p]
         L.plc_rans_decode.argtypes = [p, p, p, u64, p, p, i64, i64, i32, p, p, p]
         L.plc_reconstruct.argtypes = [dp, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_trace_kernel_events.argtypes = [C.c_int, p, p]
         _lib = L
     return _lib
 
@@ -176,3 +179,10 @@ def plc_reconstruct(dims, cand_k, cand_v, probs, symbols, esc_vals, esc_off, out
         _ptr(out_v, torch.float16), _contig(ws, torch.uint8), ws.numel(),
         _contig(status, torch.int32), _stream())
     _check(rc, "plc_reconstruct")
+
+
+def plc_trace_kernel_events(kernel_id, start=None, stop=None):
+    """start/stop: raw hipEvent_t handles (ints) or None to clear."""
+    rc = lib().plc_trace_kernel_events(int(kernel_id), C.c_void_p(start) if start else None,
+                                       C.c_void_p(stop) if stop else None)
+    _check(rc, "plc_trace_kernel_events")
