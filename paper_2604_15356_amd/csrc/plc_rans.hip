@@ -1,15 +1,22 @@
 // 32-lane interleaved rANS encoder and decoder.  The bitstream is defined in
 // include/plc.h.  The paper only asks for "standard source coding" of the
 // residuals (proof of Prop. "Layer orthogonality", Sec. 6.1); interleaved rANS
-// is the choice made here because its 32 lanes map onto half a wavefront.
+// is the choice made here because its 32 lanes advance in lock step inside a
+// wavefront and the shared word list is addressed with a ballot and a lane
+// count, without atomics, so the output is deterministic.
 //
-// Mapping: one 64-lane wavefront codes two units, lanes 0-31 one unit and
-// lanes 32-63 the next.  The 32 lanes of a unit advance in lock step, one
-// symbol group (32 symbols) per iteration; positions in the word list come
-// from a ballot and a population count, so no atomics are involved and the
-// output is deterministic.  The work per unit is a chain of dependent integer
-// steps, N/32 long, so these kernels are bound by instruction latency and by
-// how many units are in flight, not by HBM.
+// Mapping.  One wavefront codes one unit: lanes 0-31 carry the 32 rANS states
+// and lanes 32-63 mirror them exactly (same state, same LDS addresses, same
+// values), so that no step needs a lane mask and everything uniform stays in
+// scalar registers; all 64 lanes move data between HBM and LDS.  A workgroup holds up to eight
+// wavefronts that code consecutive units of the SAME stream and share that
+// stream's table in LDS.  Per unit the work is a chain of N/32 dependent
+// steps, so the kernels are bound by instruction issue and LDS latency times
+// the chain length, and by how many units are in flight -- not by HBM.  The
+// inner step is therefore written for a minimal instruction count: symbols,
+// words and table entries go through LDS staging buffers that are filled and
+// drained 16 groups at a time, and everything uniform stays in scalar
+// registers.
 #include "plc_device.h"
 
 namespace plc {
@@ -19,305 +26,473 @@ constexpr int kLanes = PLC_RANS_LANES;
 constexpr int kScaleBits = 12;
 constexpr uint32_t kScale = PLC_RANS_SCALE;
 constexpr uint32_t kLow = 1u << 16;
-constexpr int kBatch = 16;  // symbol groups between two refills of the staging buffers
+constexpr int kBatch = 16;                      // symbol groups per staging round
+constexpr int kBatchSyms = kBatch * kLanes;     // 512
+constexpr int kSuper = 4;                       // encoder: batches fetched per staging round, so that
+constexpr int kSuperGroups = kSuper * kBatch;   // the next round's HBM latency hides behind 64 groups
+constexpr int kSuperSyms = kSuperGroups * kLanes;
+constexpr int kSymStage = kSuperSyms + 32;      // 2048 symbols at any 16-byte misalignment
+constexpr int kStagePieces = 3;                 // 16-byte pieces per lane and round (192 >= 130)
+constexpr int kMaxWaves = 8;
 
 struct RansArgs {
-  const uint8_t *sym_in;  // encode
-  uint8_t *sym_out;       // decode
+  const uint8_t *sym_in;       // encode
+  uint8_t *sym_out;            // decode
   const uint16_t *freq;
-  uint32_t *states_out;      // encode
-  const uint32_t *states_in; // decode
-  uint16_t *words_out;       // encode
-  const uint16_t *words_in;  // decode
-  uint64_t words_len;        // decode
+  uint32_t *states_out;        // encode
+  const uint32_t *states_in;   // decode
+  uint16_t *words_out;         // encode
+  const uint16_t *words_in;    // decode
+  uint64_t words_len;          // decode
   const uint64_t *word_off;
-  uint64_t word_cap;         // encode
-  uint32_t *n_words_out;     // encode
-  const uint32_t *n_words_in;// decode
+  uint64_t word_cap;           // encode
+  uint32_t *n_words_out;       // encode
+  const uint32_t *n_words_in;  // decode
   uint32_t *status;
   int64_t n_units, units_per_stream, syms_per_stream, unit_syms;
+  uint32_t wgs_per_stream;
 };
 
-struct Unit {
-  bool live;
-  int64_t unit, stream, begin;
-  uint32_t len;  // symbols in this unit
-};
-
-__device__ __forceinline__ Unit locate_unit(const RansArgs &a, int half) {
-  Unit u;
-  u.unit = (int64_t)blockIdx.x * 2 + half;
-  u.live = u.unit < a.n_units;
-  const int64_t un = u.live ? u.unit : 0;
-  u.stream = un / a.units_per_stream;
-  const int64_t chunk = un - u.stream * a.units_per_stream;
-  u.begin = chunk * a.unit_syms;
-  const int64_t rest = a.syms_per_stream - u.begin;
-  u.len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
-  u.unit = un;
-  return u;
-}
-
-// Lane l of a half-wavefront gets the frequencies of symbols 8l .. 8l+7 and the
-// cumulative frequency in front of them.  Returns the table's total.
-__device__ __forceinline__ uint32_t load_freq8(const uint16_t *freq, int l, uint32_t f[8], uint32_t *cum0) {
-  const uint4 fv = *reinterpret_cast<const uint4 *>(freq + l * 8);
-  const uint32_t w[4] = {fv.x, fv.y, fv.z, fv.w};
-  uint32_t sum = 0;
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    f[r] = (w[r >> 1] >> (16 * (r & 1))) & 0xffffu;
-    sum += f[r];
-  }
-  uint32_t inc = sum;
-#pragma unroll
-  for (int off = 1; off < kLanes; off <<= 1) {
-    const uint32_t up = __shfl_up(inc, off, kLanes);
-    if (l >= off) inc += up;
-  }
+// Frequencies of symbols 4*lane .. 4*lane+3 and the cumulative frequency in
+// front of them, for all 64 lanes of a wavefront.  Returns the table's total.
+__device__ __forceinline__ uint32_t load_freq4(const uint16_t *freq, int lane, uint32_t f[4], uint32_t *cum0) {
+  const uint2 fv = *reinterpret_cast<const uint2 *>(freq + lane * 4);
+  f[0] = fv.x & 0xffffu;
+  f[1] = fv.x >> 16;
+  f[2] = fv.y & 0xffffu;
+  f[3] = fv.y >> 16;
+  const uint32_t sum = f[0] + f[1] + f[2] + f[3];
+  const uint32_t inc = wave_inclusive_scan(sum);
   *cum0 = inc - sum;
-  return __shfl(inc, kLanes - 1, kLanes);
+  return __shfl(inc, 63, 64);
 }
 
-__device__ __forceinline__ uint32_t half_mask(uint64_t ballot, int half) {
-  return half ? (uint32_t)(ballot >> 32) : (uint32_t)ballot;
+__device__ __forceinline__ void wave_sync() {
+  // LDS traffic of one wavefront executes in order; this only stops the
+  // compiler from moving LDS accesses across a staging boundary.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // ---------------------------------------------------------------------------
 // Encoder
 // ---------------------------------------------------------------------------
-// Table entry per symbol: .x = multiplier for the division by f, .y packs
-// f (13 bits) | cum (12 bits) << 13 | sh1 << 25 | sh2 << 26.  The quotient
-// floor(x / f) is exact for every 32-bit x (round-up multiplier of width 33,
-// applied as  t = mulhi(m, x);  q = (t + ((x - t) >> sh1)) >> sh2).
-__device__ __forceinline__ uint2 make_enc_entry(uint32_t f, uint32_t cum) {
-  if (f == 0) return make_uint2(0u, 0u);
+// Table entry per symbol (16 bytes).  A step is
+//     if x > thr: emit (x & 0xffff), x >>= 16        thr = f * 2^20 - 1  (f = 4096: 2^32 - 1)
+//     x' = q * (4096 - f) + x + cum                  q = floor(x / f)
+// and differs only in how the exact quotient is formed:
+//   short form, usable when every f of the table is <= 2048 (the normal case):
+//       q = mulhi(x, m) >> s   with s = ceil(log2 f) - 1, m = ceil(2^(32+s) / f).
+//     Exact because x < f * 2^20 after the renormalisation: the error term x * (m*f - 2^(32+s))
+//     stays below 2^(32+s) as long as f^2 <= 2^(12+s), i.e. s <= 10.  For f = 1 the multiplier
+//     2^32 - 1 yields x - 1, and the missing 4095 is added to the entry's cum.
+//       .x = m   .y = thr   .z = (4096 - f) | s << 24   .w = cum (+4095 if f = 1)
+//   long form, for tables with an f > 2048 (round-up reciprocal of 33 bits, exact for any x):
+//       t = mulhi(m, x);  q = (t + ((x - t) >> sh1)) >> sh2
+//       .x = m   .y = thr   .z = (4096 - f) | sh2 << 24   .w = cum | sh1 << 24
+// A symbol with f = 0 gets .w = 1 << 31, which is collected and reported if it occurs in the data.
+template <bool LONG>
+__device__ __forceinline__ uint4 make_enc_entry(uint32_t f, uint32_t cum) {
+  if (f == 0) return make_uint4(0u, 0xffffffffu, 0u, 0x80000000u);
   const uint32_t l = f > 1 ? 32u - (uint32_t)__builtin_clz(f - 1) : 0u;  // ceil(log2 f)
-  const uint64_t num = (uint64_t)((1u << l) - f) << 32;
-  const uint32_t m = (uint32_t)(num / f) + 1u;
-  const uint32_t sh1 = l < 1 ? l : 1u, sh2 = l > 1 ? l - 1u : 0u;
-  return make_uint2(m, f | ((cum & 4095u) << 13) | (sh1 << 25) | (sh2 << 26));
+  const uint32_t thr = f >= kScale ? 0xffffffffu : (f << 20) - 1u;
+  if (LONG) {
+    // floor((2^l - f) * 2^32 / f) by two 32-bit divisions (numerators stay below 2^28)
+    const uint32_t n = (1u << l) - f;
+    const uint32_t q1 = (n << 16) / f, r1 = (n << 16) - q1 * f;
+    const uint32_t m = (q1 << 16) + (r1 << 16) / f + 1u;
+    const uint32_t sh1 = l < 1 ? l : 1u, sh2 = l > 1 ? l - 1u : 0u;
+    return make_uint4(m, thr, (kScale - f) | (sh2 << 24), (cum & 0xfffu) | (sh1 << 24));
+  }
+  if (f == 1) return make_uint4(0xffffffffu, thr, kScale - 1u, (cum & 0xfffu) + (kScale - 1u));
+  // ceil(2^(32+s) / f), s = l - 1, as 2^32 * 2^s / f: again two divisions with small numerators
+  const uint32_t s = l - 1u;
+  const uint32_t n = 1u << s;  // n < f
+  const uint32_t q1 = (n << 16) / f, r1 = (n << 16) - q1 * f;
+  const uint32_t q2 = (r1 << 16) / f, r2 = (r1 << 16) - q2 * f;
+  const uint32_t m = (q1 << 16) + q2 + (r2 ? 1u : 0u);
+  return make_uint4(m, thr, (kScale - f) | (s << 24), cum & 0xfffu);
 }
 
-__global__ __launch_bounds__(64) void rans_encode_kernel(const RansArgs a) {
-  __shared__ uint2 table[2][256];
-  const int lane = threadIdx.x, half = lane >> 5, l = lane & 31;
-  const Unit u = locate_unit(a, half);
+// One coding step.  Every lane stores its low 16 bits each time -- the emitting lanes into the word
+// list, the others into a scratch slot of their own -- so that the step has no branch; `on` (MASKED
+// only) is false for lanes that hold no symbol in a ragged group.
+template <bool LONG, bool MASKED>
+__device__ __forceinline__ void enc_step(uint32_t &x, const uint4 e, uint16_t *wstage, uint16_t *scratch,
+                                         uint32_t &cnt, uint32_t &flags, uint32_t below, bool on) {
+  uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(x, e.y, 34 /* unsigned > */);
+  bool emit = x > e.y;
+  if (MASKED) {
+    emit = emit && on;
+    m32 = (uint32_t)__builtin_amdgcn_ballot_w64(emit);
+  }
+  // hardware lane h carries rANS lane 31 - h, which the encoder visits first for h = 0; `below` is the
+  // mask of the lanes under this one within its half, so that a mirror lane ranks like its twin
+  uint16_t *slot = wstage + (cnt + (uint32_t)__builtin_popcount(m32 & below));
+  *(emit ? slot : scratch) = (uint16_t)x;
+  x = emit ? x >> 16 : x;
+  cnt += (uint32_t)__builtin_popcount(m32);
+  uint32_t xn;
+  if (LONG) {
+    const uint32_t t1 = __umulhi(e.x, x);
+    const uint32_t d = (x - t1) >> ((e.w >> 24) & 31u);
+    const uint32_t q = (t1 + d) >> (e.z >> 24);
+    xn = __umul24(q, e.z) + (x + (e.w & 0xffffu));
+  } else {
+    const uint32_t q = __umulhi(e.x, x) >> (e.z >> 24);
+    xn = __umul24(q, e.z) + (x + e.w);
+  }
+  if (MASKED) {
+    x = on ? xn : x;
+    flags |= on ? e.w : 0u;
+  } else {
+    x = xn;
+    flags |= e.w;
+  }
+}
 
-  {
-    uint32_t f[8], cum;
-    const uint32_t total = load_freq8(a.freq + u.stream * 256, l, f, &cum);
-    if (u.live && total != kScale && l == 0) raise(a.status, PLC_ERR_INVALID);
+template <int W>
+__global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
+  __shared__ uint4 table[256];
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[W][2][kSymStage];
+  __shared__ __attribute__((aligned(16))) uint16_t word_stage[W][kBatchSyms + 64];  // + one scratch slot per lane
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t stream = blockIdx.x / a.wgs_per_stream;
+  const int64_t chunk = (int64_t)(blockIdx.x - stream * a.wgs_per_stream) * W + wave;
+  const bool live = chunk < a.units_per_stream;
+
+  bool long_form;
+  {  // every wavefront scans the frequencies; entry 4*lane + r is built by wavefront (4*lane + r) mod W
+    uint32_t f[4], cum;
+    const uint32_t total = load_freq4(a.freq + stream * 256, lane, f, &cum);
+    if (total != kScale && threadIdx.x == 0) raise(a.status, PLC_ERR_INVALID);
+    long_form = __ballot(f[0] > 2048u || f[1] > 2048u || f[2] > 2048u || f[3] > 2048u) != 0;  // uniform
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      table[half][l * 8 + r] = make_enc_entry(f[r], cum);
+    for (int r = 0; r < 4; ++r) {
+      const int s = lane * 4 + r;
+      if ((s & (W - 1)) == wave)
+        table[s] = long_form ? make_enc_entry<true>(f[r], cum) : make_enc_entry<false>(f[r], cum);
       cum += f[r];
     }
   }
   __syncthreads();
+  if (!live) return;  // no workgroup barrier below
 
-  const uint8_t *sp = a.sym_in + u.stream * a.syms_per_stream + u.begin;
-  uint16_t *wp = a.words_out + (u.live ? a.word_off[u.unit] : 0);
-  const int32_t G = u.live ? (int32_t)((u.len + kLanes - 1) / kLanes) : 0;
-  const int32_t n_batches = (int32_t)(((a.unit_syms + kLanes - 1) / kLanes + kBatch - 1) / kBatch);
-  uint32_t x = kLow;
-  uint64_t nw = 0;
-  bool zero_freq = false;
+  const int64_t unit = stream * a.units_per_stream + chunk;
+  const int64_t begin = chunk * a.unit_syms;
+  const int64_t rest = a.syms_per_stream - begin;
+  const uint32_t len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
+  const uint8_t *ubase = a.sym_in + stream * a.syms_per_stream + begin;
+  const uintptr_t u_lo = reinterpret_cast<uintptr_t>(ubase);
+  const uint32_t mis = (uint32_t)(u_lo & 15u);
+  const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
+  const uint32_t top_syms = len - (uint32_t)(G - 1) * kLanes;  // symbols in the last group, 1..32
+  uint16_t *wp = a.words_out + a.word_off[unit];
+  uint16_t *wstage = word_stage[wave];
+  uint16_t *scratch = wstage + kBatchSyms + lane;
 
-  // symbols of the first batch (groups G-1 down to G-16)
-  uint32_t nxt[kBatch];
+  const int rl = 31 - (lane & 31);  // rANS lane carried by this hardware lane
+  const uint32_t below = (1u << (lane & 31)) - 1u;
+  const bool coder = lane < kLanes;
+  const bool top_active = (uint32_t)rl < top_syms;
+  uint32_t x = kLow, flags = 0;
+  uint64_t flushed = 0;
+
+  // Staging rounds walk the groups from the top, 64 groups per round (the first round takes what is
+  // left over).  A round's symbols [32*glo, 32*ghi) are fetched as 16-byte pieces aligned in absolute
+  // address and placed so that symbol (group ghi-1-j, lane l) always sits at  mis + l + 32 * (63 - j).
+  auto stage_load = [&](int32_t glo, int32_t ghi, uint4 v[kStagePieces], bool take[kStagePieces]) {
+    const uintptr_t lo = u_lo + (uintptr_t)(glo > 0 ? glo : 0) * kLanes;
+    uintptr_t hi = u_lo + (uintptr_t)(ghi > 0 ? ghi : 0) * kLanes;
+    const uintptr_t end = u_lo + len;
+    hi = hi < end ? hi : end;
 #pragma unroll
-  for (int j = 0; j < kBatch; ++j) {
-    const int32_t g = G - 1 - j;
-    const int64_t t = (int64_t)g * kLanes + l;
-    nxt[j] = (g >= 0 && t < (int64_t)u.len) ? sp[t] : 0u;
-  }
-  for (int32_t b = 0; b < n_batches; ++b) {
-    uint32_t cur[kBatch];
-#pragma unroll
-    for (int j = 0; j < kBatch; ++j) cur[j] = nxt[j];
-    // fetch the next batch while this one is coded
-#pragma unroll
-    for (int j = 0; j < kBatch; ++j) {
-      const int32_t g = G - 1 - (b + 1) * kBatch - j;
-      const int64_t t = (int64_t)g * kLanes + l;
-      nxt[j] = (g >= 0 && t < (int64_t)u.len) ? sp[t] : 0u;
+    for (int i = 0; i < kStagePieces; ++i) {
+      const uintptr_t addr = (lo & ~(uintptr_t)15) + (uintptr_t)(lane + 64 * i) * 16;
+      take[i] = ghi > 0 && addr < hi;
+      if (take[i]) v[i] = load16_stream(reinterpret_cast<const void *>(addr));
     }
-    uint2 ent[kBatch];
+  };
+  auto stage_store = [&](int buf, int32_t cnt, const uint4 v[kStagePieces], const bool take[kStagePieces]) {
 #pragma unroll
-    for (int j = 0; j < kBatch; ++j) ent[j] = table[half][cur[j]];
-#pragma unroll
-    for (int j = 0; j < kBatch; ++j) {
-      const int32_t g = G - 1 - b * kBatch - j;
-      const bool active = g >= 0 && (int64_t)g * kLanes + l < (int64_t)u.len;
-      const uint32_t fs = ent[j].y & 0x1fffu;
-      const uint32_t cs = (ent[j].y >> 13) & 0xfffu;
-      const uint32_t sh1 = (ent[j].y >> 25) & 1u, sh2 = ent[j].y >> 26;
-      if (active && fs == 0) zero_freq = true;
-      // renormalise: x >= f * 2^20, tested on the high bits (f * 2^20 overflows for f = 4096)
-      const bool emit = active && (x >> 20) >= fs;
-      const uint32_t m32 = half_mask(__ballot(emit), half);
-      if (emit) {
-        // the encoder visits lane 31 first, so a lane's slot counts the emitting lanes above it
-        const uint64_t idx = nw + (uint32_t)__popc((m32 >> l) >> 1);
-        if (idx < a.word_cap) wp[idx] = (uint16_t)(x & 0xffffu);
-        x >>= 16;
+    for (int i = 0; i < kStagePieces; ++i)
+      if (take[i])
+        *reinterpret_cast<uint4 *>(&sym_stage[wave][buf][(lane + 64 * i) * 16 + kLanes * (kSuperGroups - cnt)]) = v[i];
+  };
+  // drain a batch's words, 64 consecutive words per store instruction
+  auto drain = [&](uint32_t cnt) {
+    wave_sync();
+    for (uint32_t i = lane; i < cnt; i += 64) {
+      const uint64_t idx = flushed + i;
+      if (idx < a.word_cap) wp[idx] = wstage[i];
+    }
+    flushed += cnt;
+    wave_sync();
+  };
+
+  int32_t ghi = G;
+  int32_t cnt_groups = G % kSuperGroups ? G % kSuperGroups : kSuperGroups;
+  // groups of the first round that do not fill a batch (and the top group if it is ragged) run in a
+  // rolled loop with lane masking; every other batch is 16 full groups, fully unrolled
+  int32_t head_groups = cnt_groups % kBatch;
+  if (head_groups == 0 && top_syms < kLanes) head_groups = kBatch;
+  {
+    uint4 v[kStagePieces];
+    bool take[kStagePieces];
+    stage_load(ghi - cnt_groups, ghi, v, take);
+    stage_store(0, cnt_groups, v, take);
+  }
+  wave_sync();
+  int buf = 0;
+  while (ghi > 0) {
+    const int32_t glo = ghi - cnt_groups;
+    uint4 nv[kStagePieces];
+    bool ntake[kStagePieces];
+    stage_load(glo - kSuperGroups, glo, nv, ntake);  // next round, in flight while this one is coded
+    const uint8_t *sb = &sym_stage[wave][buf][mis + rl];
+    int32_t j0 = 0;
+    if (head_groups) {
+      uint32_t cnt = 0;
+      for (int32_t j = 0; j < head_groups; ++j) {
+        const uint4 e = table[sb[kLanes * (kSuperGroups - 1 - j)]];
+        if (long_form) {
+          enc_step<true, true>(x, e, wstage, scratch, cnt, flags, below, j != 0 || top_active);
+        } else {
+          enc_step<false, true>(x, e, wstage, scratch, cnt, flags, below, j != 0 || top_active);
+        }
       }
-      nw += (uint32_t)__popc(m32);
-      if (active) {
-        const uint32_t t1 = __umulhi(ent[j].x, x);
-        const uint32_t q = (t1 + ((x - t1) >> sh1)) >> sh2;  // floor(x / f)
-        x = q * (kScale - fs) + x + cs;                      // q * 4096 + x mod f + cum
+      drain(cnt);
+      j0 = head_groups;
+    }
+    for (; j0 < cnt_groups; j0 += kBatch) {
+      const uint8_t *sbb = sb + kLanes * (kSuperGroups - kBatch - j0);  // lowest group of this batch
+      uint32_t sy[kBatch];
+      uint4 e[kBatch];
+      uint32_t cnt = 0;
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) sy[j] = sbb[kLanes * (kBatch - 1 - j)];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) e[j] = table[sy[j]];
+      if (long_form) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) enc_step<true, false>(x, e[j], wstage, scratch, cnt, flags, below, true);
+      } else {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) enc_step<false, false>(x, e[j], wstage, scratch, cnt, flags, below, true);
       }
+      drain(cnt);
     }
+    stage_store(buf ^ 1, kSuperGroups, nv, ntake);
+    wave_sync();
+    buf ^= 1;
+    ghi = glo;
+    cnt_groups = kSuperGroups;
+    head_groups = 0;
   }
-  if (u.live) {
-    a.states_out[u.unit * kLanes + l] = x;
-    if (l == 0) {
-      a.n_words_out[u.unit] = (uint32_t)(nw < 0xffffffffull ? nw : 0xffffffffull);
-      if (nw > a.word_cap) raise(a.status, PLC_ERR_CAPACITY);
-    }
-    if (zero_freq) raise(a.status, PLC_ERR_INVALID);
+  if (coder) a.states_out[unit * kLanes + rl] = x;
+  if (lane == 0) {
+    a.n_words_out[unit] = (uint32_t)(flushed < 0xffffffffull ? flushed : 0xffffffffull);
+    if (flushed > a.word_cap) raise(a.status, PLC_ERR_CAPACITY);
   }
+  if (coder && (flags & 0x80000000u)) raise(a.status, PLC_ERR_INVALID);  // a symbol with f = 0 occurred
 }
 
 // ---------------------------------------------------------------------------
 // Decoder
 // ---------------------------------------------------------------------------
 // Slot table: for each of the 4096 slots, sym | (f - 1) << 8 | (slot - cum) << 20.
-// Words are consumed from the end of the unit's list; they are staged through
-// an LDS ring of four 512-word blocks (aligned in absolute address), refilled
-// one block per batch of 16 groups, which can consume at most 512 words.
-constexpr int kRingWords = 2048, kBlockWords = 512;
+// Words are consumed from the end of the unit's list.  They are staged through
+// a per-wavefront LDS ring of four 512-word blocks (blocks aligned in absolute
+// address), refilled at most one block per batch of 16 groups, which consumes
+// at most 512 words.  The ring is stored backwards -- word i sits at position
+// (~i) mod 2048 -- so that the word of the lane with rank r is at position
+// q + r, where q = (-ptr) mod 2048 at the start of a batch and then simply
+// grows by the words consumed, in a scalar register; positions 0..543 are
+// mirrored at 2048..2591 so that q + r never needs a wrap inside a batch.
+constexpr int kRingWords = 2048, kBlockWords = 512, kRingMirror = kBlockWords + 32;
 
-__device__ __forceinline__ bool load_block(const uint16_t *aligned_base, int32_t blk, int32_t lo, int32_t hi, int l,
-                                           uint4 v[2]) {
-  bool any = false;
-#pragma unroll
-  for (int p = 0; p < 2; ++p) {
-    const int32_t first = blk * kBlockWords + (2 * l + p) * 8;  // eight words per 16-byte piece
-    v[p] = make_uint4(0u, 0u, 0u, 0u);
-    if (blk >= 0 && hi > lo && first + 8 > lo && first < hi) {  // piece holds a word of this unit
-      v[p] = *reinterpret_cast<const uint4 *>(aligned_base + first);
-      any = true;
-    }
+template <bool MASKED>
+__device__ __forceinline__ void dec_step(uint32_t &x, const uint32_t *lut, const uint16_t *&top, uint8_t *sym_slot,
+                                         uint32_t below, bool on) {
+  const uint32_t e = lut[x & (kScale - 1)];
+  const uint32_t xh = x >> kScaleBits;
+  uint32_t xn = __umul24((e >> 8) & 0xfffu, xh) + (xh + (e >> 20));  // f * (x >> 12) + slot - cum
+  uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
+  bool need = xn < kLow;
+  if (MASKED) {
+    need = need && on;
+    m32 = (uint32_t)__builtin_amdgcn_ballot_w64(need);
   }
-  return any;
+  if (need) {
+    // The decoder visits lane 0 first: a lane's word is the rank-th from the top of the list (`top`
+    // points at the top word in the backwards ring).  `below` is the mask of the lanes under this one
+    // within its half, so that a mirror lane ranks like its twin.
+    xn = (xn << 16) | top[__builtin_popcount(m32 & below)];
+  }
+  top += __builtin_popcount(m32);
+  if (MASKED) {
+    if (on) {
+      *sym_slot = (uint8_t)e;
+      x = xn;
+    }
+  } else {
+    *sym_slot = (uint8_t)e;
+    x = xn;
+  }
 }
 
-__device__ __forceinline__ void store_block(uint16_t *ring, int32_t blk, int l, const uint4 v[2]) {
-  uint4 *dst = reinterpret_cast<uint4 *>(ring + ((blk * kBlockWords) & (kRingWords - 1)));
-  dst[2 * l] = v[0];
-  dst[2 * l + 1] = v[1];
-}
-
-__global__ __launch_bounds__(64) void rans_decode_kernel(const RansArgs a) {
-  __shared__ uint32_t lut[2][kScale];
-  __shared__ __attribute__((aligned(16))) uint16_t ring[2][kRingWords];
-  __shared__ uint32_t fc[2][256];  // f | cum << 16
-  const int lane = threadIdx.x, half = lane >> 5, l = lane & 31;
-  Unit u = locate_unit(a, half);
+template <int W>
+__global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
+  __shared__ uint32_t lut[kScale];
+  __shared__ __attribute__((aligned(16))) uint16_t ring[W][kRingWords + kRingMirror];
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[W][kBatchSyms];
+  __shared__ uint32_t table_ok;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t stream = blockIdx.x / a.wgs_per_stream;
+  const int64_t chunk = (int64_t)(blockIdx.x - stream * a.wgs_per_stream) * W + wave;
+  const bool live = chunk < a.units_per_stream;
   bool bad = false;
 
-  // ---- slot table
-  {
-    uint32_t f[8], cum;
-    const uint32_t total = load_freq8(a.freq + u.stream * 256, l, f, &cum);
-    if (total != kScale) {  // not a table: decode nothing for this unit
-      if (u.live) bad = true;
-      u.live = false;
-    }
+  {  // slot table, built by all wavefronts: symbol s is filled in by wavefront s mod W
+    uint32_t f[4], cum;
+    const uint32_t total = load_freq4(a.freq + stream * 256, lane, f, &cum);
+    if (threadIdx.x == 0) table_ok = total == kScale;
+    if (total == kScale) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      fc[half][l * 8 + r] = f[r] | (cum << 16);
-      cum += f[r];
+      for (int r = 0; r < 4; ++r) {
+        const int s = lane * 4 + r;
+        if ((s & (W - 1)) == wave) {
+          for (uint32_t o = 0; o < f[r]; ++o) lut[cum + o] = (uint32_t)s | ((f[r] - 1u) << 8) | (o << 20);
+        }
+        cum += f[r];
+      }
     }
   }
   __syncthreads();
-  if (u.live) {
-    for (int s = 0; s < 256; ++s) {
-      const uint32_t e = fc[half][s];
-      const uint32_t f = e & 0xffffu, c = e >> 16;
-      for (uint32_t o = l; o < f; o += kLanes) lut[half][c + o] = (uint32_t)s | ((f - 1u) << 8) | (o << 20);
-    }
+  if (!table_ok) {  // not a table: nothing can be decoded
+    if (live && lane == 0) raise(a.status, PLC_ERR_CORRUPT);
+    return;
   }
+  if (!live) return;  // no workgroup barrier below
+
+  const int64_t unit = stream * a.units_per_stream + chunk;
+  const int64_t begin = chunk * a.unit_syms;
+  const int64_t rest = a.syms_per_stream - begin;
+  const uint32_t len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
+  uint8_t *ubase = a.sym_out + stream * a.syms_per_stream + begin;
+  const bool out_aligned = (reinterpret_cast<uintptr_t>(ubase) & 15u) == 0;
+  const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
+  const uint32_t top_syms = len - (uint32_t)(G - 1) * kLanes;
 
   // ---- word list geometry, relative to a 1 KiB-aligned address at or below the unit's first word
-  const uint64_t off = u.live ? a.word_off[u.unit] : 0;
-  uint32_t n = u.live ? a.n_words_in[u.unit] : 0;
-  if (u.live && (off > a.words_len || (uint64_t)n > a.words_len - off)) {
-    bad = true;
-    u.live = false;
-    n = 0;
+  const uint64_t off = a.word_off[unit];
+  const uint32_t n = a.n_words_in[unit];
+  if (off > a.words_len || (uint64_t)n > a.words_len - off) {
+    if (lane == 0) raise(a.status, PLC_ERR_CORRUPT);
+    return;
   }
   const uintptr_t first_addr = reinterpret_cast<uintptr_t>(a.words_in + off);
   const uintptr_t base_addr = first_addr & ~(uintptr_t)(kBlockWords * 2 - 1);
   const uint16_t *aligned_base = reinterpret_cast<const uint16_t *>(base_addr);
   const int32_t lo = (int32_t)((first_addr - base_addr) >> 1);
-  const int32_t hi = lo + (int32_t)n;  // n < 2^31 - 512 is checked on the host through syms_per_stream
+  const int32_t hi = lo + (int32_t)n;
+  uint16_t *myring = ring[wave];
+
+  // one 16-byte piece (eight words) of block blk per lane, if the piece holds a word of this unit
+  auto block_load = [&](int32_t blk, uint4 &v) -> bool {
+    const int32_t first = blk * kBlockWords + lane * 8;
+    const bool take = blk >= 0 && hi > lo && first + 8 > lo && first < hi;
+    if (take) v = *reinterpret_cast<const uint4 *>(aligned_base + first);
+    return take;
+  };
+  // word i goes to ring position (~i) mod 2048: a piece of eight words lands reversed on an aligned run
+  auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
+    if (take) {
+      const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);
+      const uint4 r = make_uint4((v.w >> 16) | (v.w << 16), (v.z >> 16) | (v.z << 16), (v.y >> 16) | (v.y << 16),
+                                 (v.x >> 16) | (v.x << 16));
+      *reinterpret_cast<uint4 *>(myring + pos) = r;
+      if (pos < kRingMirror) *reinterpret_cast<uint4 *>(myring + kRingWords + pos) = r;
+    }
+  };
+
   int32_t ptr = hi;
   int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already staged (none yet)
-  {
-    uint4 v[2];
-    for (int r = 0; r < 2; ++r) {  // the two top blocks
-      const int32_t blk = lowest - 1;
-      load_block(aligned_base, blk, lo, hi, l, v);
-      store_block(ring[half], blk, l, v);
-      lowest = blk;
-    }
+  for (int r = 0; r < 2; ++r) {          // the two top blocks
+    uint4 v;
+    const int32_t blk = lowest - 1;
+    const bool take = block_load(blk, v);
+    block_store(blk, take, v);
+    lowest = blk;
   }
-  __syncthreads();
+  wave_sync();
 
-  uint32_t x = u.live ? a.states_in[u.unit * kLanes + l] : kLow;
-  uint8_t *sp = a.sym_out + u.stream * a.syms_per_stream + u.begin;
-  const int32_t n_batches = (int32_t)(((a.unit_syms + kLanes - 1) / kLanes + kBatch - 1) / kBatch);
+  const bool coder = lane < kLanes;
+  const int rl = lane & (kLanes - 1);
+  const uint32_t below = (1u << rl) - 1u;
+  const bool top_active = (uint32_t)rl < top_syms;
+  uint32_t x = a.states_in[unit * kLanes + rl];
 
-  for (int32_t b = 0; b < n_batches; ++b) {
+  // Full batches of 16 groups are fully unrolled; the groups that do not fill a batch (and the last
+  // group if it is ragged) form a tail that runs in a rolled loop.
+  int32_t tail_groups = G % kBatch;
+  if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
+  const int32_t g_tail = G - tail_groups;
+  uint8_t *sb = &sym_stage[wave][rl];
+
+  for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
+    const bool tail = g0 >= g_tail;
+    const int32_t cnt_groups = tail ? tail_groups : kBatch;
     // stage one more block below if the coming batches may reach it
     const int32_t top = (ptr - 1) >> 9;
-    uint4 pre[2];
     const bool fetch = lowest > top - 2;
     const int32_t blk = lowest - 1;
-    if (fetch) load_block(aligned_base, blk, lo, hi, l, pre);
+    uint4 pre;
+    bool ptake = false;
+    if (fetch) ptake = block_load(blk, pre);
 
+    const uint16_t *wtop0 = myring + ((uint32_t)(-ptr) & (kRingWords - 1));
+    const uint16_t *wtop = wtop0;
+    if (tail) {
+      for (int32_t j = 0; j < cnt_groups; ++j)
+        dec_step<true>(x, lut, wtop, sb + kLanes * j, below, j != cnt_groups - 1 || top_active);
+    } else {
 #pragma unroll
-    for (int j = 0; j < kBatch; ++j) {
-      const int64_t t = ((int64_t)b * kBatch + j) * kLanes + l;
-      const bool active = u.live && t < (int64_t)u.len;
-      const uint32_t slot = x & (kScale - 1);
-      const uint32_t e = lut[half][slot];
-      if (active) {
-        x = ((e >> 8) & 0xfffu) * (x >> kScaleBits) + (x >> kScaleBits) + (e >> 20);  // f * (x >> 12) + slot - cum
-        sp[t] = (uint8_t)(e & 0xffu);
-      }
-      const bool need = active && x < kLow;
-      const uint32_t m32 = half_mask(__ballot(need), half);
-      const int32_t cnt = __popc(m32);
-      if (need) {
-        // the decoder visits lane 0 first: a lane's word is the rank-th from the top
-        const int32_t idx = ptr - 1 - __popc(m32 & ((1u << l) - 1u));
-        uint32_t w = 0;
-        if (idx >= lo) {
-          w = ring[half][idx & (kRingWords - 1)];
-        } else {
-          bad = true;  // ran out of words
-        }
-        x = (x << 16) | w;
-      }
-      ptr = ptr - cnt < lo ? lo : ptr - cnt;
+      for (int j = 0; j < kBatch; ++j) dec_step<false>(x, lut, wtop, sb + kLanes * j, below, true);
+    }
+    ptr -= (int32_t)(wtop - wtop0);
+    if (ptr < lo) {  // ran out of words: the stream is damaged
+      bad = true;
+      ptr = lo;
+    }
+    wave_sync();
+    // drain the batch's symbols
+    const uint32_t done = (uint32_t)g0 * kLanes;
+    const uint32_t room = (uint32_t)cnt_groups * kLanes;
+    const uint32_t nsym = (len - done) < room ? (len - done) : room;
+    if (out_aligned) {
+      const uint32_t full = nsym / 16;
+      if ((uint32_t)lane < full)
+        *reinterpret_cast<uint4 *>(ubase + done + lane * 16) =
+            *reinterpret_cast<const uint4 *>(&sym_stage[wave][lane * 16]);
+      const uint32_t tail = full * 16 + (uint32_t)lane;
+      if (tail < nsym) ubase[done + tail] = sym_stage[wave][tail];
+    } else {
+      for (uint32_t i = lane; i < nsym; i += 64) ubase[done + i] = sym_stage[wave][i];
     }
     if (fetch) {
-      store_block(ring[half], blk, l, pre);
+      block_store(blk, ptake, pre);
       lowest = blk;
     }
-    __syncthreads();
+    wave_sync();
   }
   // integrity: every word consumed, every lane back at the initial state
-  if (u.live && (ptr != lo || x != kLow)) bad = true;
+  if (ptr != lo || (coder && x != kLow)) bad = true;
   if (bad) raise(a.status, PLC_ERR_CORRUPT);
 }
 
-int check_common(int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms, RansArgs *a) {
+int check_common(int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms, RansArgs *a, int *waves) {
   if (n_streams < 1 || syms_per_stream < 1) return PLC_ERR_INVALID;
   if (syms_per_stream >= (1ll << 31) - 1024) return PLC_ERR_INVALID;
   if (chunk_syms < 0 || chunk_syms % kLanes) return PLC_ERR_INVALID;
@@ -325,9 +500,37 @@ int check_common(int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms,
   a->unit_syms = chunk_syms > 0 ? chunk_syms : syms_per_stream;
   a->n_units = n_streams * a->units_per_stream;
   a->syms_per_stream = syms_per_stream;
-  if ((a->n_units + 1) / 2 >= (1ll << 31)) return PLC_ERR_INVALID;
+  int w = 1;
+  while (w < kMaxWaves && 2 * w <= a->units_per_stream) w *= 2;
+  *waves = w;
+  const int64_t wgs = (a->units_per_stream + w - 1) / w;
+  if (wgs >= (1ll << 31) || n_streams * wgs >= (1ll << 31)) return PLC_ERR_INVALID;
+  a->wgs_per_stream = (uint32_t)wgs;
   return PLC_OK;
 }
+
+template <template <int> class Launcher>
+void dispatch_waves(int waves, const RansArgs &a, unsigned grid, hipStream_t st) {
+  switch (waves) {
+    case 1: Launcher<1>::run(a, grid, st); break;
+    case 2: Launcher<2>::run(a, grid, st); break;
+    case 4: Launcher<4>::run(a, grid, st); break;
+    default: Launcher<8>::run(a, grid, st); break;
+  }
+}
+
+template <int W>
+struct LaunchEncode {
+  static void run(const RansArgs &a, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL(rans_encode_kernel<W>, dim3(grid), dim3(W * 64), 0, st, a);
+  }
+};
+template <int W>
+struct LaunchDecode {
+  static void run(const RansArgs &a, unsigned grid, hipStream_t st) {
+    hipLaunchKernelGGL(rans_decode_kernel<W>, dim3(grid), dim3(W * 64), 0, st, a);
+  }
+};
 
 }  // namespace
 }  // namespace plc
@@ -344,11 +547,12 @@ extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_
                                const uint64_t *word_off, uint64_t word_cap_per_unit, uint32_t *n_words,
                                uint32_t *status, void *stream) {
   RansArgs a = {};
-  int rc = check_common(n_streams, syms_per_stream, chunk_syms, &a);
+  int waves = 1;
+  int rc = check_common(n_streams, syms_per_stream, chunk_syms, &a, &waves);
   if (rc) return rc;
   if (!symbols || !freq || !states || !word_off || !n_words || !status) return PLC_ERR_INVALID;
   if (word_cap_per_unit > 0 && !words) return PLC_ERR_INVALID;
-  if (reinterpret_cast<uintptr_t>(freq) % 16 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(freq) % 8 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
   a.sym_in = symbols;
   a.freq = freq;
   a.states_out = states;
@@ -357,10 +561,10 @@ extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_
   a.word_cap = word_cap_per_unit;
   a.n_words_out = n_words;
   a.status = status;
+  hipStream_t st = static_cast<hipStream_t>(stream);
   {
-    TraceScope trace(PLC_TRACE_RANS_ENCODE, static_cast<hipStream_t>(stream));
-    hipLaunchKernelGGL(rans_encode_kernel, dim3((unsigned)((a.n_units + 1) / 2)), dim3(64), 0,
-                       static_cast<hipStream_t>(stream), a);
+    TraceScope trace(PLC_TRACE_RANS_ENCODE, st);
+    dispatch_waves<LaunchEncode>(waves, a, (unsigned)(n_streams * a.wgs_per_stream), st);
   }
   return launch_status();
 }
@@ -370,11 +574,12 @@ extern "C" int plc_rans_decode(const uint16_t *freq, const uint32_t *states, con
                                int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms, uint8_t *symbols,
                                uint32_t *status, void *stream) {
   RansArgs a = {};
-  int rc = check_common(n_streams, syms_per_stream, chunk_syms, &a);
+  int waves = 1;
+  int rc = check_common(n_streams, syms_per_stream, chunk_syms, &a, &waves);
   if (rc) return rc;
   if (!symbols || !freq || !states || !word_off || !n_words || !status) return PLC_ERR_INVALID;
   if (words_len > 0 && !words) return PLC_ERR_INVALID;
-  if (reinterpret_cast<uintptr_t>(freq) % 16 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(freq) % 8 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
   a.sym_out = symbols;
   a.freq = freq;
   a.states_in = states;
@@ -383,10 +588,10 @@ extern "C" int plc_rans_decode(const uint16_t *freq, const uint32_t *states, con
   a.word_off = word_off;
   a.n_words_in = n_words;
   a.status = status;
+  hipStream_t st = static_cast<hipStream_t>(stream);
   {
-    TraceScope trace(PLC_TRACE_RANS_DECODE, static_cast<hipStream_t>(stream));
-    hipLaunchKernelGGL(rans_decode_kernel, dim3((unsigned)((a.n_units + 1) / 2)), dim3(64), 0,
-                       static_cast<hipStream_t>(stream), a);
+    TraceScope trace(PLC_TRACE_RANS_DECODE, st);
+    dispatch_waves<LaunchDecode>(waves, a, (unsigned)(n_streams * a.wgs_per_stream), st);
   }
   return launch_status();
 }
