@@ -17,6 +17,11 @@ namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
+// Escapes of a tile are first parked in a per-tile staging row of this many entries (a tile has 2048
+// symbols; the synthetic workloads escape 0.7 % of them).  A tile with more escapes than that is
+// gathered again from its symbols by the compaction pass.
+constexpr int kEscStage = 128;
+
 struct CodecArgs {
   const uint16_t *cand_k, *cand_v;
   const uint16_t *act_k, *act_v;  // encode only
@@ -28,6 +33,7 @@ struct CodecArgs {
   const uint64_t *esc_off;        // decode
   float *pred_out;                // encode, nullable
   uint32_t *tile_cnt;             // [n_streams * tiles_per_stream] escapes per tile
+  uint16_t *esc_stage;            // encode: [n_tiles, kEscStage] escapes of each tile in symbol order
   const uint32_t *tile_off;       // decode: exclusive prefix of tile_cnt inside a stream
   uint32_t *status;
   int32_t L, H, n, k, d8;
@@ -48,16 +54,16 @@ struct Coord {
   uint32_t stream, tile;
 };
 
-__device__ __forceinline__ Coord locate(const CodecArgs &a) {
+__device__ __forceinline__ Coord locate_chunk(const CodecArgs &a, uint32_t stream, uint32_t tile, uint32_t slot) {
   Coord q;
-  q.stream = blockIdx.x / a.tiles_per_stream;
-  q.tile = blockIdx.x - q.stream * a.tiles_per_stream;
+  q.stream = stream;
+  q.tile = tile;
   const uint32_t lh = a.L * a.H;
   const uint32_t s = q.stream / lh;
   const uint32_t r = q.stream - s * lh;
   const uint32_t l = r / a.H;
   const uint32_t h = r - l * a.H;
-  const uint32_t chunk = q.tile * kBlock + threadIdx.x;
+  const uint32_t chunk = q.tile * kBlock + slot;  // slot: which of the tile's 256 chunks
   q.valid = chunk < a.chunks_per_stream;
   const uint32_t row = chunk / (uint32_t)a.d8;  // row = i * 2 + c
   const uint32_t e8 = chunk - row * a.d8;
@@ -68,6 +74,25 @@ __device__ __forceinline__ Coord locate(const CodecArgs &a) {
   q.w = ((int64_t)s * a.n + i) * a.k;
   q.sym = (int64_t)q.stream * a.syms_per_stream + (int64_t)chunk * kChunk;
   return q;
+}
+
+// One workgroup per tile, one thread per chunk.
+__device__ __forceinline__ Coord locate(const CodecArgs &a) {
+  const uint32_t stream = blockIdx.x / a.tiles_per_stream;
+  return locate_chunk(a, stream, blockIdx.x - stream * a.tiles_per_stream, threadIdx.x);
+}
+
+// Number of escapes in the lanes below this one, from the per-lane counts 0..8, by bit planes.
+__device__ __forceinline__ uint32_t wave_escape_prefix(uint32_t n_esc, uint32_t *wave_total) {
+  uint32_t prefix = 0, total = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const uint64_t plane = __ballot((n_esc >> b) & 1u);
+    prefix += __builtin_amdgcn_mbcnt_hi((uint32_t)(plane >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)plane, 0u)) << b;
+    total += (uint32_t)__builtin_popcountll(plane) << b;
+  }
+  *wave_total = total;
+  return prefix;
 }
 
 // pred[e] = sum_j w[j] * cand_j[e], fp32 fused multiply-add, j ascending from 0.
@@ -127,11 +152,16 @@ template <int K>
 __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArgs a) {
   __shared__ uint32_t wave_cnt[kBlock / 64];
   const Coord q = locate(a);
-  uint32_t n_esc = 0;
+  uint32_t n_esc = 0, esc_bits = 0;
+  uint32_t raw[4] = {0u, 0u, 0u, 0u};
   if (q.valid) {
     const uint16_t *cand = (q.c ? a.cand_v : a.cand_k) + q.cand;
     const uint16_t *act = (q.c ? a.act_v : a.act_k) + q.act;
     const uint4 av = load16_stream(act);
+    raw[0] = av.x;
+    raw[1] = av.y;
+    raw[2] = av.z;
+    raw[3] = av.w;
     float pred[kChunk];
     predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
     const half8 x = __builtin_bit_cast(half8, av);
@@ -147,6 +177,7 @@ __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArg
       } else {
         sym = PLC_ESCAPE;
         ++n_esc;
+        esc_bits |= 1u << e;
       }
       packed[e >> 2] |= sym << (8 * (e & 3));
     }
@@ -157,13 +188,26 @@ __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArg
       po[1] = make_float4(pred[4], pred[5], pred[6], pred[7]);
     }
   }
-  // escapes in this tile (their values are gathered by a second, sparse pass)
-  uint32_t wsum = n_esc;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) wsum += __shfl_xor(wsum, off, 64);
-  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = wsum;
+  // Escapes of this tile, in symbol order, go to the tile's staging row; a later sparse pass moves
+  // them to their final place once the counts of all tiles in front are known.
+  uint32_t wave_total = 0, prefix = 0;
+  if (__ballot(n_esc != 0) != 0) prefix = wave_escape_prefix(n_esc, &wave_total);  // uniform
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) wave_cnt[wave] = wave_total;
   __syncthreads();
-  if (threadIdx.x == 0) a.tile_cnt[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+  const uint32_t c0 = wave_cnt[0], c1 = wave_cnt[1], c2 = wave_cnt[2], c3 = wave_cnt[3];
+  if (threadIdx.x == 0) a.tile_cnt[blockIdx.x] = c0 + c1 + c2 + c3;
+  if (n_esc) {
+    uint32_t pos = prefix + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
+    uint16_t *row = a.esc_stage + (int64_t)blockIdx.x * kEscStage;
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) {
+      if (esc_bits & (1u << e)) {
+        if (pos < (uint32_t)kEscStage) row[pos] = (uint16_t)((e & 1 ? raw[e >> 1] >> 16 : raw[e >> 1]) & 0xffffu);
+        ++pos;
+      }
+    }
+  }
 }
 
 // Count the escape symbols of each tile (decode side).
@@ -220,31 +264,49 @@ __global__ __launch_bounds__(kBlock) void scan_streams_kernel(const uint32_t *__
   if (threadIdx.x == 0 && carry > esc_cap) raise(status, PLC_ERR_CAPACITY);
 }
 
-// Write the raw fp16 of every escaped component to its place in the stream's list.
-__global__ __launch_bounds__(kBlock) void gather_escapes_kernel(const CodecArgs a, uint16_t *__restrict__ esc_vals,
-                                                                uint64_t esc_cap,
-                                                                const uint64_t *__restrict__ esc_off) {
-  __shared__ uint32_t smem[8];
-  if (a.tile_cnt[blockIdx.x] == 0) return;  // uniform
-  const Coord q = locate(a);
-  uint2 sv = make_uint2(0u, 0u);
-  uint32_t n_esc = 0;
-  if (q.valid) {
-    sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
-#pragma unroll
-    for (int e = 0; e < kChunk; ++e) n_esc += (((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE;
+// Move every tile's escapes from its staging row to their place in the stream's list; one wavefront
+// per tile.  A tile that overflowed its staging row is gathered again from its symbols and the actual
+// values, 64 chunks at a time.
+__global__ __launch_bounds__(kBlock) void compact_escapes_kernel(const CodecArgs a, uint16_t *__restrict__ esc_vals,
+                                                                 uint64_t esc_cap,
+                                                                 const uint64_t *__restrict__ esc_off,
+                                                                 int64_t n_tiles) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+  if (t >= n_tiles) return;
+  const uint32_t cnt = a.tile_cnt[t];
+  if (cnt == 0) return;  // uniform per wavefront
+  const uint32_t stream = (uint32_t)(t / a.tiles_per_stream);
+  const uint32_t tile = (uint32_t)(t - (int64_t)stream * a.tiles_per_stream);
+  uint64_t dst = esc_off[stream] + a.tile_off[t];
+  if (cnt <= (uint32_t)kEscStage) {
+    const uint16_t *row = a.esc_stage + t * kEscStage;
+    for (uint32_t i = lane; i < cnt; i += 64)
+      if (dst + i < esc_cap) esc_vals[dst + i] = row[i];
+    return;
   }
-  uint32_t total;
-  uint32_t rank = block_exclusive_scan(n_esc, smem, &total);
-  if (n_esc == 0) return;
-  const uint16_t *act = (q.c ? a.act_v : a.act_k) + q.act;
-  uint64_t dst = esc_off[q.stream] + a.tile_off[blockIdx.x] + rank;
+  for (int round = 0; round < kBlock / 64; ++round) {
+    const Coord q = locate_chunk(a, stream, tile, (uint32_t)(round * 64 + lane));
+    uint2 sv = make_uint2(0u, 0u);
+    uint32_t n_esc = 0;
+    if (q.valid) {
+      sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
 #pragma unroll
-  for (int e = 0; e < kChunk; ++e) {
-    if ((((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE) {
-      if (dst < esc_cap) esc_vals[dst] = act[e];
-      ++dst;
+      for (int e = 0; e < kChunk; ++e) n_esc += (((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE;
     }
+    uint32_t wave_total;
+    uint64_t at = dst + wave_escape_prefix(n_esc, &wave_total);
+    if (n_esc) {
+      const uint16_t *act = (q.c ? a.act_v : a.act_k) + q.act;
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) {
+        if ((((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE) {
+          if (at < esc_cap) esc_vals[at] = act[e];
+          ++at;
+        }
+      }
+    }
+    dst += wave_total;
   }
 }
 
@@ -304,7 +366,7 @@ __global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) 
 // ---------------------------------------------------------------------------
 struct Plan {
   int64_t n_streams, syms_per_stream, chunks_per_stream, tiles_per_stream, n_tiles, rows;
-  size_t off_weights, off_tile_cnt, off_tile_off, total;
+  size_t off_weights, off_tile_cnt, off_tile_off, off_stage, total;
 };
 
 bool make_plan(const plc_dims *dm, Plan *p) {
@@ -329,7 +391,8 @@ bool make_plan(const plc_dims *dm, Plan *p) {
   p->off_weights = 0;
   p->off_tile_cnt = align_up((size_t)p->rows * dm->k * sizeof(float), 256);
   p->off_tile_off = p->off_tile_cnt + align_up((size_t)p->n_tiles * sizeof(uint32_t), 256);
-  p->total = p->off_tile_off + align_up((size_t)p->n_tiles * sizeof(uint32_t), 256);
+  p->off_stage = p->off_tile_off + align_up((size_t)p->n_tiles * sizeof(uint32_t), 256);
+  p->total = p->off_stage + align_up((size_t)p->n_tiles * kEscStage * sizeof(uint16_t), 256);
   return true;
 }
 
@@ -340,6 +403,7 @@ void fill_args(const plc_dims *dm, const Plan &p, void *ws, CodecArgs *a) {
   a->weights = reinterpret_cast<const float *>(w + p.off_weights);
   a->tile_cnt = reinterpret_cast<uint32_t *>(w + p.off_tile_cnt);
   a->tile_off = reinterpret_cast<const uint32_t *>(w + p.off_tile_off);
+  a->esc_stage = reinterpret_cast<uint16_t *>(w + p.off_stage);
   a->L = dm->L;
   a->H = dm->H;
   a->n = dm->n;
@@ -430,8 +494,8 @@ extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, co
                      (uint32_t)p.tiles_per_stream, esc_cnt);
   hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
                      status);
-  hipLaunchKernelGGL(gather_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a, esc_vals, esc_cap,
-                     esc_off);
+  hipLaunchKernelGGL(compact_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))),
+                     dim3(kBlock), 0, st, a, esc_vals, esc_cap, esc_off, p.n_tiles);
   return launch_status();
 }
 

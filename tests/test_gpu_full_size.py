@@ -1,0 +1,124 @@
+"""Parity at the benchmark's full size, in the launch configuration bench.py times.
+
+The whole Llama-3-8B-shaped workload (256 streams of 2^20 symbols) is encoded and
+decoded on the GPU exactly as bench.py does it; the oracle then recomputes a
+sample of whole streams one by one (a stream is the unit everything downstream
+of the symbols depends on) and every artefact of those streams must match bit
+for bit.  Properties that hold at any size are checked on all streams.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2604_15356_amd.workloads import make_workload
+from tests.gpu_util import codec_for, near_tie_report, u8, u16, u32, u64
+
+pytestmark = pytest.mark.gpu
+
+SAMPLE_STREAMS = (0, 7, 100, 255)
+
+
+@pytest.fixture(scope="module")
+def run():
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    dev = torch.device("cuda:0")
+    w = make_workload("llama8b", device=dev)
+    out = {}
+    for chunk in (0, 4096):
+        print(f"full-size llama8b, chunk_syms={chunk}", flush=True)
+        codec = codec_for(w, chunk_syms=chunk, want_pred=False)
+        coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+        out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+        codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+        codec.check_status("full size")
+        out[chunk] = (codec, coded, out_k, out_v)
+    return w, out
+
+
+def _stream_inputs(w, st):
+    s, r = divmod(st, w.L * w.H)
+    l, h = divmod(r, w.H)
+    host = lambda t: t.contiguous().cpu().numpy()
+    return (host(w.cand_k[s, l, h]), host(w.cand_v[s, l, h]), host(w.probs[s]),
+            host(w.act_k[s, l, h]), host(w.act_v[s, l, h])), (s, l, h)
+
+
+@pytest.mark.parametrize("chunk", [0, 4096])
+def test_sampled_streams_match_oracle_bit_for_bit(oracle, run, chunk):
+    O = oracle
+    w, out = run
+    codec, coded, out_k, out_v = out[chunk]
+    dm = O.make_dims(1, 1, 1, w.n, w.k, w.d, w.delta, w.qmax)
+    U = codec.units_per_stream
+    words = None
+    for st in SAMPLE_STREAMS:
+        print(f"  stream {st}", flush=True)
+        (ck, cv, p, ak, av), (s, l, h) = _stream_inputs(w, st)
+        ref32 = O.predict_residual(dm, ck, cv, p, ak, av, mode=O.F32)
+        ref64 = O.predict_residual(dm, ck, cv, p, ak, av, mode=O.F64, want_u=True)
+        sym = u8(coded.symbols[st:st + 1])
+        assert np.array_equal(sym, ref32["symbols"])
+        tau = 64 * 2.0 ** -24 * 8.0 / float(np.float32(w.delta))
+        n_diff, n_ok = near_tie_report(sym, ref64["symbols"], ref64["u"], tau)
+        assert n_diff == n_ok and n_diff < 1e-4 * sym.size
+        # escape list of the stream
+        off = int(u64(coded.esc_off)[st])
+        cnt = int(u32(coded.esc_cnt)[st])
+        assert cnt == int(ref32["esc_cnt"][0])
+        assert np.array_equal(u16(coded.esc_vals[off:off + cnt]), ref32["esc_vals"])
+        # table and bitstream
+        counts = O.histogram(sym)
+        freq, cum = O.build_freq(counts)
+        assert np.array_equal(u32(coded.counts[st:st + 1]), counts)
+        assert np.array_equal(u16(coded.freq[st:st + 1]), freq)
+        enc = O.rans_encode(sym, freq, chunk_syms=chunk, word_cap_per_unit=codec.word_cap)
+        assert np.array_equal(u32(coded.n_words[st * U:(st + 1) * U]), enc["n_words"])
+        assert np.array_equal(u32(coded.states[st * U:(st + 1) * U]), enc["states"])
+        if words is None:
+            words = u16(coded.words)
+        for u in range(U):
+            o, nw = (st * U + u) * codec.word_cap, int(enc["n_words"][u])
+            assert np.array_equal(words[o:o + nw], enc["words"][u * codec.word_cap:u * codec.word_cap + nw])
+        # the oracle decodes the GPU's stream, and reconstructs what the GPU reconstructed
+        dec = O.rans_decode(freq, u32(coded.states[st * U:(st + 1) * U]),
+                            words[st * U * codec.word_cap:(st + 1) * U * codec.word_cap],
+                            np.arange(U, dtype=np.uint64) * np.uint64(codec.word_cap),
+                            u32(coded.n_words[st * U:(st + 1) * U]), 1, codec.N, chunk_syms=chunk)
+        assert np.array_equal(dec, sym)
+        rk, rv = O.reconstruct(dm, ck, cv, p, sym, ref32["esc_vals"], np.zeros(1, dtype=np.uint64), mode=O.F32)
+        assert np.array_equal(u16(out_k[s, l, h]).ravel(), rk)
+        assert np.array_equal(u16(out_v[s, l, h]).ravel(), rv)
+
+
+@pytest.mark.parametrize("chunk", [0, 4096])
+def test_properties_on_every_stream(run, chunk):
+    w, out = run
+    codec, coded, out_k, out_v = out[chunk]
+    # decoder returns the encoder's symbols
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    # tables: sum to 4096, f > 0 exactly where the symbol occurs, counts add up to N
+    freq = coded.freq.to(torch.int32) & 0xffff
+    assert bool((freq.sum(1) == 4096).all())
+    assert bool(((freq > 0) == (coded.counts > 0)).all())
+    assert bool((coded.counts.to(torch.int64).sum(1) == codec.N).all())
+    # escape offsets are the running sum of the counts
+    cnt = coded.esc_cnt.to(torch.int64)
+    assert torch.equal(coded.esc_off, torch.cumsum(cnt, 0) - cnt)
+    # coded size: within a small margin of the empirical entropy of the symbols, per stream
+    p = coded.counts.double() / codec.N
+    H = -(torch.where(p > 0, p * torch.log2(p), torch.zeros_like(p))).sum(1)
+    U = codec.units_per_stream
+    bits = 16.0 * coded.n_words.double().reshape(-1, U).sum(1) + 32 * 32 * U
+    excess = bits / codec.N - H
+    assert float(excess.min()) > -1e-9 and float(excess.max()) < (0.03 if chunk == 0 else 0.3)
+    # recovery error: at most Delta/2 plus half an fp16 ulp of the output; escapes exact
+    esc = (coded.symbols.reshape(w.S, w.L, w.H, w.n, 2, w.d) == 255)
+    delta = float(np.float32(w.delta))
+    for c, (act, outp) in enumerate(((w.act_k, out_k), (w.act_v, out_v))):
+        for l in range(w.L):
+            a, o, e = act[0, l].float(), outp[0, l].float(), esc[0, l, :, :, c, :]
+            err = (a - o).abs()
+            ulp = torch.clamp(o.abs(), min=2.0 ** -14) * 2.0 ** -10          # >= one fp16 ulp of the output
+            assert bool((err[~e] <= delta / 2 + ulp[~e] / 2 + 1e-6).all())
+            assert torch.equal(act[0, l].view(torch.int16)[e], outp[0, l].view(torch.int16)[e])

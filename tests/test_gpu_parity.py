@@ -37,6 +37,9 @@ CASES = {
     "k11_runtime_loop": ("tiny", dict(k=11, n=129, d=40, seed=15), "lhnkd", True),
     "k20": ("tiny", dict(k=20, L=1, H=2, n=65, d=128, seed=16), "lhnkd", True),
     "one_position": ("tiny", dict(L=1, H=1, n=1, d=8, seed=17), "lhnkd", False),
+    # so many escapes that tiles overflow their staging rows and take the re-gather path
+    "escape_heavy": ("tiny", dict(L=1, H=2, n=300, sigma=3.0, seed=18), "lhnkd", False),
+    "escape_heavy_ragged": ("tiny", dict(L=1, H=3, n=37, k=5, d=24, sigma=2.0, seed=19), "lnkhd", True),
 }
 
 
