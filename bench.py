@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--layout", default="lhnkd", choices=["lhnkd", "lnkhd"])
     ap.add_argument("--sessions", type=int, default=None, help="override the number of sessions")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain elementwise kernel that reads and writes 256 MiB, as the known-size "
+                         "reference for scaling HBM byte counters in a profiler run")
     ap.add_argument("--cpu-streams", type=int, default=64, help="streams the CPU oracle is timed on")
     return ap.parse_args()
 
@@ -70,6 +73,25 @@ class KernelTimer:
 
     def mean_ms(self):
         return {name: sum(a.elapsed_time(b) for a, b in pairs) / len(pairs) for name, pairs in self.ev.items()}
+
+
+def measured_traffic(kernel, config_name, k):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when there
+    is none for this workload or the kernel's sources have changed since the counters were taken."""
+    import hashlib
+    import re
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{config_name}.txt")
+    if not os.path.exists(path):
+        return None
+    h = hashlib.sha256()
+    for f in ("plc_predict.hip", "plc_device.h"):
+        with open(os.path.join(ROOT, "paper_2604_15356_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    for line in open(path):
+        m = re.match(r"machine-readable: kernel=(\S+) traffic_bytes_per_launch=(\d+) source_sha256=(\w+)", line)
+        if m and m.group(1) == f"{kernel}<{k}>" and m.group(3) == h.hexdigest():
+            return int(m.group(2))
+    return None
 
 
 def cpu_baseline(w, n_sample, torch):
@@ -141,6 +163,12 @@ def main():
         step()
     torch.cuda.synchronize()
     codec.check_status("warmup")
+    if args.calibrate_copy:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)      # 256 MiB read + 256 MiB written by one elementwise kernel
+        torch.cuda.synchronize()
+        del src, dst
     timer = KernelTimer(plc, torch, args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -181,7 +209,9 @@ def main():
     log(f"  step (encode+decode) {ms_per_step:9.4f} ms   kernels sum {sum(ms.values()):.4f} ms")
     dom = kernels["predict_residual"]
     roofline = dict(bound="hbm", kernel="predict_residual_kernel", achieved=dom["GBs"], peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=dom["frac_hbm"], traffic=None,
+                    unit="GB/s", frac=dom["frac_hbm"],
+                    traffic=measured_traffic("predict_residual_kernel", args.config, w.k)
+                    if (args.layout == "lhnkd" and not args.sessions) else None,
                     bytes_per_component=2 * w.k + 3, components=E)
 
     result = {
