@@ -41,6 +41,18 @@ struct TraceScope {
   }
 };
 
+// Stores of data that is written once and not read again by this kernel: non-temporal, so that the
+// write stream does not take L2 capacity from the reads (worth 12 % on the predict kernel).
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store8_stream(void *p, uint32_t a, uint32_t b) {
+  const u32x2 v = {a, b};
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x2 *>(p));
+}
+__device__ __forceinline__ void store16_stream(void *p, uint4 a) {
+  const u32x4 v = {a.x, a.y, a.z, a.w};
+  __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
+}
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? PLC_OK : PLC_ERR_HIP; }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

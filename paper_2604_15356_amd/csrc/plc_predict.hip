@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArg
       }
       packed[e >> 2] |= sym << (8 * (e & 3));
     }
-    *reinterpret_cast<uint2 *>(a.symbols + q.sym) = make_uint2(packed[0], packed[1]);
+    store8_stream(a.symbols + q.sym, packed[0], packed[1]);
     if (a.pred_out) {
       float4 *po = reinterpret_cast<float4 *>(a.pred_out + q.sym);
       po[0] = make_float4(pred[0], pred[1], pred[2], pred[3]);
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) 
   }
   if (q.valid) {
     uint16_t *dst = (q.c ? a.out_v : a.out_k) + q.act;
-    *reinterpret_cast<uint4 *>(dst) = __builtin_bit_cast(uint4, out);
+    store16_stream(dst, __builtin_bit_cast(uint4, out));
   }
 }
 

@@ -119,8 +119,8 @@ __device__ __forceinline__ uint4 make_enc_entry(uint32_t f, uint32_t cum) {
 // list, the others into a scratch slot of their own -- so that the step has no branch; `on` (MASKED
 // only) is false for lanes that hold no symbol in a ragged group.
 template <bool LONG, bool MASKED>
-__device__ __forceinline__ void enc_step(uint32_t &x, const uint4 e, uint16_t *wstage, uint16_t *scratch,
-                                         uint32_t &cnt, uint32_t &flags, uint32_t below, bool on) {
+__device__ __forceinline__ void enc_step(uint32_t &x, const uint4 e, uint16_t *&wtop, uint16_t *scratch,
+                                         uint32_t &flags, uint32_t below, bool on) {
   uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(x, e.y, 34 /* unsigned > */);
   bool emit = x > e.y;
   if (MASKED) {
@@ -129,10 +129,11 @@ __device__ __forceinline__ void enc_step(uint32_t &x, const uint4 e, uint16_t *w
   }
   // hardware lane h carries rANS lane 31 - h, which the encoder visits first for h = 0; `below` is the
   // mask of the lanes under this one within its half, so that a mirror lane ranks like its twin
-  uint16_t *slot = wstage + (cnt + (uint32_t)__builtin_popcount(m32 & below));
+  // (`wtop` = next free slot of the batch's word list, uniform)
+  uint16_t *slot = wtop + __builtin_popcount(m32 & below);
   *(emit ? slot : scratch) = (uint16_t)x;
   x = emit ? x >> 16 : x;
-  cnt += (uint32_t)__builtin_popcount(m32);
+  wtop += __builtin_popcount(m32);
   uint32_t xn;
   if (LONG) {
     const uint32_t t1 = __umulhi(e.x, x);
@@ -152,11 +153,59 @@ __device__ __forceinline__ void enc_step(uint32_t &x, const uint4 e, uint16_t *w
   }
 }
 
+// The same step for the unrolled batches, with its instruction order pinned.  A wavefront issues in
+// order and a dependent VALU result takes about two issue slots to arrive (measured on gfx950: 8.5
+// cycles dependent, 4.3 independent).  The step has two dependent chains that both start at the
+// compare -- the state update and the address of the word to store -- so they are interleaved one for
+// one; left to itself the compiler emits them one after the other and the wavefront idles.
+#define PLC_PIN() __builtin_amdgcn_sched_barrier(0)
+
+template <bool LONG>
+__device__ __forceinline__ void enc_step_pinned(uint32_t &x, const uint4 e, uint16_t *&wtop, uint16_t *scratch,
+                                                uint32_t &flags, uint32_t below) {
+  const uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(x, e.y, 34 /* unsigned > */);
+  const bool emit = x > e.y;
+  PLC_PIN();
+  const uint32_t x16 = x >> 16;
+  PLC_PIN();
+  const uint32_t under = m32 & below;
+  PLC_PIN();
+  const uint32_t xr = emit ? x16 : x;
+  PLC_PIN();
+  const uint32_t rank = (uint32_t)__builtin_popcount(under);
+  PLC_PIN();
+  const uint32_t t1 = __umulhi(e.x, xr);
+  PLC_PIN();
+  uint16_t *slot = wtop + rank;
+  PLC_PIN();
+  uint32_t q, xc;
+  if (LONG) {
+    const uint32_t d = (xr - t1) >> ((e.w >> 24) & 31u);
+    q = (t1 + d) >> (e.z >> 24);
+    xc = xr + (e.w & 0xffffu);
+  } else {
+    q = t1 >> (e.z >> 24);
+    xc = xr + e.w;
+  }
+  PLC_PIN();
+  slot = emit ? slot : scratch;
+  PLC_PIN();
+  const uint32_t p = __umul24(q, e.z);
+  PLC_PIN();
+  *slot = (uint16_t)x;
+  PLC_PIN();
+  wtop += __builtin_popcount(m32);
+  PLC_PIN();
+  x = p + xc;
+  PLC_PIN();
+  flags |= e.w;
+}
+
 template <int W>
 __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
   __shared__ uint4 table[256];
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[W][2][kSymStage];
-  __shared__ __attribute__((aligned(16))) uint16_t word_stage[W][kBatchSyms + 64];  // + one scratch slot per lane
+  __shared__ __attribute__((aligned(16))) uint16_t word_stage[W][kBatchSyms + 8 + 64];  // list + carry + scratch slots
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t stream = blockIdx.x / a.wgs_per_stream;
   const int64_t chunk = (int64_t)(blockIdx.x - stream * a.wgs_per_stream) * W + wave;
@@ -184,34 +233,33 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
   const int64_t rest = a.syms_per_stream - begin;
   const uint32_t len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
   const uint8_t *ubase = a.sym_in + stream * a.syms_per_stream + begin;
-  const uintptr_t u_lo = reinterpret_cast<uintptr_t>(ubase);
-  const uint32_t mis = (uint32_t)(u_lo & 15u);
+  const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(ubase) & 15u);
   const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
   const uint32_t top_syms = len - (uint32_t)(G - 1) * kLanes;  // symbols in the last group, 1..32
   uint16_t *wp = a.words_out + a.word_off[unit];
   uint16_t *wstage = word_stage[wave];
-  uint16_t *scratch = wstage + kBatchSyms + lane;
+  uint16_t *scratch = wstage + kBatchSyms + 8 + lane;
 
   const int rl = 31 - (lane & 31);  // rANS lane carried by this hardware lane
   const uint32_t below = (1u << (lane & 31)) - 1u;
   const bool coder = lane < kLanes;
   const bool top_active = (uint32_t)rl < top_syms;
   uint32_t x = kLow, flags = 0;
-  uint64_t flushed = 0;
 
   // Staging rounds walk the groups from the top, 64 groups per round (the first round takes what is
   // left over).  A round's symbols [32*glo, 32*ghi) are fetched as 16-byte pieces aligned in absolute
   // address and placed so that symbol (group ghi-1-j, lane l) always sits at  mis + l + 32 * (63 - j).
   auto stage_load = [&](int32_t glo, int32_t ghi, uint4 v[kStagePieces], bool take[kStagePieces]) {
-    const uintptr_t lo = u_lo + (uintptr_t)(glo > 0 ? glo : 0) * kLanes;
-    uintptr_t hi = u_lo + (uintptr_t)(ghi > 0 ? ghi : 0) * kLanes;
-    const uintptr_t end = u_lo + len;
-    hi = hi < end ? hi : end;
+    // byte offsets relative to the unit's first symbol; pointers are formed by plain pointer arithmetic
+    // on the kernel argument so that the loads stay global (not flat) memory instructions
+    const int64_t lo = (int64_t)(glo > 0 ? glo : 0) * kLanes;
+    int64_t hi = (int64_t)(ghi > 0 ? ghi : 0) * kLanes;
+    hi = hi < (int64_t)len ? hi : (int64_t)len;
 #pragma unroll
     for (int i = 0; i < kStagePieces; ++i) {
-      const uintptr_t addr = (lo & ~(uintptr_t)15) + (uintptr_t)(lane + 64 * i) * 16;
-      take[i] = ghi > 0 && addr < hi;
-      if (take[i]) v[i] = load16_stream(reinterpret_cast<const void *>(addr));
+      const int64_t off = lo - (int64_t)mis + (int64_t)(lane + 64 * i) * 16;  // 16-byte aligned in absolute address
+      take[i] = ghi > 0 && off < hi;
+      if (take[i]) v[i] = load16_stream(ubase + off);
     }
   };
   auto stage_store = [&](int buf, int32_t cnt, const uint4 v[kStagePieces], const bool take[kStagePieces]) {
@@ -220,14 +268,43 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
       if (take[i])
         *reinterpret_cast<uint4 *>(&sym_stage[wave][buf][(lane + 64 * i) * 16 + kLanes * (kSuperGroups - cnt)]) = v[i];
   };
-  // drain a batch's words, 64 consecutive words per store instruction
-  auto drain = [&](uint32_t cnt) {
-    wave_sync();
-    for (uint32_t i = lane; i < cnt; i += 64) {
-      const uint64_t idx = flushed + i;
-      if (idx < a.word_cap) wp[idx] = wstage[i];
+  // Words leave through an LDS list whose position p stands for the word at 16-byte-aligned address
+  // (wp - pad) + vbase + p: the first `pad` positions of the unit are padding in front of its first word.
+  // After each batch the complete 16-byte pieces are stored, one per lane, and the incomplete tail (< 8
+  // words) moves to the front of the list.  Pieces that touch the padding or the end of the unit's
+  // reservation are stored word by word.
+  // (All of this bookkeeping is uniform; readfirstlane keeps it in scalar registers.)
+  const uint32_t pad = __builtin_amdgcn_readfirstlane((uint32_t)((reinterpret_cast<uintptr_t>(wp) >> 1) & 7u));
+  const uint32_t cap = a.word_cap < 0x7fffffffull ? (uint32_t)a.word_cap : 0x7fffffffu;  // a unit has < 2^31 symbols
+  uint32_t vbase = 0;   // multiple of 8
+  uint32_t fill = pad;  // positions of the list in use
+  auto store_words = [&](uint32_t first_pos, uint32_t n_pos) {  // word-by-word, with all checks
+    for (uint32_t p = first_pos + lane; p < first_pos + n_pos; p += 64) {
+      const uint32_t v = vbase + p;
+      if (v >= pad && v - pad < cap) wp[v - pad] = wstage[p];
     }
-    flushed += cnt;
+  };
+  auto drain = [&](uint32_t new_fill_v) {
+    const uint32_t new_fill = __builtin_amdgcn_readfirstlane(new_fill_v);
+    wave_sync();
+    const uint32_t full = new_fill / 8;  // at most 65 pieces
+    const bool plain = vbase >= pad && vbase + 8 * full - pad <= cap;
+    if (plain) {
+      uint16_t *dst = wp + (vbase - pad);  // 16-byte aligned
+      if ((uint32_t)lane < full)
+        *reinterpret_cast<uint4 *>(dst + 8 * lane) = *reinterpret_cast<const uint4 *>(wstage + 8 * lane);
+      if (full > 64 && lane == 0)
+        *reinterpret_cast<uint4 *>(dst + 8 * 64) = *reinterpret_cast<const uint4 *>(wstage + 8 * 64);
+    } else {
+      store_words(0, 8 * full);
+    }
+    const uint32_t rest = new_fill - 8 * full;
+    uint16_t carry = 0;
+    if ((uint32_t)lane < rest) carry = wstage[8 * full + lane];
+    wave_sync();
+    if ((uint32_t)lane < rest) wstage[lane] = carry;
+    vbase += 8 * full;
+    fill = rest;
     wave_sync();
   };
 
@@ -252,38 +329,55 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
     stage_load(glo - kSuperGroups, glo, nv, ntake);  // next round, in flight while this one is coded
     const uint8_t *sb = &sym_stage[wave][buf][mis + rl];
     int32_t j0 = 0;
+    // The prefetched round is written to LDS after the first batch of this round and BEFORE that batch's
+    // words are stored: waiting for the loads then does not also wait for freshly issued stores (loads
+    // and stores share one counter).
+    bool landed = false;
     if (head_groups) {
-      uint32_t cnt = 0;
+      uint16_t *wtop = wstage + fill;
       for (int32_t j = 0; j < head_groups; ++j) {
         const uint4 e = table[sb[kLanes * (kSuperGroups - 1 - j)]];
         if (long_form) {
-          enc_step<true, true>(x, e, wstage, scratch, cnt, flags, below, j != 0 || top_active);
+          enc_step<true, true>(x, e, wtop, scratch, flags, below, j != 0 || top_active);
         } else {
-          enc_step<false, true>(x, e, wstage, scratch, cnt, flags, below, j != 0 || top_active);
+          enc_step<false, true>(x, e, wtop, scratch, flags, below, j != 0 || top_active);
         }
       }
-      drain(cnt);
+      stage_store(buf ^ 1, kSuperGroups, nv, ntake);
+      landed = true;
+      drain((uint32_t)(wtop - wstage));
       j0 = head_groups;
     }
     for (; j0 < cnt_groups; j0 += kBatch) {
       const uint8_t *sbb = sb + kLanes * (kSuperGroups - kBatch - j0);  // lowest group of this batch
       uint32_t sy[kBatch];
-      uint4 e[kBatch];
-      uint32_t cnt = 0;
+      uint16_t *wtop = wstage + fill;
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) sy[j] = sbb[kLanes * (kBatch - 1 - j)];
+      // table entries are fetched four groups ahead of the chain, so that their LDS time hides behind it
+      uint4 e[2][4];
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) e[j] = table[sy[j]];
-      if (long_form) {
+      for (int j = 0; j < 4; ++j) e[0][j] = table[sy[j]];
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) enc_step<true, false>(x, e[j], wstage, scratch, cnt, flags, below, true);
-      } else {
+      for (int qt = 0; qt < kBatch / 4; ++qt) {
+        if (qt + 1 < kBatch / 4) {
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) enc_step<false, false>(x, e[j], wstage, scratch, cnt, flags, below, true);
+          for (int j = 0; j < 4; ++j) e[(qt + 1) & 1][j] = table[sy[4 * (qt + 1) + j]];
+        }
+        if (long_form) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) enc_step_pinned<true>(x, e[qt & 1][j], wtop, scratch, flags, below);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) enc_step_pinned<false>(x, e[qt & 1][j], wtop, scratch, flags, below);
+        }
       }
-      drain(cnt);
+      if (!landed) {
+        stage_store(buf ^ 1, kSuperGroups, nv, ntake);
+        landed = true;
+      }
+      drain((uint32_t)(wtop - wstage));
     }
-    stage_store(buf ^ 1, kSuperGroups, nv, ntake);
     wave_sync();
     buf ^= 1;
     ghi = glo;
@@ -291,9 +385,11 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
     head_groups = 0;
   }
   if (coder) a.states_out[unit * kLanes + rl] = x;
+  store_words(0, fill);  // the incomplete last piece
+  const uint32_t n_words = vbase + fill - pad;
   if (lane == 0) {
-    a.n_words_out[unit] = (uint32_t)(flushed < 0xffffffffull ? flushed : 0xffffffffull);
-    if (flushed > a.word_cap) raise(a.status, PLC_ERR_CAPACITY);
+    a.n_words_out[unit] = n_words;
+    if ((uint64_t)n_words > a.word_cap) raise(a.status, PLC_ERR_CAPACITY);
   }
   if (coder && (flags & 0x80000000u)) raise(a.status, PLC_ERR_INVALID);  // a symbol with f = 0 occurred
 }
@@ -392,10 +488,9 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
     if (lane == 0) raise(a.status, PLC_ERR_CORRUPT);
     return;
   }
-  const uintptr_t first_addr = reinterpret_cast<uintptr_t>(a.words_in + off);
-  const uintptr_t base_addr = first_addr & ~(uintptr_t)(kBlockWords * 2 - 1);
-  const uint16_t *aligned_base = reinterpret_cast<const uint16_t *>(base_addr);
-  const int32_t lo = (int32_t)((first_addr - base_addr) >> 1);
+  const uint16_t *first_word = a.words_in + off;
+  const int32_t lo = (int32_t)((reinterpret_cast<uintptr_t>(first_word) & (uintptr_t)(kBlockWords * 2 - 1)) >> 1);
+  const uint16_t *aligned_base = first_word - lo;  // pointer arithmetic keeps the loads global, not flat
   const int32_t hi = lo + (int32_t)n;
   uint16_t *myring = ring[wave];
 
@@ -466,6 +561,12 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
       bad = true;
       ptr = lo;
     }
+    // the prefetched block goes to the ring BEFORE this batch's symbols are stored: waiting for the load
+    // then does not also wait for freshly issued stores (loads and stores share one counter)
+    if (fetch) {
+      block_store(blk, ptake, pre);
+      lowest = blk;
+    }
     wave_sync();
     // drain the batch's symbols
     const uint32_t done = (uint32_t)g0 * kLanes;
@@ -480,10 +581,6 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
       if (tail < nsym) ubase[done + tail] = sym_stage[wave][tail];
     } else {
       for (uint32_t i = lane; i < nsym; i += 64) ubase[done + i] = sym_stage[wave][i];
-    }
-    if (fetch) {
-      block_store(blk, ptake, pre);
-      lowest = blk;
     }
     wave_sync();
   }

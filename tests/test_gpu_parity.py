@@ -256,6 +256,38 @@ def test_word_list_at_odd_addresses(oracle, dev):
     assert int(status.item()) == 0 and torch.equal(dec, sym_t)
 
 
+@pytest.mark.parametrize("chunk", [0, 1024])
+def test_encoder_writes_word_lists_at_odd_addresses(oracle, dev, chunk):
+    """Word lists that start at arbitrary 2-byte offsets: every word in place, nothing outside."""
+    from paper_2604_15356_amd import plc
+    O = oracle
+    n_streams, N = 3, 40000 + 17
+    sym_t = random_bytes(n_streams, N, seed=91, kind="gauss", device=dev)
+    sym = sym_t.cpu().numpy()
+    freq_np, _ = O.build_freq(O.histogram(sym))
+    U = plc.plc_units_per_stream(N, chunk)
+    n_units = n_streams * U
+    cap = (chunk if chunk else N) + 5          # odd spacing between the lists
+    enc = O.rans_encode(sym, freq_np, chunk_syms=chunk, word_cap_per_unit=cap)
+    offs = torch.arange(n_units, dtype=torch.int64, device=dev) * cap + 3
+    guard = 0x5a5a
+    words = torch.full((n_units * cap + 16,), guard, dtype=torch.int16, device=dev)
+    states = torch.empty((n_units, 32), dtype=torch.int32, device=dev)
+    n_words = torch.empty(n_units, dtype=torch.int32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    plc.plc_rans_encode(sym_t, n_streams, N, chunk, torch.from_numpy(freq_np.view(np.int16)).to(dev), states,
+                        words[1:], offs, cap - 3, n_words, status)
+    assert int(status.item()) == 0
+    assert np.array_equal(u32(n_words), enc["n_words"]) and np.array_equal(u32(states), enc["states"])
+    got = u16(words)
+    expect = np.full(got.shape, guard, dtype=np.uint16)
+    for unit in range(n_units):
+        nw = int(enc["n_words"][unit])
+        o = 1 + 3 + unit * cap
+        expect[o:o + nw] = enc["words"][unit * cap:unit * cap + nw]
+    assert np.array_equal(got, expect)
+
+
 def test_data_dependent_errors_are_reported_not_fatal(oracle, dev):
     from paper_2604_15356_amd import plc
     O = oracle
