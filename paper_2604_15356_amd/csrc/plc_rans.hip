@@ -589,6 +589,206 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
   if (bad) raise(a.status, PLC_ERR_CORRUPT);
 }
 
+// ---------------------------------------------------------------------------
+// Decoder for streams coded as one unit (one wavefront per workgroup)
+// ---------------------------------------------------------------------------
+// With one unit per stream there are only as many wavefronts as streams, so what counts is the
+// length of the dependent chain of one step.  In the kernel above that chain holds two LDS round
+// trips: slot table, then -- for the lanes that renormalise -- the word.  Here they are folded into
+// one.  Every entry, of the slot table and of the word ring alike, is 8 bytes
+//     .x = f | (slot - cum) << 16        .y = sym | word << 16
+// and a ring entry carries, next to its word, the slot-table entry that the state will select once
+// that word has been shifted in (its low 12 bits are the word's).  A lane that renormalises reads
+// its ring entry, a lane that does not reads the slot table at its new state -- one read either
+// way, at an address chosen per lane, both tables living in one LDS array.  The ring entries are
+// formed when a block of words is staged, off the chain.
+constexpr int kRing2Entries = kRingWords + kRingMirror;
+
+template <bool MASKED>
+__device__ __forceinline__ void dec_chain_step(uint32_t &x, uint2 &e, const uint2 *tab, uint32_t &q,
+                                               uint8_t *sym_slot, uint32_t below, bool on) {
+  const uint32_t xh = x >> kScaleBits;
+  const uint32_t xn = __umul24(e.x & 0xffffu, xh) + (e.x >> 16);  // f * (x >> 12) + slot - cum
+  uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
+  bool need = xn < kLow;
+  if (MASKED) {
+    need = need && on;
+    m32 = (uint32_t)__builtin_amdgcn_ballot_w64(need);
+  }
+  // ring entry of the rank-th word from the top (lane 0 is served first), or slot-table entry of xn
+  uint32_t idx_ring = (uint32_t)kScale + q + (uint32_t)__builtin_popcount(m32 & below);
+  uint32_t idx_slot = xn & (kScale - 1);
+  asm volatile("" : "+v"(idx_ring), "+v"(idx_slot));  // both in registers: the choice is one select, not a branch
+  const uint2 en = tab[need ? idx_ring : idx_slot];
+  q += (uint32_t)__builtin_popcount(m32);
+  const uint32_t xw = (xn << 16) | (en.y >> 16);
+  if (MASKED) {
+    if (on) {
+      *sym_slot = (uint8_t)e.y;
+      x = need ? xw : xn;
+      e = en;
+    }
+  } else {
+    *sym_slot = (uint8_t)e.y;
+    x = need ? xw : xn;
+    e = en;
+  }
+}
+
+__global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a) {
+  __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing2Entries];  // slot table, then the ring
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[kBatchSyms];
+  __shared__ uint32_t fc[256];
+  const int lane = threadIdx.x;
+  const int64_t stream = blockIdx.x / a.wgs_per_stream;
+  const int64_t chunk = blockIdx.x - stream * a.wgs_per_stream;
+  bool bad = false;
+
+  {  // slot table: symbols one after the other, 64 slots per pass
+    uint32_t f[4], cum;
+    const uint32_t total = load_freq4(a.freq + stream * 256, lane, f, &cum);
+    if (total != kScale) {  // not a table: nothing can be decoded
+      if (lane == 0) raise(a.status, PLC_ERR_CORRUPT);
+      return;
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      fc[lane * 4 + r] = f[r] | (cum << 16);
+      cum += f[r];
+    }
+    wave_sync();
+    for (int s = 0; s < 256; ++s) {
+      const uint32_t v = fc[s];
+      const uint32_t fs = v & 0xffffu, cs = v >> 16;
+      for (uint32_t o = lane; o < fs; o += 64) tab[cs + o] = make_uint2(fs | (o << 16), (uint32_t)s);
+    }
+    wave_sync();
+  }
+  uint2 *ring = tab + kScale;
+
+  const int64_t unit = stream * a.units_per_stream + chunk;
+  const int64_t begin = chunk * a.unit_syms;
+  const int64_t rest = a.syms_per_stream - begin;
+  const uint32_t len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
+  uint8_t *ubase = a.sym_out + stream * a.syms_per_stream + begin;
+  const bool out_aligned = (reinterpret_cast<uintptr_t>(ubase) & 15u) == 0;
+  const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
+  const uint32_t top_syms = len - (uint32_t)(G - 1) * kLanes;
+
+  // ---- word list geometry, relative to a 1 KiB-aligned address at or below the unit's first word
+  const uint64_t off = a.word_off[unit];
+  const uint32_t n = a.n_words_in[unit];
+  if (off > a.words_len || (uint64_t)n > a.words_len - off) {
+    if (lane == 0) raise(a.status, PLC_ERR_CORRUPT);
+    return;
+  }
+  const uint16_t *first_word = a.words_in + off;
+  const int32_t lo = (int32_t)((reinterpret_cast<uintptr_t>(first_word) & (uintptr_t)(kBlockWords * 2 - 1)) >> 1);
+  const uint16_t *aligned_base = first_word - lo;  // pointer arithmetic keeps the loads global, not flat
+  const int32_t hi = lo + (int32_t)n;
+
+  // one 16-byte piece (eight words) of block blk per lane, if the piece holds a word of this unit
+  auto block_load = [&](int32_t blk, uint4 &v) -> bool {
+    const int32_t first = blk * kBlockWords + lane * 8;
+    const bool take = blk >= 0 && hi > lo && first + 8 > lo && first < hi;
+    if (take) v = *reinterpret_cast<const uint4 *>(aligned_base + first);
+    return take;
+  };
+  // Word i goes to ring position (~i) mod 2048, together with the slot-table entry of its low 12 bits.
+  auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
+    if (take) {
+      const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
+      const uint32_t w[8] = {v.x & 0xffffu, v.x >> 16, v.y & 0xffffu, v.y >> 16,
+                             v.z & 0xffffu, v.z >> 16, v.w & 0xffffu, v.w >> 16};
+      uint2 en[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) en[i] = tab[w[7 - i] & (kScale - 1)];  // en[i] belongs at pos + i
+#pragma unroll
+      for (int i = 0; i < 8; ++i) en[i].y = (en[i].y & 0xffu) | (w[7 - i] << 16);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ring[pos + i] = en[i];
+      if (pos < (uint32_t)kRingMirror) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ring[kRingWords + pos + i] = en[i];
+      }
+    }
+  };
+
+  int32_t ptr = hi;
+  int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already staged (none yet)
+  for (int r = 0; r < 2; ++r) {          // the two top blocks
+    uint4 v;
+    const int32_t blk = lowest - 1;
+    const bool take = block_load(blk, v);
+    block_store(blk, take, v);
+    lowest = blk;
+  }
+  wave_sync();
+
+  const bool coder = lane < kLanes;
+  const int rl = lane & (kLanes - 1);
+  const uint32_t below = (1u << rl) - 1u;
+  const bool top_active = (uint32_t)rl < top_syms;
+  uint32_t x = a.states_in[unit * kLanes + rl];
+  uint2 e = tab[x & (kScale - 1)];
+
+  int32_t tail_groups = G % kBatch;
+  if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
+  const int32_t g_tail = G - tail_groups;
+  uint8_t *sb = &sym_stage[rl];
+
+  for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
+    const bool tail = g0 >= g_tail;
+    const int32_t cnt_groups = tail ? tail_groups : kBatch;
+    // stage one more block below if the coming batches may reach it
+    const int32_t top = (ptr - 1) >> 9;
+    const bool fetch = lowest > top - 2;
+    const int32_t blk = lowest - 1;
+    uint4 pre;
+    bool ptake = false;
+    if (fetch) ptake = block_load(blk, pre);
+
+    const uint32_t q0 = (uint32_t)(-ptr) & (kRingWords - 1);
+    uint32_t q = q0;
+    if (tail) {
+      for (int32_t j = 0; j < cnt_groups; ++j)
+        dec_chain_step<true>(x, e, tab, q, sb + kLanes * j, below, j != cnt_groups - 1 || top_active);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) dec_chain_step<false>(x, e, tab, q, sb + kLanes * j, below, true);
+    }
+    ptr -= (int32_t)__builtin_amdgcn_readfirstlane(q - q0);
+    if (ptr < lo) {  // ran out of words: the stream is damaged
+      bad = true;
+      ptr = lo;
+    }
+    // the prefetched block goes to the ring BEFORE this batch's symbols are stored: waiting for the load
+    // then does not also wait for freshly issued stores (loads and stores share one counter)
+    if (fetch) {
+      block_store(blk, ptake, pre);
+      lowest = blk;
+    }
+    wave_sync();
+    // drain the batch's symbols
+    const uint32_t done = (uint32_t)g0 * kLanes;
+    const uint32_t room = (uint32_t)cnt_groups * kLanes;
+    const uint32_t nsym = (len - done) < room ? (len - done) : room;
+    if (out_aligned) {
+      const uint32_t full = nsym / 16;
+      if ((uint32_t)lane < full)
+        *reinterpret_cast<uint4 *>(ubase + done + lane * 16) = *reinterpret_cast<const uint4 *>(&sym_stage[lane * 16]);
+      const uint32_t rest_at = full * 16 + (uint32_t)lane;
+      if (rest_at < nsym) ubase[done + rest_at] = sym_stage[rest_at];
+    } else {
+      for (uint32_t i = lane; i < nsym; i += 64) ubase[done + i] = sym_stage[i];
+    }
+    wave_sync();
+  }
+  // integrity: every word consumed, every lane back at the initial state
+  if (ptr != lo || (coder && x != kLow)) bad = true;
+  if (bad) raise(a.status, PLC_ERR_CORRUPT);
+}
+
 int check_common(int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms, RansArgs *a, int *waves) {
   if (n_streams < 1 || syms_per_stream < 1) return PLC_ERR_INVALID;
   if (syms_per_stream >= (1ll << 31) - 1024) return PLC_ERR_INVALID;
@@ -625,7 +825,11 @@ struct LaunchEncode {
 template <int W>
 struct LaunchDecode {
   static void run(const RansArgs &a, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL(rans_decode_kernel<W>, dim3(grid), dim3(W * 64), 0, st, a);
+    if (W == 1) {  // one unit per stream: the variant with the shortest dependent chain
+      hipLaunchKernelGGL(rans_decode_chain_kernel, dim3(grid), dim3(64), 0, st, a);
+    } else {
+      hipLaunchKernelGGL(rans_decode_kernel<W>, dim3(grid), dim3(W * 64), 0, st, a);
+    }
   }
 };
 
