@@ -42,6 +42,9 @@ def parse():
                     help="also run one plain elementwise kernel that reads and writes 256 MiB, as the known-size "
                          "reference for scaling HBM byte counters in a profiler run")
     ap.add_argument("--cpu-streams", type=int, default=64, help="streams the CPU oracle is timed on")
+    ap.add_argument("--also-chunked", type=int, default=4096,
+                    help="when the headline run codes whole streams (chunk_syms 0), also time the same workload with "
+                         "rANS units of this many symbols and report it beside the headline (0 = skip)")
     return ap.parse_args()
 
 
@@ -231,6 +234,43 @@ def main():
         "max_abs_reconstruction_error": round(max_err, 6),
         "paper_context": "theoretical bound 3.3-4.3 bits per token position at perplexity 10-20 (abstract); no measured figure",
     }
+    if args.chunk_syms == 0 and args.also_chunked > 0:
+        # Same workload, same step, but every run of `also_chunked` symbols is its own rANS unit (128 B of lane
+        # states per chunk): the rANS chains become short and plentiful.  Reported beside the headline, not as it.
+        codec2 = KVDeltaCodec(w.S, w.L, w.H, w.n, w.k, w.d, w.delta, w.qmax, chunk_syms=args.also_chunked, device=dev,
+                              cand_stride=w.cand_k.stride()[:5], act_stride=w.act_k.stride()[:4])
+
+        def step2():
+            codec2.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+            codec2.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+
+        for _ in range(args.warmup):
+            step2()
+        torch.cuda.synchronize()
+        timer2 = KernelTimer(plc, torch, args.steps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            timer2.arm(i)
+            step2()
+        torch.cuda.synchronize()
+        dt2 = time.perf_counter() - t0
+        timer2.disarm()
+        codec2.check_status("chunked steps")
+        nw2 = codec2.n_words.cpu().numpy().view(np.uint32).astype(np.int64)
+        bits2 = 16 * int(nw2.sum()) + 16 * n_esc + 32 * 32 * codec2.n_units + (256 * 16 + 3 * 32) * w.n_streams
+        ms2 = timer2.mean_ms()
+        result["chunked"] = {
+            "chunk_syms": args.also_chunked, "rans_units": codec2.n_units,
+            "value": round(w.kv_bytes / (dt2 / args.steps) / 1e9, 2), "unit": "GB/s",
+            "ms_per_step": round(dt2 / args.steps * 1e3, 4),
+            "coded_bits_per_token": round(bits2 / (w.S * w.n), 1),
+            "roundtrip_symbols_exact": bool(torch.equal(codec2.dec_symbols, codec2.symbols)),
+            "kernels_ms": {k: round(v, 4) for k, v in ms2.items()},
+        }
+        log(f"  with rANS units of {args.also_chunked} symbols: step {dt2 / args.steps * 1e3:.4f} ms "
+            f"({result['chunked']['value']} GB/s), rans_encode {ms2['rans_encode']:.4f} ms, rans_decode {ms2['rans_decode']:.4f} ms")
+        del codec2
     if not args.no_cpu_baseline:
         base, sym64 = cpu_baseline(w, args.cpu_streams, torch)
         result["cpu_baseline"] = base

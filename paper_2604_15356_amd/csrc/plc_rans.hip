@@ -825,7 +825,10 @@ struct LaunchEncode {
 template <int W>
 struct LaunchDecode {
   static void run(const RansArgs &a, unsigned grid, hipStream_t st) {
-    if (W == 1) {  // one unit per stream: the variant with the shortest dependent chain
+    // One unit per stream and no more units than the chip has compute-unit halves: time is the length of one
+    // unit's chain, so take the variant with the shortest step.  With more units its 60 KB of LDS per
+    // wavefront would cost more in occupancy than the shorter step gains.
+    if (W == 1 && a.n_units <= 512) {
       hipLaunchKernelGGL(rans_decode_chain_kernel, dim3(grid), dim3(64), 0, st, a);
     } else {
       hipLaunchKernelGGL(rans_decode_kernel<W>, dim3(grid), dim3(W * 64), 0, st, a);

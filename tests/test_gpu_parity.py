@@ -175,7 +175,8 @@ def test_special_values_escape_bit_exactly(oracle, dev):
 
 # --------------------------------------------------------------------------- byte-stream calls on their own
 
-BYTE_CASES = [(1, 1, "gauss"), (3, 5, "gauss"), (2, 33, "uniform"), (5, 1000, "gauss"), (2, 4097, "two"),
+BYTE_CASES = [(600, 1000, "gauss"),        # more single-unit streams than the chain decoder takes
+              (1, 1, "gauss"), (3, 5, "gauss"), (2, 33, "uniform"), (5, 1000, "gauss"), (2, 4097, "two"),
               (3, 70001, "gauss"), (2, 200000, "constant"), (4, 131072, "uniform"), (1, 262144 + 17, "gauss")]
 
 
