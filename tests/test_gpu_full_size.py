@@ -122,3 +122,57 @@ def test_properties_on_every_stream(run, chunk):
             ulp = torch.clamp(o.abs(), min=2.0 ** -14) * 2.0 ** -10          # >= one fp16 ulp of the output
             assert bool((err[~e] <= delta / 2 + ulp[~e] / 2 + 1e-6).all())
             assert torch.equal(act[0, l].view(torch.int16)[e], outp[0, l].view(torch.int16)[e])
+
+
+# --------------------------------------------------------------------------- the other configurations, full size
+
+OTHER = {
+    # name: sampled streams
+    "long": (0, 255),          # 8.4 M symbols per stream: stream length, 64-bit offsets (17 GB of candidates)
+    "70b": (0, 5119),          # 5,120 streams (the paper's example dimensions)
+    "batched": (0, 16383),     # 64 sessions with their own perplexity and noise, 16,384 streams, 137 GB of candidates
+}
+
+
+@pytest.mark.parametrize("name", list(OTHER))
+def test_other_configurations_full_size(oracle, name):
+    """Encode + decode of a whole configuration on the GPU; sampled streams against the oracle bit for
+    bit (symbols, escapes, table, rANS states and words, reconstruction), round trip on every stream."""
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    O = oracle
+    dev = torch.device("cuda:0")
+    free, _ = torch.cuda.mem_get_info()
+    print(f"{name}: drawing inputs ({free / 2**30:.0f} GiB free)", flush=True)
+    w = make_workload(name, device=dev)
+    codec = codec_for(w, word_frac=0.625)              # 10 bits per symbol reserved; ~7.4 are used
+    coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+    out_k, out_v = torch.empty_like(w.act_k), torch.empty_like(w.act_v)
+    codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+    codec.check_status(name)
+    print(f"{name}: coded, checking", flush=True)
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    freq = coded.freq.to(torch.int32) & 0xffff
+    assert bool((freq.sum(1) == 4096).all())
+    cnt = coded.esc_cnt.to(torch.int64)
+    assert torch.equal(coded.esc_off, torch.cumsum(cnt, 0) - cnt)
+    dm = O.make_dims(1, 1, 1, w.n, w.k, w.d, w.delta, w.qmax)
+    for st in OTHER[name]:
+        (ck, cv, p, ak, av), (s, l, h) = _stream_inputs(w, st)
+        ref = O.predict_residual(dm, ck, cv, p, ak, av, mode=O.F32)
+        sym = u8(coded.symbols[st:st + 1])
+        assert np.array_equal(sym, ref["symbols"]), f"{name} stream {st}"
+        off, n_esc = int(u64(coded.esc_off)[st]), int(u32(coded.esc_cnt)[st])
+        assert n_esc == int(ref["esc_cnt"][0])
+        assert np.array_equal(u16(coded.esc_vals[off:off + n_esc]), ref["esc_vals"])
+        fr, _ = O.build_freq(O.histogram(sym))
+        assert np.array_equal(u16(coded.freq[st:st + 1]), fr)
+        enc = O.rans_encode(sym, fr, word_cap_per_unit=codec.word_cap)
+        nw = int(enc["n_words"][0])
+        assert int(u32(coded.n_words[st:st + 1])[0]) == nw
+        assert np.array_equal(u32(coded.states[st:st + 1]), enc["states"])
+        assert np.array_equal(u16(coded.words[st * codec.word_cap:st * codec.word_cap + nw]), enc["words"][:nw])
+        rk, rv = O.reconstruct(dm, ck, cv, p, sym, ref["esc_vals"], np.zeros(1, dtype=np.uint64), mode=O.F32)
+        assert np.array_equal(u16(out_k[s, l, h]).ravel(), rk) and np.array_equal(u16(out_v[s, l, h]).ravel(), rv)
+    del codec, coded, out_k, out_v, w
+    torch.cuda.empty_cache()
