@@ -123,13 +123,26 @@ static int check_dims(const plco_dims *dm) {
 /* Encode side: predict, subtract, quantise (Sec. 7.2, integration point 1)  */
 /* ------------------------------------------------------------------------- */
 
-int plco_predict_residual(const plco_dims *dm, int mode,
-                          const uint16_t *cand_k, const uint16_t *cand_v,
-                          const float *probs,
-                          const uint16_t *act_k, const uint16_t *act_v,
-                          uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
-                          uint32_t *esc_cnt, uint64_t *esc_off,
-                          double *pred_out, double *u_out) {
+/* Which prediction a position uses.  Without a `chosen` array every position
+ * takes the weighted mean of Sec. 7.1.  With one, chosen[s*n+i] = j in [0,k)
+ * says that the true token at the position is candidate j: by Lemma "KV
+ * determinism" the KV vector is a function of the token prefix, so the
+ * prediction is that candidate's vector itself; -1 says the token is not among
+ * the candidates, and the weighted mean is used.  Returns -2 for any other value. */
+static int position_choice(const int32_t *chosen, int64_t row, int k) {
+  if (!chosen) return -1;
+  int32_t j = chosen[row];
+  if (j < -1 || j >= k) return -2;
+  return (int)j;
+}
+
+static int encode_positions(const plco_dims *dm, int mode,
+                            const uint16_t *cand_k, const uint16_t *cand_v,
+                            const float *probs, const int32_t *chosen,
+                            const uint16_t *act_k, const uint16_t *act_v,
+                            uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                            uint32_t *esc_cnt, uint64_t *esc_off,
+                            double *pred_out, double *u_out) {
   int rc = check_dims(dm);
   if (rc) return rc;
   const int S = dm->S, L = dm->L, H = dm->H, n = dm->n, k = dm->k, d = dm->d;
@@ -147,6 +160,8 @@ int plco_predict_residual(const plco_dims *dm, int mode,
         for (int i = 0; i < n; ++i) {
           rc = plco_weights(probs + ((int64_t)s * n + i) * k, k, mode, w);
           if (rc) return rc;
+          const int pick = position_choice(chosen, (int64_t)s * n + i, k);
+          if (pick == -2) return PLCO_ERR_INVALID;
           for (int c = 0; c < 2; ++c) {
             const uint16_t *cand = c ? cand_v : cand_k;
             const uint16_t *act = c ? act_v : act_k;
@@ -155,7 +170,9 @@ int plco_predict_residual(const plco_dims *dm, int mode,
             int64_t abase = s * dm->act_stride[0] + l * dm->act_stride[1] +
                             h * dm->act_stride[2] + i * dm->act_stride[3];
             for (int e = 0; e < d; ++e, ++out) {
-              double pred = predict_one(w, cand + cbase + e, dm->cand_stride[4], k, mode);
+              double pred = pick >= 0
+                  ? plco_half_to_double(cand[cbase + (int64_t)pick * dm->cand_stride[4] + e])
+                  : predict_one(w, cand + cbase + e, dm->cand_stride[4], k, mode);
               uint16_t raw = act[abase + e];
               double a = plco_half_to_double(raw);
               double u, q;
@@ -185,6 +202,29 @@ int plco_predict_residual(const plco_dims *dm, int mode,
         esc_cnt[stream] = cnt;
       }
   return PLCO_OK;
+}
+
+int plco_predict_residual(const plco_dims *dm, int mode,
+                          const uint16_t *cand_k, const uint16_t *cand_v,
+                          const float *probs,
+                          const uint16_t *act_k, const uint16_t *act_v,
+                          uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                          uint32_t *esc_cnt, uint64_t *esc_off,
+                          double *pred_out, double *u_out) {
+  return encode_positions(dm, mode, cand_k, cand_v, probs, NULL, act_k, act_v, symbols,
+                          esc_vals, esc_cap, esc_cnt, esc_off, pred_out, u_out);
+}
+
+int plco_predict_residual_cond(const plco_dims *dm, int mode,
+                               const uint16_t *cand_k, const uint16_t *cand_v,
+                               const float *probs, const int32_t *chosen,
+                               const uint16_t *act_k, const uint16_t *act_v,
+                               uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                               uint32_t *esc_cnt, uint64_t *esc_off,
+                               double *pred_out, double *u_out) {
+  if (!chosen) return PLCO_ERR_INVALID;
+  return encode_positions(dm, mode, cand_k, cand_v, probs, chosen, act_k, act_v, symbols,
+                          esc_vals, esc_cap, esc_cnt, esc_off, pred_out, u_out);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -380,11 +420,12 @@ int plco_rans_decode(const uint16_t *freq, const uint32_t *states,
 /* Decode side: dequantise, add the prediction back (Sec. 7.2, point 2)      */
 /* ------------------------------------------------------------------------- */
 
-int plco_reconstruct(const plco_dims *dm, int mode,
-                     const uint16_t *cand_k, const uint16_t *cand_v,
-                     const float *probs, const uint8_t *symbols,
-                     const uint16_t *esc_vals, const uint64_t *esc_off,
-                     uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
+static int decode_positions(const plco_dims *dm, int mode,
+                            const uint16_t *cand_k, const uint16_t *cand_v,
+                            const float *probs, const int32_t *chosen,
+                            const uint8_t *symbols,
+                            const uint16_t *esc_vals, const uint64_t *esc_off,
+                            uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
   int rc = check_dims(dm);
   if (rc) return rc;
   const int S = dm->S, L = dm->L, H = dm->H, n = dm->n, k = dm->k, d = dm->d;
@@ -400,6 +441,8 @@ int plco_reconstruct(const plco_dims *dm, int mode,
         for (int i = 0; i < n; ++i) {
           rc = plco_weights(probs + ((int64_t)s * n + i) * k, k, mode, w);
           if (rc) return rc;
+          const int pick = position_choice(chosen, (int64_t)s * n + i, k);
+          if (pick == -2) return PLCO_ERR_INVALID;
           for (int c = 0; c < 2; ++c) {
             const uint16_t *cand = c ? cand_v : cand_k;
             uint16_t *out = c ? out_v : out_k;
@@ -415,7 +458,9 @@ int plco_reconstruct(const plco_dims *dm, int mode,
                 if (pre_round_out) pre_round_out[in] = plco_half_to_double(raw);
                 continue;
               }
-              double pred = predict_one(w, cand + cbase + e, dm->cand_stride[4], k, mode);
+              double pred = pick >= 0
+                  ? plco_half_to_double(cand[cbase + (int64_t)pick * dm->cand_stride[4] + e])
+                  : predict_one(w, cand + cbase + e, dm->cand_stride[4], k, mode);
               int q = (int)sym - ZERO_SYMBOL;
               double xhat;
               if (mode == PLCO_F32) {
@@ -429,5 +474,189 @@ int plco_reconstruct(const plco_dims *dm, int mode,
           }
         }
       }
+  return PLCO_OK;
+}
+
+int plco_reconstruct(const plco_dims *dm, int mode,
+                     const uint16_t *cand_k, const uint16_t *cand_v,
+                     const float *probs, const uint8_t *symbols,
+                     const uint16_t *esc_vals, const uint64_t *esc_off,
+                     uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
+  return decode_positions(dm, mode, cand_k, cand_v, probs, NULL, symbols, esc_vals, esc_off,
+                          out_k, out_v, pre_round_out);
+}
+
+int plco_reconstruct_cond(const plco_dims *dm, int mode,
+                          const uint16_t *cand_k, const uint16_t *cand_v,
+                          const float *probs, const int32_t *chosen,
+                          const uint8_t *symbols,
+                          const uint16_t *esc_vals, const uint64_t *esc_off,
+                          uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
+  if (!chosen) return PLCO_ERR_INVALID;
+  return decode_positions(dm, mode, cand_k, cand_v, probs, chosen, symbols, esc_vals, esc_off,
+                          out_k, out_v, pre_round_out);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Token-conditional coding: which candidate is the true token, and the code  */
+/* of that index under the model's own probabilities (Thm. "Sequential       */
+/* entropy bound": the cost of a position is at most the token's surprisal)  */
+/* ------------------------------------------------------------------------- */
+
+/* The candidate whose layer-0, head-0 key row is nearest (squared distance,
+ * components ascending) to the actual one; lowest index on ties; a distance
+ * that is NaN never wins.  If the nearest is farther than max_mean_sq per
+ * component, or none compares, the position is a miss (-1). */
+int plco_select_candidate(const plco_dims *dm, int mode, const uint16_t *cand_k,
+                          const uint16_t *act_k, float max_mean_sq, int32_t *chosen) {
+  int rc = check_dims(dm);
+  if (rc) return rc;
+  const int S = dm->S, n = dm->n, k = dm->k, d = dm->d;
+  for (int s = 0; s < S; ++s)
+    for (int i = 0; i < n; ++i) {
+      int64_t cbase = s * dm->cand_stride[0] + i * dm->cand_stride[3]; /* l = 0, h = 0 */
+      int64_t abase = s * dm->act_stride[0] + i * dm->act_stride[3];
+      int best_j = -1;
+      double best = 0.0;
+      for (int j = 0; j < k; ++j) {
+        double D;
+        if (mode == PLCO_F32) {
+          float acc = 0.0f;
+          for (int e = 0; e < d; ++e) {
+            float a = (float)plco_half_to_double(act_k[abase + e]);
+            float c = (float)plco_half_to_double(cand_k[cbase + (int64_t)j * dm->cand_stride[4] + e]);
+            float diff = a - c;
+            acc = fmaf(diff, diff, acc);
+          }
+          D = (double)acc;
+        } else {
+          double acc = 0.0;
+          for (int e = 0; e < d; ++e) {
+            double a = plco_half_to_double(act_k[abase + e]);
+            double c = plco_half_to_double(cand_k[cbase + (int64_t)j * dm->cand_stride[4] + e]);
+            acc = acc + (a - c) * (a - c);
+          }
+          D = acc;
+        }
+        if (best_j < 0 ? (D == D) : (D < best)) {
+          best_j = j;
+          best = D;
+        }
+      }
+      double limit = (mode == PLCO_F32) ? (double)(max_mean_sq * (float)d)
+                                        : (double)max_mean_sq * (double)d;
+      if (best_j >= 0 && !(best <= limit)) best_j = -1;
+      chosen[(int64_t)s * n + i] = best_j;
+    }
+  return PLCO_OK;
+}
+
+/* Frequencies of the k + 1 index symbols of one position on the 2^12 scale:
+ * symbol j < k is "the token is candidate j", symbol k is "none of them" and
+ * owns the mass the k probabilities leave.  Boundaries are the floored, scaled
+ * running sums of the raw probabilities in single precision (c = c + p_j, j
+ * ascending), clipped at 4096; then every symbol that got nothing takes one
+ * unit from the currently largest (lowest index on ties), j ascending, so that
+ * each of the k + 1 symbols can be coded. */
+int plco_index_table(const float *p, int k, uint16_t *f) {
+  uint32_t fr[PLCO_MAX_K + 1];
+  uint32_t prev = 0;
+  float c = 0.0f;
+  int j;
+  if (k < 1 || k > PLCO_MAX_K) return PLCO_ERR_INVALID;
+  for (j = 0; j < k; ++j)
+    if (isnan(p[j]) || p[j] < 0.0f) return PLCO_ERR_INVALID;
+  for (j = 0; j < k; ++j) {
+    c = c + p[j];
+    float scaled = floorf(c * 4096.0f);
+    if (!(scaled < 4096.0f)) scaled = 4096.0f;
+    uint32_t b = (uint32_t)scaled;
+    fr[j] = b - prev;
+    prev = b;
+  }
+  fr[k] = RANS_SCALE - prev;
+  for (j = 0; j <= k; ++j) {
+    if (fr[j] == 0) {
+      int donor = 0, m;
+      for (m = 1; m <= k; ++m)
+        if (fr[m] > fr[donor]) donor = m;
+      fr[donor] -= 1;
+      fr[j] = 1;
+    }
+  }
+  for (j = 0; j <= k; ++j) f[j] = (uint16_t)fr[j];
+  return PLCO_OK;
+}
+
+/* The index stream of a session: one symbol per position (chosen, or k for
+ * -1), coded with the same 32-lane rANS as the residuals (position i in lane
+ * i mod 32, last position first, words in emission order), except that every
+ * position has its own table. */
+int plco_index_encode(const float *probs, const int32_t *chosen, int32_t S, int32_t n,
+                      int32_t k, uint32_t *states, uint16_t *words,
+                      const uint64_t *word_off, uint64_t word_cap, uint32_t *n_words) {
+  if (S < 0 || n < 1 || k < 1 || k > PLCO_MAX_K) return PLCO_ERR_INVALID;
+  for (int s = 0; s < S; ++s) {
+    uint32_t x[RANS_LANES];
+    uint16_t *out = words + word_off[s];
+    uint64_t nw = 0;
+    for (int lane = 0; lane < RANS_LANES; ++lane) x[lane] = RANS_LOW;
+    for (int i = n - 1; i >= 0; --i) {
+      int64_t row = (int64_t)s * n + i;
+      uint16_t f[PLCO_MAX_K + 1];
+      int rc = plco_index_table(probs + row * k, k, f);
+      if (rc) return rc;
+      int32_t j = chosen[row];
+      if (j < -1 || j >= k) return PLCO_ERR_INVALID;
+      int sym = j < 0 ? k : j;
+      uint32_t fs = f[sym], cs = 0;
+      for (int m = 0; m < sym; ++m) cs += f[m];
+      int lane = i % RANS_LANES;
+      if ((x[lane] >> 20) >= fs) {
+        if (nw >= word_cap) return PLCO_ERR_CAPACITY;
+        out[nw++] = (uint16_t)(x[lane] & 0xffffu);
+        x[lane] >>= 16;
+      }
+      x[lane] = (x[lane] / fs) * RANS_SCALE + (x[lane] % fs) + cs;
+    }
+    for (int lane = 0; lane < RANS_LANES; ++lane) states[(int64_t)s * RANS_LANES + lane] = x[lane];
+    n_words[s] = (uint32_t)nw;
+  }
+  return PLCO_OK;
+}
+
+int plco_index_decode(const float *probs, const uint32_t *states, const uint16_t *words,
+                      const uint64_t *word_off, const uint32_t *n_words, int32_t S,
+                      int32_t n, int32_t k, int32_t *chosen) {
+  if (S < 0 || n < 1 || k < 1 || k > PLCO_MAX_K) return PLCO_ERR_INVALID;
+  for (int s = 0; s < S; ++s) {
+    uint32_t x[RANS_LANES];
+    const uint16_t *in = words + word_off[s];
+    uint64_t ptr = n_words[s];
+    for (int lane = 0; lane < RANS_LANES; ++lane) x[lane] = states[(int64_t)s * RANS_LANES + lane];
+    for (int i = 0; i < n; ++i) {
+      int64_t row = (int64_t)s * n + i;
+      uint16_t f[PLCO_MAX_K + 1];
+      int rc = plco_index_table(probs + row * k, k, f);
+      if (rc) return rc;
+      int lane = i % RANS_LANES;
+      uint32_t slot = x[lane] & (RANS_SCALE - 1);
+      uint32_t cs = 0;
+      int sym = 0;
+      while (cs + f[sym] <= slot) { /* the symbol whose interval holds the slot */
+        cs += f[sym];
+        ++sym;
+      }
+      chosen[row] = sym == k ? -1 : sym;
+      x[lane] = (uint32_t)f[sym] * (x[lane] >> RANS_SCALE_BITS) + slot - cs;
+      if (x[lane] < RANS_LOW) {
+        if (ptr == 0) return PLCO_ERR_CORRUPT;
+        x[lane] = (x[lane] << 16) | in[--ptr];
+      }
+    }
+    if (ptr != 0) return PLCO_ERR_CORRUPT;
+    for (int lane = 0; lane < RANS_LANES; ++lane)
+      if (x[lane] != RANS_LOW) return PLCO_ERR_CORRUPT;
+  }
   return PLCO_OK;
 }

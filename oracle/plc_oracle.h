@@ -47,7 +47,13 @@
  * the synthetic workload; frequency tables match closed forms; rANS
  * round-trips on brute-force edge cases, matches a hand-worked example and
  * obeys the size law against the table's cross entropy.
- * Parity unpinned: the exact bit layout of the rANS stream is this format's
+ * Token-conditional functions: all positions marked "not a candidate" reduce
+ * to the functions above bit for bit; a chosen candidate equals the weighted
+ * mean under a one-hot row; noise-free actual vectors give all-zero residuals;
+ * symbol entropy matches the closed-form pmf of a quantised Gaussian; index
+ * tables match closed forms for dyadic rows; the index stream's length obeys
+ * the size law against the tokens' surprisal and a hand-worked example.
+ * Parity unpinned: the exact bit layout of the rANS streams is this format's
  * own definition, so agreement with any external coder is not sought.
  */
 #ifndef PLC_ORACLE_H
@@ -139,6 +145,54 @@ int plco_reconstruct(const plco_dims *dm, int mode,
                      const float *probs, const uint8_t *symbols,
                      const uint16_t *esc_vals, const uint64_t *esc_off,
                      uint16_t *out_k, uint16_t *out_v, double *pre_round_out);
+
+/* ---- Token-conditional coding (Lemma "KV determinism", Thm. "Sequential entropy bound") ----
+ * Given the token, the KV vector is determined; so when the true token is one
+ * of the k candidates the prediction is that candidate's vector and only the
+ * index has to be paid for, at about the token's surprisal.
+ *
+ * chosen: i32 [S,n]; j in [0,k) = the true token is candidate j (prediction =
+ * candidate j, exactly); -1 = not among the candidates (prediction = the
+ * weighted mean, as in plco_predict_residual).  Everything else as in the
+ * functions without the suffix. */
+#define PLCO_MAX_K 32
+
+int plco_predict_residual_cond(const plco_dims *dm, int mode,
+                               const uint16_t *cand_k, const uint16_t *cand_v,
+                               const float *probs, const int32_t *chosen,
+                               const uint16_t *act_k, const uint16_t *act_v,
+                               uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                               uint32_t *esc_cnt, uint64_t *esc_off,
+                               double *pred_out, double *u_out);
+
+int plco_reconstruct_cond(const plco_dims *dm, int mode,
+                          const uint16_t *cand_k, const uint16_t *cand_v,
+                          const float *probs, const int32_t *chosen,
+                          const uint8_t *symbols,
+                          const uint16_t *esc_vals, const uint64_t *esc_off,
+                          uint16_t *out_k, uint16_t *out_v, double *pre_round_out);
+
+/* Encoder-side recovery of `chosen` from the vectors alone: per (s, i), the
+ * candidate whose key row in layer 0, head 0 is nearest to the actual one in
+ * squared distance (components ascending; F32: diff in fp32, fused
+ * multiply-add accumulate); -1 if that distance exceeds max_mean_sq * d. */
+int plco_select_candidate(const plco_dims *dm, int mode, const uint16_t *cand_k,
+                          const uint16_t *act_k, float max_mean_sq, int32_t *chosen);
+
+/* Frequencies (sum 4096, all >= 1) of the k+1 index symbols of one position
+ * from its raw top-k probabilities; symbol k = "not among the candidates". */
+int plco_index_table(const float *p, int k, uint16_t *f);
+
+/* One 32-lane rANS unit per session over the n index symbols, each coded with
+ * its own position's table.  states: u32 [S,32]; session s writes
+ * words[word_off[s] .. +n_words[s]). */
+int plco_index_encode(const float *probs, const int32_t *chosen, int32_t S, int32_t n,
+                      int32_t k, uint32_t *states, uint16_t *words,
+                      const uint64_t *word_off, uint64_t word_cap, uint32_t *n_words);
+
+int plco_index_decode(const float *probs, const uint32_t *states, const uint16_t *words,
+                      const uint64_t *word_off, const uint32_t *n_words, int32_t S,
+                      int32_t n, int32_t k, int32_t *chosen);
 
 #ifdef __cplusplus
 }

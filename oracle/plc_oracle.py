@@ -86,6 +86,13 @@ def lib():
                                        C.c_uint64, p]
         L.plco_rans_decode.argtypes = [p, p, p, p, p, C.c_int64, C.c_int64, C.c_int32, p]
         L.plco_reconstruct.argtypes = [C.POINTER(Dims), C.c_int, p, p, p, p, p, p, p, p, p]
+        L.plco_predict_residual_cond.argtypes = [C.POINTER(Dims), C.c_int, p, p, p, p, p, p, p, p,
+                                                 C.c_uint64, p, p, p, p]
+        L.plco_reconstruct_cond.argtypes = [C.POINTER(Dims), C.c_int, p, p, p, p, p, p, p, p, p, p]
+        L.plco_select_candidate.argtypes = [C.POINTER(Dims), C.c_int, p, p, C.c_float, p]
+        L.plco_index_table.argtypes = [p, C.c_int, p]
+        L.plco_index_encode.argtypes = [p, p, C.c_int32, C.c_int32, C.c_int32, p, p, p, C.c_uint64, p]
+        L.plco_index_decode.argtypes = [p, p, p, p, p, C.c_int32, C.c_int32, C.c_int32, p]
         _lib = L
     return _lib
 
@@ -123,12 +130,17 @@ def weights(p, mode=F64):
     return w
 
 
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
 def predict_residual(dm: Dims, cand_k, cand_v, probs, act_k, act_v, mode=F64,
-                     want_pred=False, want_u=False, esc_cap=None):
+                     want_pred=False, want_u=False, esc_cap=None, chosen=None):
     """Returns dict(symbols [streams, N] u8, esc_vals u16, esc_cnt u32, esc_off u64, pred, u).
 
     cand_* / act_* are numpy arrays holding the tensors' storage (fp16 or u16);
     elements are addressed through dm's strides, so any layout works.
+    chosen (i32 [S,n], optional) selects the token-conditional variant.
     """
     ck, cv, ak, av = _u16(cand_k), _u16(cand_v), _u16(act_k), _u16(act_v)
     probs = np.ascontiguousarray(probs, dtype=np.float32)
@@ -143,9 +155,16 @@ def predict_residual(dm: Dims, cand_k, cand_v, probs, act_k, act_v, mode=F64,
     esc_off = np.zeros(n_streams, dtype=np.uint64)
     pred = np.empty((n_streams, N), dtype=np.float64) if want_pred else None
     u = np.empty((n_streams, N), dtype=np.float64) if want_u else None
-    rc = lib().plco_predict_residual(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs),
-                                     _ptr(ak), _ptr(av), _ptr(symbols), _ptr(esc_vals),
-                                     int(esc_cap), _ptr(esc_cnt), _ptr(esc_off), _ptr(pred), _ptr(u))
+    if chosen is None:
+        rc = lib().plco_predict_residual(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs),
+                                         _ptr(ak), _ptr(av), _ptr(symbols), _ptr(esc_vals),
+                                         int(esc_cap), _ptr(esc_cnt), _ptr(esc_off), _ptr(pred), _ptr(u))
+    else:
+        ch = _i32(chosen)
+        assert ch.size == dm.S * dm.n
+        rc = lib().plco_predict_residual_cond(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(ch),
+                                              _ptr(ak), _ptr(av), _ptr(symbols), _ptr(esc_vals),
+                                              int(esc_cap), _ptr(esc_cnt), _ptr(esc_off), _ptr(pred), _ptr(u))
     _check(rc, "predict_residual")
     total = int(esc_cnt.sum())
     return dict(symbols=symbols, esc_vals=esc_vals[:total].copy(), esc_cnt=esc_cnt,
@@ -207,7 +226,7 @@ def rans_decode(freq, states, words, word_off, n_words, n_streams, N, chunk_syms
 
 
 def reconstruct(dm: Dims, cand_k, cand_v, probs, symbols, esc_vals, esc_off, mode=F64,
-                want_pre_round=False, out_elems=None):
+                want_pre_round=False, out_elems=None, chosen=None):
     """Returns (out_k, out_v) as u16 bit-pattern arrays addressed through dm.act_stride."""
     ck, cv = _u16(cand_k), _u16(cand_v)
     probs = np.ascontiguousarray(probs, dtype=np.float32)
@@ -221,12 +240,66 @@ def reconstruct(dm: Dims, cand_k, cand_v, probs, symbols, esc_vals, esc_off, mod
     out_k = np.zeros(out_elems, dtype=np.uint16)
     out_v = np.zeros(out_elems, dtype=np.uint16)
     pre = np.empty(symbols.size, dtype=np.float64) if want_pre_round else None
-    rc = lib().plco_reconstruct(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(symbols),
-                                _ptr(esc_vals), _ptr(esc_off), _ptr(out_k), _ptr(out_v), _ptr(pre))
+    if chosen is None:
+        rc = lib().plco_reconstruct(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(symbols),
+                                    _ptr(esc_vals), _ptr(esc_off), _ptr(out_k), _ptr(out_v), _ptr(pre))
+    else:
+        ch = _i32(chosen)
+        assert ch.size == dm.S * dm.n
+        rc = lib().plco_reconstruct_cond(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(ch),
+                                         _ptr(symbols), _ptr(esc_vals), _ptr(esc_off), _ptr(out_k),
+                                         _ptr(out_v), _ptr(pre))
     _check(rc, "reconstruct")
     if want_pre_round:
         return out_k, out_v, pre.reshape(symbols.shape)
     return out_k, out_v
+
+
+def select_candidate(dm: Dims, cand_k, act_k, max_mean_sq, mode=F64):
+    """chosen i32 [S, n]: nearest candidate by the layer-0 / head-0 key row, -1 beyond the limit."""
+    ck, ak = _u16(cand_k), _u16(act_k)
+    chosen = np.empty((dm.S, dm.n), dtype=np.int32)
+    _check(lib().plco_select_candidate(C.byref(dm), mode, _ptr(ck), _ptr(ak), float(max_mean_sq),
+                                       _ptr(chosen)), "select_candidate")
+    return chosen
+
+
+def index_table(p):
+    """Frequencies u16 [k+1] of one position's index symbols (last = not among the candidates)."""
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    f = np.empty(p.shape[0] + 1, dtype=np.uint16)
+    _check(lib().plco_index_table(_ptr(p), p.shape[0], _ptr(f)), "index_table")
+    return f
+
+
+def index_encode(probs, chosen, word_cap=None):
+    """probs fp32 [S,n,k], chosen i32 [S,n] -> dict(states [S,32], words, word_off [S], n_words [S])."""
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    S, n, k = probs.shape
+    ch = _i32(chosen)
+    assert ch.shape == (S, n)
+    if word_cap is None:
+        word_cap = n
+    states = np.empty((S, 32), dtype=np.uint32)
+    words = np.zeros(max(S * word_cap, 1), dtype=np.uint16)
+    word_off = np.arange(S, dtype=np.uint64) * np.uint64(word_cap)
+    n_words = np.zeros(S, dtype=np.uint32)
+    _check(lib().plco_index_encode(_ptr(probs), _ptr(ch), S, n, k, _ptr(states), _ptr(words),
+                                   _ptr(word_off), int(word_cap), _ptr(n_words)), "index_encode")
+    return dict(states=states, words=words, word_off=word_off, n_words=n_words)
+
+
+def index_decode(probs, states, words, word_off, n_words):
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    S, n, k = probs.shape
+    states = np.ascontiguousarray(states, dtype=np.uint32)
+    words = np.ascontiguousarray(words, dtype=np.uint16)
+    word_off = np.ascontiguousarray(word_off, dtype=np.uint64)
+    n_words = np.ascontiguousarray(n_words, dtype=np.uint32)
+    chosen = np.empty((S, n), dtype=np.int32)
+    _check(lib().plco_index_decode(_ptr(probs), _ptr(states), _ptr(words), _ptr(word_off), _ptr(n_words),
+                                   S, n, k, _ptr(chosen)), "index_decode")
+    return chosen
 
 
 def coded_bits(n_words, esc_cnt, n_streams):

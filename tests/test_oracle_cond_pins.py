@@ -1,0 +1,297 @@
+"""Pins for the token-conditional part of the CPU oracle.
+
+Lemma "KV determinism" (Sec. 4.1): the KV vector is a function of the token
+prefix, so once the true token is known to be one of the k candidates its
+vector is the prediction and the residual is what noise is left; Thm.
+"Sequential entropy bound" (Sec. 4.2): what that knowledge costs is the token's
+surprisal.  The oracle is checked against the functions pinned in
+test_oracle_pins.py (special cases that must coincide), closed forms, a
+hand-worked example and brute force, never against itself or the device path.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+from scipy.stats import norm
+
+from paper_2604_15356_amd.workloads import make_workload
+from tests.test_oracle_pins import GOLDEN, _dims, _encode_floats, _np, _storage
+
+
+def _encode_cond(O, w, chosen, mode=None, **kw):
+    mode = O.F64 if mode is None else mode
+    return O.predict_residual(_dims(O, w), _storage(w.cand_k), _storage(w.cand_v), _np(w.probs),
+                              _storage(w.act_k), _storage(w.act_v), mode=mode, chosen=chosen, **kw)
+
+
+def _reconstruct(O, w, r, chosen=None, mode=None, **kw):
+    mode = O.F64 if mode is None else mode
+    return O.reconstruct(_dims(O, w), _storage(w.cand_k), _storage(w.cand_v), _np(w.probs), r["symbols"],
+                         r["esc_vals"], r["esc_off"], mode=mode, chosen=chosen, **kw)
+
+
+# --------------------------------------------------------------------------- prediction
+
+@pytest.mark.parametrize("mode_name", ["F64", "F32"])
+def test_all_misses_reduce_to_the_weighted_mean_path(oracle, mode_name):
+    mode = getattr(oracle, mode_name)
+    w = make_workload("tiny", overrides=dict(n=96), random_rows=True)
+    miss = np.full((w.S, w.n), -1, dtype=np.int32)
+    a = _encode_floats(oracle, w, mode=mode, want_pred=True)
+    b = _encode_cond(oracle, w, miss, mode=mode, want_pred=True)
+    for key in ("symbols", "esc_vals", "esc_cnt", "esc_off", "pred"):
+        assert np.array_equal(a[key], b[key]), key
+    ka, va = _reconstruct(oracle, w, a, mode=mode)
+    kb, vb = _reconstruct(oracle, w, b, chosen=miss, mode=mode)
+    assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+
+
+@pytest.mark.parametrize("layout", ["lhnkd", "lnkhd"])
+def test_chosen_candidate_equals_weighted_mean_under_a_one_hot_row(oracle, layout):
+    """With all probability on candidate j the weighted mean *is* candidate j; the conditional
+    path given j must produce the same prediction and symbols from any probabilities."""
+    w = make_workload("tiny", overrides=dict(n=80), layout=layout)
+    rng = np.random.default_rng(5)
+    pick = rng.integers(0, w.k, (w.S, w.n)).astype(np.int32)      # unrelated to the true candidate
+    one_hot = torch.zeros_like(w.probs).scatter_(2, torch.from_numpy(pick).long()[..., None], 1.0)
+    ref = oracle.predict_residual(_dims(oracle, w), _storage(w.cand_k), _storage(w.cand_v), _np(one_hot),
+                                  _storage(w.act_k), _storage(w.act_v), want_pred=True)
+    got = _encode_cond(oracle, w, pick, want_pred=True)
+    assert np.array_equal(ref["pred"], got["pred"])
+    assert np.array_equal(ref["symbols"], got["symbols"])
+    assert np.array_equal(ref["esc_vals"], got["esc_vals"])
+    # and the prediction is the candidate's stored value, exactly
+    cand = torch.stack([w.cand_k, w.cand_v], dim=4)               # [S,L,H,n,2,k,d]
+    idx = torch.from_numpy(pick).long()[:, None, None, :, None, None, None].expand(w.S, w.L, w.H, w.n, 2, 1, w.d)
+    want = cand.gather(5, idx).squeeze(5).double().reshape(w.n_streams, -1).numpy()
+    assert np.array_equal(got["pred"], want)
+
+
+def test_true_candidate_without_noise_codes_to_nothing(oracle):
+    """Given the token, nothing is left to say about the KV vector (Lemma KV determinism)."""
+    w = make_workload("tiny", overrides=dict(n=64, sigma=0.0))
+    r = _encode_cond(oracle, w, w.chosen.numpy())
+    assert (r["symbols"] == 127).all() and r["esc_cnt"].sum() == 0
+    freq, _ = oracle.build_freq(oracle.histogram(r["symbols"]))
+    enc = oracle.rans_encode(r["symbols"], freq)
+    assert (enc["n_words"] == 0).all() and (enc["states"] == 1 << 16).all()
+    ok, ov = _reconstruct(oracle, w, r, chosen=w.chosen.numpy())
+    assert np.array_equal(ok, _np(w.act_k).view(np.uint16).ravel())
+    assert np.array_equal(ov, _np(w.act_v).view(np.uint16).ravel())
+
+
+def test_invalid_index_is_rejected(oracle):
+    w = make_workload("tiny", overrides=dict(n=8, L=1, H=1))
+    for bad in (w.k, -2, 1000):
+        ch = w.chosen.numpy().astype(np.int32).copy()
+        ch[0, 3] = bad
+        with pytest.raises(oracle.OracleError):
+            _encode_cond(oracle, w, ch)
+
+
+@pytest.mark.parametrize("mode_name", ["F64", "F32"])
+def test_recovery_error_is_the_quantiser_error(oracle, mode_name):
+    """Prop. three-layer composition: recovered = prediction + quantised residual, so the
+    error is the quantiser's, at most Delta/2; with misses mixed in as well."""
+    mode = getattr(oracle, mode_name)
+    w = make_workload("tiny", overrides=dict(n=256))
+    ch = w.chosen.numpy().astype(np.int32).copy()
+    ch[0, ::7] = -1
+    r = _encode_cond(oracle, w, ch, mode=mode)
+    _, _, pre = _reconstruct(oracle, w, r, chosen=ch, mode=mode, want_pre_round=True)
+    act = torch.stack([w.act_k, w.act_v], dim=4).double().reshape(w.n_streams, -1).numpy()
+    keep = r["symbols"] != 255
+    err = np.abs(act - pre)[keep]
+    slack = 1e-5 if mode == oracle.F64 else 1e-3
+    assert err.max() <= w.delta / 2 * (1 + slack)
+    assert abs((err ** 2).mean() / (w.delta ** 2 / 12) - 1) < 0.02
+    assert np.array_equal(pre[~keep], act[~keep])
+
+
+@pytest.mark.parametrize("name", ["tiny", "llama8b", "70b"])
+def test_symbol_entropy_is_that_of_the_quantised_noise(oracle, name):
+    """Residual against the true candidate = the N(0, sigma^2) noise (plus fp16 rounding of
+    the stored vector), so the symbol pmf is a quantised Gaussian of sigma/Delta steps:
+    about log2(sigma/Delta * sqrt(2 pi e)) bits, half of what the weighted mean leaves."""
+    w = make_workload(name, overrides=dict(L=1, H=2, n=1024))
+    sd = float(w.sigma[0]) / float(np.float32(w.delta))
+    q = np.arange(-127, 128)
+    pmf = norm.cdf((q + 0.5) / sd) - norm.cdf((q - 0.5) / sd)
+    H = -(pmf[pmf > 0] * np.log2(pmf[pmf > 0])).sum()
+    assert abs(H - np.log2(sd * np.sqrt(2 * np.pi * np.e))) < 0.02      # fine-quantisation limit
+    r = _encode_cond(oracle, w, w.chosen.numpy())
+    counts = oracle.histogram(r["symbols"]).sum(0).astype(np.float64)
+    emp = counts / counts.sum()
+    H_emp = -(emp[emp > 0] * np.log2(emp[emp > 0])).sum()
+    assert abs(H_emp - H) < 0.02, (H_emp, H)
+    assert 0.5 * np.abs(emp[:255] - pmf).sum() < 0.01
+    assert r["esc_cnt"].sum() == 0
+    # against the weighted mean on the same data: less than half the bits
+    base = _encode_floats(oracle, w)
+    cb = oracle.histogram(base["symbols"]).sum(0).astype(np.float64)
+    eb = cb / cb.sum()
+    assert H_emp < 0.56 * -(eb[eb > 0] * np.log2(eb[eb > 0])).sum()
+
+
+# --------------------------------------------------------------------------- recovering the index
+
+@pytest.mark.parametrize("mode_name", ["F64", "F32"])
+def test_select_candidate_recovers_the_drawn_index(oracle, mode_name):
+    mode = getattr(oracle, mode_name)
+    w = make_workload("tiny", overrides=dict(n=200), layout="lnkhd")
+    limit = (4 * float(w.sigma[0])) ** 2
+    got = oracle.select_candidate(_dims(oracle, w), _storage(w.cand_k), _storage(w.act_k), limit, mode=mode)
+    assert np.array_equal(got, w.chosen.numpy())
+    # positions whose vector is none of the candidates are reported as misses
+    fresh = torch.randn((w.d,), generator=torch.Generator().manual_seed(3)).to(torch.float16)
+    w.act_k[0, 0, 0, 17] = fresh
+    w.act_k[0, 0, 0, 60] = float("nan")
+    got = oracle.select_candidate(_dims(oracle, w), _storage(w.cand_k), _storage(w.act_k), limit, mode=mode)
+    want = w.chosen.numpy().copy()
+    want[0, 17] = want[0, 60] = -1
+    assert np.array_equal(got, want)
+
+
+def test_select_candidate_brute_force_with_ties(oracle):
+    """Against numpy on small integers (every operation exact): nearest row, lowest index on
+    ties, and the limit is inclusive."""
+    rng = np.random.default_rng(11)
+    S, n, k, d = 1, 50, 5, 8
+    cand = rng.integers(-3, 4, (S, 1, 1, n, k, d)).astype(np.float16)
+    cand[..., 3, :] = cand[..., 1, :]                                  # candidates 1 and 3 coincide
+    act = rng.integers(-3, 4, (S, 1, 1, n, d)).astype(np.float16)
+    dm = oracle.make_dims(S, 1, 1, n, k, d, 0.02)
+    D = ((cand.astype(np.float64) - act[..., None, :].astype(np.float64)) ** 2).sum(-1)[0, 0, 0]    # [n, k]
+    for limit_total in (1000.0, 16.0, 8.0):
+        got = oracle.select_candidate(dm, cand, act, limit_total / d)
+        want = np.where(D.min(1) <= limit_total, D.argmin(1), -1)     # argmin: first minimum
+        assert np.array_equal(got[0], want)
+        assert (got[0] != 3).all()
+
+
+# --------------------------------------------------------------------------- index tables
+
+def test_index_table_closed_forms(oracle):
+    assert list(oracle.index_table([0.5, 0.25, 0.125])) == [2048, 1024, 512, 512]
+    assert list(oracle.index_table([0.5])) == [2048, 2048]
+    assert list(oracle.index_table([0.0, 0.0])) == [1, 1, 4094]            # zeros repaired from the largest
+    assert list(oracle.index_table([1.0])) == [4095, 1]                     # no mass left for a miss
+    assert list(oracle.index_table([0.5, 0.5])) == [2047, 2048, 1]          # donor: largest, lowest index
+    assert list(oracle.index_table([2.0, 1.0])) == [4094, 1, 1]             # mass above one is clipped
+    assert list(oracle.index_table([np.inf, 0.25])) == [4094, 1, 1]
+    f = oracle.index_table(np.full(32, 2.0 ** -5))
+    assert list(f[:32]) == [127] + [128] * 31 and f[32] == 1               # ties: lowest index gives
+    for bad in ([-0.1, 0.5], [np.nan, 0.5]):
+        with pytest.raises(oracle.OracleError):
+            oracle.index_table(bad)
+
+
+def test_index_table_invariants_on_random_rows(oracle):
+    rng = np.random.default_rng(2)
+    for trial in range(300):
+        k = int(rng.integers(1, 33))
+        p = rng.dirichlet(np.full(k + 1, 0.3))[:k].astype(np.float32)
+        if trial % 5 == 0:
+            p[rng.integers(0, k)] = 0.0
+        f = oracle.index_table(p).astype(np.int64)
+        assert f.sum() == 4096 and (f >= 1).all()
+        full = np.append(p.astype(np.float64), max(0.0, 1.0 - p.astype(np.float64).sum()))
+        # a scaled, floored interval is within one unit of its mass; repairs move a few more
+        assert np.abs(f - 4096 * full).max() < 1.01 + (f == 1).sum() + 4096 * k * 2.0 ** -24
+
+
+# --------------------------------------------------------------------------- index stream
+
+def _parse_index_example():
+    spec = {"row": {}, "table": {}}
+    with open(os.path.join(GOLDEN, "index_hand_example.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            key, *rest = line.split()
+            if key in ("row", "table"):
+                spec[key][rest[0]] = rest[1:]
+            else:
+                spec[key] = rest
+    return spec
+
+
+def _expand(items, n, cast):
+    out = [None] * n
+    for it in items:                       # generic entries first, specific ones override
+        where, v = it.split(":")
+        if where in ("even", "odd"):
+            for i in range(n):
+                if i % 2 == (where == "odd"):
+                    out[i] = cast(v)
+    for it in items:
+        where, v = it.split(":")
+        if where in ("even", "odd"):
+            continue
+        lo, _, hi = where.partition("-")
+        for i in range(int(lo), int(hi or lo) + 1):
+            out[i] = cast(v)
+    return out
+
+
+def test_index_stream_matches_hand_worked_example(oracle):
+    spec = _parse_index_example()
+    k, n = int(spec["k"][0]), int(spec["n"][0])
+    for name, row in spec["row"].items():
+        assert list(oracle.index_table([float(x) for x in row])) == [int(x) for x in spec["table"][name]]
+    names = _expand(spec["rows"], n, str)
+    probs = np.array([[float(x) for x in spec["row"][nm]] for nm in names], dtype=np.float32)[None]
+    chosen = np.array(_expand(spec["chosen"], n, int), dtype=np.int32)[None]
+    want_states = np.array(_expand(spec["state"], 32, int), dtype=np.uint32)
+    want_words = [int(x) for x in spec["words"]]
+    enc = oracle.index_encode(probs, chosen)
+    assert list(enc["states"][0]) == list(want_states)
+    assert int(enc["n_words"][0]) == len(want_words)
+    assert list(enc["words"][:len(want_words)]) == want_words
+    dec = oracle.index_decode(probs, want_states[None], np.array(want_words, dtype=np.uint16),
+                              np.zeros(1, dtype=np.uint64), np.array([len(want_words)], dtype=np.uint32))
+    assert np.array_equal(dec, chosen)
+
+
+@pytest.mark.parametrize("n", [1, 5, 31, 32, 33, 100, 1000])
+def test_index_round_trip_with_misses(oracle, n):
+    rng = np.random.default_rng(n)
+    S, k = 3, 6
+    probs = rng.dirichlet(np.full(k + 1, 0.5), (S, n))[..., :k].astype(np.float32)
+    chosen = rng.integers(-1, k, (S, n)).astype(np.int32)
+    enc = oracle.index_encode(probs, chosen)
+    dec = oracle.index_decode(probs, enc["states"], enc["words"], enc["word_off"], enc["n_words"])
+    assert np.array_equal(dec, chosen)
+    if n >= 100:
+        nw = int(enc["n_words"][0])
+        words = enc["words"].copy()
+        words[nw // 2] ^= 0x10
+        try:
+            bad = oracle.index_decode(probs, enc["states"], words, enc["word_off"], enc["n_words"])
+            assert not np.array_equal(bad, chosen)
+        except oracle.OracleError as e:
+            assert e.code == oracle.ERR_CORRUPT
+        with pytest.raises(oracle.OracleError):
+            oracle.index_encode(probs, chosen, word_cap=nw - 1)
+
+
+def test_index_stream_costs_the_tokens_surprisal(oracle):
+    """Thm. sequential entropy bound: a position costs at most the token's surprisal.  The
+    stream's length is the sum of log2(4096 / f) over the coded symbols up to what the 32 lane
+    states hold, and that sum is the surprisal -log2 p(token) up to the 12-bit table grain."""
+    w = make_workload("llama8b", overrides=dict(L=1, H=1, d=8, n=4096))
+    probs = _np(w.probs)
+    chosen = w.chosen.numpy().astype(np.int32)
+    enc = oracle.index_encode(probs, chosen)
+    f = oracle.index_table(probs[0, 0]).astype(np.float64)
+    X = np.log2(4096.0 / f[chosen[0]]).sum()
+    bits = 16.0 * enc["n_words"][0]
+    assert X - 512 <= bits <= 1.001 * X + 16
+    surprisal = -np.log2(probs[0, 0].astype(np.float64)[chosen[0]]).sum()
+    assert abs(X - surprisal) / w.n < 0.01
+    # population value for this Zipf row (perplexity 15, top 8 renormalised): sum_j w_j log2(1/p_j)
+    p = probs[0, 0].astype(np.float64)
+    expect = (p / p.sum() * -np.log2(p)).sum()
+    assert abs(surprisal / w.n - expect) < 0.1
+    assert 1.5 < (bits + 1024) / w.n < 3.0         # bits per token position, all layers and heads together
