@@ -198,6 +198,81 @@ int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v
                     void *ws, size_t ws_bytes, uint32_t *status, void *stream);
 
 /*
+ * ---- Token-conditional coding -------------------------------------------------
+ * Lemma "KV determinism" (Sec. 4.1): the KV vector of a position is a function
+ * of the token prefix.  So when the token that was actually produced is one of
+ * the k candidates, its candidate vector IS the prediction, the residual is
+ * only what numerical noise separates the two, and all that has to be stored
+ * besides is which candidate it was -- at a cost of the token's surprisal
+ * (Thm. "Sequential entropy bound", Sec. 4.2).  The calls below add that path
+ * next to the weighted-mean path above; histogram, table and rANS calls serve
+ * both.
+ *
+ *   chosen   i32 [S,n], one entry per (session, position), shared by every
+ *            layer, head, K and V:  j in [0,k) = the token is candidate j, the
+ *            prediction is cand_j itself (its fp16 values, exactly);  -1 = the
+ *            token is not among the candidates, the prediction is the weighted
+ *            mean exactly as in plc_predict_residual.  Any other value raises
+ *            status PLC_ERR_INVALID and is treated as -1.
+ * Everything else (arguments, layouts, escapes, workspace, status) is as in
+ * the call of the same name without the suffix.
+ */
+int plc_predict_residual_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                              const float *probs, const int32_t *chosen, const void *act_k,
+                              const void *act_v, uint8_t *symbols, uint16_t *esc_vals,
+                              uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off,
+                              float *pred_out, void *ws, size_t ws_bytes, uint32_t *status,
+                              void *stream);
+
+int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                         const float *probs, const int32_t *chosen, const uint8_t *symbols,
+                         const uint16_t *esc_vals, uint64_t esc_len, const uint64_t *esc_off,
+                         void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
+                         void *stream);
+
+/*
+ * `chosen` from the vectors alone, for an encoder that is not told the token:
+ * by the same lemma one row identifies it.  Per (s, i): D_j = sum_e (act[e] -
+ * cand_j[e])^2 over the key row of layer 0, head 0 (fp32; the difference, then
+ * a fused multiply-add accumulate, e ascending); chosen = the j with the
+ * smallest D_j (lowest j on ties; a NaN distance never wins), or -1 when that
+ * distance exceeds max_mean_sq * d or no distance compares.
+ *   cand_k, act_k  as in plc_predict_residual.   chosen  out, i32 [S,n].
+ */
+int plc_select_candidate(const plc_dims *dims, const void *cand_k, const void *act_k,
+                         float max_mean_sq, int32_t *chosen, void *stream);
+
+/*
+ * The index stream: `chosen` coded under the model's own probabilities, one
+ * 32-lane rANS unit per session (same coder as plc_rans_encode: position i in
+ * lane i mod 32, last position first, 16-bit words in emission order), with a
+ * table per position.  Position (s,i) has k+1 symbols, j < k for chosen = j
+ * and k for chosen = -1, with frequencies on the 2^12 scale made from the raw
+ * probabilities p = probs[s,i,:] in fp32:  c_0 = 0, c_{j+1} = c_j + p_j;
+ * b_j = min(4096, floor(4096 * c_j)) for j <= k, b_{k+1} = 4096;  f_j =
+ * b_{j+1} - b_j;  then, j ascending, every f_j = 0 takes one unit from the
+ * currently largest frequency (lowest index on ties).  The symbol k so owns
+ * the probability the top k leave, and a chosen candidate costs about
+ * -log2 p_j bits.  A row with a negative or NaN entry raises status
+ * PLC_ERR_INVALID (its bad entries count as 0).
+ *   probs     fp32 [S,n,k].   chosen  i32 [S,n] (values outside [-1,k): PLC_ERR_INVALID, coded as -1).
+ *   states    out, u32 [S,32].   words  out, u16: session s writes words[word_off[s] .. + n_words[s]);
+ *   word_cap  entries reserved per session (n always suffices); overflow raises PLC_ERR_CAPACITY
+ *             and nothing is written past the reservation.   n_words  out, u32 [S].
+ */
+int plc_index_encode(const float *probs, const int32_t *chosen, int32_t S, int32_t n, int32_t k,
+                     uint32_t *states, uint16_t *words, const uint64_t *word_off,
+                     uint64_t word_cap, uint32_t *n_words, uint32_t *status, void *stream);
+
+/* Inverse of plc_index_encode; same integrity rule as plc_rans_decode (all words used, all
+ * lanes back at 2^16, else PLC_ERR_CORRUPT); reads stay inside words[0 .. words_len).
+ *   chosen  out, i32 [S,n]. */
+int plc_index_decode(const float *probs, const uint32_t *states, const uint16_t *words,
+                     uint64_t words_len, const uint64_t *word_off, const uint32_t *n_words,
+                     int32_t S, int32_t n, int32_t k, int32_t *chosen, uint32_t *status,
+                     void *stream);
+
+/*
  * Instrumentation for benchmarks (not part of the coding path; process-wide,
  * not thread-safe).  While a pair of hipEvent_t (passed as void*) is set for
  * a kernel id, each later call records `start` immediately before and `stop`
@@ -209,7 +284,9 @@ int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v
 #define PLC_TRACE_HISTOGRAM 2
 #define PLC_TRACE_RANS_ENCODE 3
 #define PLC_TRACE_RANS_DECODE 4
-#define PLC_TRACE_COUNT 5
+#define PLC_TRACE_PREDICT_COND 5     /* main kernel of plc_predict_residual_cond */
+#define PLC_TRACE_RECONSTRUCT_COND 6 /* main kernel of plc_reconstruct_cond      */
+#define PLC_TRACE_COUNT 7
 int plc_trace_kernel_events(int kernel_id, void *start, void *stop);
 
 #ifdef __cplusplus

@@ -1,7 +1,12 @@
-"""Buffer management around the six libplc calls: allocate once, then encode
-and decode a KV cache of fixed shape any number of times.  Every step of the
+"""Buffer management around the libplc calls: allocate once, then encode and
+decode a KV cache of fixed shape any number of times.  Every step of the
 coding path runs inside libplc; this class only owns torch tensors and calls
-the entry points in order."""
+the entry points in order.
+
+Two paths share the buffers: the weighted-mean path (encode / decode) and the
+token-conditional path (encode_cond / decode_cond), which predicts every
+position from the candidate of its true token and codes that candidate's index
+in a stream of its own."""
 from __future__ import annotations
 
 import dataclasses
@@ -25,6 +30,12 @@ class Coded:
     words: torch.Tensor      # i16 [units * word_cap]
     word_off: torch.Tensor   # i64 [units]
     n_words: torch.Tensor    # i32 [units]
+    # token-conditional path only
+    chosen: torch.Tensor = None         # i32 [S, n] as used by the encoder
+    idx_states: torch.Tensor = None     # i32 [S, 32]
+    idx_words: torch.Tensor = None      # i16 [S * idx_word_cap]
+    idx_word_off: torch.Tensor = None   # i64 [S]
+    idx_n_words: torch.Tensor = None    # i32 [S]
 
 
 class KVDeltaCodec:
@@ -64,6 +75,14 @@ class KVDeltaCodec:
         self.pred = (torch.empty((self.n_streams, self.N), dtype=torch.float32, device=dev)
                      if want_pred else None)
         self.dec_symbols = torch.empty_like(self.symbols)
+        # index stream of the token-conditional path: at most one word per position
+        self.idx_word_cap = (n + 7) // 8 * 8
+        self.chosen = torch.empty((S, n), dtype=torch.int32, device=dev)
+        self.dec_chosen = torch.empty_like(self.chosen)
+        self.idx_states = torch.empty((S, 32), dtype=torch.int32, device=dev)
+        self.idx_words = torch.empty(S * self.idx_word_cap, dtype=torch.int16, device=dev)
+        self.idx_word_off = torch.arange(S, dtype=torch.int64, device=dev) * self.idx_word_cap
+        self.idx_n_words = torch.empty(S, dtype=torch.int32, device=dev)
 
     # -- single steps -------------------------------------------------------------------
     def predict_residual(self, cand_k, cand_v, probs, act_k, act_v):
@@ -105,7 +124,42 @@ class KVDeltaCodec:
         self.rans_decode()
         self.reconstruct(cand_k, cand_v, probs, out_k, out_v)
 
-    def coded(self) -> Coded:
+    # -- token-conditional path ----------------------------------------------------------
+    def select_candidate(self, cand_k, act_k, max_mean_sq):
+        plc.plc_select_candidate(self.dims, cand_k, act_k, max_mean_sq, self.chosen)
+        return self.chosen
+
+    def encode_cond(self, cand_k, cand_v, probs, act_k, act_v, chosen=None, max_mean_sq=None) -> Coded:
+        """chosen: int32 [S,n] on the device, or None to recover it from the vectors (max_mean_sq =
+        largest mean squared distance per component at which a candidate still counts as the token)."""
+        if chosen is None:
+            if max_mean_sq is None:
+                raise ValueError("either chosen or max_mean_sq is needed")
+            self.select_candidate(cand_k, act_k, max_mean_sq)
+        elif chosen is not self.chosen:
+            self.chosen.copy_(chosen)
+        plc.plc_predict_residual_cond(self.dims, cand_k, cand_v, probs, self.chosen, act_k, act_v,
+                                      self.symbols, self.esc_vals, self.esc_cnt, self.esc_off, self.ws,
+                                      self.status, pred_out=self.pred)
+        self.histogram()
+        self.build_freq()
+        self.rans_encode()
+        plc.plc_index_encode(probs, self.chosen, self.S, self.n, self.k, self.idx_states, self.idx_words,
+                             self.idx_word_off, self.idx_word_cap, self.idx_n_words, self.status)
+        return self.coded(cond=True)
+
+    def decode_cond(self, cand_k, cand_v, probs, out_k, out_v):
+        plc.plc_index_decode(probs, self.idx_states, self.idx_words, self.idx_word_off, self.idx_n_words,
+                             self.S, self.n, self.k, self.dec_chosen, self.status)
+        self.rans_decode()
+        plc.plc_reconstruct_cond(self.dims, cand_k, cand_v, probs, self.dec_chosen, self.dec_symbols,
+                                 self.esc_vals, self.esc_off, out_k, out_v, self.ws, self.status)
+
+    def coded(self, cond=False) -> Coded:
+        if cond:
+            return Coded(self.symbols, self.esc_vals, self.esc_cnt, self.esc_off, self.counts, self.freq,
+                         self.cum, self.states, self.words, self.word_off, self.n_words, self.chosen,
+                         self.idx_states, self.idx_words, self.idx_word_off, self.idx_n_words)
         return Coded(self.symbols, self.esc_vals, self.esc_cnt, self.esc_off, self.counts, self.freq,
                      self.cum, self.states, self.words, self.word_off, self.n_words)
 

@@ -1,0 +1,191 @@
+// The index stream of token-conditional coding: which of the k candidates the true token was (or
+// that it was none of them), one symbol per position, coded under the model's own probabilities so
+// that a position costs about the token's surprisal (Thm. "Sequential entropy bound", Sec. 4.2).
+// See include/plc.h for the format.
+//
+// The stream is tiny next to the residuals (one symbol per position against 2*L*H*d of them), so
+// these kernels are written for clarity: one wavefront per session, lanes 0..31 are the 32 rANS
+// lanes, every lane builds the table of its own position in registers / private memory, and words go
+// straight to global memory at positions ranked from the emission mask.
+#include "plc_device.h"
+
+namespace plc {
+namespace {
+
+constexpr int kLanes = PLC_RANS_LANES;
+constexpr uint32_t kScale = PLC_RANS_SCALE;
+constexpr uint32_t kLow = 1u << 16;
+constexpr int kMaxK = 32;
+
+// Frequencies of the k + 1 index symbols of one probability row; returns false for an invalid row
+// (its negative / NaN entries are taken as 0, so the table is usable either way).
+__device__ bool index_table(const float *__restrict__ p, int k, uint32_t f[kMaxK + 1]) {
+  bool ok = true;
+  float c = 0.0f;
+  uint32_t prev = 0;
+  for (int j = 0; j < k; ++j) {
+    float pj = p[j];
+    if (!(pj >= 0.0f)) {
+      ok = false;
+      pj = 0.0f;
+    }
+    c = c + pj;
+    float scaled = __builtin_floorf(c * 4096.0f);
+    if (!(scaled < 4096.0f)) scaled = 4096.0f;  // probability above one (or an overflow) is clipped
+    const uint32_t b = (uint32_t)scaled;
+    f[j] = b - prev;
+    prev = b;
+  }
+  f[k] = kScale - prev;
+  for (int j = 0; j <= k; ++j) {
+    if (f[j] == 0) {
+      int donor = 0;
+      for (int m = 1; m <= k; ++m)
+        if (f[m] > f[donor]) donor = m;
+      f[donor] -= 1;
+      f[j] = 1;
+    }
+  }
+  return ok;
+}
+
+__global__ __launch_bounds__(64) void index_encode_kernel(const float *__restrict__ probs,
+                                                          const int32_t *__restrict__ chosen, int n, int k,
+                                                          uint32_t *__restrict__ states, uint16_t *__restrict__ words,
+                                                          const uint64_t *__restrict__ word_off, uint64_t word_cap,
+                                                          uint32_t *__restrict__ n_words, uint32_t *status) {
+  const int s = blockIdx.x;
+  const int lane = threadIdx.x;
+  const bool rans_lane = lane < kLanes;
+  uint16_t *out = words + word_off[s];
+  uint32_t x = kLow;
+  uint64_t nw = 0;  // uniform
+  const int groups = (n + kLanes - 1) / kLanes;
+  for (int g = groups - 1; g >= 0; --g) {
+    const int i = g * kLanes + lane;
+    const bool has = rans_lane && i < n;
+    uint32_t fs = 1, cs = 0;
+    if (has) {
+      const int64_t row = (int64_t)s * n + i;
+      uint32_t f[kMaxK + 1];
+      if (!index_table(probs + row * k, k, f)) raise(status, PLC_ERR_INVALID);
+      int j = chosen[row];
+      if (j < -1 || j >= k) {
+        raise(status, PLC_ERR_INVALID);
+        j = -1;
+      }
+      const int sym = j < 0 ? k : j;
+      for (int m = 0; m < sym; ++m) cs += f[m];
+      fs = f[sym];
+    }
+    // The sequential definition visits lane 31 first: a lane's word comes after those of the
+    // emitting lanes above it.
+    const bool emit = has && (x >> 20) >= fs;
+    const uint32_t mask = (uint32_t)__ballot(emit);
+    if (emit) {
+      const uint32_t above = lane == 31 ? 0u : mask >> (lane + 1);
+      const uint64_t pos = nw + (uint32_t)__builtin_popcount(above);
+      if (pos < word_cap) {
+        out[pos] = (uint16_t)(x & 0xffffu);
+      } else {
+        raise(status, PLC_ERR_CAPACITY);
+      }
+      x >>= 16;
+    }
+    nw += (uint32_t)__builtin_popcount(mask);
+    if (has) x = (x / fs) * kScale + (x % fs) + cs;
+  }
+  if (rans_lane) states[(int64_t)s * kLanes + lane] = x;
+  if (lane == 0) n_words[s] = (uint32_t)(nw < word_cap ? nw : word_cap);
+}
+
+__global__ __launch_bounds__(64) void index_decode_kernel(const float *__restrict__ probs,
+                                                          const uint32_t *__restrict__ states,
+                                                          const uint16_t *__restrict__ words, uint64_t words_len,
+                                                          const uint64_t *__restrict__ word_off,
+                                                          const uint32_t *__restrict__ n_words, int n, int k,
+                                                          int32_t *__restrict__ chosen, uint32_t *status) {
+  const int s = blockIdx.x;
+  const int lane = threadIdx.x;
+  const bool rans_lane = lane < kLanes;
+  const uint64_t base = word_off[s];
+  uint64_t ptr = n_words[s];  // uniform
+  bool corrupt = base > words_len || ptr > words_len - base;
+  if (corrupt) ptr = 0;
+  uint32_t x = rans_lane ? states[(int64_t)s * kLanes + lane] : kLow;
+  const int groups = (n + kLanes - 1) / kLanes;
+  for (int g = 0; g < groups; ++g) {
+    const int i = g * kLanes + lane;
+    const bool has = rans_lane && i < n;
+    if (has) {
+      const int64_t row = (int64_t)s * n + i;
+      uint32_t f[kMaxK + 1];
+      if (!index_table(probs + row * k, k, f)) raise(status, PLC_ERR_INVALID);
+      const uint32_t slot = x & (kScale - 1);
+      uint32_t cs = 0;
+      int sym = 0;
+      while (sym < k && cs + f[sym] <= slot) {  // the symbol whose interval holds the slot
+        cs += f[sym];
+        ++sym;
+      }
+      chosen[row] = sym == k ? -1 : sym;
+      x = f[sym] * (x >> 12) + slot - cs;
+    }
+    // Reading lanes are served from the end of the list, lane 0 first.
+    const bool need = has && x < kLow;
+    const uint32_t mask = (uint32_t)__ballot(need);
+    if (need) {
+      const uint32_t below = mask & ((1u << lane) - 1u);
+      const uint64_t rank = (uint32_t)__builtin_popcount(below);
+      uint32_t word = 0;
+      if (rank < ptr) {
+        word = words[base + ptr - 1 - rank];
+      } else {
+        corrupt = true;
+      }
+      x = (x << 16) | word;
+    }
+    const uint32_t used = (uint32_t)__builtin_popcount(mask);
+    ptr = used < ptr ? ptr - used : 0;
+  }
+  if (ptr != 0 || (rans_lane && x != kLow)) corrupt = true;
+  if (corrupt) raise(status, PLC_ERR_CORRUPT);
+}
+
+int check(const float *probs, int32_t S, int32_t n, int32_t k, const void *states, const void *word_off,
+          const void *n_words, const void *chosen, const void *status) {
+  if (S < 1 || n < 1 || k < 1 || k > kMaxK) return PLC_ERR_INVALID;
+  if (!probs || !states || !word_off || !n_words || !chosen || !status) return PLC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(probs) % 4 || reinterpret_cast<uintptr_t>(states) % 4 ||
+      reinterpret_cast<uintptr_t>(word_off) % 8 || reinterpret_cast<uintptr_t>(n_words) % 4 ||
+      reinterpret_cast<uintptr_t>(chosen) % 4 || reinterpret_cast<uintptr_t>(status) % 4)
+    return PLC_ERR_INVALID;
+  return PLC_OK;
+}
+
+}  // namespace
+}  // namespace plc
+
+using namespace plc;
+
+extern "C" int plc_index_encode(const float *probs, const int32_t *chosen, int32_t S, int32_t n, int32_t k,
+                                uint32_t *states, uint16_t *words, const uint64_t *word_off, uint64_t word_cap,
+                                uint32_t *n_words, uint32_t *status, void *stream) {
+  const int rc = check(probs, S, n, k, states, word_off, n_words, chosen, status);
+  if (rc) return rc;
+  if ((word_cap > 0 && !words) || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
+  hipLaunchKernelGGL(index_encode_kernel, dim3((unsigned)S), dim3(64), 0, static_cast<hipStream_t>(stream), probs,
+                     chosen, n, k, states, words, word_off, word_cap, n_words, status);
+  return launch_status();
+}
+
+extern "C" int plc_index_decode(const float *probs, const uint32_t *states, const uint16_t *words,
+                                uint64_t words_len, const uint64_t *word_off, const uint32_t *n_words, int32_t S,
+                                int32_t n, int32_t k, int32_t *chosen, uint32_t *status, void *stream) {
+  const int rc = check(probs, S, n, k, states, word_off, n_words, chosen, status);
+  if (rc) return rc;
+  if ((words_len > 0 && !words) || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
+  hipLaunchKernelGGL(index_decode_kernel, dim3((unsigned)S), dim3(64), 0, static_cast<hipStream_t>(stream), probs,
+                     states, words, words_len, word_off, n_words, n, k, chosen, status);
+  return launch_status();
+}

@@ -27,6 +27,7 @@ struct CodecArgs {
   const uint16_t *act_k, *act_v;  // encode only
   uint16_t *out_k, *out_v;        // decode only
   const float *weights;           // [S, n, k] renormalised weights
+  const int32_t *chosen;          // [S, n] index of the true candidate or -1 (token-conditional calls only)
   uint8_t *symbols;               // encode: out, decode: in
   const uint16_t *esc_in;         // decode
   uint64_t esc_len;               // decode
@@ -49,6 +50,7 @@ struct Coord {
   int64_t cand;  // element offset of candidate 0, component 0 of the chunk
   int64_t act;   // element offset in act / out
   int64_t w;     // offset of the weight row
+  int64_t row;   // s * n + i, the position's entry in per-position arrays
   int64_t sym;   // offset in symbols / pred_out
   int c;         // 0 = K, 1 = V
   uint32_t stream, tile;
@@ -71,7 +73,8 @@ __device__ __forceinline__ Coord locate_chunk(const CodecArgs &a, uint32_t strea
   q.c = row & 1;
   q.cand = s * a.cs[0] + l * a.cs[1] + h * a.cs[2] + (int64_t)i * a.cs[3] + e8 * kChunk;
   q.act = s * a.as[0] + l * a.as[1] + h * a.as[2] + (int64_t)i * a.as[3] + e8 * kChunk;
-  q.w = ((int64_t)s * a.n + i) * a.k;
+  q.row = (int64_t)s * a.n + i;
+  q.w = q.row * a.k;
   q.sym = (int64_t)q.stream * a.syms_per_stream + (int64_t)chunk * kChunk;
   return q;
 }
@@ -125,6 +128,27 @@ __device__ __forceinline__ void predict8(const uint16_t *cand, int64_t sj, const
   }
 }
 
+// The prediction of one chunk.  COND: the position names its true candidate, whose vector then is the
+// prediction (Lemma "KV determinism"); -1 falls back to the weighted mean.
+template <int K, bool COND>
+__device__ __forceinline__ void predict_chunk(const CodecArgs &a, const Coord &q, const uint16_t *cand,
+                                              float pred[kChunk]) {
+  if constexpr (COND) {
+    int pick = a.chosen[q.row];
+    if (pick < -1 || pick >= a.k) {
+      raise(a.status, PLC_ERR_INVALID);
+      pick = -1;
+    }
+    if (pick >= 0) {
+      const half8 c = __builtin_bit_cast(half8, load16_stream(cand + pick * a.cs[4]));
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) pred[e] = (float)c[e];
+      return;
+    }
+  }
+  predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
+}
+
 // ---------------------------------------------------------------------------
 // w[s,i,j] = p[s,i,j] / sum_m p[s,i,m]   (one thread per probability row)
 // ---------------------------------------------------------------------------
@@ -148,7 +172,7 @@ __global__ __launch_bounds__(kBlock) void weights_kernel(const float *__restrict
 // ---------------------------------------------------------------------------
 // Encode: symbols and per-tile escape counts
 // ---------------------------------------------------------------------------
-template <int K>
+template <int K, bool COND>
 __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArgs a) {
   __shared__ uint32_t wave_cnt[kBlock / 64];
   const Coord q = locate(a);
@@ -163,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArg
     raw[2] = av.z;
     raw[3] = av.w;
     float pred[kChunk];
-    predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
+    predict_chunk<K, COND>(a, q, cand, pred);
     const half8 x = __builtin_bit_cast(half8, av);
     uint32_t packed[2] = {0u, 0u};
 #pragma unroll
@@ -313,7 +337,7 @@ __global__ __launch_bounds__(kBlock) void compact_escapes_kernel(const CodecArgs
 // ---------------------------------------------------------------------------
 // Decode: prediction again, plus the dequantised residual
 // ---------------------------------------------------------------------------
-template <int K>
+template <int K, bool COND>
 __global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) {
   __shared__ uint32_t smem[8];
   const Coord q = locate(a);
@@ -325,13 +349,18 @@ __global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) 
     const uint16_t *cand = (q.c ? a.cand_v : a.cand_k) + q.cand;
     sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
     float pred[kChunk];
-    predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
+    predict_chunk<K, COND>(a, q, cand, pred);
 #pragma unroll
     for (int e = 0; e < kChunk; ++e) {
       const uint32_t sym = ((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u;
       n_esc += sym == PLC_ESCAPE;
       const float qf = (float)((int)sym - (int)kZeroSymbol);
-      out[e] = (_Float16)__builtin_fmaf(qf, a.delta, pred[e]);  // fp32 -> fp16, nearest even
+      float v = __builtin_fmaf(qf, a.delta, pred[e]);
+      // Two roundings are the contract: to fp32 here, then to fp16 (nearest even).  Left to itself the
+      // compiler may merge both into one fused multiply-add with an fp16 result, which rounds once and
+      // lands on the other neighbour when the fp32 value is an exact fp16 tie.
+      asm("" : "+v"(v));
+      out[e] = (_Float16)v;
     }
   }
   if (tile_has_escapes) {
@@ -436,15 +465,52 @@ void dispatch_k(int k, const CodecArgs &a, unsigned grid, hipStream_t st) {
 template <int K>
 struct LaunchPredict {
   static void run(const CodecArgs &a, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL(predict_residual_kernel<K>, dim3(grid), dim3(kBlock), 0, st, a);
+    if (a.chosen) {
+      hipLaunchKernelGGL((predict_residual_kernel<K, true>), dim3(grid), dim3(kBlock), 0, st, a);
+    } else {
+      hipLaunchKernelGGL((predict_residual_kernel<K, false>), dim3(grid), dim3(kBlock), 0, st, a);
+    }
   }
 };
 template <int K>
 struct LaunchReconstruct {
   static void run(const CodecArgs &a, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL(reconstruct_kernel<K>, dim3(grid), dim3(kBlock), 0, st, a);
+    if (a.chosen) {
+      hipLaunchKernelGGL((reconstruct_kernel<K, true>), dim3(grid), dim3(kBlock), 0, st, a);
+    } else {
+      hipLaunchKernelGGL((reconstruct_kernel<K, false>), dim3(grid), dim3(kBlock), 0, st, a);
+    }
   }
 };
+
+// Nearest candidate of every position by the key row of layer 0, head 0; one thread per position.
+__global__ __launch_bounds__(kBlock) void select_candidate_kernel(const uint16_t *__restrict__ cand_k,
+                                                                  const uint16_t *__restrict__ act_k, int64_t rows,
+                                                                  int n, int k, int d, int64_t cs_s, int64_t cs_i,
+                                                                  int64_t cs_j, int64_t as_s, int64_t as_i,
+                                                                  float limit, int32_t *__restrict__ chosen) {
+  const int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (row >= rows) return;
+  const int64_t s = row / n, i = row - s * n;
+  const _Float16 *act = reinterpret_cast<const _Float16 *>(act_k) + s * as_s + i * as_i;
+  const _Float16 *cand = reinterpret_cast<const _Float16 *>(cand_k) + s * cs_s + i * cs_i;
+  int best_j = -1;
+  float best = 0.0f;
+  for (int j = 0; j < k; ++j) {
+    const _Float16 *c = cand + j * cs_j;
+    float acc = 0.0f;
+    for (int e = 0; e < d; ++e) {
+      const float diff = (float)act[e] - (float)c[e];
+      acc = __builtin_fmaf(diff, diff, acc);
+    }
+    if (best_j < 0 ? (acc == acc) : (acc < best)) {
+      best_j = j;
+      best = acc;
+    }
+  }
+  if (best_j >= 0 && !(best <= limit)) best_j = -1;
+  chosen[row] = best_j;
+}
 
 }  // namespace
 }  // namespace plc
@@ -456,11 +522,13 @@ extern "C" size_t plc_workspace_bytes(const plc_dims *dims) {
   return make_plan(dims, &p) ? p.total : 0;
 }
 
-extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, const void *cand_v,
-                                    const float *probs, const void *act_k, const void *act_v,
-                                    uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
-                                    uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out, void *ws,
-                                    size_t ws_bytes, uint32_t *status, void *stream) {
+namespace plc {
+namespace {
+
+int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
+                  const int32_t *chosen, int trace_id, const void *act_k, const void *act_v, uint8_t *symbols,
+                  uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
+                  void *ws, size_t ws_bytes, uint32_t *status, void *stream) {
   Plan p;
   if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
   if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(act_k, 16) || !aligned(act_v, 16))
@@ -481,13 +549,14 @@ extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, co
   a.symbols = symbols;
   a.pred_out = pred_out;
   a.status = status;
+  a.chosen = chosen;
   float *weights = const_cast<float *>(a.weights);
   uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
 
   hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
                      weights, p.rows, dims->k, status);
   {
-    TraceScope trace(PLC_TRACE_PREDICT, st);
+    TraceScope trace(trace_id, st);
     dispatch_k<LaunchPredict>(dims->k, a, (unsigned)p.n_tiles, st);
   }
   hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
@@ -499,10 +568,10 @@ extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, co
   return launch_status();
 }
 
-extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
-                               const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
-                               const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
-                               uint32_t *status, void *stream) {
+int decode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
+                  const int32_t *chosen, int trace_id, const uint8_t *symbols, const uint16_t *esc_vals,
+                  uint64_t esc_len, const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
+                  uint32_t *status, void *stream) {
   Plan p;
   if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
   if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(out_k, 16) || !aligned(out_v, 16))
@@ -523,6 +592,7 @@ extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const v
   a.esc_len = esc_len;
   a.esc_off = esc_off;
   a.status = status;
+  a.chosen = chosen;
   float *weights = const_cast<float *>(a.weights);
   uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
 
@@ -532,8 +602,62 @@ extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const v
   hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
                      (uint32_t)p.tiles_per_stream, (uint32_t *)nullptr);
   {
-    TraceScope trace(PLC_TRACE_RECONSTRUCT, st);
+    TraceScope trace(trace_id, st);
     dispatch_k<LaunchReconstruct>(dims->k, a, (unsigned)p.n_tiles, st);
   }
+  return launch_status();
+}
+
+}  // namespace
+}  // namespace plc
+
+extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                    const float *probs, const void *act_k, const void *act_v,
+                                    uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                                    uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out, void *ws,
+                                    size_t ws_bytes, uint32_t *status, void *stream) {
+  return encode_floats(dims, cand_k, cand_v, probs, nullptr, PLC_TRACE_PREDICT, act_k, act_v, symbols, esc_vals,
+                       esc_cap, esc_cnt, esc_off, pred_out, ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_predict_residual_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                         const float *probs, const int32_t *chosen, const void *act_k,
+                                         const void *act_v, uint8_t *symbols, uint16_t *esc_vals,
+                                         uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
+                                         void *ws, size_t ws_bytes, uint32_t *status, void *stream) {
+  if (!aligned(chosen, 4)) return PLC_ERR_INVALID;
+  return encode_floats(dims, cand_k, cand_v, probs, chosen, PLC_TRACE_PREDICT_COND, act_k, act_v, symbols,
+                       esc_vals, esc_cap, esc_cnt, esc_off, pred_out, ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
+                               const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
+                               const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
+                               uint32_t *status, void *stream) {
+  return decode_floats(dims, cand_k, cand_v, probs, nullptr, PLC_TRACE_RECONSTRUCT, symbols, esc_vals, esc_len,
+                       esc_off, out_k, out_v, ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                    const float *probs, const int32_t *chosen, const uint8_t *symbols,
+                                    const uint16_t *esc_vals, uint64_t esc_len, const uint64_t *esc_off,
+                                    void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
+                                    void *stream) {
+  if (!aligned(chosen, 4)) return PLC_ERR_INVALID;
+  return decode_floats(dims, cand_k, cand_v, probs, chosen, PLC_TRACE_RECONSTRUCT_COND, symbols, esc_vals,
+                       esc_len, esc_off, out_k, out_v, ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_select_candidate(const plc_dims *dims, const void *cand_k, const void *act_k,
+                                    float max_mean_sq, int32_t *chosen, void *stream) {
+  Plan p;
+  if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  if (!aligned(cand_k, 16) || !aligned(act_k, 16) || !aligned(chosen, 4)) return PLC_ERR_INVALID;
+  if (!(max_mean_sq >= 0.0f)) return PLC_ERR_INVALID;
+  hipLaunchKernelGGL(select_candidate_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint16_t *>(cand_k),
+                     static_cast<const uint16_t *>(act_k), p.rows, dims->n, dims->k, dims->d, dims->cand_stride[0],
+                     dims->cand_stride[3], dims->cand_stride[4], dims->act_stride[0], dims->act_stride[3],
+                     max_mean_sq * (float)dims->d, chosen);
   return launch_status();
 }

@@ -21,9 +21,12 @@ PLC_ESCAPE = 255
 
 EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_stream",
            "plc_predict_residual", "plc_histogram", "plc_build_freq", "plc_rans_encode",
-           "plc_rans_decode", "plc_reconstruct", "plc_trace_kernel_events")
+           "plc_rans_decode", "plc_reconstruct", "plc_trace_kernel_events",
+           "plc_predict_residual_cond", "plc_reconstruct_cond", "plc_select_candidate",
+           "plc_index_encode", "plc_index_decode")
 
-TRACE_PREDICT, TRACE_RECONSTRUCT, TRACE_HISTOGRAM, TRACE_RANS_ENCODE, TRACE_RANS_DECODE = range(5)
+(TRACE_PREDICT, TRACE_RECONSTRUCT, TRACE_HISTOGRAM, TRACE_RANS_ENCODE, TRACE_RANS_DECODE,
+ TRACE_PREDICT_COND, TRACE_RECONSTRUCT_COND) = range(7)
 
 
 class PlcError(RuntimeError):
@@ -65,6 +68,11 @@ def lib() -> C.CDLL:
         L.plc_rans_decode.argtypes = [p, p, p, u64, p, p, i64, i64, i32, p, p, p]
         L.plc_reconstruct.argtypes = [dp, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
         L.plc_trace_kernel_events.argtypes = [C.c_int, p, p]
+        L.plc_predict_residual_cond.argtypes = [dp, p, p, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_reconstruct_cond.argtypes = [dp, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_select_candidate.argtypes = [dp, p, p, C.c_float, p, p]
+        L.plc_index_encode.argtypes = [p, p, i32, i32, i32, p, p, p, u64, p, p, p]
+        L.plc_index_decode.argtypes = [p, p, p, u64, p, p, i32, i32, i32, p, p, p]
         _lib = L
     return _lib
 
@@ -179,6 +187,52 @@ def plc_reconstruct(dims, cand_k, cand_v, probs, symbols, esc_vals, esc_off, out
         _ptr(out_v, torch.float16), _contig(ws, torch.uint8), ws.numel(),
         _contig(status, torch.int32), _stream())
     _check(rc, "plc_reconstruct")
+
+
+def plc_predict_residual_cond(dims, cand_k, cand_v, probs, chosen, act_k, act_v, symbols, esc_vals,
+                              esc_cnt, esc_off, ws, status, pred_out=None):
+    """As plc_predict_residual, with chosen int32 [S,n] (candidate index of the true token, -1 = none)."""
+    rc = lib().plc_predict_residual_cond(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _contig(chosen, torch.int32), _ptr(act_k, torch.float16),
+        _ptr(act_v, torch.float16), _contig(symbols, torch.uint8), _contig(esc_vals, None),
+        esc_vals.numel(), _contig(esc_cnt, torch.int32), _contig(esc_off, torch.int64),
+        _contig(pred_out, torch.float32), _contig(ws, torch.uint8), ws.numel(),
+        _contig(status, torch.int32), _stream())
+    _check(rc, "plc_predict_residual_cond")
+
+
+def plc_reconstruct_cond(dims, cand_k, cand_v, probs, chosen, symbols, esc_vals, esc_off, out_k, out_v,
+                         ws, status):
+    rc = lib().plc_reconstruct_cond(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _contig(chosen, torch.int32), _contig(symbols, torch.uint8),
+        _contig(esc_vals, None), esc_vals.numel(), _contig(esc_off, torch.int64),
+        _ptr(out_k, torch.float16), _ptr(out_v, torch.float16), _contig(ws, torch.uint8), ws.numel(),
+        _contig(status, torch.int32), _stream())
+    _check(rc, "plc_reconstruct_cond")
+
+
+def plc_select_candidate(dims, cand_k, act_k, max_mean_sq, chosen):
+    rc = lib().plc_select_candidate(C.byref(dims), _ptr(cand_k, torch.float16), _ptr(act_k, torch.float16),
+                                    float(max_mean_sq), _contig(chosen, torch.int32), _stream())
+    _check(rc, "plc_select_candidate")
+
+
+def plc_index_encode(probs, chosen, S, n, k, states, words, word_off, word_cap, n_words, status):
+    rc = lib().plc_index_encode(_contig(probs, torch.float32), _contig(chosen, torch.int32), S, n, k,
+                                _contig(states, torch.int32), _contig(words, torch.int16),
+                                _contig(word_off, torch.int64), int(word_cap),
+                                _contig(n_words, torch.int32), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_index_encode")
+
+
+def plc_index_decode(probs, states, words, word_off, n_words, S, n, k, chosen, status):
+    rc = lib().plc_index_decode(_contig(probs, torch.float32), _contig(states, torch.int32),
+                                _contig(words, torch.int16), words.numel(),
+                                _contig(word_off, torch.int64), _contig(n_words, torch.int32), S, n, k,
+                                _contig(chosen, torch.int32), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_index_decode")
 
 
 def plc_trace_kernel_events(kernel_id, start=None, stop=None):

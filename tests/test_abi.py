@@ -74,6 +74,22 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert L.plc_rans_encode(p, 1, 100, -32, p, p, p, p, 100, p, p, None) == 1
     assert L.plc_rans_decode(p, p, p, 10, p, p, 1, 0, 0, p, p, None) == 1
     assert L.plc_rans_decode(p, p, p, 10, p, p, 1, 1 << 31, 0, p, p, None) == 1
+    # token-conditional calls
+    dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
+    odd4 = C.c_void_p(4098)
+    assert L.plc_predict_residual_cond(C.byref(dm), p, p, p, None, p, p, p, p, 0, p, p, None, p, 1 << 20, p, None) == 1
+    assert L.plc_predict_residual_cond(C.byref(dm), p, p, p, odd4, p, p, p, p, 0, p, p, None, p, 1 << 20, p, None) == 1
+    assert L.plc_reconstruct_cond(C.byref(dm), p, p, p, None, p, p, 0, p, p, p, p, 1 << 20, p, None) == 1
+    assert L.plc_reconstruct_cond(C.byref(dm), p, p, p, p, p, p, 0, p, p, p, p, 16, p, None) == 1       # ws too small
+    assert L.plc_select_candidate(C.byref(dm), p, p, C.c_float(-1.0), p, None) == 1
+    assert L.plc_select_candidate(C.byref(dm), p, p, C.c_float(float("nan")), p, None) == 1
+    assert L.plc_select_candidate(C.byref(dm), p, None, C.c_float(1.0), p, None) == 1
+    assert L.plc_index_encode(p, p, 1, 16, 0, p, p, p, 16, p, p, None) == 1        # k out of range
+    assert L.plc_index_encode(p, p, 1, 16, 33, p, p, p, 16, p, p, None) == 1
+    assert L.plc_index_encode(p, p, 0, 16, 4, p, p, p, 16, p, p, None) == 1
+    assert L.plc_index_encode(p, None, 1, 16, 4, p, p, p, 16, p, p, None) == 1
+    assert L.plc_index_decode(p, p, None, 10, p, p, 1, 16, 4, p, p, None) == 1
+    assert L.plc_index_decode(p, p, p, 10, p, p, 1, 0, 4, p, p, None) == 1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -353,3 +353,79 @@ def test_runs_are_deterministic(oracle, dev):
     for unit in range(codec.n_units):
         o = unit * codec.word_cap
         assert torch.equal(words1[o:o + int(nw[unit])], codec.words[o:o + int(nw[unit])])
+
+
+def _double_rounding_cases(delta32, limit=4096):
+    """(q, c) with c an fp16 value such that fp32(q * delta + c) is an exact tie between two fp16
+    values while the unrounded sum is not: rounding to fp32 and then to fp16 (the contract) ends on
+    the even neighbour, a single rounding of the exact sum on the other one."""
+    d = float(delta32)
+    c = np.arange(0x2400, 0x4800, dtype=np.uint16)                 # 2^-6 .. 8, positive
+    c = np.concatenate([c, c | 0x8000]).view(np.float16).astype(np.float64)
+    found = []
+    for q in range(-127, 128):
+        if q == 0:
+            continue
+        v = q * d + c                                              # exact in fp64 (32 + 11 significant bits)
+        r32 = v.astype(np.float32).astype(np.float64)
+        with np.errstate(over="ignore"):
+            h = r32.astype(np.float16)                             # tie -> even
+        hv = h.astype(np.float64)
+        other = np.where(hv > r32, np.nextafter(h, np.float16(-np.inf)), np.nextafter(h, np.float16(np.inf)))
+        tie = (np.abs(hv - r32) == np.abs(other.astype(np.float64) - r32)) & (hv != r32)
+        # a single rounding would go to `other` when the exact sum lies on its side of the tie
+        flips = tie & (np.sign(v - r32) == np.sign(other.astype(np.float64) - r32)) & (v != r32)
+        for cc in c[flips]:
+            found.append((q, cc))
+    assert len(found) > 100
+    return found[:limit]
+
+
+@pytest.mark.parametrize("k,cond", [(1, False), (4, False), (9, False), (4, True), (9, True)])
+def test_reconstruct_rounds_to_fp32_then_to_fp16(oracle, dev, k, cond):
+    """The recovered value is fma(q, Delta, pred) rounded to fp32 and then to fp16; inputs chosen so
+    that merging the two roundings would give the neighbouring fp16 value."""
+    O = oracle
+    from paper_2604_15356_amd import plc
+    delta = np.float32(0.02)
+    cases = _double_rounding_cases(delta)
+    d = 8
+    n = (len(cases) + d - 1) // d
+    cases = (cases * 2)[:n * d]
+    q = np.array([c[0] for c in cases], dtype=np.int64).reshape(n, d)
+    cv = np.array([c[1] for c in cases], dtype=np.float16).reshape(n, d)
+    g = torch.Generator(device=dev).manual_seed(k)
+    cand_k = torch.randn((1, 1, 1, n, k, d), generator=g, device=dev).to(torch.float16)
+    cand_v = torch.randn((1, 1, 1, n, k, d), generator=g, device=dev).to(torch.float16)
+    j = k - 1                                                       # the candidate that carries all weight
+    cand_k[0, 0, 0, :, j] = torch.from_numpy(cv).to(dev)
+    cand_v[0, 0, 0, :, j] = torch.from_numpy(-cv).to(dev)
+    probs = torch.zeros((1, n, k), dtype=torch.float32, device=dev)
+    probs[:, :, j] = 0.25                                           # renormalises to exactly 1
+    sym = torch.empty((1, n, 2, d), dtype=torch.uint8, device=dev)
+    sym[0, :, 0] = torch.from_numpy((q + 127).astype(np.uint8)).to(dev)
+    sym[0, :, 1] = torch.from_numpy((-q + 127).astype(np.uint8)).to(dev)
+    sym = sym.reshape(1, 2 * n * d)
+    from paper_2604_15356_amd.codec import KVDeltaCodec
+    codec = KVDeltaCodec(1, 1, 1, n, k, d, float(delta))
+    out_k = torch.zeros((1, 1, 1, n, d), dtype=torch.float16, device=dev)
+    out_v = torch.zeros_like(out_k)
+    chosen = torch.full((1, n), j, dtype=torch.int32, device=dev)
+    chosen[0, ::3] = -1                                             # both kinds of position
+    if cond:
+        plc.plc_reconstruct_cond(codec.dims, cand_k, cand_v, probs, chosen, sym, codec.esc_vals, codec.esc_off,
+                                 out_k, out_v, codec.ws, codec.status)
+    else:
+        codec.reconstruct(cand_k, cand_v, probs, out_k, out_v, symbols=sym)
+    codec.check_status()
+    dm = O.make_dims(1, 1, 1, n, k, d, float(delta))
+    rk, rv = O.reconstruct(dm, cand_k.cpu().numpy(), cand_v.cpu().numpy(), probs.cpu().numpy(), u8(sym),
+                           np.zeros(1, dtype=np.uint16), np.zeros(1, dtype=np.uint64), mode=O.F32,
+                           chosen=chosen.cpu().numpy() if cond else None)
+    assert np.array_equal(u16(out_k).ravel(), rk)
+    assert np.array_equal(u16(out_v).ravel(), rv)
+    # the cases are what they claim to be: a single rounding of the exact sum differs everywhere
+    exact = q.astype(np.float64) * float(delta) + cv.astype(np.float64)
+    with np.errstate(over="ignore"):
+        once = exact.astype(np.float16).view(np.uint16).ravel()
+    assert (once != rk).all()
