@@ -45,16 +45,22 @@ def parse():
     ap.add_argument("--also-chunked", type=int, default=4096,
                     help="when the headline run codes whole streams (chunk_syms 0), also time the same workload with "
                          "rANS units of this many symbols and report it beside the headline (0 = skip)")
+    ap.add_argument("--no-conditional", action="store_true",
+                    help="skip the side measurement of the token-conditional path (prediction = the true token's "
+                         "candidate, its index coded in a stream of its own)")
     return ap.parse_args()
 
 
 class KernelTimer:
     """HIP event pairs recorded by libplc around the main kernel of each call."""
 
-    def __init__(self, plc, torch, steps):
+    def __init__(self, plc, torch, steps, conditional=False):
         self.plc, self.ids = plc, {"predict_residual": plc.TRACE_PREDICT, "reconstruct": plc.TRACE_RECONSTRUCT,
                                    "histogram": plc.TRACE_HISTOGRAM, "rans_encode": plc.TRACE_RANS_ENCODE,
                                    "rans_decode": plc.TRACE_RANS_DECODE}
+        if conditional:
+            del self.ids["predict_residual"], self.ids["reconstruct"]
+            self.ids.update(predict_residual_cond=plc.TRACE_PREDICT_COND, reconstruct_cond=plc.TRACE_RECONSTRUCT_COND)
         self.ev = {}
         for name in self.ids:
             pairs = []
@@ -271,6 +277,65 @@ def main():
         log(f"  with rANS units of {args.also_chunked} symbols: step {dt2 / args.steps * 1e3:.4f} ms "
             f"({result['chunked']['value']} GB/s), rans_encode {ms2['rans_encode']:.4f} ms, rans_decode {ms2['rans_decode']:.4f} ms")
         del codec2
+    if not args.no_conditional:
+        # Token-conditional path on the same workload and in the same format (whole streams unless --chunk-syms):
+        # every position is predicted by the candidate of its true token (given, as the serving loop knows it),
+        # whose index goes into a per-session stream coded under the model's probabilities.  Per component a
+        # position then moves 2 B of one candidate instead of 2k B of all of them: 5 algorithmic bytes.
+        codec3 = KVDeltaCodec(w.S, w.L, w.H, w.n, w.k, w.d, w.delta, w.qmax, chunk_syms=args.chunk_syms, device=dev,
+                              cand_stride=w.cand_k.stride()[:5], act_stride=w.act_k.stride()[:4])
+        chosen = w.chosen.to(torch.int32).contiguous()
+
+        def step3():
+            codec3.encode_cond(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen=chosen)
+            codec3.decode_cond(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+
+        for _ in range(args.warmup):
+            step3()
+        torch.cuda.synchronize()
+        timer3 = KernelTimer(plc, torch, args.steps, conditional=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            timer3.arm(i)
+            step3()
+        torch.cuda.synchronize()
+        dt3 = time.perf_counter() - t0
+        timer3.disarm()
+        codec3.check_status("token-conditional steps")
+        nw3 = codec3.n_words.cpu().numpy().view(np.uint32).astype(np.int64)
+        esc3 = int(codec3.esc_cnt.cpu().numpy().view(np.uint32).astype(np.int64).sum())
+        idx_bits = 16 * int(codec3.idx_n_words.cpu().numpy().view(np.uint32).astype(np.int64).sum()) + 32 * 32 * w.S
+        bits3 = (16 * int(nw3.sum()) + 16 * esc3 + 32 * 32 * codec3.n_units + (256 * 16 + 3 * 32) * w.n_streams
+                 + idx_bits)
+        err3 = 0.0
+        for s_ in range(w.S):
+            for l_ in range(w.L):
+                for got, want in ((out_k, w.act_k), (out_v, w.act_v)):
+                    diff = (got[s_, l_].float() - want[s_, l_].float()).abs()
+                    err3 = max(err3, float(torch.nan_to_num(diff, nan=0.0, posinf=0.0).max()))
+        ms3 = timer3.mean_ms()
+        k3 = {}
+        for name in ("predict_residual_cond", "reconstruct_cond"):
+            gbs = 5.0 * E / (ms3[name] * 1e-3) / 1e9
+            k3[name] = dict(ms=round(ms3[name], 4), GBs=round(gbs, 1), frac_hbm=round(gbs / HBM_PEAK_GBS, 4))
+        result["token_conditional"] = {
+            "value": round(w.kv_bytes / (dt3 / args.steps) / 1e9, 2), "unit": "GB/s",
+            "ms_per_step": round(dt3 / args.steps * 1e3, 4), "bytes_per_component": 5,
+            "coded_bits_per_token": round(bits3 / (w.S * w.n), 1),
+            "payload_bits_per_symbol": round((16 * int(nw3.sum()) + 16 * esc3) / E, 4),
+            "index_bits_per_token": round(idx_bits / (w.S * w.n), 3),
+            "escape_rate": round(esc3 / E, 6),
+            "roundtrip_symbols_exact": bool(torch.equal(codec3.dec_symbols, codec3.symbols)),
+            "roundtrip_indices_exact": bool(torch.equal(codec3.dec_chosen, chosen)),
+            "max_abs_reconstruction_error": round(err3, 6),
+            "kernels": k3, "kernels_ms": {k: round(v, 4) for k, v in ms3.items()},
+        }
+        log(f"  token-conditional: step {dt3 / args.steps * 1e3:.4f} ms ({result['token_conditional']['value']} GB/s), "
+            f"{result['token_conditional']['payload_bits_per_symbol']} bits/component + "
+            f"{result['token_conditional']['index_bits_per_token']} index bits/token; "
+            + ", ".join(f"{k} {v['ms']} ms = {100 * v['frac_hbm']:.1f} % of HBM peak" for k, v in k3.items()))
+        del codec3
     if not args.no_cpu_baseline:
         base, sym64 = cpu_baseline(w, args.cpu_streams, torch)
         result["cpu_baseline"] = base

@@ -172,39 +172,54 @@ __global__ __launch_bounds__(kBlock) void weights_kernel(const float *__restrict
 // ---------------------------------------------------------------------------
 // Encode: symbols and per-tile escape counts
 // ---------------------------------------------------------------------------
-template <int K, bool COND>
+// Residual of one chunk against its prediction, quantised: the 8 symbols packed low byte first, the number
+// of escapes among them and a bit mask of which.
+__device__ __forceinline__ void quantise8(const half8 x, const float pred[kChunk], float delta, float qmax,
+                                          uint32_t packed[2], uint32_t *n_esc, uint32_t *esc_bits) {
+  packed[0] = packed[1] = 0u;
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) {
+    const float r = (float)x[e] - pred[e];
+    const float u = r / delta;
+    const float qf = __builtin_rintf(u);  // round half to even
+    uint32_t sym;
+    if (__builtin_fabsf(qf) <= qmax) {  // false for NaN and infinities
+      sym = (uint32_t)((int)qf + (int)kZeroSymbol);
+    } else {
+      sym = PLC_ESCAPE;
+      *n_esc += 1;
+      *esc_bits |= 1u << e;
+    }
+    packed[e >> 2] |= sym << (8 * (e & 3));
+  }
+}
+
+// Park a thread's escapes (raw fp16 of the actual values) in the tile's staging row from position `pos` on.
+__device__ __forceinline__ void stage_escapes(uint16_t *row, uint32_t pos, uint32_t esc_bits, const uint4 av) {
+  const uint32_t raw[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) {
+    if (esc_bits & (1u << e)) {
+      if (pos < (uint32_t)kEscStage) row[pos] = (uint16_t)((e & 1 ? raw[e >> 1] >> 16 : raw[e >> 1]) & 0xffffu);
+      ++pos;
+    }
+  }
+}
+
+template <int K>
 __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArgs a) {
   __shared__ uint32_t wave_cnt[kBlock / 64];
   const Coord q = locate(a);
   uint32_t n_esc = 0, esc_bits = 0;
-  uint32_t raw[4] = {0u, 0u, 0u, 0u};
+  uint4 av = make_uint4(0u, 0u, 0u, 0u);
   if (q.valid) {
     const uint16_t *cand = (q.c ? a.cand_v : a.cand_k) + q.cand;
     const uint16_t *act = (q.c ? a.act_v : a.act_k) + q.act;
-    const uint4 av = load16_stream(act);
-    raw[0] = av.x;
-    raw[1] = av.y;
-    raw[2] = av.z;
-    raw[3] = av.w;
+    av = load16_stream(act);
     float pred[kChunk];
-    predict_chunk<K, COND>(a, q, cand, pred);
-    const half8 x = __builtin_bit_cast(half8, av);
-    uint32_t packed[2] = {0u, 0u};
-#pragma unroll
-    for (int e = 0; e < kChunk; ++e) {
-      const float r = (float)x[e] - pred[e];
-      const float u = r / a.delta;
-      const float qf = __builtin_rintf(u);  // round half to even
-      uint32_t sym;
-      if (__builtin_fabsf(qf) <= a.qmax) {  // false for NaN and infinities
-        sym = (uint32_t)((int)qf + (int)kZeroSymbol);
-      } else {
-        sym = PLC_ESCAPE;
-        ++n_esc;
-        esc_bits |= 1u << e;
-      }
-      packed[e >> 2] |= sym << (8 * (e & 3));
-    }
+    predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
+    uint32_t packed[2];
+    quantise8(__builtin_bit_cast(half8, av), pred, a.delta, a.qmax, packed, &n_esc, &esc_bits);
     store8_stream(a.symbols + q.sym, packed[0], packed[1]);
     if (a.pred_out) {
       float4 *po = reinterpret_cast<float4 *>(a.pred_out + q.sym);
@@ -222,14 +237,85 @@ __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArg
   const uint32_t c0 = wave_cnt[0], c1 = wave_cnt[1], c2 = wave_cnt[2], c3 = wave_cnt[3];
   if (threadIdx.x == 0) a.tile_cnt[blockIdx.x] = c0 + c1 + c2 + c3;
   if (n_esc) {
-    uint32_t pos = prefix + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
-    uint16_t *row = a.esc_stage + (int64_t)blockIdx.x * kEscStage;
+    const uint32_t pos = prefix + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
+    stage_escapes(a.esc_stage + (int64_t)blockIdx.x * kEscStage, pos, esc_bits, av);
+  }
+}
+
+// Token-conditional encode.  A position whose token is a candidate reads 2 bytes per component of that
+// candidate instead of 2k of all of them, so a thread has only two loads to keep in flight per chunk; a
+// workgroup therefore takes kCondTiles consecutive tiles and issues the loads of all of them first (two
+// tiles measured best; with four the quantiser's arithmetic, 8 IEEE divides per chunk, starts to queue
+// behind the loads instead of overlapping them).
+constexpr int kCondTiles = 2;
+
+template <int K>
+__global__ __launch_bounds__(kBlock) void predict_residual_cond_kernel(const CodecArgs a, uint32_t n_tiles) {
+  __shared__ uint32_t wave_cnt[kCondTiles][kBlock / 64];
+  Coord q[kCondTiles];
+  uint4 av[kCondTiles], cv[kCondTiles];
+  int pick[kCondTiles];
 #pragma unroll
-    for (int e = 0; e < kChunk; ++e) {
-      if (esc_bits & (1u << e)) {
-        if (pos < (uint32_t)kEscStage) row[pos] = (uint16_t)((e & 1 ? raw[e >> 1] >> 16 : raw[e >> 1]) & 0xffffu);
-        ++pos;
+  for (int t = 0; t < kCondTiles; ++t) {
+    const uint32_t g = blockIdx.x * kCondTiles + t;
+    const bool inside = g < n_tiles;  // uniform
+    const uint32_t gg = inside ? g : 0u;
+    const uint32_t stream = gg / a.tiles_per_stream;
+    q[t] = locate_chunk(a, stream, gg - stream * a.tiles_per_stream, threadIdx.x);
+    q[t].valid = q[t].valid && inside;
+    av[t] = cv[t] = make_uint4(0u, 0u, 0u, 0u);
+    pick[t] = -1;
+    if (q[t].valid) {
+      av[t] = load16_stream((q[t].c ? a.act_v : a.act_k) + q[t].act);
+      pick[t] = a.chosen[q[t].row];
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < kCondTiles; ++t) {
+    if (pick[t] < -1 || pick[t] >= a.k) {
+      raise(a.status, PLC_ERR_INVALID);
+      pick[t] = -1;
+    }
+    if (pick[t] >= 0) cv[t] = load16_stream((q[t].c ? a.cand_v : a.cand_k) + q[t].cand + pick[t] * a.cs[4]);
+  }
+  uint32_t n_esc[kCondTiles], esc_bits[kCondTiles], prefix[kCondTiles];
+  const int wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int t = 0; t < kCondTiles; ++t) {
+    n_esc[t] = esc_bits[t] = 0;
+    if (q[t].valid) {
+      float pred[kChunk];
+      if (pick[t] >= 0) {
+        const half8 c = __builtin_bit_cast(half8, cv[t]);
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) pred[e] = (float)c[e];
+      } else {
+        predict8<K>((q[t].c ? a.cand_v : a.cand_k) + q[t].cand, a.cs[4], a.weights + q[t].w, a.k, pred);
       }
+      uint32_t packed[2];
+      quantise8(__builtin_bit_cast(half8, av[t]), pred, a.delta, a.qmax, packed, &n_esc[t], &esc_bits[t]);
+      store8_stream(a.symbols + q[t].sym, packed[0], packed[1]);
+      if (a.pred_out) {
+        float4 *po = reinterpret_cast<float4 *>(a.pred_out + q[t].sym);
+        po[0] = make_float4(pred[0], pred[1], pred[2], pred[3]);
+        po[1] = make_float4(pred[4], pred[5], pred[6], pred[7]);
+      }
+    }
+    uint32_t wave_total = 0;
+    prefix[t] = 0;
+    if (__ballot(n_esc[t] != 0) != 0) prefix[t] = wave_escape_prefix(n_esc[t], &wave_total);  // uniform
+    if ((threadIdx.x & 63) == 0) wave_cnt[t][wave] = wave_total;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int t = 0; t < kCondTiles; ++t) {
+    const uint32_t g = blockIdx.x * kCondTiles + t;
+    if (g >= n_tiles) break;
+    const uint32_t c0 = wave_cnt[t][0], c1 = wave_cnt[t][1], c2 = wave_cnt[t][2], c3 = wave_cnt[t][3];
+    if (threadIdx.x == 0) a.tile_cnt[g] = c0 + c1 + c2 + c3;
+    if (n_esc[t]) {
+      const uint32_t pos = prefix[t] + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
+      stage_escapes(a.esc_stage + (int64_t)g * kEscStage, pos, esc_bits[t], av[t]);
     }
   }
 }
@@ -466,9 +552,10 @@ template <int K>
 struct LaunchPredict {
   static void run(const CodecArgs &a, unsigned grid, hipStream_t st) {
     if (a.chosen) {
-      hipLaunchKernelGGL((predict_residual_kernel<K, true>), dim3(grid), dim3(kBlock), 0, st, a);
+      hipLaunchKernelGGL(predict_residual_cond_kernel<K>, dim3((grid + kCondTiles - 1) / kCondTiles), dim3(kBlock), 0,
+                         st, a, grid);
     } else {
-      hipLaunchKernelGGL((predict_residual_kernel<K, false>), dim3(grid), dim3(kBlock), 0, st, a);
+      hipLaunchKernelGGL(predict_residual_kernel<K>, dim3(grid), dim3(kBlock), 0, st, a);
     }
   }
 };

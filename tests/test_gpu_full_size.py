@@ -176,3 +176,74 @@ def test_other_configurations_full_size(oracle, name):
         assert np.array_equal(u16(out_k[s, l, h]).ravel(), rk) and np.array_equal(u16(out_v[s, l, h]).ravel(), rv)
     del codec, coded, out_k, out_v, w
     torch.cuda.empty_cache()
+
+
+# --------------------------------------------------------------------------- token-conditional path, full size
+
+@pytest.mark.parametrize("chunk", [0, 4096])
+def test_token_conditional_full_size(oracle, chunk):
+    """The Llama-shaped configuration through the token-conditional path as bench.py runs it (true
+    candidate given, whole streams or 4096-symbol units); one position in 16 is declared a miss so that
+    both kinds of prediction occur.  Sampled streams bit for bit against the oracle, the index stream
+    completely, properties on everything."""
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    O = oracle
+    dev = torch.device("cuda:0")
+    w = make_workload("llama8b", device=dev)
+    chosen = w.chosen.to(torch.int32).clone()
+    chosen[:, 5::16] = -1
+    ch = chosen.cpu().numpy()
+    codec = codec_for(w, chunk_syms=chunk)
+    print(f"token-conditional llama8b, chunk_syms={chunk}", flush=True)
+    coded = codec.encode_cond(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen=chosen)
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.chosen.fill_(-7)
+    codec.decode_cond(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+    codec.check_status("token-conditional, full size")
+    assert np.array_equal(codec.dec_chosen.cpu().numpy(), ch)
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    probs = w.probs.cpu().numpy()
+    ienc = O.index_encode(probs, ch, word_cap=codec.idx_word_cap)
+    assert np.array_equal(u32(coded.idx_states), ienc["states"])
+    assert np.array_equal(u32(coded.idx_n_words), ienc["n_words"])
+    nw = int(ienc["n_words"][0])
+    assert np.array_equal(u16(coded.idx_words)[:nw], ienc["words"][:nw])
+    dm = O.make_dims(1, 1, 1, w.n, w.k, w.d, w.delta, w.qmax)
+    U = codec.units_per_stream
+    words = u16(coded.words)
+    for st in (3, 200):
+        print(f"  stream {st}", flush=True)
+        (ck, cv, p, ak, av), (s, l, h) = _stream_inputs(w, st)
+        ref = O.predict_residual(dm, ck, cv, p, ak, av, mode=O.F32, chosen=ch[s:s + 1])
+        sym = u8(coded.symbols[st:st + 1])
+        assert np.array_equal(sym, ref["symbols"])
+        off, cnt = int(u64(coded.esc_off)[st]), int(u32(coded.esc_cnt)[st])
+        assert cnt == int(ref["esc_cnt"][0])
+        assert np.array_equal(u16(coded.esc_vals[off:off + cnt]), ref["esc_vals"])
+        freq, _ = O.build_freq(O.histogram(sym))
+        assert np.array_equal(u16(coded.freq[st:st + 1]), freq)
+        enc = O.rans_encode(sym, freq, chunk_syms=chunk, word_cap_per_unit=codec.word_cap)
+        assert np.array_equal(u32(coded.n_words[st * U:(st + 1) * U]), enc["n_words"])
+        assert np.array_equal(u32(coded.states[st * U:(st + 1) * U]), enc["states"])
+        for u in range(U):
+            o, n_w = (st * U + u) * codec.word_cap, int(enc["n_words"][u])
+            assert np.array_equal(words[o:o + n_w], enc["words"][u * codec.word_cap:u * codec.word_cap + n_w])
+        rk, rv = O.reconstruct(dm, ck, cv, p, sym, ref["esc_vals"], np.zeros(1, dtype=np.uint64), mode=O.F32,
+                               chosen=ch[s:s + 1])
+        assert np.array_equal(u16(out_k[s, l, h]).ravel(), rk)
+        assert np.array_equal(u16(out_v[s, l, h]).ravel(), rv)
+    # recovery error on everything: at most Delta/2 plus half an fp16 ulp of the output; escapes exact
+    esc = (coded.symbols.reshape(w.S, w.L, w.H, w.n, 2, w.d) == 255)
+    delta = float(np.float32(w.delta))
+    for c, (act, outp) in enumerate(((w.act_k, out_k), (w.act_v, out_v))):
+        for l in range(w.L):
+            a, o, e = act[0, l].float(), outp[0, l].float(), esc[0, l, :, :, c, :]
+            ulp = torch.clamp(o.abs(), min=2.0 ** -14) * 2.0 ** -10
+            assert bool(((a - o).abs()[~e] <= delta / 2 + ulp[~e] / 2 + 1e-6).all())
+            assert torch.equal(act[0, l].view(torch.int16)[e], outp[0, l].view(torch.int16)[e])
+    # positions given their token never escape; the misses do, at the weighted-mean path's rate
+    by_pos = esc.any(dim=5).any(dim=4)[0].any(dim=0).any(dim=0).cpu().numpy()          # [n]
+    assert not by_pos[ch[0] >= 0].any()
+    del codec, coded, out_k, out_v, w
+    torch.cuda.empty_cache()
