@@ -395,6 +395,282 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// Encoder for few, long units: three wavefronts per unit
+// ---------------------------------------------------------------------------
+// When there are no more units than compute units, time is the length of one unit's chain of steps,
+// and a lone wavefront issues one vector instruction every ~4.3 cycles and one LDS instruction every
+// ~16.  So everything that is not the state recurrence moves to two helper wavefronts of the same
+// workgroup, which run on other SIMDs of the compute unit:
+//   feeder  stages the symbols (64 groups ahead, as above) and turns every (group, lane) of the next
+//           batch into its 16-byte table entry at a fixed place of an LDS ring; a lane without a symbol
+//           (ragged top group, or a step past the unit's first group) gets an identity entry;
+//   coder   per step: one LDS read of its entry, one LDS write of its state before the step, and the
+//           recurrence itself -- no ranking, no addresses to compute, no branches;
+//   packer  one batch behind, recovers from the stored states which lanes emitted (x > thr), ranks
+//           them with one ballot per two steps, packs the 16-bit words and writes them out.
+// The three meet at one workgroup barrier per batch of 16 steps.
+constexpr int kEntrySlots = 3;  // feeder writes b+1, coder reads b, packer reads b-1
+constexpr int kStateSlots = 2;  // coder writes b, packer reads b-1
+constexpr int kIdentity = 256;  // table index of the entry that leaves a state unchanged
+constexpr int64_t kPipeMaxUnits = 512;
+
+template <bool LONG>
+__device__ __forceinline__ void pipe_step(uint32_t &x, const uint4 e) {
+  const bool emit = x > e.y;
+  const uint32_t xr = emit ? x >> 16 : x;
+  const uint32_t t1 = __umulhi(e.x, xr);
+  uint32_t q, xc;
+  if (LONG) {
+    const uint32_t d = (xr - t1) >> ((e.w >> 24) & 31u);
+    q = (t1 + d) >> (e.z >> 24);
+    xc = xr + (e.w & 0xffffu);
+  } else {
+    q = t1 >> (e.z >> 24);
+    xc = xr + e.w;
+  }
+  x = __umul24(q, e.z) + xc;
+}
+
+// One batch of the coder.  Entries are fetched kAhead steps before their use, so that the LDS round
+// trip (longer than a step while the helpers are busy on the same LDS) stays off the chain.
+template <bool LONG>
+__device__ __forceinline__ void pipe_batch(uint32_t &x, const uint4 *eb, uint32_t *xb) {
+  constexpr int kAhead = 4;
+  uint4 e[kAhead];
+#pragma unroll
+  for (int j = 0; j < kAhead; ++j) e[j] = eb[j * kLanes];
+  uint32_t x_even = 0;
+#pragma unroll
+  for (int j = 0; j < kBatch; ++j) {
+    const uint4 cur = e[j % kAhead];
+    PLC_PIN();
+    if (j + kAhead < kBatch) e[j % kAhead] = eb[(j + kAhead) * kLanes];
+    if (j & 1) {  // the states before steps j - 1 and j leave in one LDS instruction
+      xb[(j - 1) * kLanes] = x_even;
+      xb[j * kLanes] = x;
+    } else {
+      x_even = x;
+    }
+    PLC_PIN();
+    pipe_step<LONG>(x, cur);
+  }
+}
+
+__global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a) {
+  __shared__ uint4 table[kIdentity + 1];
+  __shared__ uint4 entry_ring[kEntrySlots][kBatch][kLanes];
+  __shared__ uint32_t state_ring[kStateSlots][kBatch][kLanes];
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][kSymStage];
+  __shared__ __attribute__((aligned(16))) uint16_t word_stage[2 * kBatchSyms + 8];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t unit = blockIdx.x;  // one unit per stream, one workgroup per unit
+
+  bool long_form;
+  {  // every wavefront scans the frequencies; of a lane's four entries the coder builds one, the feeder
+     // one and the packer two
+    uint32_t f[4], cum;
+    const uint32_t total = load_freq4(a.freq + unit * 256, lane, f, &cum);
+    if (total != kScale && threadIdx.x == 0) raise(a.status, PLC_ERR_INVALID);
+    long_form = __ballot(f[0] > 2048u || f[1] > 2048u || f[2] > 2048u || f[3] > 2048u) != 0;  // uniform
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      if ((r < 2 ? r : 2) == wave)
+        table[lane * 4 + r] = long_form ? make_enc_entry<true>(f[r], cum) : make_enc_entry<false>(f[r], cum);
+      cum += f[r];
+    }
+    if (threadIdx.x == 0) table[kIdentity] = make_uint4(0u, 0xffffffffu, 0u, 0u);  // never emits, x' = x
+  }
+  __syncthreads();
+
+  const uint32_t len = (uint32_t)a.syms_per_stream;
+  const uint8_t *ubase = a.sym_in + unit * a.syms_per_stream;
+  const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(ubase) & 15u);
+  const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
+  // Batch 0 holds the top G mod 16 groups (a full 16 if that is 0) followed by identity steps; every
+  // later batch is 16 full groups.  Batch b codes groups top(b)-1 down to top(b)-16.
+  const int32_t head = G % kBatch ? G % kBatch : kBatch;
+  const int32_t n_batches = (G - head) / kBatch + 1;
+  auto batch_top = [&](int32_t b) { return b == 0 ? G : G - head - (b - 1) * kBatch; };
+  // Symbol staging rounds of four batches; a round's buffer starts at the 16-byte-aligned address at or
+  // below its lowest symbol, so the symbol at unit offset t sits at  t - 32 * bottom + mis.
+  auto round_bottom = [&](int32_t r) {
+    const int32_t g = batch_top(4 * r + 3) - kBatch;
+    return g > 0 ? g : 0;
+  };
+  const int32_t n_rounds = (n_batches + 3) / 4;
+
+  uint32_t x = kLow;              // coder
+  bool bad_symbol = false;        // feeder
+  uint4 nv[kStagePieces];         // feeder: next round's symbols in flight
+  bool ntake[kStagePieces];
+  // packer: the word list, as in the single-wavefront encoder
+  uint16_t *wp = a.words_out + a.word_off[unit];
+  const uint32_t pad = __builtin_amdgcn_readfirstlane((uint32_t)((reinterpret_cast<uintptr_t>(wp) >> 1) & 7u));
+  const uint32_t cap = a.word_cap < 0x7fffffffull ? (uint32_t)a.word_cap : 0x7fffffffu;
+  uint32_t vbase = 0, fill = pad;
+
+  auto round_load = [&](int32_t r) {
+    const int64_t lo = (int64_t)round_bottom(r) * kLanes;
+    int64_t hi = (int64_t)batch_top(4 * r) * kLanes;
+    hi = hi < (int64_t)len ? hi : (int64_t)len;
+#pragma unroll
+    for (int i = 0; i < kStagePieces; ++i) {
+      const int64_t off = lo - (int64_t)mis + (int64_t)(lane + 64 * i) * 16;  // 16-byte aligned in absolute address
+      ntake[i] = r < n_rounds && off < hi;
+      if (ntake[i]) nv[i] = load16_stream(ubase + off);
+    }
+  };
+  auto round_store = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < kStagePieces; ++i)
+      if (ntake[i]) *reinterpret_cast<uint4 *>(&sym_stage[buf][(lane + 64 * i) * 16]) = nv[i];
+  };
+  if (wave == 1) {
+    round_load(0);
+    round_store(0);
+    round_load(1);
+  }
+
+  int eslot_feed = 0, eslot_code = 0, eslot_pack = 0, sslot_code = 0, sslot_pack = 0;
+  for (int32_t it = 0; it < n_batches + 2; ++it) {
+    if (wave == 1) {
+      // ---- feeder: entries of batch `it`
+      if (it < n_batches) {
+        const int32_t r = it >> 2;
+        if ((it & 3) == 0 && it > 0) {  // first batch of a new round: land it, start the one after
+          round_store(r & 1);
+          round_load(r + 1);
+        }
+        const int32_t top = batch_top(it), bottom = round_bottom(r);
+        const uint8_t *sb = sym_stage[r & 1];
+        // lane (half h, l) serves step 2p + h of the batch: group top - 1 - 2p - h, rANS lane l
+        const int half = lane >> 5, l = lane & 31;
+        uint4 *eo = &entry_ring[eslot_feed][half][l];
+        if (it > 0) {
+          // 16 full groups: all symbol reads, then all table reads, then all ring writes, so that the LDS
+          // round trips overlap instead of queueing one behind the other
+          const uint8_t *s0 = sb + ((top - bottom - 2 * (kBatch / 2 - 1) - 1 - half) * kLanes + l + (int32_t)mis);
+          uint32_t sy[kBatch / 2];
+          u32x4 e[kBatch / 2];  // native vectors: each entry moves as one 16-byte LDS access
+#pragma unroll
+          for (int p = 0; p < kBatch / 2; ++p) sy[p] = s0[2 * kLanes * (kBatch / 2 - 1 - p)];
+#pragma unroll
+          for (int p = 0; p < kBatch / 2; ++p) e[p] = *reinterpret_cast<const u32x4 *>(&table[sy[p]]);
+          uint32_t any = 0;
+#pragma unroll
+          for (int p = 0; p < kBatch / 2; ++p) {
+            any |= e[p].w;
+            *reinterpret_cast<u32x4 *>(eo + 2 * p * kLanes) = e[p];
+          }
+          bad_symbol = bad_symbol || (any & 0x80000000u) != 0;
+        } else {
+          // the top batch: `head` groups, the first of them possibly ragged, then identity steps
+#pragma unroll
+          for (int p = 0; p < kBatch / 2; ++p) {
+            const int j = 2 * p + half;
+            const int64_t t = (int64_t)(top - 1 - j) * kLanes + l;
+            const bool has = j < head && t < (int64_t)len;
+            const int64_t idx = has ? t - (int64_t)bottom * kLanes + mis : 0;
+            const uint32_t byte = sb[idx];
+            const uint4 e = table[has ? byte : (uint32_t)kIdentity];
+            bad_symbol = bad_symbol || (e.w & 0x80000000u) != 0;
+            eo[2 * p * kLanes] = e;
+          }
+        }
+        eslot_feed = eslot_feed == kEntrySlots - 1 ? 0 : eslot_feed + 1;
+      }
+    } else if (wave == 0) {
+      // ---- coder: batch `it - 1`
+      if (it >= 1 && it <= n_batches) {
+        const uint4 *eb = &entry_ring[eslot_code][0][lane & 31];
+        uint32_t *xb = &state_ring[sslot_code][0][lane & 31];
+        if (long_form) {
+          pipe_batch<true>(x, eb, xb);
+        } else {
+          pipe_batch<false>(x, eb, xb);
+        }
+        eslot_code = eslot_code == kEntrySlots - 1 ? 0 : eslot_code + 1;
+        sslot_code ^= 1;
+      }
+    } else {
+      // ---- packer: batch `it - 2`
+      if (it >= 2) {
+        uint32_t top_fill = fill;  // uniform
+        // hardware lane h of a half carries rANS lane 31 - h, which the encoder visits first
+        const uint32_t *xs = &state_ring[sslot_pack][lane >> 5][31 - (lane & 31)];
+        const uint32_t *ts = &entry_ring[eslot_pack][lane >> 5][31 - (lane & 31)].y;
+        uint32_t xps[kBatch / 2], thrs[kBatch / 2];
+#pragma unroll
+        for (int p = 0; p < kBatch / 2; ++p) {
+          xps[p] = xs[2 * p * kLanes];
+          thrs[p] = ts[2 * p * kLanes * 4];
+        }
+#pragma unroll
+        for (int p = 0; p < kBatch / 2; ++p) {
+          const uint32_t xp = xps[p];
+          const bool emit = xp > thrs[p];
+          const uint64_t mask = __ballot(emit);
+          const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+          if (emit) word_stage[top_fill + rank] = (uint16_t)xp;
+          top_fill += (uint32_t)__builtin_popcountll(mask);
+        }
+        eslot_pack = eslot_pack == kEntrySlots - 1 ? 0 : eslot_pack + 1;
+        sslot_pack ^= 1;
+        fill = __builtin_amdgcn_readfirstlane(top_fill);
+        // Every second batch (the list holds two batches' words) the complete 16-byte pieces leave, up
+        // to two per lane, and the incomplete tail moves to the front.
+        if ((it & 1) || it == n_batches + 1) {
+          wave_sync();
+          const uint32_t full = fill / 8;  // at most 129 pieces
+          const bool plain = vbase >= pad && vbase + 8 * full - pad <= cap;
+          if (plain) {
+            uint16_t *dst = wp + (vbase - pad);  // 16-byte aligned
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+              if ((uint32_t)(lane + 64 * h) < full)
+                *reinterpret_cast<uint4 *>(dst + 8 * (lane + 64 * h)) =
+                    *reinterpret_cast<const uint4 *>(word_stage + 8 * (lane + 64 * h));
+            if (full > 128 && lane == 0)
+              *reinterpret_cast<uint4 *>(dst + 8 * 128) = *reinterpret_cast<const uint4 *>(word_stage + 8 * 128);
+          } else {
+            for (uint32_t q = lane; q < 8 * full; q += 64) {
+              const uint32_t v = vbase + q;
+              if (v >= pad && v - pad < cap) wp[v - pad] = word_stage[q];
+            }
+          }
+          const uint32_t rest = fill - 8 * full;
+          uint16_t carry = 0;
+          if ((uint32_t)lane < rest) carry = word_stage[8 * full + lane];
+          wave_sync();
+          if ((uint32_t)lane < rest) word_stage[lane] = carry;
+          vbase += 8 * full;
+          fill = rest;
+          wave_sync();
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  if (wave == 0) {
+    if (lane < kLanes) a.states_out[unit * kLanes + lane] = x;
+  } else if (wave == 1) {
+    if (bad_symbol) raise(a.status, PLC_ERR_INVALID);  // a symbol with f = 0 occurred
+  } else {
+    for (uint32_t q = lane; q < fill; q += 64) {  // the incomplete last piece
+      const uint32_t v = vbase + q;
+      if (v >= pad && v - pad < cap) wp[v - pad] = word_stage[q];
+    }
+    const uint32_t n_words = vbase + fill - pad;
+    if (lane == 0) {
+      a.n_words_out[unit] = n_words;
+      if ((uint64_t)n_words > a.word_cap) raise(a.status, PLC_ERR_CAPACITY);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
 // Decoder
 // ---------------------------------------------------------------------------
 // Slot table: for each of the 4096 slots, sym | (f - 1) << 8 | (slot - cum) << 20.
@@ -868,7 +1144,14 @@ extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_
   hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_RANS_ENCODE, st);
-    dispatch_waves<LaunchEncode>(waves, a, (unsigned)(n_streams * a.wgs_per_stream), st);
+    if (a.units_per_stream == 1 && a.n_units <= kPipeMaxUnits) {
+      // no more units than compute-unit halves: the chain of one unit is the time, so give each unit three
+      // wavefronts (with more units, three wavefronts per unit cost more in occupancy than the shorter
+      // chain gains)
+      hipLaunchKernelGGL(rans_encode_pipe_kernel, dim3((unsigned)a.n_units), dim3(192), 0, st, a);
+    } else {
+      dispatch_waves<LaunchEncode>(waves, a, (unsigned)(n_streams * a.wgs_per_stream), st);
+    }
   }
   return launch_status();
 }
