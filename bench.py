@@ -316,12 +316,15 @@ def main():
                     err3 = max(err3, float(torch.nan_to_num(diff, nan=0.0, posinf=0.0).max()))
         ms3 = timer3.mean_ms()
         k3 = {}
+        miss_share = float((chosen < 0).float().mean())     # those positions read all k candidates
+        cond_bytes = (1.0 - miss_share) * 5.0 + miss_share * (2 * w.k + 3)
         for name in ("predict_residual_cond", "reconstruct_cond"):
-            gbs = 5.0 * E / (ms3[name] * 1e-3) / 1e9
+            gbs = cond_bytes * E / (ms3[name] * 1e-3) / 1e9
             k3[name] = dict(ms=round(ms3[name], 4), GBs=round(gbs, 1), frac_hbm=round(gbs / HBM_PEAK_GBS, 4))
         result["token_conditional"] = {
             "value": round(w.kv_bytes / (dt3 / args.steps) / 1e9, 2), "unit": "GB/s",
-            "ms_per_step": round(dt3 / args.steps * 1e3, 4), "bytes_per_component": 5,
+            "ms_per_step": round(dt3 / args.steps * 1e3, 4), "bytes_per_component": round(cond_bytes, 3),
+            "miss_share": round(miss_share, 4),
             "coded_bits_per_token": round(bits3 / (w.S * w.n), 1),
             "payload_bits_per_symbol": round((16 * int(nw3.sum()) + 16 * esc3) / E, 4),
             "index_bits_per_token": round(idx_bits / (w.S * w.n), 3),

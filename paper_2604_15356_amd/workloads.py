@@ -12,6 +12,11 @@ head of a Zipf(s = 1.1) distribution over a 50,000-token vocabulary whose
 temperature is set so that the *full* distribution has the requested
 perplexity; the true candidate is sampled from the renormalised top-k row; the
 actual vector is that candidate plus N(0, sigma^2) noise, rounded to fp16.
+
+A configuration with `misses` also draws positions whose true token is none of
+the k candidates, with the probability the top k leave (1 - their sum): there
+`chosen` is -1 and the actual vectors are fresh N(0,1) draws in every layer and
+head (plus the same noise).
 """
 from __future__ import annotations
 
@@ -32,6 +37,9 @@ CONFIGS = {
     "70b":     dict(S=1,  L=80, H=64, d=128, n=2048,  k=4, pp=20.0, sigma=0.08, delta=0.03, seed=3),
     "batched": dict(S=64, L=32, H=8,  d=128, n=2048,  k=8, pp=(5.0, 40.0), sigma=(0.01, 0.2),
                     delta=0.02, seed=4),
+    # the paper's suggested k = 20 (Sec. 7.1), with the top-k misses a real model would have
+    "miss20":  dict(S=1,  L=32, H=8,  d=128, n=4096,  k=20, pp=15.0, sigma=0.05, delta=0.02, seed=5,
+                    misses=True),
 }
 
 
@@ -79,7 +87,7 @@ class Workload:
     sigma: np.ndarray          # [S] noise level of each session
     perplexity: np.ndarray     # [S]
     probs: torch.Tensor        # fp32 [S, n, k], raw top-k probabilities
-    chosen: torch.Tensor       # int64 [S, n], index of the true candidate
+    chosen: torch.Tensor       # int64 [S, n], index of the true candidate (-1: none of them)
     cand_k: torch.Tensor       # fp16, logical [S, L, H, n, k, d] (any strides, d contiguous)
     cand_v: torch.Tensor
     act_k: torch.Tensor        # fp16 [S, L, H, n, d]
@@ -141,6 +149,10 @@ def make_workload(name: str = "tiny", device="cpu", layout: str = "lhnkd",
         probs = probs.contiguous()
     sel = probs / probs.sum(-1, keepdim=True)
     chosen = torch.multinomial(sel.reshape(S * n, k), 1, generator=gen).reshape(S, n)
+    miss = None
+    if cfg.get("misses"):
+        left = (1.0 - probs.sum(-1)).clamp_(0.0, 1.0)                                  # [S, n]
+        miss = torch.rand((S, n), generator=gen, device=dev, dtype=torch.float32) < left
     if one_hot:
         probs = torch.zeros_like(probs).scatter_(2, chosen[..., None], 1.0)
         sigma = np.zeros(S)
@@ -156,8 +168,13 @@ def make_workload(name: str = "tiny", device="cpu", layout: str = "lhnkd",
                 c = torch.randn((H, n, k, d), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
                 z = torch.randn((H, n, d), generator=gen, device=dev, dtype=torch.float32)
                 true = c.gather(2, idx).squeeze(2).to(torch.float32)
+                if miss is not None:
+                    fresh = torch.randn((H, n, d), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+                    true = torch.where(miss[s][None, :, None], fresh.to(torch.float32), true)
                 cand[s, l].copy_(c)
                 act[s, l].copy_((true + float(sigma[s]) * z).to(torch.float16))
+    if miss is not None:
+        chosen = torch.where(miss, torch.full_like(chosen, -1), chosen)
     return Workload(name=name, S=S, L=L, H=H, n=n, k=k, d=d, delta=float(cfg["delta"]), qmax=127,
                     sigma=sigma, perplexity=pp, probs=probs, chosen=chosen,
                     cand_k=cand_k, cand_v=cand_v, act_k=act_k, act_v=act_v)

@@ -39,6 +39,8 @@ CASES = {
     "all_misses": ("tiny", dict(n=64, seed=26), "lhnkd", True, 1.0),
     "one_position": ("tiny", dict(L=1, H=1, n=1, d=8, seed=27), "lhnkd", False, 0.0),
     "three_sessions": ("tiny", dict(S=3, L=1, H=2, n=100, seed=28), "lhnkd", True, 0.15),
+    # the generator's own misses (fresh vectors where the token is none of the k = 20 candidates)
+    "k20_with_misses": ("miss20", dict(L=1, H=2, n=300, seed=29), "lhnkd", False, 0.0),
 }
 
 

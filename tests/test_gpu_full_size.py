@@ -131,6 +131,7 @@ OTHER = {
     "long": (0, 255),          # 8.4 M symbols per stream: stream length, 64-bit offsets (17 GB of candidates)
     "70b": (0, 5119),          # 5,120 streams (the paper's example dimensions)
     "batched": (0, 16383),     # 64 sessions with their own perplexity and noise, 16,384 streams, 137 GB of candidates
+    "miss20": (0, 255),        # k = 20 candidates (43 bytes per component), 12 % of the positions are misses
 }
 
 
@@ -180,8 +181,8 @@ def test_other_configurations_full_size(oracle, name):
 
 # --------------------------------------------------------------------------- token-conditional path, full size
 
-@pytest.mark.parametrize("chunk", [0, 4096])
-def test_token_conditional_full_size(oracle, chunk):
+@pytest.mark.parametrize("name,chunk", [("llama8b", 0), ("llama8b", 4096), ("miss20", 0)])
+def test_token_conditional_full_size(oracle, name, chunk):
     """The Llama-shaped configuration through the token-conditional path as bench.py runs it (true
     candidate given, whole streams or 4096-symbol units); one position in 16 is declared a miss so that
     both kinds of prediction occur.  Sampled streams bit for bit against the oracle, the index stream
@@ -190,12 +191,12 @@ def test_token_conditional_full_size(oracle, chunk):
         pytest.skip("needs a GPU")
     O = oracle
     dev = torch.device("cuda:0")
-    w = make_workload("llama8b", device=dev)
-    chosen = w.chosen.to(torch.int32).clone()
+    w = make_workload(name, device=dev)
+    chosen = w.chosen.to(torch.int32).clone()          # miss20: already holds the generator's misses
     chosen[:, 5::16] = -1
     ch = chosen.cpu().numpy()
     codec = codec_for(w, chunk_syms=chunk)
-    print(f"token-conditional llama8b, chunk_syms={chunk}", flush=True)
+    print(f"token-conditional {name}, chunk_syms={chunk}", flush=True)
     coded = codec.encode_cond(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen=chosen)
     out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
     codec.chosen.fill_(-7)

@@ -40,6 +40,8 @@ CASES = {
     # so many escapes that tiles overflow their staging rows and take the re-gather path
     "escape_heavy": ("tiny", dict(L=1, H=2, n=300, sigma=3.0, seed=18), "lhnkd", False),
     "escape_heavy_ragged": ("tiny", dict(L=1, H=3, n=37, k=5, d=24, sigma=2.0, seed=19), "lnkhd", True),
+    # k = 20 with positions whose true vector is none of the candidates
+    "k20_with_misses": ("miss20", dict(L=1, H=2, n=300, seed=20), "lhnkd", False),
 }
 
 

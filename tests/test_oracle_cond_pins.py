@@ -295,3 +295,50 @@ def test_index_stream_costs_the_tokens_surprisal(oracle):
     expect = (p / p.sum() * -np.log2(p)).sum()
     assert abs(surprisal / w.n - expect) < 0.1
     assert 1.5 < (bits + 1024) / w.n < 3.0         # bits per token position, all layers and heads together
+
+
+# --------------------------------------------------------------------------- positions whose token is no candidate
+
+def test_miss_workload_statistics(oracle):
+    """The k = 20 configuration with misses (Sec. 7.1: the top 20 hold most, not all, of the mass).
+    A miss leaves a fresh N(0,1) vector against the weighted mean: variance 1 + sum w^2 + sigma^2 per
+    component.  Closed-form symbol pmf for both paths, miss rate, and the index stream's cost
+    sum_j p_j log2(1/p_j) + (1-Z) log2(1/(1-Z)) per position."""
+    from paper_2604_15356_amd.workloads import zipf_topk_probs
+    from tests.test_oracle_pins import _closed_form_pmf
+    w = make_workload("miss20", overrides=dict(L=1, H=2, n=2048))
+    p = zipf_topk_probs(15.0, 20)
+    Z = p.sum()
+    ch = w.chosen.numpy()
+    miss = ch < 0
+    assert abs(miss.mean() - (1 - Z)) < 4 * np.sqrt(Z * (1 - Z) / ch.size)
+    wts = p / Z
+    sigma, delta = float(w.sigma[0]), float(np.float32(w.delta))
+    q = np.arange(-127, 128)
+
+    def gauss_pmf(var):
+        sd = np.sqrt(var) / delta
+        pm = np.zeros(256)
+        pm[:255] = norm.cdf((q + 0.5) / sd) - norm.cdf((q - 0.5) / sd)
+        pm[255] = 2 * norm.sf(127.5 / sd)
+        return pm
+
+    hit_mix = np.bincount(ch[~miss], minlength=w.k) / ch.size            # realised shares, misses excluded
+    pm_miss = gauss_pmf(1 + (wts ** 2).sum() + sigma ** 2)
+    expect_mean = _closed_form_pmf(wts, sigma, delta, mix=hit_mix) + miss.mean() * pm_miss
+    expect_cond = (1 - miss.mean()) * gauss_pmf(sigma ** 2) + miss.mean() * pm_miss
+    for chosen, expect in ((None, expect_mean), (ch.astype(np.int32), expect_cond)):
+        r = _encode_cond(oracle, w, chosen) if chosen is not None else _encode_floats(oracle, w)
+        counts = oracle.histogram(r["symbols"]).sum(0).astype(np.float64)
+        emp = counts / counts.sum()
+        assert abs(expect.sum() - 1) < 1e-9
+        assert 0.5 * np.abs(emp - expect).sum() < 0.02
+        H_emp = -(emp[emp > 0] * np.log2(emp[emp > 0])).sum()
+        H = -(expect[expect > 0] * np.log2(expect[expect > 0])).sum()
+        assert abs(H_emp - H) < 0.03, (H_emp, H)
+        assert abs(emp[255] - expect[255]) < 0.3 * expect[255] + 5 / counts.sum()
+    # index stream: what the tokens cost, misses included
+    enc = oracle.index_encode(_np(w.probs), ch.astype(np.int32))
+    bits = (16.0 * enc["n_words"][0] + 1024) / w.n
+    expect_bits = -(p * np.log2(p)).sum() - (1 - Z) * np.log2(1 - Z)
+    assert abs(bits - expect_bits) < 0.6        # 2048 positions: sampling noise and the 1024 bits of lane states
