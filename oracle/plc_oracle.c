@@ -136,9 +136,23 @@ static int position_choice(const int32_t *chosen, int64_t row, int k) {
   return (int)j;
 }
 
+/* Quantiser step of a position.  Without `bits` it is dm->delta everywhere.
+ * With it (Def. "Surprisal-adaptive quantizer", Sec. 5.3: b_i bits per residual
+ * component at position i; Cor. "Practical bit allocation", Sec. 9.4: b bits
+ * mean a step of range / 2^b) the step is range * 2^-bits[s*n+i], an exact
+ * scaling of the fp32 value `range` by a power of two.  Returns 0 for a bit
+ * depth outside 1..PLCO_MAX_BITS. */
+static float position_step(const plco_dims *dm, const uint8_t *bits, float range, int64_t row) {
+  if (!bits) return dm->delta;
+  int b = bits[row];
+  if (b < 1 || b > PLCO_MAX_BITS) return 0.0f;
+  return ldexpf(range, -b);
+}
+
 static int encode_positions(const plco_dims *dm, int mode,
                             const uint16_t *cand_k, const uint16_t *cand_v,
                             const float *probs, const int32_t *chosen,
+                            const uint8_t *bits, float range,
                             const uint16_t *act_k, const uint16_t *act_v,
                             uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
                             uint32_t *esc_cnt, uint64_t *esc_off,
@@ -162,6 +176,8 @@ static int encode_positions(const plco_dims *dm, int mode,
           if (rc) return rc;
           const int pick = position_choice(chosen, (int64_t)s * n + i, k);
           if (pick == -2) return PLCO_ERR_INVALID;
+          const float step = position_step(dm, bits, range, (int64_t)s * n + i);
+          if (!(step > 0.0f)) return PLCO_ERR_INVALID;
           for (int c = 0; c < 2; ++c) {
             const uint16_t *cand = c ? cand_v : cand_k;
             const uint16_t *act = c ? act_v : act_k;
@@ -178,12 +194,12 @@ static int encode_positions(const plco_dims *dm, int mode,
               double u, q;
               if (mode == PLCO_F32) {
                 float r = (float)a - (float)pred; /* Def. KV residual */
-                float uf = r / dm->delta;
+                float uf = r / step;
                 u = (double)uf;
                 q = (double)rintf(uf); /* round half to even */
               } else {
                 double r = a - pred;
-                u = r / (double)dm->delta;
+                u = r / (double)step;
                 q = nearbyint(u);
               }
               if (pred_out) pred_out[out] = pred;
@@ -211,7 +227,7 @@ int plco_predict_residual(const plco_dims *dm, int mode,
                           uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
                           uint32_t *esc_cnt, uint64_t *esc_off,
                           double *pred_out, double *u_out) {
-  return encode_positions(dm, mode, cand_k, cand_v, probs, NULL, act_k, act_v, symbols,
+  return encode_positions(dm, mode, cand_k, cand_v, probs, NULL, NULL, 0.0f, act_k, act_v, symbols,
                           esc_vals, esc_cap, esc_cnt, esc_off, pred_out, u_out);
 }
 
@@ -223,8 +239,21 @@ int plco_predict_residual_cond(const plco_dims *dm, int mode,
                                uint32_t *esc_cnt, uint64_t *esc_off,
                                double *pred_out, double *u_out) {
   if (!chosen) return PLCO_ERR_INVALID;
-  return encode_positions(dm, mode, cand_k, cand_v, probs, chosen, act_k, act_v, symbols,
+  return encode_positions(dm, mode, cand_k, cand_v, probs, chosen, NULL, 0.0f, act_k, act_v, symbols,
                           esc_vals, esc_cap, esc_cnt, esc_off, pred_out, u_out);
+}
+
+int plco_predict_residual_adapt(const plco_dims *dm, int mode,
+                                const uint16_t *cand_k, const uint16_t *cand_v,
+                                const float *probs, const int32_t *chosen,
+                                const uint8_t *bits, float range,
+                                const uint16_t *act_k, const uint16_t *act_v,
+                                uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                                uint32_t *esc_cnt, uint64_t *esc_off,
+                                double *pred_out, double *u_out) {
+  if (!chosen || !bits || !(range > 0.0f) || !isfinite(range)) return PLCO_ERR_INVALID;
+  return encode_positions(dm, mode, cand_k, cand_v, probs, chosen, bits, range, act_k, act_v,
+                          symbols, esc_vals, esc_cap, esc_cnt, esc_off, pred_out, u_out);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -423,6 +452,7 @@ int plco_rans_decode(const uint16_t *freq, const uint32_t *states,
 static int decode_positions(const plco_dims *dm, int mode,
                             const uint16_t *cand_k, const uint16_t *cand_v,
                             const float *probs, const int32_t *chosen,
+                            const uint8_t *bits, float range,
                             const uint8_t *symbols,
                             const uint16_t *esc_vals, const uint64_t *esc_off,
                             uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
@@ -443,6 +473,8 @@ static int decode_positions(const plco_dims *dm, int mode,
           if (rc) return rc;
           const int pick = position_choice(chosen, (int64_t)s * n + i, k);
           if (pick == -2) return PLCO_ERR_INVALID;
+          const float step = position_step(dm, bits, range, (int64_t)s * n + i);
+          if (!(step > 0.0f)) return PLCO_ERR_INVALID;
           for (int c = 0; c < 2; ++c) {
             const uint16_t *cand = c ? cand_v : cand_k;
             uint16_t *out = c ? out_v : out_k;
@@ -464,9 +496,9 @@ static int decode_positions(const plco_dims *dm, int mode,
               int q = (int)sym - ZERO_SYMBOL;
               double xhat;
               if (mode == PLCO_F32) {
-                xhat = (double)fmaf((float)q, dm->delta, (float)pred);
+                xhat = (double)fmaf((float)q, step, (float)pred);
               } else {
-                xhat = pred + (double)q * (double)dm->delta;
+                xhat = pred + (double)q * (double)step;
               }
               if (pre_round_out) pre_round_out[in] = xhat;
               out[abase + e] = plco_double_to_half(xhat);
@@ -482,8 +514,8 @@ int plco_reconstruct(const plco_dims *dm, int mode,
                      const float *probs, const uint8_t *symbols,
                      const uint16_t *esc_vals, const uint64_t *esc_off,
                      uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
-  return decode_positions(dm, mode, cand_k, cand_v, probs, NULL, symbols, esc_vals, esc_off,
-                          out_k, out_v, pre_round_out);
+  return decode_positions(dm, mode, cand_k, cand_v, probs, NULL, NULL, 0.0f, symbols, esc_vals,
+                          esc_off, out_k, out_v, pre_round_out);
 }
 
 int plco_reconstruct_cond(const plco_dims *dm, int mode,
@@ -493,8 +525,19 @@ int plco_reconstruct_cond(const plco_dims *dm, int mode,
                           const uint16_t *esc_vals, const uint64_t *esc_off,
                           uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
   if (!chosen) return PLCO_ERR_INVALID;
-  return decode_positions(dm, mode, cand_k, cand_v, probs, chosen, symbols, esc_vals, esc_off,
-                          out_k, out_v, pre_round_out);
+  return decode_positions(dm, mode, cand_k, cand_v, probs, chosen, NULL, 0.0f, symbols, esc_vals,
+                          esc_off, out_k, out_v, pre_round_out);
+}
+
+int plco_reconstruct_adapt(const plco_dims *dm, int mode,
+                           const uint16_t *cand_k, const uint16_t *cand_v,
+                           const float *probs, const int32_t *chosen,
+                           const uint8_t *bits, float range, const uint8_t *symbols,
+                           const uint16_t *esc_vals, const uint64_t *esc_off,
+                           uint16_t *out_k, uint16_t *out_v, double *pre_round_out) {
+  if (!chosen || !bits || !(range > 0.0f) || !isfinite(range)) return PLCO_ERR_INVALID;
+  return decode_positions(dm, mode, cand_k, cand_v, probs, chosen, bits, range, symbols, esc_vals,
+                          esc_off, out_k, out_v, pre_round_out);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -657,6 +700,175 @@ int plco_index_decode(const float *probs, const uint32_t *states, const uint16_t
     if (ptr != 0) return PLCO_ERR_CORRUPT;
     for (int lane = 0; lane < RANS_LANES; ++lane)
       if (x[lane] != RANS_LOW) return PLCO_ERR_CORRUPT;
+  }
+  return PLCO_OK;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Surprisal-adaptive quantiser (Sec. 5.3) with one table per bit depth       */
+/* ------------------------------------------------------------------------- */
+
+/* b_i = min(bmax, max(1, floor(b0 * h_i / hbar))) with h_i the position's coded
+ * surprisal log2(4096 / f), f the index-table frequency of its token (symbol k
+ * for a miss).  floor(b0 * h / hbar) >= m  <=>  f <= 4096 * 2^(-m * hbar / b0),
+ * so the depth is a count of integer comparisons against the thresholds
+ * thr[m] = floor(4096 * 2^(-m * hbar / b0)), m = 2..bmax (thr[0], thr[1] unused),
+ * which the caller derives from b0 and hbar. */
+int plco_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n,
+                        int32_t k, const uint16_t *thr, int32_t bmax, uint8_t *bits) {
+  if (S < 0 || n < 1 || k < 1 || k > PLCO_MAX_K || bmax < 1 || bmax > PLCO_MAX_BITS)
+    return PLCO_ERR_INVALID;
+  for (int64_t row = 0; row < (int64_t)S * n; ++row) {
+    uint16_t f[PLCO_MAX_K + 1];
+    int rc = plco_index_table(probs + row * k, k, f);
+    if (rc) return rc;
+    int32_t j = chosen[row];
+    if (j < -1 || j >= k) return PLCO_ERR_INVALID;
+    uint32_t fs = f[j < 0 ? k : j];
+    int b = 1;
+    for (int m = 2; m <= bmax; ++m)
+      if (fs <= thr[m]) b = m;
+    bits[row] = (uint8_t)b;
+  }
+  return PLCO_OK;
+}
+
+/* Counts per (stream, bit depth): counts[(stream * n_tables + b - 1) * 256 + sym].
+ * Stream st belongs to session st / streams_per_session; symbol t of a stream
+ * belongs to position t / syms_per_pos. */
+int plco_histogram_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                            int32_t syms_per_pos, int32_t streams_per_session,
+                            const uint8_t *bits, int32_t n_tables, uint32_t *counts) {
+  if (n_streams < 0 || syms_per_stream < 1 || syms_per_pos < 1 || streams_per_session < 1 ||
+      n_tables < 1 || n_tables > PLCO_MAX_BITS || syms_per_stream % syms_per_pos)
+    return PLCO_ERR_INVALID;
+  const int64_t n = syms_per_stream / syms_per_pos;
+  memset(counts, 0, (size_t)n_streams * n_tables * 256 * sizeof(uint32_t));
+  for (int64_t st = 0; st < n_streams; ++st)
+    for (int64_t t = 0; t < syms_per_stream; ++t) {
+      int b = bits[(st / streams_per_session) * n + t / syms_per_pos];
+      if (b < 1 || b > n_tables) return PLCO_ERR_INVALID;
+      counts[(st * n_tables + (b - 1)) * 256 + symbols[st * syms_per_stream + t]] += 1;
+    }
+  return PLCO_OK;
+}
+
+/* Frequency tables for rows of counts where a row may be empty (a bit depth
+ * that does not occur in a stream): such a row gets all-zero frequencies. */
+int plco_build_freq_sparse(const uint32_t *counts, int64_t n_rows, uint16_t *freq) {
+  for (int64_t r = 0; r < n_rows; ++r) {
+    uint64_t T = 0;
+    for (int s = 0; s < 256; ++s) T += counts[r * 256 + s];
+    if (T == 0) {
+      memset(freq + r * 256, 0, 256 * sizeof(uint16_t));
+    } else {
+      int rc = plco_build_freq(counts + r * 256, 1, freq + r * 256, NULL);
+      if (rc) return rc;
+    }
+  }
+  return PLCO_OK;
+}
+
+/* rANS as above, except that symbol t of a stream is coded with the table of
+ * its position's bit depth: freq[(stream * n_tables + b - 1) * 256 + sym]. */
+static int bucket_of(const uint8_t *bits, int64_t st, int64_t t, int64_t n, int32_t syms_per_pos,
+                     int32_t streams_per_session, int32_t n_tables) {
+  int b = bits[(st / streams_per_session) * n + t / syms_per_pos];
+  return (b < 1 || b > n_tables) ? -1 : b - 1;
+}
+
+int plco_rans_encode_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                              int32_t chunk_syms, int32_t syms_per_pos,
+                              int32_t streams_per_session, const uint8_t *bits, int32_t n_tables,
+                              const uint16_t *freq, uint32_t *states, uint16_t *words,
+                              const uint64_t *word_off, uint64_t word_cap_per_unit,
+                              uint32_t *n_words) {
+  int rc = check_rans_args(n_streams, syms_per_stream, chunk_syms);
+  if (rc) return rc;
+  if (syms_per_pos < 1 || syms_per_stream % syms_per_pos || n_tables < 1 || n_tables > PLCO_MAX_BITS)
+    return PLCO_ERR_INVALID;
+  const int64_t N = syms_per_stream, n = N / syms_per_pos;
+  const int64_t U = plco_units_per_stream(N, chunk_syms);
+  const int64_t C = chunk_syms > 0 ? chunk_syms : N;
+  for (int64_t st = 0; st < n_streams; ++st) {
+    uint32_t cum[PLCO_MAX_BITS][257];
+    for (int b = 0; b < n_tables; ++b) {
+      const uint16_t *f = freq + (st * n_tables + b) * 256;
+      cum[b][0] = 0;
+      for (int s = 0; s < 256; ++s) cum[b][s + 1] = cum[b][s] + f[s];
+      if (cum[b][256] != RANS_SCALE && cum[b][256] != 0) return PLCO_ERR_INVALID;
+    }
+    for (int64_t u = 0; u < U; ++u) {
+      int64_t unit = st * U + u, begin = u * C;
+      int64_t len = (begin + C <= N) ? C : (N - begin);
+      uint32_t x[RANS_LANES];
+      uint16_t *out = words + word_off[unit];
+      uint64_t nw = 0;
+      for (int lane = 0; lane < RANS_LANES; ++lane) x[lane] = RANS_LOW;
+      for (int64_t t = len - 1; t >= 0; --t) {
+        int lane = (int)(t % RANS_LANES);
+        int b = bucket_of(bits, st, begin + t, n, syms_per_pos, streams_per_session, n_tables);
+        if (b < 0) return PLCO_ERR_INVALID;
+        uint8_t sym = symbols[st * N + begin + t];
+        uint32_t fs = freq[(st * n_tables + b) * 256 + sym], cs = cum[b][sym];
+        if (fs == 0) return PLCO_ERR_INVALID;
+        if ((x[lane] >> 20) >= fs) {
+          if (nw >= word_cap_per_unit) return PLCO_ERR_CAPACITY;
+          out[nw++] = (uint16_t)(x[lane] & 0xffffu);
+          x[lane] >>= 16;
+        }
+        x[lane] = (x[lane] / fs) * RANS_SCALE + (x[lane] % fs) + cs;
+      }
+      for (int lane = 0; lane < RANS_LANES; ++lane) states[unit * RANS_LANES + lane] = x[lane];
+      n_words[unit] = (uint32_t)nw;
+    }
+  }
+  return PLCO_OK;
+}
+
+int plco_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const uint16_t *words,
+                              const uint64_t *word_off, const uint32_t *n_words,
+                              int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms,
+                              int32_t syms_per_pos, int32_t streams_per_session,
+                              const uint8_t *bits, int32_t n_tables, uint8_t *symbols) {
+  int rc = check_rans_args(n_streams, syms_per_stream, chunk_syms);
+  if (rc) return rc;
+  if (syms_per_pos < 1 || syms_per_stream % syms_per_pos || n_tables < 1 || n_tables > PLCO_MAX_BITS)
+    return PLCO_ERR_INVALID;
+  const int64_t N = syms_per_stream, n = N / syms_per_pos;
+  const int64_t U = plco_units_per_stream(N, chunk_syms);
+  const int64_t C = chunk_syms > 0 ? chunk_syms : N;
+  for (int64_t st = 0; st < n_streams; ++st) {
+    for (int64_t u = 0; u < U; ++u) {
+      int64_t unit = st * U + u, begin = u * C;
+      int64_t len = (begin + C <= N) ? C : (N - begin);
+      uint32_t x[RANS_LANES];
+      const uint16_t *in = words + word_off[unit];
+      uint64_t ptr = n_words[unit];
+      for (int lane = 0; lane < RANS_LANES; ++lane) x[lane] = states[unit * RANS_LANES + lane];
+      for (int64_t t = 0; t < len; ++t) {
+        int lane = (int)(t % RANS_LANES);
+        int b = bucket_of(bits, st, begin + t, n, syms_per_pos, streams_per_session, n_tables);
+        if (b < 0) return PLCO_ERR_INVALID;
+        const uint16_t *f = freq + (st * n_tables + b) * 256;
+        uint32_t slot = x[lane] & (RANS_SCALE - 1), cs = 0;
+        int sym = 0;
+        while (sym < 256 && cs + f[sym] <= slot) { /* the symbol whose interval holds the slot */
+          cs += f[sym];
+          ++sym;
+        }
+        if (sym == 256) return PLCO_ERR_CORRUPT; /* empty table */
+        symbols[st * N + begin + t] = (uint8_t)sym;
+        x[lane] = (uint32_t)f[sym] * (x[lane] >> RANS_SCALE_BITS) + slot - cs;
+        if (x[lane] < RANS_LOW) {
+          if (ptr == 0) return PLCO_ERR_CORRUPT;
+          x[lane] = (x[lane] << 16) | in[--ptr];
+        }
+      }
+      if (ptr != 0) return PLCO_ERR_CORRUPT;
+      for (int lane = 0; lane < RANS_LANES; ++lane)
+        if (x[lane] != RANS_LOW) return PLCO_ERR_CORRUPT;
+    }
   }
   return PLCO_OK;
 }

@@ -53,6 +53,11 @@
  * symbol entropy matches the closed-form pmf of a quantised Gaussian; index
  * tables match closed forms for dyadic rows; the index stream's length obeys
  * the size law against the tokens' surprisal and a hand-worked example.
+ * Adaptive quantiser functions: one bit depth everywhere reduces to the fixed
+ * step functions bit for bit (and one table to the plain histogram, table and
+ * rANS functions); bit depths match the floating formula of the definition on
+ * every frequency; error at most half the position's step; per-depth symbol
+ * statistics match the closed-form pmf.
  * Parity unpinned: the exact bit layout of the rANS streams is this format's
  * own definition, so agreement with any external coder is not sought.
  */
@@ -193,6 +198,53 @@ int plco_index_encode(const float *probs, const int32_t *chosen, int32_t S, int3
 int plco_index_decode(const float *probs, const uint32_t *states, const uint16_t *words,
                       const uint64_t *word_off, const uint32_t *n_words, int32_t S,
                       int32_t n, int32_t k, int32_t *chosen);
+
+/* ---- Surprisal-adaptive quantiser (Def. in Sec. 5.3; Cor. "Practical bit allocation") ----
+ * bits: u8 [S,n], b_i in 1..PLCO_MAX_BITS; the quantiser step of position i is
+ * range * 2^-b_i (range: fp32 > 0, scaled exactly).  chosen as above (all -1
+ * = weighted mean everywhere).  Symbols of positions with depth b are counted
+ * and coded with the stream's table number b - 1. */
+#define PLCO_MAX_BITS 4
+
+int plco_predict_residual_adapt(const plco_dims *dm, int mode,
+                                const uint16_t *cand_k, const uint16_t *cand_v,
+                                const float *probs, const int32_t *chosen,
+                                const uint8_t *bits, float range,
+                                const uint16_t *act_k, const uint16_t *act_v,
+                                uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                                uint32_t *esc_cnt, uint64_t *esc_off,
+                                double *pred_out, double *u_out);
+
+int plco_reconstruct_adapt(const plco_dims *dm, int mode,
+                           const uint16_t *cand_k, const uint16_t *cand_v,
+                           const float *probs, const int32_t *chosen,
+                           const uint8_t *bits, float range, const uint8_t *symbols,
+                           const uint16_t *esc_vals, const uint64_t *esc_off,
+                           uint16_t *out_k, uint16_t *out_v, double *pre_round_out);
+
+/* Bit depth per position from the token's coded surprisal and integer
+ * thresholds thr[2..bmax] (non-increasing): b = the largest m with f <= thr[m], else 1. */
+int plco_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n,
+                        int32_t k, const uint16_t *thr, int32_t bmax, uint8_t *bits);
+
+int plco_histogram_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                            int32_t syms_per_pos, int32_t streams_per_session,
+                            const uint8_t *bits, int32_t n_tables, uint32_t *counts);
+
+int plco_build_freq_sparse(const uint32_t *counts, int64_t n_rows, uint16_t *freq);
+
+int plco_rans_encode_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                              int32_t chunk_syms, int32_t syms_per_pos,
+                              int32_t streams_per_session, const uint8_t *bits, int32_t n_tables,
+                              const uint16_t *freq, uint32_t *states, uint16_t *words,
+                              const uint64_t *word_off, uint64_t word_cap_per_unit,
+                              uint32_t *n_words);
+
+int plco_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const uint16_t *words,
+                              const uint64_t *word_off, const uint32_t *n_words,
+                              int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms,
+                              int32_t syms_per_pos, int32_t streams_per_session,
+                              const uint8_t *bits, int32_t n_tables, uint8_t *symbols);
 
 #ifdef __cplusplus
 }

@@ -93,6 +93,16 @@ def lib():
         L.plco_index_table.argtypes = [p, C.c_int, p]
         L.plco_index_encode.argtypes = [p, p, C.c_int32, C.c_int32, C.c_int32, p, p, p, C.c_uint64, p]
         L.plco_index_decode.argtypes = [p, p, p, p, p, C.c_int32, C.c_int32, C.c_int32, p]
+        L.plco_predict_residual_adapt.argtypes = [C.POINTER(Dims), C.c_int, p, p, p, p, p, C.c_float, p, p, p, p,
+                                                  C.c_uint64, p, p, p, p]
+        L.plco_reconstruct_adapt.argtypes = [C.POINTER(Dims), C.c_int, p, p, p, p, p, C.c_float, p, p, p, p, p, p]
+        L.plco_surprisal_bits.argtypes = [p, p, C.c_int32, C.c_int32, C.c_int32, p, C.c_int32, p]
+        L.plco_histogram_bucketed.argtypes = [p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, p, C.c_int32, p]
+        L.plco_build_freq_sparse.argtypes = [p, C.c_int64, p]
+        L.plco_rans_encode_bucketed.argtypes = [p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_int32, p,
+                                                C.c_int32, p, p, p, p, C.c_uint64, p]
+        L.plco_rans_decode_bucketed.argtypes = [p, p, p, p, p, C.c_int64, C.c_int64, C.c_int32, C.c_int32,
+                                                C.c_int32, p, C.c_int32, p]
         _lib = L
     return _lib
 
@@ -135,12 +145,13 @@ def _i32(a):
 
 
 def predict_residual(dm: Dims, cand_k, cand_v, probs, act_k, act_v, mode=F64,
-                     want_pred=False, want_u=False, esc_cap=None, chosen=None):
+                     want_pred=False, want_u=False, esc_cap=None, chosen=None, bits=None, step_range=None):
     """Returns dict(symbols [streams, N] u8, esc_vals u16, esc_cnt u32, esc_off u64, pred, u).
 
     cand_* / act_* are numpy arrays holding the tensors' storage (fp16 or u16);
     elements are addressed through dm's strides, so any layout works.
-    chosen (i32 [S,n], optional) selects the token-conditional variant.
+    chosen (i32 [S,n], optional) selects the token-conditional variant; bits (u8 [S,n]) with
+    step_range (fp32) on top of it the surprisal-adaptive quantiser.
     """
     ck, cv, ak, av = _u16(cand_k), _u16(cand_v), _u16(act_k), _u16(act_v)
     probs = np.ascontiguousarray(probs, dtype=np.float32)
@@ -159,12 +170,20 @@ def predict_residual(dm: Dims, cand_k, cand_v, probs, act_k, act_v, mode=F64,
         rc = lib().plco_predict_residual(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs),
                                          _ptr(ak), _ptr(av), _ptr(symbols), _ptr(esc_vals),
                                          int(esc_cap), _ptr(esc_cnt), _ptr(esc_off), _ptr(pred), _ptr(u))
-    else:
+    elif bits is None:
         ch = _i32(chosen)
         assert ch.size == dm.S * dm.n
         rc = lib().plco_predict_residual_cond(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(ch),
                                               _ptr(ak), _ptr(av), _ptr(symbols), _ptr(esc_vals),
                                               int(esc_cap), _ptr(esc_cnt), _ptr(esc_off), _ptr(pred), _ptr(u))
+    else:
+        ch = _i32(chosen)
+        bt = np.ascontiguousarray(bits, dtype=np.uint8)
+        assert ch.size == dm.S * dm.n and bt.size == dm.S * dm.n
+        rc = lib().plco_predict_residual_adapt(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(ch),
+                                               _ptr(bt), float(np.float32(step_range)), _ptr(ak), _ptr(av),
+                                               _ptr(symbols), _ptr(esc_vals), int(esc_cap), _ptr(esc_cnt),
+                                               _ptr(esc_off), _ptr(pred), _ptr(u))
     _check(rc, "predict_residual")
     total = int(esc_cnt.sum())
     return dict(symbols=symbols, esc_vals=esc_vals[:total].copy(), esc_cnt=esc_cnt,
@@ -226,7 +245,7 @@ def rans_decode(freq, states, words, word_off, n_words, n_streams, N, chunk_syms
 
 
 def reconstruct(dm: Dims, cand_k, cand_v, probs, symbols, esc_vals, esc_off, mode=F64,
-                want_pre_round=False, out_elems=None, chosen=None):
+                want_pre_round=False, out_elems=None, chosen=None, bits=None, step_range=None):
     """Returns (out_k, out_v) as u16 bit-pattern arrays addressed through dm.act_stride."""
     ck, cv = _u16(cand_k), _u16(cand_v)
     probs = np.ascontiguousarray(probs, dtype=np.float32)
@@ -243,12 +262,19 @@ def reconstruct(dm: Dims, cand_k, cand_v, probs, symbols, esc_vals, esc_off, mod
     if chosen is None:
         rc = lib().plco_reconstruct(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(symbols),
                                     _ptr(esc_vals), _ptr(esc_off), _ptr(out_k), _ptr(out_v), _ptr(pre))
-    else:
+    elif bits is None:
         ch = _i32(chosen)
         assert ch.size == dm.S * dm.n
         rc = lib().plco_reconstruct_cond(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(ch),
                                          _ptr(symbols), _ptr(esc_vals), _ptr(esc_off), _ptr(out_k),
                                          _ptr(out_v), _ptr(pre))
+    else:
+        ch = _i32(chosen)
+        bt = np.ascontiguousarray(bits, dtype=np.uint8)
+        assert ch.size == dm.S * dm.n and bt.size == dm.S * dm.n
+        rc = lib().plco_reconstruct_adapt(C.byref(dm), mode, _ptr(ck), _ptr(cv), _ptr(probs), _ptr(ch), _ptr(bt),
+                                          float(np.float32(step_range)), _ptr(symbols), _ptr(esc_vals),
+                                          _ptr(esc_off), _ptr(out_k), _ptr(out_v), _ptr(pre))
     _check(rc, "reconstruct")
     if want_pre_round:
         return out_k, out_v, pre.reshape(symbols.shape)
@@ -300,6 +326,84 @@ def index_decode(probs, states, words, word_off, n_words):
     _check(lib().plco_index_decode(_ptr(probs), _ptr(states), _ptr(words), _ptr(word_off), _ptr(n_words),
                                    S, n, k, _ptr(chosen)), "index_decode")
     return chosen
+
+
+MAX_BITS = 4
+
+
+def surprisal_thresholds(b0, hbar, bmax=MAX_BITS):
+    """thr[m] = floor(4096 * 2^(-m * hbar / b0)) for m = 2..bmax (entries 0 and 1 unused)."""
+    thr = np.zeros(bmax + 1, dtype=np.uint16)
+    for m in range(2, bmax + 1):
+        thr[m] = int(np.floor(4096.0 * 2.0 ** (-m * float(hbar) / float(b0))))
+    return thr
+
+
+def surprisal_bits(probs, chosen, thr):
+    probs = np.ascontiguousarray(probs, dtype=np.float32)
+    S, n, k = probs.shape
+    ch = _i32(chosen)
+    thr = np.ascontiguousarray(thr, dtype=np.uint16)
+    bits = np.empty((S, n), dtype=np.uint8)
+    _check(lib().plco_surprisal_bits(_ptr(probs), _ptr(ch), S, n, k, _ptr(thr), thr.size - 1, _ptr(bits)),
+           "surprisal_bits")
+    return bits
+
+
+def histogram_bucketed(symbols, syms_per_pos, streams_per_session, bits, n_tables=MAX_BITS):
+    symbols = np.ascontiguousarray(symbols, dtype=np.uint8)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    n_streams, N = symbols.shape
+    counts = np.empty((n_streams, n_tables, 256), dtype=np.uint32)
+    _check(lib().plco_histogram_bucketed(_ptr(symbols), n_streams, N, syms_per_pos, streams_per_session,
+                                         _ptr(bits), n_tables, _ptr(counts)), "histogram_bucketed")
+    return counts
+
+
+def build_freq_sparse(counts):
+    counts = np.ascontiguousarray(counts, dtype=np.uint32)
+    freq = np.empty(counts.shape, dtype=np.uint16)
+    _check(lib().plco_build_freq_sparse(_ptr(counts), counts.size // 256, _ptr(freq)), "build_freq_sparse")
+    return freq
+
+
+def rans_encode_bucketed(symbols, freq, syms_per_pos, streams_per_session, bits, chunk_syms=0,
+                         word_cap_per_unit=None):
+    symbols = np.ascontiguousarray(symbols, dtype=np.uint8)
+    freq = np.ascontiguousarray(freq, dtype=np.uint16)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    n_streams, N = symbols.shape
+    n_tables = freq.shape[1]
+    U = units_per_stream(N, chunk_syms)
+    unit_syms = chunk_syms if chunk_syms > 0 else N
+    if word_cap_per_unit is None:
+        word_cap_per_unit = unit_syms
+    n_units = n_streams * U
+    states = np.empty((n_units, 32), dtype=np.uint32)
+    words = np.zeros(max(n_units * word_cap_per_unit, 1), dtype=np.uint16)
+    word_off = np.arange(n_units, dtype=np.uint64) * np.uint64(word_cap_per_unit)
+    n_words = np.zeros(n_units, dtype=np.uint32)
+    rc = lib().plco_rans_encode_bucketed(_ptr(symbols), n_streams, N, chunk_syms, syms_per_pos,
+                                         streams_per_session, _ptr(bits), n_tables, _ptr(freq), _ptr(states),
+                                         _ptr(words), _ptr(word_off), int(word_cap_per_unit), _ptr(n_words))
+    _check(rc, "rans_encode_bucketed")
+    return dict(states=states, words=words, word_off=word_off, n_words=n_words)
+
+
+def rans_decode_bucketed(freq, states, words, word_off, n_words, n_streams, N, syms_per_pos,
+                         streams_per_session, bits, chunk_syms=0):
+    freq = np.ascontiguousarray(freq, dtype=np.uint16)
+    states = np.ascontiguousarray(states, dtype=np.uint32)
+    words = np.ascontiguousarray(words, dtype=np.uint16)
+    word_off = np.ascontiguousarray(word_off, dtype=np.uint64)
+    n_words = np.ascontiguousarray(n_words, dtype=np.uint32)
+    bits = np.ascontiguousarray(bits, dtype=np.uint8)
+    symbols = np.empty((n_streams, N), dtype=np.uint8)
+    rc = lib().plco_rans_decode_bucketed(_ptr(freq), _ptr(states), _ptr(words), _ptr(word_off), _ptr(n_words),
+                                         n_streams, N, chunk_syms, syms_per_pos, streams_per_session,
+                                         _ptr(bits), freq.shape[1], _ptr(symbols))
+    _check(rc, "rans_decode_bucketed")
+    return symbols
 
 
 def coded_bits(n_words, esc_cnt, n_streams):
