@@ -273,6 +273,80 @@ int plc_index_decode(const float *probs, const uint32_t *states, const uint16_t 
                      void *stream);
 
 /*
+ * ---- Surprisal-adaptive quantiser ---------------------------------------------
+ * Def. "Surprisal-adaptive quantizer" (Sec. 5.3): position i gets b_i = max(1,
+ * floor(b0 * h_i / hbar)) bits per residual component, h_i its surprisal and
+ * hbar the average; Cor. "Practical bit allocation" (Sec. 9.4): b bits stand
+ * for a uniform step of range / 2^b.  Here b_i is capped at PLC_MAX_BITS, the
+ * step of position i is the fp32 value range * 2^-b_i (an exact scaling), and
+ * the symbols of positions with depth b are counted and coded with table number
+ * b - 1 of their stream, so that each depth has statistics of its own.
+ *
+ *   bits    u8 [S,n], values 1..PLC_MAX_BITS, shared by all layers, heads, K and V of a position
+ *           (any other value raises status PLC_ERR_INVALID and counts as 1).
+ *   range   fp32 > 0.
+ */
+#define PLC_MAX_BITS 4
+
+/*
+ * b_i from the token's coded surprisal h_i = log2(4096 / f), f the frequency of the position's
+ * index symbol (see plc_index_encode; symbol k for chosen = -1):
+ *   floor(b0 * h_i / hbar) >= m   <=>   f <= 4096 * 2^(-m * hbar / b0),
+ * so with thr[m] = floor(4096 * 2^(-m * hbar / b0)) for m = 2..bmax (host array of bmax + 1
+ * entries, entries 0 and 1 unused, non-increasing) the depth is the largest m with f <= thr[m],
+ * or 1.  Integer comparisons only: encoder and decoder agree bit for bit.
+ *   bits  out, u8 [S,n].
+ */
+int plc_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n, int32_t k,
+                       const uint16_t *thr /* host */, int32_t bmax, uint8_t *bits,
+                       uint32_t *status, void *stream);
+
+/* As plc_predict_residual_cond / plc_reconstruct_cond (chosen all -1 = weighted mean everywhere),
+ * with the step of position (s,i) = range * 2^-bits[s,i] in place of dims->delta. */
+int plc_predict_residual_adapt(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                               const float *probs, const int32_t *chosen, const uint8_t *bits,
+                               float range, const void *act_k, const void *act_v, uint8_t *symbols,
+                               uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt,
+                               uint64_t *esc_off, float *pred_out, void *ws, size_t ws_bytes,
+                               uint32_t *status, void *stream);
+
+int plc_reconstruct_adapt(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                          const float *probs, const int32_t *chosen, const uint8_t *bits,
+                          float range, const uint8_t *symbols, const uint16_t *esc_vals,
+                          uint64_t esc_len, const uint64_t *esc_off, void *out_k, void *out_v,
+                          void *ws, size_t ws_bytes, uint32_t *status, void *stream);
+
+/*
+ * Statistics, tables and rANS with one table per depth.  Stream st belongs to session
+ * st / streams_per_session; symbol t of a stream belongs to position t / syms_per_pos
+ * (syms_per_pos = 2d for the KV layout; a multiple of 32, so that a group of 32 symbols never
+ * straddles two positions; syms_per_stream a multiple of it).
+ *   counts  out, u32 [n_streams, n_tables, 256];   freq  u16 [n_streams, n_tables, 256]: a depth that
+ *           does not occur in a stream has an all-zero table, the others sum to 4096 exactly as in
+ *           plc_build_freq.  n_tables in 1..PLC_MAX_BITS.  symbols 16-byte aligned.
+ * Everything else as in plc_histogram / plc_build_freq / plc_rans_encode / plc_rans_decode.
+ */
+int plc_histogram_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                           int32_t syms_per_pos, int32_t streams_per_session, const uint8_t *bits,
+                           int32_t n_tables, uint32_t *counts, uint32_t *status, void *stream);
+
+int plc_build_freq_bucketed(const uint32_t *counts, int64_t n_streams, int32_t n_tables,
+                            uint16_t *freq, uint32_t *status, void *stream);
+
+int plc_rans_encode_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                             int32_t chunk_syms, int32_t syms_per_pos, int32_t streams_per_session,
+                             const uint8_t *bits, int32_t n_tables, const uint16_t *freq,
+                             uint32_t *states, uint16_t *words, const uint64_t *word_off,
+                             uint64_t word_cap_per_unit, uint32_t *n_words, uint32_t *status,
+                             void *stream);
+
+int plc_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const uint16_t *words,
+                             uint64_t words_len, const uint64_t *word_off, const uint32_t *n_words,
+                             int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms,
+                             int32_t syms_per_pos, int32_t streams_per_session, const uint8_t *bits,
+                             int32_t n_tables, uint8_t *symbols, uint32_t *status, void *stream);
+
+/*
  * Instrumentation for benchmarks (not part of the coding path; process-wide,
  * not thread-safe).  While a pair of hipEvent_t (passed as void*) is set for
  * a kernel id, each later call records `start` immediately before and `stop`

@@ -6,7 +6,9 @@ the entry points in order.
 Two paths share the buffers: the weighted-mean path (encode / decode) and the
 token-conditional path (encode_cond / decode_cond), which predicts every
 position from the candidate of its true token and codes that candidate's index
-in a stream of its own."""
+in a stream of its own.  encode_adapt / decode_adapt add the surprisal-adaptive
+quantiser on top of the latter: a bit depth per position from the token's
+surprisal, a step of range / 2^depth, and one frequency table per depth."""
 from __future__ import annotations
 
 import dataclasses
@@ -36,6 +38,10 @@ class Coded:
     idx_words: torch.Tensor = None      # i16 [S * idx_word_cap]
     idx_word_off: torch.Tensor = None   # i64 [S]
     idx_n_words: torch.Tensor = None    # i32 [S]
+    # adaptive path only
+    bits: torch.Tensor = None           # u8 [S, n] bit depth per position
+    counts_d: torch.Tensor = None       # i32 [streams, MAX_BITS, 256]
+    freq_d: torch.Tensor = None         # i16 [streams, MAX_BITS, 256]
 
 
 class KVDeltaCodec:
@@ -123,6 +129,49 @@ class KVDeltaCodec:
     def decode(self, cand_k, cand_v, probs, out_k, out_v):
         self.rans_decode()
         self.reconstruct(cand_k, cand_v, probs, out_k, out_v)
+
+    # -- surprisal-adaptive quantiser on the token-conditional path --------------------------
+    def _adapt_buffers(self):
+        if not hasattr(self, "bits"):
+            dev = self.device
+            self.bits = torch.empty((self.S, self.n), dtype=torch.uint8, device=dev)
+            self.dec_bits = torch.empty_like(self.bits)
+            self.counts_d = torch.empty((self.n_streams, plc.MAX_BITS, 256), dtype=torch.int32, device=dev)
+            self.freq_d = torch.empty((self.n_streams, plc.MAX_BITS, 256), dtype=torch.int16, device=dev)
+
+    def encode_adapt(self, cand_k, cand_v, probs, act_k, act_v, chosen, thr, step_range) -> Coded:
+        """thr: thresholds from plc.surprisal_thresholds(b0, hbar); step_range: fp32 range of the quantiser."""
+        self._adapt_buffers()
+        if chosen is not self.chosen:
+            self.chosen.copy_(chosen)
+        B, spp, sps = plc.MAX_BITS, 2 * self.d, self.L * self.H
+        plc.plc_surprisal_bits(probs, self.chosen, self.S, self.n, self.k, thr, self.bits, self.status)
+        plc.plc_predict_residual_adapt(self.dims, cand_k, cand_v, probs, self.chosen, self.bits, step_range, act_k,
+                                       act_v, self.symbols, self.esc_vals, self.esc_cnt, self.esc_off, self.ws,
+                                       self.status, pred_out=self.pred)
+        plc.plc_histogram_bucketed(self.symbols, self.n_streams, self.N, spp, sps, self.bits, B, self.counts_d,
+                                   self.status)
+        plc.plc_build_freq_bucketed(self.counts_d, self.n_streams, B, self.freq_d, self.status)
+        plc.plc_rans_encode_bucketed(self.symbols, self.n_streams, self.N, self.chunk_syms, spp, sps, self.bits, B,
+                                     self.freq_d, self.states, self.words, self.word_off, self.word_cap,
+                                     self.n_words, self.status)
+        plc.plc_index_encode(probs, self.chosen, self.S, self.n, self.k, self.idx_states, self.idx_words,
+                             self.idx_word_off, self.idx_word_cap, self.idx_n_words, self.status)
+        c = self.coded(cond=True)
+        c.bits, c.counts_d, c.freq_d = self.bits, self.counts_d, self.freq_d
+        return c
+
+    def decode_adapt(self, cand_k, cand_v, probs, out_k, out_v, thr, step_range):
+        """From the coded artefacts alone: the index stream gives the tokens, the tokens the bit depths."""
+        B, spp, sps = plc.MAX_BITS, 2 * self.d, self.L * self.H
+        plc.plc_index_decode(probs, self.idx_states, self.idx_words, self.idx_word_off, self.idx_n_words,
+                             self.S, self.n, self.k, self.dec_chosen, self.status)
+        plc.plc_surprisal_bits(probs, self.dec_chosen, self.S, self.n, self.k, thr, self.dec_bits, self.status)
+        plc.plc_rans_decode_bucketed(self.freq_d, self.states, self.words, self.word_off, self.n_words,
+                                     self.n_streams, self.N, self.chunk_syms, spp, sps, self.dec_bits, B,
+                                     self.dec_symbols, self.status)
+        plc.plc_reconstruct_adapt(self.dims, cand_k, cand_v, probs, self.dec_chosen, self.dec_bits, step_range,
+                                  self.dec_symbols, self.esc_vals, self.esc_off, out_k, out_v, self.ws, self.status)
 
     # -- token-conditional path ----------------------------------------------------------
     def select_candidate(self, cand_k, act_k, max_mean_sq):

@@ -59,10 +59,56 @@ __global__ __launch_bounds__(kBlock) void histogram_kernel(const uint8_t *__rest
   if (c) atomicAdd(&counts[(int64_t)stream * 256 + threadIdx.x], c);
 }
 
-// One wavefront per stream; lane L owns symbols 4L .. 4L+3.
+// The same with one histogram per bit depth: the depth of a symbol is that of its position, and a
+// thread's 16 symbols always share a position (positions hold a multiple of 16 symbols).
+__global__ __launch_bounds__(kBlock) void histogram_bucketed_kernel(const uint8_t *__restrict__ symbols,
+                                                                    int64_t syms_per_stream, uint32_t segs_per_stream,
+                                                                    uint32_t syms_per_pos, uint32_t streams_per_session,
+                                                                    const uint8_t *__restrict__ bits, int n_tables,
+                                                                    uint32_t *__restrict__ counts, uint32_t *status) {
+  __shared__ uint32_t hist[kBlock / 64][PLC_MAX_BITS][256];
+  const uint32_t stream = blockIdx.x / segs_per_stream;
+  const uint32_t seg = blockIdx.x - stream * segs_per_stream;
+  const int wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int w = 0; w < kBlock / 64; ++w)
+#pragma unroll
+    for (int t = 0; t < PLC_MAX_BITS; ++t) hist[w][t][threadIdx.x] = 0u;
+  __syncthreads();
+
+  const int64_t seg_begin = (int64_t)seg * kHistSegment;
+  const int64_t seg_end = seg_begin + kHistSegment < syms_per_stream ? seg_begin + kHistSegment : syms_per_stream;
+  const uint8_t *base = symbols + (int64_t)stream * syms_per_stream;
+  const uint8_t *brow = bits + (int64_t)(stream / streams_per_session) * (syms_per_stream / syms_per_pos);
+  for (int64_t t0 = seg_begin + (int64_t)threadIdx.x * 16; t0 < seg_end; t0 += kBlock * 16) {
+    int b = brow[t0 / syms_per_pos];
+    if (b < 1 || b > n_tables) {
+      raise(status, PLC_ERR_INVALID);
+      b = 1;
+    }
+    uint32_t *h = hist[wave][b - 1];
+    const uint4 v = load16_stream(base + t0);
+    const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) atomicAdd(&h[(wds[j] >> (8 * q)) & 255u], 1u);
+    }
+  }
+  __syncthreads();
+  for (int t = 0; t < n_tables; ++t) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) c += hist[w][t][threadIdx.x];
+    if (c) atomicAdd(&counts[((int64_t)stream * n_tables + t) * 256 + threadIdx.x], c);
+  }
+}
+
+// One wavefront per stream; lane L owns symbols 4L .. 4L+3.  `allow_empty`: a row without any count is
+// not an error and gets all-zero frequencies (a bit depth that does not occur in a stream).
 __global__ __launch_bounds__(kBlock) void build_freq_kernel(const uint32_t *__restrict__ counts, int64_t n_streams,
                                                             uint16_t *__restrict__ freq, uint16_t *__restrict__ cum,
-                                                            uint32_t *status) {
+                                                            bool allow_empty, uint32_t *status) {
   const int lane = threadIdx.x & 63;
   const int64_t stream = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
   if (stream >= n_streams) return;  // uniform per wavefront
@@ -84,7 +130,7 @@ __global__ __launch_bounds__(kBlock) void build_freq_kernel(const uint32_t *__re
   const uint64_t before = inc - run[3];
   const uint64_t T = __shfl(inc, 63, 64);
   if (T == 0) {
-    if (lane == 0) raise(status, PLC_ERR_INVALID);
+    if (lane == 0 && !allow_empty) raise(status, PLC_ERR_INVALID);
     *reinterpret_cast<uint2 *>(freq + stream * 256 + lane * 4) = make_uint2(0u, 0u);
     if (cum) {
       for (int r = 0; r < 4; ++r) cum[stream * 257 + lane * 4 + r] = 0;
@@ -179,6 +225,37 @@ extern "C" int plc_build_freq(const uint32_t *counts, int64_t n_streams, uint16_
   const int64_t blocks = (n_streams + kBlock / 64 - 1) / (kBlock / 64);
   if (blocks >= (1ll << 31)) return PLC_ERR_INVALID;
   hipLaunchKernelGGL(build_freq_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, static_cast<hipStream_t>(stream),
-                     counts, n_streams, freq, cum, status);
+                     counts, n_streams, freq, cum, false, status);
+  return launch_status();
+}
+
+extern "C" int plc_histogram_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                                      int32_t syms_per_pos, int32_t streams_per_session, const uint8_t *bits,
+                                      int32_t n_tables, uint32_t *counts, uint32_t *status, void *stream) {
+  if (!symbols || !counts || !bits || !status || n_streams < 1 || syms_per_stream < 1) return PLC_ERR_INVALID;
+  if (syms_per_stream >= (1ll << 32) || n_tables < 1 || n_tables > PLC_MAX_BITS) return PLC_ERR_INVALID;
+  if (syms_per_pos < 32 || syms_per_pos % 32 || syms_per_stream % syms_per_pos || streams_per_session < 1)
+    return PLC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(counts) % 16 || reinterpret_cast<uintptr_t>(symbols) % 16) return PLC_ERR_INVALID;
+  const int64_t segs = (syms_per_stream + kHistSegment - 1) / kHistSegment;
+  if (n_streams * segs >= (1ll << 31) || n_streams >= (1ll << 31) / (256 * PLC_MAX_BITS)) return PLC_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t n = n_streams * n_tables * 256;
+  hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, counts, n);
+  hipLaunchKernelGGL(histogram_bucketed_kernel, dim3((unsigned)(n_streams * segs)), dim3(kBlock), 0, st, symbols,
+                     syms_per_stream, (uint32_t)segs, (uint32_t)syms_per_pos, (uint32_t)streams_per_session, bits,
+                     n_tables, counts, status);
+  return launch_status();
+}
+
+extern "C" int plc_build_freq_bucketed(const uint32_t *counts, int64_t n_streams, int32_t n_tables, uint16_t *freq,
+                                       uint32_t *status, void *stream) {
+  if (!counts || !freq || !status || n_streams < 1 || n_tables < 1 || n_tables > PLC_MAX_BITS) return PLC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(counts) % 16 || reinterpret_cast<uintptr_t>(freq) % 8) return PLC_ERR_INVALID;
+  const int64_t rows = n_streams * n_tables;
+  const int64_t blocks = (rows + kBlock / 64 - 1) / (kBlock / 64);
+  if (blocks >= (1ll << 31)) return PLC_ERR_INVALID;
+  hipLaunchKernelGGL(build_freq_kernel, dim3((unsigned)blocks), dim3(kBlock), 0, static_cast<hipStream_t>(stream),
+                     counts, rows, freq, (uint16_t *)nullptr, true, status);
   return launch_status();
 }

@@ -152,6 +152,31 @@ __global__ __launch_bounds__(64) void index_decode_kernel(const float *__restric
   if (corrupt) raise(status, PLC_ERR_CORRUPT);
 }
 
+struct Thresholds {
+  uint16_t thr[PLC_MAX_BITS + 1];
+};
+
+// Bit depth of every position from the frequency of its index symbol; one thread per position.
+__global__ __launch_bounds__(kBlock) void surprisal_bits_kernel(const float *__restrict__ probs,
+                                                                const int32_t *__restrict__ chosen, int64_t rows,
+                                                                int k, Thresholds t, int bmax,
+                                                                uint8_t *__restrict__ bits, uint32_t *status) {
+  const int64_t row = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (row >= rows) return;
+  uint32_t f[kMaxK + 1];
+  if (!index_table(probs + row * k, k, f)) raise(status, PLC_ERR_INVALID);
+  int j = chosen[row];
+  if (j < -1 || j >= k) {
+    raise(status, PLC_ERR_INVALID);
+    j = -1;
+  }
+  const uint32_t fs = f[j < 0 ? k : j];
+  int b = 1;
+  for (int m = 2; m <= bmax; ++m)
+    if (fs <= t.thr[m]) b = m;
+  bits[row] = (uint8_t)b;
+}
+
 int check(const float *probs, int32_t S, int32_t n, int32_t k, const void *states, const void *word_off,
           const void *n_words, const void *chosen, const void *status) {
   if (S < 1 || n < 1 || k < 1 || k > kMaxK) return PLC_ERR_INVALID;
@@ -187,5 +212,24 @@ extern "C" int plc_index_decode(const float *probs, const uint32_t *states, cons
   if ((words_len > 0 && !words) || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
   hipLaunchKernelGGL(index_decode_kernel, dim3((unsigned)S), dim3(64), 0, static_cast<hipStream_t>(stream), probs,
                      states, words, words_len, word_off, n_words, n, k, chosen, status);
+  return launch_status();
+}
+
+extern "C" int plc_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n, int32_t k,
+                                  const uint16_t *thr, int32_t bmax, uint8_t *bits, uint32_t *status,
+                                  void *stream) {
+  if (S < 1 || n < 1 || k < 1 || k > kMaxK || bmax < 1 || bmax > PLC_MAX_BITS) return PLC_ERR_INVALID;
+  if (!probs || !chosen || !thr || !bits || !status) return PLC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(probs) % 4 || reinterpret_cast<uintptr_t>(chosen) % 4 ||
+      reinterpret_cast<uintptr_t>(status) % 4)
+    return PLC_ERR_INVALID;
+  Thresholds t = {};
+  for (int m = 2; m <= bmax; ++m) {
+    if (m > 2 && thr[m] > thr[m - 1]) return PLC_ERR_INVALID;
+    t.thr[m] = thr[m];
+  }
+  const int64_t rows = (int64_t)S * n;
+  hipLaunchKernelGGL(surprisal_bits_kernel, dim3((unsigned)((rows + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                     static_cast<hipStream_t>(stream), probs, chosen, rows, k, t, bmax, bits, status);
   return launch_status();
 }

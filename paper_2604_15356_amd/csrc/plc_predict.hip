@@ -28,6 +28,8 @@ struct CodecArgs {
   uint16_t *out_k, *out_v;        // decode only
   const float *weights;           // [S, n, k] renormalised weights
   const int32_t *chosen;          // [S, n] index of the true candidate or -1 (token-conditional calls only)
+  const uint8_t *bits;            // [S, n] bit depth of the position (adaptive calls only)
+  float range;                    // adaptive calls: step = range * 2^-bits
   uint8_t *symbols;               // encode: out, decode: in
   const uint16_t *esc_in;         // decode
   uint64_t esc_len;               // decode
@@ -126,6 +128,17 @@ __device__ __forceinline__ void predict8(const uint16_t *cand, int64_t sj, const
       for (int e = 0; e < kChunk; ++e) pred[e] = __builtin_fmaf(wj, (float)c[e], pred[e]);
     }
   }
+}
+
+// Quantiser step of a chunk's position: the configured one, or range * 2^-b for the adaptive calls.
+__device__ __forceinline__ float position_step(const CodecArgs &a, int64_t row) {
+  if (!a.bits) return a.delta;
+  int b = a.bits[row];
+  if (b < 1 || b > PLC_MAX_BITS) {
+    raise(a.status, PLC_ERR_INVALID);
+    b = 1;
+  }
+  return __builtin_ldexpf(a.range, -b);
 }
 
 // The prediction of one chunk.  COND: the position names its true candidate, whose vector then is the
@@ -293,7 +306,8 @@ __global__ __launch_bounds__(kBlock) void predict_residual_cond_kernel(const Cod
         predict8<K>((q[t].c ? a.cand_v : a.cand_k) + q[t].cand, a.cs[4], a.weights + q[t].w, a.k, pred);
       }
       uint32_t packed[2];
-      quantise8(__builtin_bit_cast(half8, av[t]), pred, a.delta, a.qmax, packed, &n_esc[t], &esc_bits[t]);
+      quantise8(__builtin_bit_cast(half8, av[t]), pred, position_step(a, q[t].row), a.qmax, packed, &n_esc[t],
+                &esc_bits[t]);
       store8_stream(a.symbols + q[t].sym, packed[0], packed[1]);
       if (a.pred_out) {
         float4 *po = reinterpret_cast<float4 *>(a.pred_out + q[t].sym);
@@ -436,12 +450,13 @@ __global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) 
     sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
     float pred[kChunk];
     predict_chunk<K, COND>(a, q, cand, pred);
+    const float step = COND ? position_step(a, q.row) : a.delta;
 #pragma unroll
     for (int e = 0; e < kChunk; ++e) {
       const uint32_t sym = ((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u;
       n_esc += sym == PLC_ESCAPE;
       const float qf = (float)((int)sym - (int)kZeroSymbol);
-      float v = __builtin_fmaf(qf, a.delta, pred[e]);
+      float v = __builtin_fmaf(qf, step, pred[e]);
       // Two roundings are the contract: to fp32 here, then to fp16 (nearest even).  Left to itself the
       // compiler may merge both into one fused multiply-add with an fp16 result, which rounds once and
       // lands on the other neighbour when the fp32 value is an exact fp16 tie.
@@ -613,7 +628,7 @@ namespace plc {
 namespace {
 
 int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
-                  const int32_t *chosen, int trace_id, const void *act_k, const void *act_v, uint8_t *symbols,
+                  const int32_t *chosen, const uint8_t *bits, float range, int trace_id, const void *act_k, const void *act_v, uint8_t *symbols,
                   uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
                   void *ws, size_t ws_bytes, uint32_t *status, void *stream) {
   Plan p;
@@ -637,6 +652,8 @@ int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
   a.pred_out = pred_out;
   a.status = status;
   a.chosen = chosen;
+  a.bits = bits;
+  a.range = range;
   float *weights = const_cast<float *>(a.weights);
   uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
 
@@ -656,7 +673,7 @@ int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
 }
 
 int decode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
-                  const int32_t *chosen, int trace_id, const uint8_t *symbols, const uint16_t *esc_vals,
+                  const int32_t *chosen, const uint8_t *bits, float range, int trace_id, const uint8_t *symbols, const uint16_t *esc_vals,
                   uint64_t esc_len, const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
                   uint32_t *status, void *stream) {
   Plan p;
@@ -680,6 +697,8 @@ int decode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
   a.esc_off = esc_off;
   a.status = status;
   a.chosen = chosen;
+  a.bits = bits;
+  a.range = range;
   float *weights = const_cast<float *>(a.weights);
   uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
 
@@ -703,7 +722,7 @@ extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, co
                                     uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
                                     uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out, void *ws,
                                     size_t ws_bytes, uint32_t *status, void *stream) {
-  return encode_floats(dims, cand_k, cand_v, probs, nullptr, PLC_TRACE_PREDICT, act_k, act_v, symbols, esc_vals,
+  return encode_floats(dims, cand_k, cand_v, probs, nullptr, nullptr, 0.0f, PLC_TRACE_PREDICT, act_k, act_v, symbols, esc_vals,
                        esc_cap, esc_cnt, esc_off, pred_out, ws, ws_bytes, status, stream);
 }
 
@@ -713,7 +732,7 @@ extern "C" int plc_predict_residual_cond(const plc_dims *dims, const void *cand_
                                          uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
                                          void *ws, size_t ws_bytes, uint32_t *status, void *stream) {
   if (!aligned(chosen, 4)) return PLC_ERR_INVALID;
-  return encode_floats(dims, cand_k, cand_v, probs, chosen, PLC_TRACE_PREDICT_COND, act_k, act_v, symbols,
+  return encode_floats(dims, cand_k, cand_v, probs, chosen, nullptr, 0.0f, PLC_TRACE_PREDICT_COND, act_k, act_v, symbols,
                        esc_vals, esc_cap, esc_cnt, esc_off, pred_out, ws, ws_bytes, status, stream);
 }
 
@@ -721,7 +740,7 @@ extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const v
                                const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
                                const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
                                uint32_t *status, void *stream) {
-  return decode_floats(dims, cand_k, cand_v, probs, nullptr, PLC_TRACE_RECONSTRUCT, symbols, esc_vals, esc_len,
+  return decode_floats(dims, cand_k, cand_v, probs, nullptr, nullptr, 0.0f, PLC_TRACE_RECONSTRUCT, symbols, esc_vals, esc_len,
                        esc_off, out_k, out_v, ws, ws_bytes, status, stream);
 }
 
@@ -731,8 +750,29 @@ extern "C" int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, co
                                     void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
                                     void *stream) {
   if (!aligned(chosen, 4)) return PLC_ERR_INVALID;
-  return decode_floats(dims, cand_k, cand_v, probs, chosen, PLC_TRACE_RECONSTRUCT_COND, symbols, esc_vals,
+  return decode_floats(dims, cand_k, cand_v, probs, chosen, nullptr, 0.0f, PLC_TRACE_RECONSTRUCT_COND, symbols, esc_vals,
                        esc_len, esc_off, out_k, out_v, ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_predict_residual_adapt(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                          const float *probs, const int32_t *chosen, const uint8_t *bits,
+                                          float range, const void *act_k, const void *act_v, uint8_t *symbols,
+                                          uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt,
+                                          uint64_t *esc_off, float *pred_out, void *ws, size_t ws_bytes,
+                                          uint32_t *status, void *stream) {
+  if (!aligned(chosen, 4) || !bits || !(range > 0.0f) || !(range < 3.0e38f)) return PLC_ERR_INVALID;
+  return encode_floats(dims, cand_k, cand_v, probs, chosen, bits, range, PLC_TRACE_PREDICT_COND, act_k, act_v,
+                       symbols, esc_vals, esc_cap, esc_cnt, esc_off, pred_out, ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_reconstruct_adapt(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                     const float *probs, const int32_t *chosen, const uint8_t *bits, float range,
+                                     const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
+                                     const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
+                                     uint32_t *status, void *stream) {
+  if (!aligned(chosen, 4) || !bits || !(range > 0.0f) || !(range < 3.0e38f)) return PLC_ERR_INVALID;
+  return decode_floats(dims, cand_k, cand_v, probs, chosen, bits, range, PLC_TRACE_RECONSTRUCT_COND, symbols,
+                       esc_vals, esc_len, esc_off, out_k, out_v, ws, ws_bytes, status, stream);
 }
 
 extern "C" int plc_select_candidate(const plc_dims *dims, const void *cand_k, const void *act_k,

@@ -51,7 +51,23 @@ struct RansArgs {
   uint32_t *status;
   int64_t n_units, units_per_stream, syms_per_stream, unit_syms;
   uint32_t wgs_per_stream;
+  // one table per bit depth (the *_bucketed calls): symbol t of a stream uses table bits[...] - 1 of its position
+  const uint8_t *bits;
+  int32_t syms_per_pos, streams_per_session, n_tables;
 };
+
+// Offset (in table entries of `stride` each) of the table that the 32 symbols from unit-relative group g on use.
+__device__ __forceinline__ uint32_t group_table(const RansArgs &a, int64_t stream, int64_t begin, int32_t g,
+                                                uint32_t stride, bool *bad) {
+  const int64_t pos = (begin + (int64_t)g * kLanes) / a.syms_per_pos;
+  const int64_t n_pos = a.syms_per_stream / a.syms_per_pos;
+  int b = a.bits[(stream / a.streams_per_session) * n_pos + pos];
+  if (b < 1 || b > a.n_tables) {
+    *bad = true;
+    b = 1;
+  }
+  return (uint32_t)(b - 1) * stride;
+}
 
 // Frequencies of symbols 4*lane .. 4*lane+3 and the cumulative frequency in
 // front of them, for all 64 lanes of a wavefront.  Returns the table's total.
@@ -201,9 +217,10 @@ __device__ __forceinline__ void enc_step_pinned(uint32_t &x, const uint4 e, uint
   flags |= e.w;
 }
 
-template <int W>
+template <int W, bool ADAPT>
 __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
-  __shared__ uint4 table[256];
+  __shared__ uint4 table[ADAPT ? PLC_MAX_BITS * 256 : 256];
+  __shared__ uint16_t table_of_group[ADAPT ? W : 1][2][kSuperGroups];  // ADAPT: table offset of each staged group
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[W][2][kSymStage];
   __shared__ __attribute__((aligned(16))) uint16_t word_stage[W][kBatchSyms + 8 + 64];  // list + carry + scratch slots
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -211,8 +228,8 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
   const int64_t chunk = (int64_t)(blockIdx.x - stream * a.wgs_per_stream) * W + wave;
   const bool live = chunk < a.units_per_stream;
 
-  bool long_form;
-  {  // every wavefront scans the frequencies; entry 4*lane + r is built by wavefront (4*lane + r) mod W
+  bool long_form = false;
+  if (!ADAPT) {  // every wavefront scans the frequencies; entry 4*lane + r is built by wavefront (4*lane + r) mod W
     uint32_t f[4], cum;
     const uint32_t total = load_freq4(a.freq + stream * 256, lane, f, &cum);
     if (total != kScale && threadIdx.x == 0) raise(a.status, PLC_ERR_INVALID);
@@ -223,6 +240,22 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
       if ((s & (W - 1)) == wave)
         table[s] = long_form ? make_enc_entry<true>(f[r], cum) : make_enc_entry<false>(f[r], cum);
       cum += f[r];
+    }
+  } else {  // one table per bit depth; an all-zero table (a depth the stream does not use) holds only invalid entries
+    uint32_t f[PLC_MAX_BITS][4], cum[PLC_MAX_BITS];
+    for (int t = 0; t < a.n_tables; ++t) {
+      const uint32_t total = load_freq4(a.freq + (stream * a.n_tables + t) * 256, lane, f[t], &cum[t]);
+      if (total != kScale && total != 0 && threadIdx.x == 0) raise(a.status, PLC_ERR_INVALID);
+      long_form = long_form || __ballot(f[t][0] > 2048u || f[t][1] > 2048u || f[t][2] > 2048u || f[t][3] > 2048u) != 0;
+    }
+    for (int t = 0; t < a.n_tables; ++t) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int s = lane * 4 + r;
+        if ((s & (W - 1)) == wave)
+          table[t * 256 + s] = long_form ? make_enc_entry<true>(f[t][r], cum[t]) : make_enc_entry<false>(f[t][r], cum[t]);
+        cum[t] += f[t][r];
+      }
     }
   }
   __syncthreads();
@@ -249,6 +282,13 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
   // Staging rounds walk the groups from the top, 64 groups per round (the first round takes what is
   // left over).  A round's symbols [32*glo, 32*ghi) are fetched as 16-byte pieces aligned in absolute
   // address and placed so that symbol (group ghi-1-j, lane l) always sits at  mis + l + 32 * (63 - j).
+  bool bad_depth = false;
+  // ADAPT: the table of the group that stage position `lane` will hold (group ghi - 64 + lane), fetched with the symbols
+  auto group_load = [&](int32_t glo, int32_t ghi) -> uint32_t {
+    const int32_t g = ghi - kSuperGroups + lane;
+    if (!ADAPT || ghi <= 0 || g < (glo > 0 ? glo : 0) || g >= ghi) return 0u;
+    return group_table(a, stream, begin, g, 256u, &bad_depth);
+  };
   auto stage_load = [&](int32_t glo, int32_t ghi, uint4 v[kStagePieces], bool take[kStagePieces]) {
     // byte offsets relative to the unit's first symbol; pointers are formed by plain pointer arithmetic
     // on the kernel argument so that the loads stay global (not flat) memory instructions
@@ -319,6 +359,7 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
     bool take[kStagePieces];
     stage_load(ghi - cnt_groups, ghi, v, take);
     stage_store(0, cnt_groups, v, take);
+    if (ADAPT) table_of_group[wave][0][lane] = (uint16_t)group_load(ghi - cnt_groups, ghi);
   }
   wave_sync();
   int buf = 0;
@@ -327,6 +368,8 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
     uint4 nv[kStagePieces];
     bool ntake[kStagePieces];
     stage_load(glo - kSuperGroups, glo, nv, ntake);  // next round, in flight while this one is coded
+    const uint32_t ngt = group_load(glo - kSuperGroups, glo);
+    const uint16_t *gt = table_of_group[ADAPT ? wave : 0][buf];  // group j from the round's top sits at 63 - j
     const uint8_t *sb = &sym_stage[wave][buf][mis + rl];
     int32_t j0 = 0;
     // The prefetched round is written to LDS after the first batch of this round and BEFORE that batch's
@@ -336,7 +379,7 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
     if (head_groups) {
       uint16_t *wtop = wstage + fill;
       for (int32_t j = 0; j < head_groups; ++j) {
-        const uint4 e = table[sb[kLanes * (kSuperGroups - 1 - j)]];
+        const uint4 e = table[sb[kLanes * (kSuperGroups - 1 - j)] + (ADAPT ? gt[kSuperGroups - 1 - j] : 0u)];
         if (long_form) {
           enc_step<true, true>(x, e, wtop, scratch, flags, below, j != 0 || top_active);
         } else {
@@ -344,6 +387,7 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
         }
       }
       stage_store(buf ^ 1, kSuperGroups, nv, ntake);
+      if (ADAPT) table_of_group[wave][buf ^ 1][lane] = (uint16_t)ngt;
       landed = true;
       drain((uint32_t)(wtop - wstage));
       j0 = head_groups;
@@ -354,6 +398,11 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
       uint16_t *wtop = wstage + fill;
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) sy[j] = sbb[kLanes * (kBatch - 1 - j)];
+      if (ADAPT) {
+        const uint16_t *gtb = gt + (kSuperGroups - kBatch - j0);
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) sy[j] += gtb[kBatch - 1 - j];
+      }
       // table entries are fetched four groups ahead of the chain, so that their LDS time hides behind it
       uint4 e[2][4];
 #pragma unroll
@@ -374,6 +423,7 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
       }
       if (!landed) {
         stage_store(buf ^ 1, kSuperGroups, nv, ntake);
+        if (ADAPT) table_of_group[wave][buf ^ 1][lane] = (uint16_t)ngt;
         landed = true;
       }
       drain((uint32_t)(wtop - wstage));
@@ -392,6 +442,7 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
     if ((uint64_t)n_words > a.word_cap) raise(a.status, PLC_ERR_CAPACITY);
   }
   if (coder && (flags & 0x80000000u)) raise(a.status, PLC_ERR_INVALID);  // a symbol with f = 0 occurred
+  if (bad_depth) raise(a.status, PLC_ERR_INVALID);
 }
 
 // ---------------------------------------------------------------------------
@@ -686,8 +737,8 @@ constexpr int kRingWords = 2048, kBlockWords = 512, kRingMirror = kBlockWords + 
 
 template <bool MASKED>
 __device__ __forceinline__ void dec_step(uint32_t &x, const uint32_t *lut, const uint16_t *&top, uint8_t *sym_slot,
-                                         uint32_t below, bool on) {
-  const uint32_t e = lut[x & (kScale - 1)];
+                                         uint32_t below, bool on, uint32_t table_off = 0) {
+  const uint32_t e = lut[(x & (kScale - 1)) + table_off];
   const uint32_t xh = x >> kScaleBits;
   uint32_t xn = __umul24((e >> 8) & 0xfffu, xh) + (xh + (e >> 20));  // f * (x >> 12) + slot - cum
   uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
@@ -714,9 +765,12 @@ __device__ __forceinline__ void dec_step(uint32_t &x, const uint32_t *lut, const
   }
 }
 
-template <int W>
+template <int W, bool ADAPT>
 __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
-  __shared__ uint32_t lut[kScale];
+  __shared__ uint32_t lut_one[ADAPT ? 1 : kScale];
+  extern __shared__ uint32_t lut_per_depth[];  // ADAPT: n_tables slot tables, sized at launch
+  uint32_t *lut = ADAPT ? lut_per_depth : lut_one;
+  __shared__ uint16_t table_of_group[ADAPT ? W : 1][2][kBatch];  // ADAPT: table offset of each group of a batch
   __shared__ __attribute__((aligned(16))) uint16_t ring[W][kRingWords + kRingMirror];
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[W][kBatchSyms];
   __shared__ uint32_t table_ok;
@@ -726,7 +780,7 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
   const bool live = chunk < a.units_per_stream;
   bool bad = false;
 
-  {  // slot table, built by all wavefronts: symbol s is filled in by wavefront s mod W
+  if (!ADAPT) {  // slot table, built by all wavefronts: symbol s is filled in by wavefront s mod W
     uint32_t f[4], cum;
     const uint32_t total = load_freq4(a.freq + stream * 256, lane, f, &cum);
     if (threadIdx.x == 0) table_ok = total == kScale;
@@ -740,6 +794,27 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
         cum += f[r];
       }
     }
+  } else {  // one slot table per bit depth; the table of a depth the stream does not use is all zero
+    bool ok = true;
+    for (int t = 0; t < a.n_tables; ++t) {
+      uint32_t f[4], cum;
+      const uint32_t total = load_freq4(a.freq + (stream * a.n_tables + t) * 256, lane, f, &cum);
+      ok = ok && (total == kScale || total == 0);
+      uint32_t *lt = lut + t * kScale;
+      if (total == kScale) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int s = lane * 4 + r;
+          if ((s & (W - 1)) == wave) {
+            for (uint32_t o = 0; o < f[r]; ++o) lt[cum + o] = (uint32_t)s | ((f[r] - 1u) << 8) | (o << 20);
+          }
+          cum += f[r];
+        }
+      } else {
+        for (uint32_t o = threadIdx.x; o < kScale; o += W * 64) lt[o] = 0u;
+      }
+    }
+    if (threadIdx.x == 0) table_ok = ok;
   }
   __syncthreads();
   if (!table_ok) {  // not a table: nothing can be decoded
@@ -812,6 +887,20 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
   const int32_t g_tail = G - tail_groups;
   uint8_t *sb = &sym_stage[wave][rl];
 
+  // ADAPT: table offsets of the batch's 16 groups, fetched one batch ahead by lanes 0..15
+  bool bad_depth = false;
+  auto group_load = [&](int32_t g0) -> uint32_t {
+    const int32_t g = g0 + lane;
+    if (!ADAPT || lane >= kBatch || g >= G) return 0u;
+    return group_table(a, stream, begin, g, kScale, &bad_depth);
+  };
+  if (ADAPT) {
+    const uint32_t gt0 = group_load(0);
+    if (lane < kBatch) table_of_group[wave][0][lane] = (uint16_t)gt0;
+    wave_sync();
+  }
+  int gbuf = 0;
+
   for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
     const bool tail = g0 >= g_tail;
     const int32_t cnt_groups = tail ? tail_groups : kBatch;
@@ -822,15 +911,21 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
     uint4 pre;
     bool ptake = false;
     if (fetch) ptake = block_load(blk, pre);
+    const uint32_t ngt = group_load(g0 + kBatch);
+    const uint16_t *gt = table_of_group[ADAPT ? wave : 0][gbuf];
 
     const uint16_t *wtop0 = myring + ((uint32_t)(-ptr) & (kRingWords - 1));
     const uint16_t *wtop = wtop0;
     if (tail) {
       for (int32_t j = 0; j < cnt_groups; ++j)
-        dec_step<true>(x, lut, wtop, sb + kLanes * j, below, j != cnt_groups - 1 || top_active);
+        dec_step<true>(x, lut, wtop, sb + kLanes * j, below, j != cnt_groups - 1 || top_active, ADAPT ? gt[j] : 0u);
     } else {
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) dec_step<false>(x, lut, wtop, sb + kLanes * j, below, true);
+      for (int j = 0; j < kBatch; ++j) dec_step<false>(x, lut, wtop, sb + kLanes * j, below, true, ADAPT ? gt[j] : 0u);
+    }
+    if (ADAPT) {
+      if (lane < kBatch) table_of_group[wave][gbuf ^ 1][lane] = (uint16_t)ngt;
+      gbuf ^= 1;
     }
     ptr -= (int32_t)(wtop - wtop0);
     if (ptr < lo) {  // ran out of words: the stream is damaged
@@ -863,6 +958,7 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
   // integrity: every word consumed, every lane back at the initial state
   if (ptr != lo || (coder && x != kLow)) bad = true;
   if (bad) raise(a.status, PLC_ERR_CORRUPT);
+  if (bad_depth) raise(a.status, PLC_ERR_INVALID);
 }
 
 // ---------------------------------------------------------------------------
@@ -1095,7 +1191,11 @@ void dispatch_waves(int waves, const RansArgs &a, unsigned grid, hipStream_t st)
 template <int W>
 struct LaunchEncode {
   static void run(const RansArgs &a, unsigned grid, hipStream_t st) {
-    hipLaunchKernelGGL(rans_encode_kernel<W>, dim3(grid), dim3(W * 64), 0, st, a);
+    if (a.bits) {
+      hipLaunchKernelGGL((rans_encode_kernel<W, true>), dim3(grid), dim3(W * 64), 0, st, a);
+    } else {
+      hipLaunchKernelGGL((rans_encode_kernel<W, false>), dim3(grid), dim3(W * 64), 0, st, a);
+    }
   }
 };
 template <int W>
@@ -1104,10 +1204,15 @@ struct LaunchDecode {
     // One unit per stream and no more units than the chip has compute-unit halves: time is the length of one
     // unit's chain, so take the variant with the shortest step.  With more units its 60 KB of LDS per
     // wavefront would cost more in occupancy than the shorter step gains.
-    if (W == 1 && a.n_units <= 512) {
+    if (a.bits) {
+      const size_t lds = (size_t)a.n_tables * kScale * sizeof(uint32_t);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_kernel<W, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipLaunchKernelGGL((rans_decode_kernel<W, true>), dim3(grid), dim3(W * 64), lds, st, a);
+    } else if (W == 1 && a.n_units <= 512) {
       hipLaunchKernelGGL(rans_decode_chain_kernel, dim3(grid), dim3(64), 0, st, a);
     } else {
-      hipLaunchKernelGGL(rans_decode_kernel<W>, dim3(grid), dim3(W * 64), 0, st, a);
+      hipLaunchKernelGGL((rans_decode_kernel<W, false>), dim3(grid), dim3(W * 64), 0, st, a);
     }
   }
 };
@@ -1122,11 +1227,25 @@ extern "C" int64_t plc_units_per_stream(int64_t syms_per_stream, int32_t chunk_s
   return (syms_per_stream + chunk_syms - 1) / chunk_syms;
 }
 
-extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
-                               int32_t chunk_syms, const uint16_t *freq, uint32_t *states, uint16_t *words,
-                               const uint64_t *word_off, uint64_t word_cap_per_unit, uint32_t *n_words,
-                               uint32_t *status, void *stream) {
-  RansArgs a = {};
+namespace plc {
+namespace {
+
+// Arguments of the calls with one table per bit depth.
+int check_depths(int64_t syms_per_stream, int32_t chunk_syms, int32_t syms_per_pos, int32_t streams_per_session,
+                 const uint8_t *bits, int32_t n_tables, RansArgs *a) {
+  if (!bits || n_tables < 1 || n_tables > PLC_MAX_BITS || streams_per_session < 1) return PLC_ERR_INVALID;
+  if (syms_per_pos < kLanes || syms_per_pos % kLanes || syms_per_stream % syms_per_pos) return PLC_ERR_INVALID;
+  (void)chunk_syms;  // a multiple of 32 already: groups never straddle positions
+  a->bits = bits;
+  a->syms_per_pos = syms_per_pos;
+  a->streams_per_session = streams_per_session;
+  a->n_tables = n_tables;
+  return PLC_OK;
+}
+
+int encode_impl(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms,
+                const uint16_t *freq, uint32_t *states, uint16_t *words, const uint64_t *word_off,
+                uint64_t word_cap_per_unit, uint32_t *n_words, uint32_t *status, void *stream, RansArgs a) {
   int waves = 1;
   int rc = check_common(n_streams, syms_per_stream, chunk_syms, &a, &waves);
   if (rc) return rc;
@@ -1144,7 +1263,7 @@ extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_
   hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_RANS_ENCODE, st);
-    if (a.units_per_stream == 1 && a.n_units <= kPipeMaxUnits) {
+    if (!a.bits && a.units_per_stream == 1 && a.n_units <= kPipeMaxUnits) {
       // no more units than compute-unit halves: the chain of one unit is the time, so give each unit three
       // wavefronts (with more units, three wavefronts per unit cost more in occupancy than the shorter
       // chain gains)
@@ -1156,11 +1275,9 @@ extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_
   return launch_status();
 }
 
-extern "C" int plc_rans_decode(const uint16_t *freq, const uint32_t *states, const uint16_t *words,
-                               uint64_t words_len, const uint64_t *word_off, const uint32_t *n_words,
-                               int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms, uint8_t *symbols,
-                               uint32_t *status, void *stream) {
-  RansArgs a = {};
+int decode_impl(const uint16_t *freq, const uint32_t *states, const uint16_t *words, uint64_t words_len,
+                const uint64_t *word_off, const uint32_t *n_words, int64_t n_streams, int64_t syms_per_stream,
+                int32_t chunk_syms, uint8_t *symbols, uint32_t *status, void *stream, RansArgs a) {
   int waves = 1;
   int rc = check_common(n_streams, syms_per_stream, chunk_syms, &a, &waves);
   if (rc) return rc;
@@ -1181,4 +1298,48 @@ extern "C" int plc_rans_decode(const uint16_t *freq, const uint32_t *states, con
     dispatch_waves<LaunchDecode>(waves, a, (unsigned)(n_streams * a.wgs_per_stream), st);
   }
   return launch_status();
+}
+
+}  // namespace
+}  // namespace plc
+
+extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                               int32_t chunk_syms, const uint16_t *freq, uint32_t *states, uint16_t *words,
+                               const uint64_t *word_off, uint64_t word_cap_per_unit, uint32_t *n_words,
+                               uint32_t *status, void *stream) {
+  return encode_impl(symbols, n_streams, syms_per_stream, chunk_syms, freq, states, words, word_off,
+                     word_cap_per_unit, n_words, status, stream, RansArgs{});
+}
+
+extern "C" int plc_rans_decode(const uint16_t *freq, const uint32_t *states, const uint16_t *words,
+                               uint64_t words_len, const uint64_t *word_off, const uint32_t *n_words,
+                               int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms, uint8_t *symbols,
+                               uint32_t *status, void *stream) {
+  return decode_impl(freq, states, words, words_len, word_off, n_words, n_streams, syms_per_stream, chunk_syms,
+                     symbols, status, stream, RansArgs{});
+}
+
+extern "C" int plc_rans_encode_bucketed(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,
+                                        int32_t chunk_syms, int32_t syms_per_pos, int32_t streams_per_session,
+                                        const uint8_t *bits, int32_t n_tables, const uint16_t *freq,
+                                        uint32_t *states, uint16_t *words, const uint64_t *word_off,
+                                        uint64_t word_cap_per_unit, uint32_t *n_words, uint32_t *status,
+                                        void *stream) {
+  RansArgs a = {};
+  const int rc = check_depths(syms_per_stream, chunk_syms, syms_per_pos, streams_per_session, bits, n_tables, &a);
+  if (rc) return rc;
+  return encode_impl(symbols, n_streams, syms_per_stream, chunk_syms, freq, states, words, word_off,
+                     word_cap_per_unit, n_words, status, stream, a);
+}
+
+extern "C" int plc_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const uint16_t *words,
+                                        uint64_t words_len, const uint64_t *word_off, const uint32_t *n_words,
+                                        int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms,
+                                        int32_t syms_per_pos, int32_t streams_per_session, const uint8_t *bits,
+                                        int32_t n_tables, uint8_t *symbols, uint32_t *status, void *stream) {
+  RansArgs a = {};
+  const int rc = check_depths(syms_per_stream, chunk_syms, syms_per_pos, streams_per_session, bits, n_tables, &a);
+  if (rc) return rc;
+  return decode_impl(freq, states, words, words_len, word_off, n_words, n_streams, syms_per_stream, chunk_syms,
+                     symbols, status, stream, a);
 }

@@ -23,7 +23,12 @@ EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_
            "plc_predict_residual", "plc_histogram", "plc_build_freq", "plc_rans_encode",
            "plc_rans_decode", "plc_reconstruct", "plc_trace_kernel_events",
            "plc_predict_residual_cond", "plc_reconstruct_cond", "plc_select_candidate",
-           "plc_index_encode", "plc_index_decode")
+           "plc_index_encode", "plc_index_decode",
+           "plc_surprisal_bits", "plc_predict_residual_adapt", "plc_reconstruct_adapt",
+           "plc_histogram_bucketed", "plc_build_freq_bucketed", "plc_rans_encode_bucketed",
+           "plc_rans_decode_bucketed")
+
+MAX_BITS = 4
 
 (TRACE_PREDICT, TRACE_RECONSTRUCT, TRACE_HISTOGRAM, TRACE_RANS_ENCODE, TRACE_RANS_DECODE,
  TRACE_PREDICT_COND, TRACE_RECONSTRUCT_COND) = range(7)
@@ -73,6 +78,13 @@ def lib() -> C.CDLL:
         L.plc_select_candidate.argtypes = [dp, p, p, C.c_float, p, p]
         L.plc_index_encode.argtypes = [p, p, i32, i32, i32, p, p, p, u64, p, p, p]
         L.plc_index_decode.argtypes = [p, p, p, u64, p, p, i32, i32, i32, p, p, p]
+        L.plc_surprisal_bits.argtypes = [p, p, i32, i32, i32, C.POINTER(C.c_uint16), i32, p, p, p]
+        L.plc_predict_residual_adapt.argtypes = [dp, p, p, p, p, p, C.c_float, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_reconstruct_adapt.argtypes = [dp, p, p, p, p, p, C.c_float, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_histogram_bucketed.argtypes = [p, i64, i64, i32, i32, p, i32, p, p, p]
+        L.plc_build_freq_bucketed.argtypes = [p, i64, i32, p, p, p]
+        L.plc_rans_encode_bucketed.argtypes = [p, i64, i64, i32, i32, i32, p, i32, p, p, p, p, u64, p, p, p]
+        L.plc_rans_decode_bucketed.argtypes = [p, p, p, u64, p, p, i64, i64, i32, i32, i32, p, i32, p, p, p]
         _lib = L
     return _lib
 
@@ -233,6 +245,80 @@ def plc_index_decode(probs, states, words, word_off, n_words, S, n, k, chosen, s
                                 _contig(word_off, torch.int64), _contig(n_words, torch.int32), S, n, k,
                                 _contig(chosen, torch.int32), _contig(status, torch.int32), _stream())
     _check(rc, "plc_index_decode")
+
+
+def surprisal_thresholds(b0, hbar, bmax=MAX_BITS):
+    """Host helper: thr[m] = floor(4096 * 2^(-m * hbar / b0)), m = 2..bmax (entries 0, 1 unused)."""
+    import math
+    return [0, 0] + [int(math.floor(4096.0 * 2.0 ** (-m * float(hbar) / float(b0)))) for m in range(2, bmax + 1)]
+
+
+def plc_surprisal_bits(probs, chosen, S, n, k, thr, bits, status):
+    """thr: host sequence of bmax + 1 integers (see surprisal_thresholds); bits: uint8 [S,n] out."""
+    arr = (C.c_uint16 * len(thr))(*[int(t) for t in thr])
+    rc = lib().plc_surprisal_bits(_contig(probs, torch.float32), _contig(chosen, torch.int32), S, n, k, arr,
+                                  len(thr) - 1, _contig(bits, torch.uint8), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_surprisal_bits")
+
+
+def plc_predict_residual_adapt(dims, cand_k, cand_v, probs, chosen, bits, step_range, act_k, act_v, symbols,
+                               esc_vals, esc_cnt, esc_off, ws, status, pred_out=None):
+    rc = lib().plc_predict_residual_adapt(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _contig(chosen, torch.int32), _contig(bits, torch.uint8),
+        float(step_range), _ptr(act_k, torch.float16), _ptr(act_v, torch.float16),
+        _contig(symbols, torch.uint8), _contig(esc_vals, None), esc_vals.numel(),
+        _contig(esc_cnt, torch.int32), _contig(esc_off, torch.int64), _contig(pred_out, torch.float32),
+        _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_predict_residual_adapt")
+
+
+def plc_reconstruct_adapt(dims, cand_k, cand_v, probs, chosen, bits, step_range, symbols, esc_vals, esc_off,
+                          out_k, out_v, ws, status):
+    rc = lib().plc_reconstruct_adapt(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _contig(chosen, torch.int32), _contig(bits, torch.uint8),
+        float(step_range), _contig(symbols, torch.uint8), _contig(esc_vals, None), esc_vals.numel(),
+        _contig(esc_off, torch.int64), _ptr(out_k, torch.float16), _ptr(out_v, torch.float16),
+        _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_reconstruct_adapt")
+
+
+def plc_histogram_bucketed(symbols, n_streams, syms_per_stream, syms_per_pos, streams_per_session, bits,
+                           n_tables, counts, status):
+    rc = lib().plc_histogram_bucketed(_contig(symbols, torch.uint8), n_streams, syms_per_stream, syms_per_pos,
+                                      streams_per_session, _contig(bits, torch.uint8), n_tables,
+                                      _contig(counts, torch.int32), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_histogram_bucketed")
+
+
+def plc_build_freq_bucketed(counts, n_streams, n_tables, freq, status):
+    rc = lib().plc_build_freq_bucketed(_contig(counts, torch.int32), n_streams, n_tables,
+                                       _contig(freq, torch.int16), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_build_freq_bucketed")
+
+
+def plc_rans_encode_bucketed(symbols, n_streams, syms_per_stream, chunk_syms, syms_per_pos,
+                             streams_per_session, bits, n_tables, freq, states, words, word_off,
+                             word_cap_per_unit, n_words, status):
+    rc = lib().plc_rans_encode_bucketed(_contig(symbols, torch.uint8), n_streams, syms_per_stream, chunk_syms,
+                                        syms_per_pos, streams_per_session, _contig(bits, torch.uint8), n_tables,
+                                        _contig(freq, torch.int16), _contig(states, torch.int32),
+                                        _contig(words, torch.int16), _contig(word_off, torch.int64),
+                                        int(word_cap_per_unit), _contig(n_words, torch.int32),
+                                        _contig(status, torch.int32), _stream())
+    _check(rc, "plc_rans_encode_bucketed")
+
+
+def plc_rans_decode_bucketed(freq, states, words, word_off, n_words, n_streams, syms_per_stream, chunk_syms,
+                             syms_per_pos, streams_per_session, bits, n_tables, symbols, status):
+    rc = lib().plc_rans_decode_bucketed(_contig(freq, torch.int16), _contig(states, torch.int32),
+                                        _contig(words, torch.int16), words.numel(),
+                                        _contig(word_off, torch.int64), _contig(n_words, torch.int32),
+                                        n_streams, syms_per_stream, chunk_syms, syms_per_pos,
+                                        streams_per_session, _contig(bits, torch.uint8), n_tables,
+                                        _contig(symbols, torch.uint8), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_rans_decode_bucketed")
 
 
 def plc_trace_kernel_events(kernel_id, start=None, stop=None):

@@ -90,6 +90,23 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert L.plc_index_encode(p, None, 1, 16, 4, p, p, p, 16, p, p, None) == 1
     assert L.plc_index_decode(p, p, None, 10, p, p, 1, 16, 4, p, p, None) == 1
     assert L.plc_index_decode(p, p, p, 10, p, p, 1, 0, 4, p, p, None) == 1
+    # surprisal-adaptive calls
+    thr = (C.c_uint16 * 5)(0, 0, 1000, 500, 250)
+    up = (C.c_uint16 * 5)(0, 0, 100, 500, 250)                # thresholds must not increase
+    assert L.plc_surprisal_bits(p, p, 1, 16, 4, up, 4, p, p, None) == 1
+    assert L.plc_surprisal_bits(p, p, 1, 16, 4, thr, 5, p, p, None) == 1        # bmax beyond PLC_MAX_BITS
+    assert L.plc_surprisal_bits(p, None, 1, 16, 4, thr, 4, p, p, None) == 1
+    f0, fneg = C.c_float(0.0), C.c_float(-1.0)
+    assert L.plc_predict_residual_adapt(C.byref(dm), p, p, p, p, p, f0, p, p, p, p, 0, p, p, None, p, 1 << 20, p, None) == 1
+    assert L.plc_predict_residual_adapt(C.byref(dm), p, p, p, p, None, C.c_float(0.3), p, p, p, p, 0, p, p, None, p, 1 << 20, p, None) == 1
+    assert L.plc_reconstruct_adapt(C.byref(dm), p, p, p, p, p, fneg, p, p, 0, p, p, p, p, 1 << 20, p, None) == 1
+    assert L.plc_histogram_bucketed(p, 2, 1024, 48, 1, p, 4, p, p, None) == 1   # positions must hold a multiple of 32
+    assert L.plc_histogram_bucketed(p, 2, 1000, 64, 1, p, 4, p, p, None) == 1   # and divide the stream
+    assert L.plc_histogram_bucketed(p, 2, 1024, 64, 1, p, 5, p, p, None) == 1
+    assert L.plc_build_freq_bucketed(p, 2, 0, p, p, None) == 1
+    assert L.plc_rans_encode_bucketed(p, 1, 1024, 0, 64, 1, None, 4, p, p, p, p, 100, p, p, None) == 1
+    assert L.plc_rans_encode_bucketed(p, 1, 1024, 0, 16, 1, p, 4, p, p, p, p, 100, p, p, None) == 1
+    assert L.plc_rans_decode_bucketed(p, p, p, 10, p, p, 1, 1024, 48, 64, 1, p, 4, p, p, None) == 1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
