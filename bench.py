@@ -48,6 +48,11 @@ def parse():
     ap.add_argument("--no-conditional", action="store_true",
                     help="skip the side measurement of the token-conditional path (prediction = the true token's "
                          "candidate, its index coded in a stream of its own)")
+    ap.add_argument("--no-adaptive", action="store_true",
+                    help="skip the side measurement of the surprisal-adaptive quantiser (bit depth per position from "
+                         "the token's surprisal, one table per depth) on the token-conditional path")
+    ap.add_argument("--adaptive-b0", type=float, default=3.0, help="target average bit depth b0")
+    ap.add_argument("--adaptive-range", type=float, default=0.32, help="quantiser range: step = range / 2^depth")
     return ap.parse_args()
 
 
@@ -339,6 +344,67 @@ def main():
             f"{result['token_conditional']['index_bits_per_token']} index bits/token; "
             + ", ".join(f"{k} {v['ms']} ms = {100 * v['frac_hbm']:.1f} % of HBM peak" for k, v in k3.items()))
         del codec3
+    if not args.no_adaptive and w.d % 16 == 0:
+        # Surprisal-adaptive quantiser on the token-conditional path: depth b_i = min(4, max(1, floor(b0 * h_i / hbar)))
+        # from the token's coded surprisal (hbar = log2 of the configuration's perplexity), step = range / 2^b_i,
+        # one frequency table per depth.  Same format as the headline otherwise (whole streams unless --chunk-syms).
+        codec4 = KVDeltaCodec(w.S, w.L, w.H, w.n, w.k, w.d, w.delta, w.qmax, chunk_syms=args.chunk_syms, device=dev,
+                              cand_stride=w.cand_k.stride()[:5], act_stride=w.act_k.stride()[:4])
+        chosen4 = w.chosen.to(torch.int32).contiguous()
+        hbar = float(np.log2(np.mean(w.perplexity)))
+        thr = plc.surprisal_thresholds(args.adaptive_b0, hbar)
+
+        def step4():
+            codec4.encode_adapt(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen4, thr, args.adaptive_range)
+            codec4.decode_adapt(w.cand_k, w.cand_v, w.probs, out_k, out_v, thr, args.adaptive_range)
+
+        for _ in range(args.warmup):
+            step4()
+        torch.cuda.synchronize()
+        timer4 = KernelTimer(plc, torch, args.steps, conditional=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            timer4.arm(i)
+            step4()
+        torch.cuda.synchronize()
+        dt4 = time.perf_counter() - t0
+        timer4.disarm()
+        codec4.check_status("surprisal-adaptive steps")
+        nw4 = codec4.n_words.cpu().numpy().view(np.uint32).astype(np.int64)
+        esc4 = int(codec4.esc_cnt.cpu().numpy().view(np.uint32).astype(np.int64).sum())
+        idx4 = 16 * int(codec4.idx_n_words.cpu().numpy().view(np.uint32).astype(np.int64).sum()) + 32 * 32 * w.S
+        tables = int((codec4.freq_d.to(torch.int32).abs().sum(-1) > 0).sum())          # tables actually used
+        bits4 = (16 * int(nw4.sum()) + 16 * esc4 + 32 * 32 * codec4.n_units + 256 * 16 * tables + 3 * 32 * w.n_streams
+                 + idx4)
+        depth = codec4.bits.cpu().numpy()
+        sq = 0.0
+        for s_ in range(w.S):
+            for l_ in range(w.L):
+                for got, want in ((out_k, w.act_k), (out_v, w.act_v)):
+                    diff = torch.nan_to_num(got[s_, l_].float() - want[s_, l_].float(), nan=0.0, posinf=0.0, neginf=0.0)
+                    sq += float((diff.double() ** 2).sum())
+        ms4 = timer4.mean_ms()
+        result["surprisal_adaptive"] = {
+            "b0": args.adaptive_b0, "hbar": round(hbar, 4), "range": args.adaptive_range, "thresholds": thr[2:],
+            "depth_shares": {str(b): round(float((depth == b).mean()), 4) for b in range(1, plc.MAX_BITS + 1)},
+            "mean_depth": round(float(depth.mean()), 3),
+            "value": round(w.kv_bytes / (dt4 / args.steps) / 1e9, 2), "unit": "GB/s",
+            "ms_per_step": round(dt4 / args.steps * 1e3, 4),
+            "coded_bits_per_token": round(bits4 / (w.S * w.n), 1),
+            "payload_bits_per_symbol": round((16 * int(nw4.sum()) + 16 * esc4) / E, 4),
+            "mean_square_error": float(f"{sq / E:.4e}"),
+            "fixed_step_mean_square_error": float(f"{float(np.float32(w.delta)) ** 2 / 12:.4e}"),
+            "roundtrip_symbols_exact": bool(torch.equal(codec4.dec_symbols, codec4.symbols)),
+            "roundtrip_depths_exact": bool(torch.equal(codec4.dec_bits, codec4.bits)),
+            "kernels_ms": {k: round(v, 4) for k, v in ms4.items() if k != "histogram"},
+        }
+        r4 = result["surprisal_adaptive"]
+        log(f"  surprisal-adaptive (b0 {args.adaptive_b0}, range {args.adaptive_range}): step {r4['ms_per_step']} ms "
+            f"({r4['value']} GB/s), mean depth {r4['mean_depth']}, {r4['payload_bits_per_symbol']} bits/component, "
+            f"mse {r4['mean_square_error']:.3e} (fixed step: {r4['fixed_step_mean_square_error']:.3e}); "
+            f"rans_encode {ms4['rans_encode']:.3f} ms, rans_decode {ms4['rans_decode']:.3f} ms")
+        del codec4
     if not args.no_cpu_baseline:
         base, sym64 = cpu_baseline(w, args.cpu_streams, torch)
         result["cpu_baseline"] = base
