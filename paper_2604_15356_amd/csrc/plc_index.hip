@@ -3,10 +3,9 @@
 // that a position costs about the token's surprisal (Thm. "Sequential entropy bound", Sec. 4.2).
 // See include/plc.h for the format.
 //
-// The stream is tiny next to the residuals (one symbol per position against 2*L*H*d of them), so
-// these kernels are written for clarity: one wavefront per session, lanes 0..31 are the 32 rANS
-// lanes, every lane builds the table of its own position in registers / private memory, and words go
-// straight to global memory at positions ranked from the emission mask.
+// The stream is tiny next to the residuals (one symbol per position against 2*L*H*d of them), but with
+// one session it is a single chain of n / 32 steps, so the per-position tables are prepared off the
+// chain; words go straight to global memory at positions ranked from the emission mask.
 #include "plc_device.h"
 
 namespace plc {
@@ -49,64 +48,126 @@ __device__ bool index_table(const float *__restrict__ p, int k, uint32_t f[kMaxK
   return ok;
 }
 
-__global__ __launch_bounds__(64) void index_encode_kernel(const float *__restrict__ probs,
-                                                          const int32_t *__restrict__ chosen, int n, int k,
-                                                          uint32_t *__restrict__ states, uint16_t *__restrict__ words,
-                                                          const uint64_t *__restrict__ word_off, uint64_t word_cap,
-                                                          uint32_t *__restrict__ n_words, uint32_t *status) {
+// Both coders give a session one workgroup of four wavefronts.  The chain of rANS steps is sequential,
+// but what a step needs from its position -- the table made from that position's probabilities -- is not:
+// wavefronts 1-3 prepare the tables of the next six groups (192 positions, one per thread, the table living
+// in the thread's own LDS row) while wavefront 0 codes the current six from LDS; one barrier per tile.
+constexpr int kTileGroups = 6;
+constexpr int kTilePos = kTileGroups * kLanes;  // 192 = the three helper wavefronts
+constexpr int kRow = kMaxK + 2;                 // k + 1 frequencies or k + 2 cumulative values, padded
+
+// Frequencies of one row into an LDS row (same arithmetic as index_table).
+__device__ __forceinline__ bool index_table_lds(const float *__restrict__ p, int k, uint16_t *f) {
+  bool ok = true;
+  float c = 0.0f;
+  uint32_t prev = 0;
+  for (int j = 0; j < k; ++j) {
+    float pj = p[j];
+    if (!(pj >= 0.0f)) {
+      ok = false;
+      pj = 0.0f;
+    }
+    c = c + pj;
+    float scaled = __builtin_floorf(c * 4096.0f);
+    if (!(scaled < 4096.0f)) scaled = 4096.0f;
+    const uint32_t b = (uint32_t)scaled;
+    f[j] = (uint16_t)(b - prev);
+    prev = b;
+  }
+  f[k] = (uint16_t)(kScale - prev);
+  for (int j = 0; j <= k; ++j) {
+    if (f[j] == 0) {
+      int donor = 0;
+      for (int m = 1; m <= k; ++m)
+        if (f[m] > f[donor]) donor = m;
+      f[donor] -= 1;
+      f[j] = 1;
+    }
+  }
+  return ok;
+}
+
+__global__ __launch_bounds__(256) void index_encode_kernel(const float *__restrict__ probs,
+                                                           const int32_t *__restrict__ chosen, int n, int k,
+                                                           uint32_t *__restrict__ states, uint16_t *__restrict__ words,
+                                                           const uint64_t *__restrict__ word_off, uint64_t word_cap,
+                                                           uint32_t *__restrict__ n_words, uint32_t *status) {
+  __shared__ uint16_t rows[kTilePos][kRow];
+  __shared__ uint32_t pair[2][kTileGroups][kLanes];  // f | cum << 16 of the symbol to code
   const int s = blockIdx.x;
-  const int lane = threadIdx.x;
-  const bool rans_lane = lane < kLanes;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint16_t *out = words + word_off[s];
   uint32_t x = kLow;
   uint64_t nw = 0;  // uniform
   const int groups = (n + kLanes - 1) / kLanes;
-  for (int g = groups - 1; g >= 0; --g) {
-    const int i = g * kLanes + lane;
-    const bool has = rans_lane && i < n;
-    uint32_t fs = 1, cs = 0;
-    if (has) {
-      const int64_t row = (int64_t)s * n + i;
-      uint32_t f[kMaxK + 1];
-      if (!index_table(probs + row * k, k, f)) raise(status, PLC_ERR_INVALID);
-      int j = chosen[row];
-      if (j < -1 || j >= k) {
-        raise(status, PLC_ERR_INVALID);
-        j = -1;
+  const int tiles = (groups + kTileGroups - 1) / kTileGroups;
+  // tile t holds groups top(t) - 1 down to top(t) - 6, top(t) = groups - 6 t (the encoder walks downwards)
+  for (int it = 0; it <= tiles; ++it) {
+    if (wave > 0) {
+      if (it < tiles) {
+        const int u = threadIdx.x - 64, gi = u >> 5, l = u & 31;
+        const int g = groups - kTileGroups * it - 1 - gi;
+        const int i = g * kLanes + l;
+        uint32_t v = 1u;  // f = 1, cum = 0 for lanes without a symbol (never used)
+        if (g >= 0 && i < n) {
+          const int64_t row = (int64_t)s * n + i;
+          if (!index_table_lds(probs + row * k, k, rows[u])) raise(status, PLC_ERR_INVALID);
+          int j = chosen[row];
+          if (j < -1 || j >= k) {
+            raise(status, PLC_ERR_INVALID);
+            j = -1;
+          }
+          const int sym = j < 0 ? k : j;
+          uint32_t cs = 0;
+          for (int m = 0; m < sym; ++m) cs += rows[u][m];
+          v = (uint32_t)rows[u][sym] | (cs << 16);
+        }
+        pair[it & 1][gi][l] = v;
       }
-      const int sym = j < 0 ? k : j;
-      for (int m = 0; m < sym; ++m) cs += f[m];
-      fs = f[sym];
-    }
-    // The sequential definition visits lane 31 first: a lane's word comes after those of the
-    // emitting lanes above it.
-    const bool emit = has && (x >> 20) >= fs;
-    const uint32_t mask = (uint32_t)__ballot(emit);
-    if (emit) {
-      const uint32_t above = lane == 31 ? 0u : mask >> (lane + 1);
-      const uint64_t pos = nw + (uint32_t)__builtin_popcount(above);
-      if (pos < word_cap) {
-        out[pos] = (uint16_t)(x & 0xffffu);
-      } else {
-        raise(status, PLC_ERR_CAPACITY);
+    } else if (it > 0) {
+      const int t = it - 1;
+      for (int gi = 0; gi < kTileGroups; ++gi) {
+        const int g = groups - kTileGroups * t - 1 - gi;
+        if (g < 0) break;  // uniform
+        const int i = g * kLanes + lane;
+        const bool has = lane < kLanes && i < n;
+        const uint32_t v = pair[t & 1][gi][lane & 31];
+        const uint32_t fs = v & 0xffffu, cs = v >> 16;
+        // The sequential definition visits lane 31 first: a lane's word comes after those of the
+        // emitting lanes above it.
+        const bool emit = has && (x >> 20) >= fs;
+        const uint32_t mask = (uint32_t)__ballot(emit);
+        if (emit) {
+          const uint32_t above = lane == 31 ? 0u : mask >> (lane + 1);
+          const uint64_t pos = nw + (uint32_t)__builtin_popcount(above);
+          if (pos < word_cap) {
+            out[pos] = (uint16_t)(x & 0xffffu);
+          } else {
+            raise(status, PLC_ERR_CAPACITY);
+          }
+          x >>= 16;
+        }
+        nw += (uint32_t)__builtin_popcount(mask);
+        if (has) x = (x / fs) * kScale + (x % fs) + cs;
       }
-      x >>= 16;
     }
-    nw += (uint32_t)__builtin_popcount(mask);
-    if (has) x = (x / fs) * kScale + (x % fs) + cs;
+    __syncthreads();
   }
-  if (rans_lane) states[(int64_t)s * kLanes + lane] = x;
-  if (lane == 0) n_words[s] = (uint32_t)(nw < word_cap ? nw : word_cap);
+  if (wave == 0) {
+    if (lane < kLanes) states[(int64_t)s * kLanes + lane] = x;
+    if (lane == 0) n_words[s] = (uint32_t)(nw < word_cap ? nw : word_cap);
+  }
 }
 
-__global__ __launch_bounds__(64) void index_decode_kernel(const float *__restrict__ probs,
-                                                          const uint32_t *__restrict__ states,
-                                                          const uint16_t *__restrict__ words, uint64_t words_len,
-                                                          const uint64_t *__restrict__ word_off,
-                                                          const uint32_t *__restrict__ n_words, int n, int k,
-                                                          int32_t *__restrict__ chosen, uint32_t *status) {
+__global__ __launch_bounds__(256) void index_decode_kernel(const float *__restrict__ probs,
+                                                           const uint32_t *__restrict__ states,
+                                                           const uint16_t *__restrict__ words, uint64_t words_len,
+                                                           const uint64_t *__restrict__ word_off,
+                                                           const uint32_t *__restrict__ n_words, int n, int k,
+                                                           int32_t *__restrict__ chosen, uint32_t *status) {
+  __shared__ uint16_t cums[2][kTilePos][kRow];  // cumulative frequencies cum[0..k+1] of every position of a tile
   const int s = blockIdx.x;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bool rans_lane = lane < kLanes;
   const uint64_t base = word_off[s];
   uint64_t ptr = n_words[s];  // uniform
@@ -114,42 +175,64 @@ __global__ __launch_bounds__(64) void index_decode_kernel(const float *__restric
   if (corrupt) ptr = 0;
   uint32_t x = rans_lane ? states[(int64_t)s * kLanes + lane] : kLow;
   const int groups = (n + kLanes - 1) / kLanes;
-  for (int g = 0; g < groups; ++g) {
-    const int i = g * kLanes + lane;
-    const bool has = rans_lane && i < n;
-    if (has) {
-      const int64_t row = (int64_t)s * n + i;
-      uint32_t f[kMaxK + 1];
-      if (!index_table(probs + row * k, k, f)) raise(status, PLC_ERR_INVALID);
-      const uint32_t slot = x & (kScale - 1);
-      uint32_t cs = 0;
-      int sym = 0;
-      while (sym < k && cs + f[sym] <= slot) {  // the symbol whose interval holds the slot
-        cs += f[sym];
-        ++sym;
+  const int tiles = (groups + kTileGroups - 1) / kTileGroups;
+  for (int it = 0; it <= tiles; ++it) {
+    if (wave > 0) {
+      if (it < tiles) {
+        const int u = threadIdx.x - 64;
+        const int i = (kTileGroups * it + (u >> 5)) * kLanes + (u & 31);
+        if (i < n) {
+          uint16_t *row = cums[it & 1][u];
+          if (!index_table_lds(probs + ((int64_t)s * n + i) * k, k, row)) raise(status, PLC_ERR_INVALID);
+          uint32_t acc = 0;
+          for (int m = 0; m <= k; ++m) {  // frequencies -> exclusive prefix sums, in place
+            const uint32_t f = row[m];
+            row[m] = (uint16_t)acc;
+            acc += f;
+          }
+          row[k + 1] = (uint16_t)acc;  // 4096
+        }
       }
-      chosen[row] = sym == k ? -1 : sym;
-      x = f[sym] * (x >> 12) + slot - cs;
-    }
-    // Reading lanes are served from the end of the list, lane 0 first.
-    const bool need = has && x < kLow;
-    const uint32_t mask = (uint32_t)__ballot(need);
-    if (need) {
-      const uint32_t below = mask & ((1u << lane) - 1u);
-      const uint64_t rank = (uint32_t)__builtin_popcount(below);
-      uint32_t word = 0;
-      if (rank < ptr) {
-        word = words[base + ptr - 1 - rank];
-      } else {
-        corrupt = true;
+    } else if (it > 0) {
+      const int t = it - 1;
+      for (int gi = 0; gi < kTileGroups; ++gi) {
+        const int g = kTileGroups * t + gi;
+        if (g >= groups) break;  // uniform
+        const int i = g * kLanes + lane;
+        const bool has = rans_lane && i < n;
+        if (has) {
+          const uint16_t *row = cums[t & 1][gi * kLanes + lane];
+          const uint32_t slot = x & (kScale - 1);
+          int sym = 0;
+          while (sym < k && row[sym + 1] <= slot) ++sym;  // the symbol whose interval holds the slot
+          const uint32_t cs = row[sym], fs = (uint32_t)row[sym + 1] - cs;
+          chosen[(int64_t)s * n + i] = sym == k ? -1 : sym;
+          x = fs * (x >> 12) + slot - cs;
+        }
+        // Reading lanes are served from the end of the list, lane 0 first.
+        const bool need = has && x < kLow;
+        const uint32_t mask = (uint32_t)__ballot(need);
+        if (need) {
+          const uint32_t below = mask & ((1u << lane) - 1u);
+          const uint64_t rank = (uint32_t)__builtin_popcount(below);
+          uint32_t word = 0;
+          if (rank < ptr) {
+            word = words[base + ptr - 1 - rank];
+          } else {
+            corrupt = true;
+          }
+          x = (x << 16) | word;
+        }
+        const uint32_t used = (uint32_t)__builtin_popcount(mask);
+        ptr = used < ptr ? ptr - used : 0;
       }
-      x = (x << 16) | word;
     }
-    const uint32_t used = (uint32_t)__builtin_popcount(mask);
-    ptr = used < ptr ? ptr - used : 0;
+    __syncthreads();
   }
-  if (ptr != 0 || (rans_lane && x != kLow)) corrupt = true;
-  if (corrupt) raise(status, PLC_ERR_CORRUPT);
+  if (wave == 0) {
+    if (ptr != 0 || (rans_lane && x != kLow)) corrupt = true;
+    if (corrupt) raise(status, PLC_ERR_CORRUPT);
+  }
 }
 
 struct Thresholds {
@@ -199,7 +282,7 @@ extern "C" int plc_index_encode(const float *probs, const int32_t *chosen, int32
   const int rc = check(probs, S, n, k, states, word_off, n_words, chosen, status);
   if (rc) return rc;
   if ((word_cap > 0 && !words) || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
-  hipLaunchKernelGGL(index_encode_kernel, dim3((unsigned)S), dim3(64), 0, static_cast<hipStream_t>(stream), probs,
+  hipLaunchKernelGGL(index_encode_kernel, dim3((unsigned)S), dim3(256), 0, static_cast<hipStream_t>(stream), probs,
                      chosen, n, k, states, words, word_off, word_cap, n_words, status);
   return launch_status();
 }
@@ -210,7 +293,7 @@ extern "C" int plc_index_decode(const float *probs, const uint32_t *states, cons
   const int rc = check(probs, S, n, k, states, word_off, n_words, chosen, status);
   if (rc) return rc;
   if ((words_len > 0 && !words) || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
-  hipLaunchKernelGGL(index_decode_kernel, dim3((unsigned)S), dim3(64), 0, static_cast<hipStream_t>(stream), probs,
+  hipLaunchKernelGGL(index_decode_kernel, dim3((unsigned)S), dim3(256), 0, static_cast<hipStream_t>(stream), probs,
                      states, words, words_len, word_off, n_words, n, k, chosen, status);
   return launch_status();
 }
