@@ -462,7 +462,7 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
 // The three meet at one workgroup barrier per batch of 16 steps.
 constexpr int kEntrySlots = 3;  // feeder writes b+1, coder reads b, packer reads b-1
 constexpr int kStateSlots = 2;  // coder writes b, packer reads b-1
-constexpr int kIdentity = 256;  // table index of the entry that leaves a state unchanged
+constexpr int kIdentity = PLC_MAX_BITS * 256;  // table index of the entry that leaves a state unchanged
 constexpr int64_t kPipeMaxUnits = 512;
 
 template <bool LONG>
@@ -507,8 +507,10 @@ __device__ __forceinline__ void pipe_batch(uint32_t &x, const uint4 *eb, uint32_
   }
 }
 
+template <bool ADAPT>  // ADAPT: one table per bit depth (the *_bucketed call)
 __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a) {
   __shared__ uint4 table[kIdentity + 1];
+  __shared__ uint16_t table_of_group[2][kSuperGroups];  // ADAPT: table offset of each group of a staging round
   __shared__ uint4 entry_ring[kEntrySlots][kBatch][kLanes];
   __shared__ uint32_t state_ring[kStateSlots][kBatch][kLanes];
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][kSymStage];
@@ -516,18 +518,24 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t unit = blockIdx.x;  // one unit per stream, one workgroup per unit
 
-  bool long_form;
+  bool long_form = false;
   {  // every wavefront scans the frequencies; of a lane's four entries the coder builds one, the feeder
      // one and the packer two
-    uint32_t f[4], cum;
-    const uint32_t total = load_freq4(a.freq + unit * 256, lane, f, &cum);
-    if (total != kScale && threadIdx.x == 0) raise(a.status, PLC_ERR_INVALID);
-    long_form = __ballot(f[0] > 2048u || f[1] > 2048u || f[2] > 2048u || f[3] > 2048u) != 0;  // uniform
+    const int n_tables = ADAPT ? a.n_tables : 1;
+    uint32_t f[ADAPT ? PLC_MAX_BITS : 1][4], cum[ADAPT ? PLC_MAX_BITS : 1];
+    for (int t = 0; t < n_tables; ++t) {
+      const uint32_t total = load_freq4(a.freq + (unit * n_tables + t) * 256, lane, f[t], &cum[t]);
+      if (total != kScale && !(ADAPT && total == 0) && threadIdx.x == 0) raise(a.status, PLC_ERR_INVALID);
+      long_form = long_form || __ballot(f[t][0] > 2048u || f[t][1] > 2048u || f[t][2] > 2048u || f[t][3] > 2048u) != 0;
+    }
+    for (int t = 0; t < n_tables; ++t) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      if ((r < 2 ? r : 2) == wave)
-        table[lane * 4 + r] = long_form ? make_enc_entry<true>(f[r], cum) : make_enc_entry<false>(f[r], cum);
-      cum += f[r];
+      for (int r = 0; r < 4; ++r) {
+        if ((r < 2 ? r : 2) == wave)
+          table[t * 256 + lane * 4 + r] =
+              long_form ? make_enc_entry<true>(f[t][r], cum[t]) : make_enc_entry<false>(f[t][r], cum[t]);
+        cum[t] += f[t][r];
+      }
     }
     if (threadIdx.x == 0) table[kIdentity] = make_uint4(0u, 0xffffffffu, 0u, 0u);  // never emits, x' = x
   }
@@ -552,8 +560,10 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
 
   uint32_t x = kLow;              // coder
   bool bad_symbol = false;        // feeder
+  bool bad_depth = false;
   uint4 nv[kStagePieces];         // feeder: next round's symbols in flight
   bool ntake[kStagePieces];
+  uint32_t ntog = 0;              // feeder, ADAPT: table offset of group bottom + lane of the next round
   // packer: the word list, as in the single-wavefront encoder
   uint16_t *wp = a.words_out + a.word_off[unit];
   const uint32_t pad = __builtin_amdgcn_readfirstlane((uint32_t)((reinterpret_cast<uintptr_t>(wp) >> 1) & 7u));
@@ -570,11 +580,16 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
       ntake[i] = r < n_rounds && off < hi;
       if (ntake[i]) nv[i] = load16_stream(ubase + off);
     }
+    if (ADAPT) {
+      const int32_t g = round_bottom(r) + lane;
+      ntog = (r < n_rounds && g < batch_top(4 * r)) ? group_table(a, unit, 0, g, 256u, &bad_depth) : 0u;
+    }
   };
   auto round_store = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < kStagePieces; ++i)
       if (ntake[i]) *reinterpret_cast<uint4 *>(&sym_stage[buf][(lane + 64 * i) * 16]) = nv[i];
+    if (ADAPT) table_of_group[buf][lane] = (uint16_t)ntog;
   };
   if (wave == 1) {
     round_load(0);
@@ -605,6 +620,11 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
           u32x4 e[kBatch / 2];  // native vectors: each entry moves as one 16-byte LDS access
 #pragma unroll
           for (int p = 0; p < kBatch / 2; ++p) sy[p] = s0[2 * kLanes * (kBatch / 2 - 1 - p)];
+          if (ADAPT) {  // the group of step 2p + half sits at top - bottom - 1 - half - 2p of the round
+            const uint16_t *tg = &table_of_group[r & 1][top - bottom - 2 * (kBatch / 2 - 1) - 1 - half];
+#pragma unroll
+            for (int p = 0; p < kBatch / 2; ++p) sy[p] += tg[2 * (kBatch / 2 - 1 - p)];
+          }
 #pragma unroll
           for (int p = 0; p < kBatch / 2; ++p) e[p] = *reinterpret_cast<const u32x4 *>(&table[sy[p]]);
           uint32_t any = 0;
@@ -622,7 +642,8 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
             const int64_t t = (int64_t)(top - 1 - j) * kLanes + l;
             const bool has = j < head && t < (int64_t)len;
             const int64_t idx = has ? t - (int64_t)bottom * kLanes + mis : 0;
-            const uint32_t byte = sb[idx];
+            uint32_t byte = sb[idx];
+            if (ADAPT && has) byte += table_of_group[r & 1][top - 1 - j - bottom];
             const uint4 e = table[has ? byte : (uint32_t)kIdentity];
             bad_symbol = bad_symbol || (e.w & 0x80000000u) != 0;
             eo[2 * p * kLanes] = e;
@@ -707,7 +728,7 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
   if (wave == 0) {
     if (lane < kLanes) a.states_out[unit * kLanes + lane] = x;
   } else if (wave == 1) {
-    if (bad_symbol) raise(a.status, PLC_ERR_INVALID);  // a symbol with f = 0 occurred
+    if (bad_symbol || bad_depth) raise(a.status, PLC_ERR_INVALID);  // a symbol with f = 0, or a bad depth
   } else {
     for (uint32_t q = lane; q < fill; q += 64) {  // the incomplete last piece
       const uint32_t v = vbase + q;
@@ -1263,11 +1284,15 @@ int encode_impl(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stre
   hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_RANS_ENCODE, st);
-    if (!a.bits && a.units_per_stream == 1 && a.n_units <= kPipeMaxUnits) {
+    if (a.units_per_stream == 1 && a.n_units <= kPipeMaxUnits) {
       // no more units than compute-unit halves: the chain of one unit is the time, so give each unit three
       // wavefronts (with more units, three wavefronts per unit cost more in occupancy than the shorter
       // chain gains)
-      hipLaunchKernelGGL(rans_encode_pipe_kernel, dim3((unsigned)a.n_units), dim3(192), 0, st, a);
+      if (a.bits) {
+        hipLaunchKernelGGL(rans_encode_pipe_kernel<true>, dim3((unsigned)a.n_units), dim3(192), 0, st, a);
+      } else {
+        hipLaunchKernelGGL(rans_encode_pipe_kernel<false>, dim3((unsigned)a.n_units), dim3(192), 0, st, a);
+      }
     } else {
       dispatch_waves<LaunchEncode>(waves, a, (unsigned)(n_streams * a.wgs_per_stream), st);
     }
