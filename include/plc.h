@@ -347,6 +347,42 @@ int plc_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const
                              int32_t n_tables, uint8_t *symbols, uint32_t *status, void *stream);
 
 /*
+ * ---- Linear-embedding predictor ------------------------------------------------
+ * Sec. 7.1, "Linear embedding approximation": per layer the KV vector is taken as linear in the
+ * embedding of the next token, F(t_<i, t) ~ c(t_<i) + A E(t), so that the predicted KV vector is
+ * c + A Ebar_i with Ebar_i = sum_t P(t | t_<i) E(t), the expected embedding -- one weighted sum over
+ * the whole vocabulary.  Readings: A is one matrix per layer (a per-position matrix, as the text has
+ * it, would outweigh the cache by orders of magnitude); c has the shape of the KV cache.  Both steps
+ * are dense contractions (fp16 operands, fp32 accumulation on the matrix cores).
+ *
+ *   probs_full  fp16 [rows, V], rows = S*n: the full next-token distribution of every position.
+ *   embed_t     fp16 [m, V]: the embedding table, transposed (vocabulary index contiguous).
+ *   ebar        fp16 [rows, m] (out of plc_expected_embedding, in of the other two).
+ *   A           fp16 [L, H, 2, d, m]: row (h, c, e) of layer l maps an embedding to component e of
+ *               K (c = 0) or V (c = 1) of head h.
+ *   bias_k/v    fp16, logical [S,L,H,n,d] through dims->act_stride (the c of the formula).
+ * rows, n multiples of 128; m and 2*H*d multiples of 128; V a multiple of 32; all pointers 16-byte
+ * aligned.  dims->k and dims->cand_stride are not used.  Residual, quantiser, symbols, escapes and
+ * the reconstruction are those of plc_predict_residual / plc_reconstruct with this prediction; the
+ * accumulation order inside the matrix cores is the hardware's, the same on the encode and the
+ * decode side.
+ */
+int plc_expected_embedding(const void *probs_full, const void *embed_t, int64_t rows, int32_t V,
+                           int32_t m, void *ebar, void *stream);
+
+int plc_predict_residual_linear(const plc_dims *dims, const void *ebar, int32_t m, const void *A,
+                                const void *bias_k, const void *bias_v, const void *act_k,
+                                const void *act_v, uint8_t *symbols, uint16_t *esc_vals,
+                                uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, void *ws,
+                                size_t ws_bytes, uint32_t *status, void *stream);
+
+int plc_reconstruct_linear(const plc_dims *dims, const void *ebar, int32_t m, const void *A,
+                           const void *bias_k, const void *bias_v, const uint8_t *symbols,
+                           const uint16_t *esc_vals, uint64_t esc_len, const uint64_t *esc_off,
+                           void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
+                           void *stream);
+
+/*
  * Instrumentation for benchmarks (not part of the coding path; process-wide,
  * not thread-safe).  While a pair of hipEvent_t (passed as void*) is set for
  * a kernel id, each later call records `start` immediately before and `stop`
@@ -360,7 +396,10 @@ int plc_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const
 #define PLC_TRACE_RANS_DECODE 4
 #define PLC_TRACE_PREDICT_COND 5     /* main kernel of plc_predict_residual_cond */
 #define PLC_TRACE_RECONSTRUCT_COND 6 /* main kernel of plc_reconstruct_cond      */
-#define PLC_TRACE_COUNT 7
+#define PLC_TRACE_EXPECTED_EMBEDDING 7 /* plc_expected_embedding                     */
+#define PLC_TRACE_PREDICT_LINEAR 8     /* contraction of plc_predict_residual_linear */
+#define PLC_TRACE_RECONSTRUCT_LINEAR 9 /* contraction of plc_reconstruct_linear      */
+#define PLC_TRACE_COUNT 10
 int plc_trace_kernel_events(int kernel_id, void *start, void *stop);
 
 #ifdef __cplusplus

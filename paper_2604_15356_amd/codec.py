@@ -130,6 +130,30 @@ class KVDeltaCodec:
         self.rans_decode()
         self.reconstruct(cand_k, cand_v, probs, out_k, out_v)
 
+    # -- linear-embedding predictor ------------------------------------------------------------
+    def encode_linear(self, probs_full, embed_t, A, bias_k, bias_v, act_k, act_v) -> Coded:
+        """Prediction c + A * Ebar with Ebar = probs_full @ embed_t^T (both contractions on the matrix cores),
+        then the core path's residual, quantiser, statistics and rANS."""
+        rows, m = probs_full.shape[0], embed_t.shape[0]
+        if not hasattr(self, "ebar") or self.ebar.shape != (rows, m):
+            self.ebar = torch.empty((rows, m), dtype=torch.float16, device=self.device)
+        plc.plc_expected_embedding(probs_full, embed_t, self.ebar)
+        plc.plc_predict_residual_linear(self.dims, self.ebar, A, bias_k, bias_v, act_k, act_v, self.symbols,
+                                        self.esc_vals, self.esc_cnt, self.esc_off, self.ws, self.status)
+        self.histogram()
+        self.build_freq()
+        self.rans_encode()
+        return self.coded()
+
+    def decode_linear(self, probs_full, embed_t, A, bias_k, bias_v, out_k, out_v):
+        rows, m = probs_full.shape[0], embed_t.shape[0]
+        if not hasattr(self, "ebar") or self.ebar.shape != (rows, m):
+            self.ebar = torch.empty((rows, m), dtype=torch.float16, device=self.device)
+        plc.plc_expected_embedding(probs_full, embed_t, self.ebar)      # recomputed, as a decoder would
+        self.rans_decode()
+        plc.plc_reconstruct_linear(self.dims, self.ebar, A, bias_k, bias_v, self.dec_symbols, self.esc_vals,
+                                   self.esc_off, out_k, out_v, self.ws, self.status)
+
     # -- surprisal-adaptive quantiser on the token-conditional path --------------------------
     def _adapt_buffers(self):
         if not hasattr(self, "bits"):

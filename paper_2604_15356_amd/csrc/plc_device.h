@@ -53,6 +53,16 @@ __device__ __forceinline__ void store16_stream(void *p, uint4 a) {
   __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
 }
 
+// Escape bookkeeping for callers that produce or consume symbols outside the tile-structured kernels
+// (plc_predict.hip): collect the escaped components' raw fp16 values of `act` into the per-stream lists /
+// overwrite the escaped components of `out` from the lists.  dims->k and the candidate strides are not used.
+int gather_escapes(const plc_dims *dims, const void *act_k, const void *act_v, const uint8_t *symbols,
+                   uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, void *ws,
+                   size_t ws_bytes, uint32_t *status, hipStream_t st);
+int patch_escapes(const plc_dims *dims, const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
+                  const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
+                  hipStream_t st);
+
 inline int launch_status() { return hipGetLastError() == hipSuccess ? PLC_OK : PLC_ERR_HIP; }
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

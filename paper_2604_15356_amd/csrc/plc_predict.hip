@@ -394,7 +394,7 @@ __global__ __launch_bounds__(kBlock) void scan_streams_kernel(const uint32_t *__
 __global__ __launch_bounds__(kBlock) void compact_escapes_kernel(const CodecArgs a, uint16_t *__restrict__ esc_vals,
                                                                  uint64_t esc_cap,
                                                                  const uint64_t *__restrict__ esc_off,
-                                                                 int64_t n_tiles) {
+                                                                 int64_t n_tiles, bool staged) {
   const int lane = threadIdx.x & 63;
   const int64_t t = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
   if (t >= n_tiles) return;
@@ -403,7 +403,7 @@ __global__ __launch_bounds__(kBlock) void compact_escapes_kernel(const CodecArgs
   const uint32_t stream = (uint32_t)(t / a.tiles_per_stream);
   const uint32_t tile = (uint32_t)(t - (int64_t)stream * a.tiles_per_stream);
   uint64_t dst = esc_off[stream] + a.tile_off[t];
-  if (cnt <= (uint32_t)kEscStage) {
+  if (staged && cnt <= (uint32_t)kEscStage) {
     const uint16_t *row = a.esc_stage + t * kEscStage;
     for (uint32_t i = lane; i < cnt; i += 64)
       if (dst + i < esc_cap) esc_vals[dst + i] = row[i];
@@ -488,6 +488,38 @@ __global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) 
   if (q.valid) {
     uint16_t *dst = (q.c ? a.out_v : a.out_k) + q.act;
     store16_stream(dst, __builtin_bit_cast(uint4, out));
+  }
+}
+
+// Overwrite the escaped components of a tile's output with their raw values from the stream's list
+// (for outputs written by a kernel that does not handle escapes itself); one workgroup per tile.
+__global__ __launch_bounds__(kBlock) void patch_escapes_kernel(const CodecArgs a) {
+  __shared__ uint32_t smem[8];
+  if (a.tile_cnt[blockIdx.x] == 0) return;  // uniform
+  const Coord q = locate(a);
+  uint2 sv = make_uint2(0u, 0u);
+  uint32_t n_esc = 0;
+  if (q.valid) {
+    sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) n_esc += (((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE;
+  }
+  uint32_t total;
+  const uint32_t rank = block_exclusive_scan(n_esc, smem, &total);
+  if (n_esc) {
+    uint64_t src = a.esc_off[q.stream] + a.tile_off[blockIdx.x] + rank;
+    uint16_t *dst = (q.c ? a.out_v : a.out_k) + q.act;
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) {
+      if ((((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE) {
+        if (src < a.esc_len) {
+          dst[e] = a.esc_in[src];
+        } else {
+          raise(a.status, PLC_ERR_CORRUPT);
+        }
+        ++src;
+      }
+    }
   }
 }
 
@@ -668,7 +700,7 @@ int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
   hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
                      status);
   hipLaunchKernelGGL(compact_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))),
-                     dim3(kBlock), 0, st, a, esc_vals, esc_cap, esc_off, p.n_tiles);
+                     dim3(kBlock), 0, st, a, esc_vals, esc_cap, esc_off, p.n_tiles, true);
   return launch_status();
 }
 
@@ -716,6 +748,58 @@ int decode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
 
 }  // namespace
 }  // namespace plc
+
+int plc::gather_escapes(const plc_dims *dims, const void *act_k, const void *act_v, const uint8_t *symbols,
+                        uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, void *ws,
+                        size_t ws_bytes, uint32_t *status, hipStream_t st) {
+  Plan p;
+  if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  if (!aligned(act_k, 16) || !aligned(act_v, 16) || !aligned(symbols, 8) || !aligned(esc_cnt, 4) ||
+      !aligned(esc_off, 8) || !aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total)
+    return PLC_ERR_INVALID;
+  if (esc_cap > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
+  CodecArgs a = {};
+  fill_args(dims, p, ws, &a);
+  a.act_k = static_cast<const uint16_t *>(act_k);
+  a.act_v = static_cast<const uint16_t *>(act_v);
+  a.symbols = const_cast<uint8_t *>(symbols);
+  a.status = status;
+  uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
+  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
+  hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
+                     (uint32_t)p.tiles_per_stream, esc_cnt);
+  hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
+                     status);
+  hipLaunchKernelGGL(compact_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))),
+                     dim3(kBlock), 0, st, a, esc_vals, esc_cap, esc_off, p.n_tiles, false);
+  return launch_status();
+}
+
+int plc::patch_escapes(const plc_dims *dims, const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
+                       const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
+                       uint32_t *status, hipStream_t st) {
+  Plan p;
+  if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  if (!aligned(out_k, 16) || !aligned(out_v, 16) || !aligned(symbols, 8) || !aligned(esc_off, 8) ||
+      !aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total)
+    return PLC_ERR_INVALID;
+  if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
+  CodecArgs a = {};
+  fill_args(dims, p, ws, &a);
+  a.out_k = static_cast<uint16_t *>(out_k);
+  a.out_v = static_cast<uint16_t *>(out_v);
+  a.symbols = const_cast<uint8_t *>(symbols);
+  a.esc_in = esc_vals;
+  a.esc_len = esc_len;
+  a.esc_off = esc_off;
+  a.status = status;
+  uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
+  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
+  hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
+                     (uint32_t)p.tiles_per_stream, (uint32_t *)nullptr);
+  hipLaunchKernelGGL(patch_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
+  return launch_status();
+}
 
 extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, const void *cand_v,
                                     const float *probs, const void *act_k, const void *act_v,

@@ -26,12 +26,14 @@ EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_
            "plc_index_encode", "plc_index_decode",
            "plc_surprisal_bits", "plc_predict_residual_adapt", "plc_reconstruct_adapt",
            "plc_histogram_bucketed", "plc_build_freq_bucketed", "plc_rans_encode_bucketed",
-           "plc_rans_decode_bucketed")
+           "plc_rans_decode_bucketed",
+           "plc_expected_embedding", "plc_predict_residual_linear", "plc_reconstruct_linear")
 
 MAX_BITS = 4
 
 (TRACE_PREDICT, TRACE_RECONSTRUCT, TRACE_HISTOGRAM, TRACE_RANS_ENCODE, TRACE_RANS_DECODE,
- TRACE_PREDICT_COND, TRACE_RECONSTRUCT_COND) = range(7)
+ TRACE_PREDICT_COND, TRACE_RECONSTRUCT_COND, TRACE_EXPECTED_EMBEDDING, TRACE_PREDICT_LINEAR,
+ TRACE_RECONSTRUCT_LINEAR) = range(10)
 
 
 class PlcError(RuntimeError):
@@ -85,6 +87,9 @@ def lib() -> C.CDLL:
         L.plc_build_freq_bucketed.argtypes = [p, i64, i32, p, p, p]
         L.plc_rans_encode_bucketed.argtypes = [p, i64, i64, i32, i32, i32, p, i32, p, p, p, p, u64, p, p, p]
         L.plc_rans_decode_bucketed.argtypes = [p, p, p, u64, p, p, i64, i64, i32, i32, i32, p, i32, p, p, p]
+        L.plc_expected_embedding.argtypes = [p, p, i64, i32, i32, p, p]
+        L.plc_predict_residual_linear.argtypes = [dp, p, i32, p, p, p, p, p, p, p, u64, p, p, p, sz, p, p]
+        L.plc_reconstruct_linear.argtypes = [dp, p, i32, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
         _lib = L
     return _lib
 
@@ -319,6 +324,36 @@ def plc_rans_decode_bucketed(freq, states, words, word_off, n_words, n_streams, 
                                         streams_per_session, _contig(bits, torch.uint8), n_tables,
                                         _contig(symbols, torch.uint8), _contig(status, torch.int32), _stream())
     _check(rc, "plc_rans_decode_bucketed")
+
+
+def plc_expected_embedding(probs_full, embed_t, ebar):
+    """probs_full fp16 [rows, V], embed_t fp16 [m, V] -> ebar fp16 [rows, m]."""
+    rows, V = probs_full.shape
+    m = embed_t.shape[0]
+    rc = lib().plc_expected_embedding(_contig(probs_full, torch.float16), _contig(embed_t, torch.float16), rows, V,
+                                      m, _contig(ebar, torch.float16), _stream())
+    _check(rc, "plc_expected_embedding")
+
+
+def plc_predict_residual_linear(dims, ebar, A, bias_k, bias_v, act_k, act_v, symbols, esc_vals, esc_cnt, esc_off,
+                                ws, status):
+    m = A.shape[-1]
+    rc = lib().plc_predict_residual_linear(
+        C.byref(dims), _contig(ebar, torch.float16), m, _contig(A, torch.float16), _ptr(bias_k, torch.float16),
+        _ptr(bias_v, torch.float16), _ptr(act_k, torch.float16), _ptr(act_v, torch.float16),
+        _contig(symbols, torch.uint8), _contig(esc_vals, None), esc_vals.numel(), _contig(esc_cnt, torch.int32),
+        _contig(esc_off, torch.int64), _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_predict_residual_linear")
+
+
+def plc_reconstruct_linear(dims, ebar, A, bias_k, bias_v, symbols, esc_vals, esc_off, out_k, out_v, ws, status):
+    m = A.shape[-1]
+    rc = lib().plc_reconstruct_linear(
+        C.byref(dims), _contig(ebar, torch.float16), m, _contig(A, torch.float16), _ptr(bias_k, torch.float16),
+        _ptr(bias_v, torch.float16), _contig(symbols, torch.uint8), _contig(esc_vals, None), esc_vals.numel(),
+        _contig(esc_off, torch.int64), _ptr(out_k, torch.float16), _ptr(out_v, torch.float16),
+        _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_reconstruct_linear")
 
 
 def plc_trace_kernel_events(kernel_id, start=None, stop=None):

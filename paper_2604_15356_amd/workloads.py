@@ -199,3 +199,91 @@ def random_bytes(n_streams: int, syms_per_stream: int, seed: int, kind: str = "g
         r = torch.rand(shape, generator=gen, device=device)
         return torch.where(r < 1e-3, 255, 127).to(torch.uint8)
     raise ValueError(kind)
+
+
+# ------------------------------------------------------------------------------------------------
+# Inputs of the linear-embedding predictor: a full-vocabulary distribution per position, an embedding
+# table, one matrix per layer and a bias of the KV cache's shape; the actual vectors are linear in the
+# true token's embedding plus noise.
+
+LINEAR_CONFIGS = {
+    # name: sessions, layers, KV heads, head dim, positions, embedding dim, vocabulary, perplexity, noise, step, seed
+    "tiny":    dict(S=1, L=2,  H=2, d=64,  n=256,  m=256,  V=1024,  pp=12.0, sigma=0.05, delta=0.02, seed=10),
+    "llama8b": dict(S=1, L=32, H=8, d=128, n=4096, m=4096, V=50016, pp=15.0, sigma=0.05, delta=0.02, seed=11),
+}
+
+
+@dataclasses.dataclass
+class LinearWorkload:
+    name: str
+    S: int
+    L: int
+    H: int
+    n: int
+    d: int
+    m: int
+    V: int
+    delta: float
+    qmax: int
+    sigma: float
+    probs_full: torch.Tensor   # fp16 [S*n, V]
+    embed_t: torch.Tensor      # fp16 [m, V]
+    A: torch.Tensor            # fp16 [L, H, 2, d, m]
+    bias_k: torch.Tensor       # fp16 [S, L, H, n, d]
+    bias_v: torch.Tensor
+    act_k: torch.Tensor        # fp16 [S, L, H, n, d]
+    act_v: torch.Tensor
+    token: torch.Tensor        # int64 [S*n] the true token of every position
+
+    @property
+    def kv_bytes(self) -> int:
+        return 2 * self.S * self.L * self.H * self.n * self.d * 2
+
+
+def zipf_full_probs(perplexity: float, vocab: int, s: float = ZIPF_S) -> np.ndarray:
+    """The whole distribution p_j ~ j^(-s/T) with exp(entropy) = perplexity (see zipf_topk_probs)."""
+    return zipf_topk_probs(perplexity, vocab, vocab=vocab, s=s)
+
+
+def make_linear_workload(name: str = "tiny", device="cpu", overrides: Optional[dict] = None,
+                         one_hot: bool = False) -> LinearWorkload:
+    """`one_hot` puts all probability on the true token and sets the noise to zero."""
+    cfg = dict(LINEAR_CONFIGS[name])
+    if overrides:
+        cfg.update(overrides)
+    S, L, H, d, n, m, V = (cfg[x] for x in ("S", "L", "H", "d", "n", "m", "V"))
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(int(cfg["seed"]))
+    sigma = 0.0 if one_hot else float(cfg["sigma"])
+    zipf = torch.from_numpy(zipf_full_probs(float(cfg["pp"]), V).astype(np.float32)).to(dev)
+    rows = S * n
+    # every position ranks the vocabulary its own way: a per-position rotation of the Zipf row
+    shift = torch.randint(0, V, (rows,), generator=gen, device=dev)
+    probs_full = torch.empty((rows, V), dtype=torch.float16, device=dev)
+    token = torch.empty(rows, dtype=torch.int64, device=dev)
+    ar = torch.arange(V, device=dev)
+    for r0 in range(0, rows, 512):
+        idx = (ar[None, :] + shift[r0:r0 + 512, None]) % V
+        p = zipf[idx]
+        token[r0:r0 + 512] = torch.multinomial(p, 1, generator=gen).squeeze(1)
+        if one_hot:
+            p = torch.zeros_like(p).scatter_(1, token[r0:r0 + 512, None], 1.0)
+        probs_full[r0:r0 + 512] = p.to(torch.float16)
+    embed_t = torch.randn((m, V), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+    A = (torch.randn((L, H, 2, d, m), generator=gen, device=dev, dtype=torch.float32) / float(np.sqrt(m))).to(torch.float16)
+    bias_k = torch.randn((S, L, H, n, d), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+    bias_v = torch.randn((S, L, H, n, d), generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+    act_k = torch.empty_like(bias_k)
+    act_v = torch.empty_like(bias_v)
+    e_true = embed_t[:, token].t().to(torch.float32).reshape(S, n, m)              # [S, n, m]
+    for s in range(S):
+        for l in range(L):
+            lin = e_true[s] @ A[l].reshape(2 * H * d, m).to(torch.float32).t()      # [n, 2Hd]
+            lin = lin.reshape(n, H, 2, d).permute(1, 2, 0, 3)                       # [H, 2, n, d]
+            for c, (bias, act) in enumerate(((bias_k, act_k), (bias_v, act_v))):
+                z = torch.randn((H, n, d), generator=gen, device=dev, dtype=torch.float32)
+                act[s, l].copy_((bias[s, l].to(torch.float32) + lin[:, c] + sigma * z).to(torch.float16))
+    return LinearWorkload(name=name, S=S, L=L, H=H, n=n, d=d, m=m, V=V, delta=float(cfg["delta"]), qmax=127,
+                          sigma=sigma, probs_full=probs_full, embed_t=embed_t, A=A, bias_k=bias_k, bias_v=bias_v,
+                          act_k=act_k, act_v=act_v, token=token)
