@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--no-adaptive", action="store_true",
                     help="skip the side measurement of the surprisal-adaptive quantiser (bit depth per position from "
                          "the token's surprisal, one table per depth) on the token-conditional path")
+    ap.add_argument("--no-linear", action="store_true",
+                    help="skip the side measurement of the linear-embedding predictor (two fp16 contractions on the "
+                         "matrix cores; Llama-shaped configuration only)")
     ap.add_argument("--adaptive-b0", type=float, default=3.0, help="target average bit depth b0")
     ap.add_argument("--adaptive-range", type=float, default=0.32, help="quantiser range: step = range / 2^depth")
     return ap.parse_args()
@@ -59,13 +62,17 @@ def parse():
 class KernelTimer:
     """HIP event pairs recorded by libplc around the main kernel of each call."""
 
-    def __init__(self, plc, torch, steps, conditional=False):
+    def __init__(self, plc, torch, steps, conditional=False, linear=False):
         self.plc, self.ids = plc, {"predict_residual": plc.TRACE_PREDICT, "reconstruct": plc.TRACE_RECONSTRUCT,
                                    "histogram": plc.TRACE_HISTOGRAM, "rans_encode": plc.TRACE_RANS_ENCODE,
                                    "rans_decode": plc.TRACE_RANS_DECODE}
         if conditional:
             del self.ids["predict_residual"], self.ids["reconstruct"]
             self.ids.update(predict_residual_cond=plc.TRACE_PREDICT_COND, reconstruct_cond=plc.TRACE_RECONSTRUCT_COND)
+        if linear:
+            del self.ids["predict_residual"], self.ids["reconstruct"]
+            self.ids.update(expected_embedding=plc.TRACE_EXPECTED_EMBEDDING, predict_linear=plc.TRACE_PREDICT_LINEAR,
+                            reconstruct_linear=plc.TRACE_RECONSTRUCT_LINEAR)
         self.ev = {}
         for name in self.ids:
             pairs = []
@@ -405,6 +412,72 @@ def main():
             f"mse {r4['mean_square_error']:.3e} (fixed step: {r4['fixed_step_mean_square_error']:.3e}); "
             f"rans_encode {ms4['rans_encode']:.3f} ms, rans_decode {ms4['rans_decode']:.3f} ms")
         del codec4
+    if not args.no_linear and args.config == "llama8b" and not args.sessions:
+        # Linear-embedding predictor on a workload of the same KV shape: prediction = c + A * Ebar with
+        # Ebar = P * E over a 50,016-token vocabulary (embedding dimension 4096), both contractions in fp16 on the
+        # matrix cores with fp32 accumulation; the expected embedding is recomputed on the decode side.
+        from paper_2604_15356_amd.workloads import make_linear_workload
+        MFMA_PEAK_TFLOPS = 2500.0           # MI355X dense fp16, published
+        t0 = time.perf_counter()
+        lw = make_linear_workload("llama8b", device=dev)
+        torch.cuda.synchronize()
+        log(f"  linear-predictor workload: m {lw.m}, V {lw.V} drawn in {time.perf_counter() - t0:.1f} s")
+        codec5 = KVDeltaCodec(lw.S, lw.L, lw.H, lw.n, 1, lw.d, lw.delta, lw.qmax, chunk_syms=args.chunk_syms, device=dev)
+        lo_k, lo_v = torch.empty_like(lw.act_k), torch.empty_like(lw.act_v)
+
+        def step5():
+            codec5.encode_linear(lw.probs_full, lw.embed_t, lw.A, lw.bias_k, lw.bias_v, lw.act_k, lw.act_v)
+            codec5.decode_linear(lw.probs_full, lw.embed_t, lw.A, lw.bias_k, lw.bias_v, lo_k, lo_v)
+
+        lin_steps = max(2, args.steps // 4)
+        for _ in range(min(2, args.warmup)):
+            step5()
+        torch.cuda.synchronize()
+        timer5 = KernelTimer(plc, torch, lin_steps, linear=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(lin_steps):
+            timer5.arm(i)
+            step5()
+        torch.cuda.synchronize()
+        dt5 = time.perf_counter() - t0
+        timer5.disarm()
+        codec5.check_status("linear-predictor steps")
+        ms5 = timer5.mean_ms()
+        rows5 = lw.S * lw.n
+        flops = {"expected_embedding": 2.0 * rows5 * lw.m * lw.V,
+                 "predict_linear": 2.0 * lw.S * lw.L * lw.n * (2 * lw.H * lw.d) * lw.m,
+                 "reconstruct_linear": 2.0 * lw.S * lw.L * lw.n * (2 * lw.H * lw.d) * lw.m}
+        k5 = {}
+        for name, fl in flops.items():
+            tf = fl / (ms5[name] * 1e-3) / 1e12
+            k5[name] = dict(ms=round(ms5[name], 4), TFLOPs=round(tf, 1), frac_mfma=round(tf / MFMA_PEAK_TFLOPS, 4))
+        E5 = lw.S * lw.L * lw.H * lw.n * 2 * lw.d
+        nw5 = codec5.n_words.cpu().numpy().view(np.uint32).astype(np.int64)
+        esc5 = int(codec5.esc_cnt.cpu().numpy().view(np.uint32).astype(np.int64).sum())
+        err5 = 0.0
+        for l_ in range(lw.L):
+            for got, want in ((lo_k, lw.act_k), (lo_v, lw.act_v)):
+                diff = (got[0, l_].float() - want[0, l_].float()).abs()
+                err5 = max(err5, float(torch.nan_to_num(diff, nan=0.0, posinf=0.0).max()))
+        dom5 = k5["predict_linear"]
+        result["linear_predictor"] = {
+            "workload": f"S={lw.S} L={lw.L} H={lw.H} d={lw.d} n={lw.n} m={lw.m} V={lw.V}", "steps": lin_steps,
+            "value": round(lw.kv_bytes / (dt5 / lin_steps) / 1e9, 2), "unit": "GB/s",
+            "ms_per_step": round(dt5 / lin_steps * 1e3, 4),
+            "roofline": dict(bound="mfma", kernel="gemm_nt_kernel<EncodeLinear>", achieved=dom5["TFLOPs"],
+                             peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=dom5["frac_mfma"], traffic=None),
+            "kernels": k5, "kernels_ms": {k: round(v, 4) for k, v in ms5.items()},
+            "payload_bits_per_symbol": round((16 * int(nw5.sum()) + 16 * esc5) / E5, 4),
+            "escape_rate": round(esc5 / E5, 6),
+            "roundtrip_symbols_exact": bool(torch.equal(codec5.dec_symbols, codec5.symbols)),
+            "max_abs_reconstruction_error": round(err5, 6),
+        }
+        log(f"  linear predictor: step {result['linear_predictor']['ms_per_step']} ms ({result['linear_predictor']['value']} GB/s); "
+            + ", ".join(f"{k} {v['ms']} ms = {v['TFLOPs']} TFLOP/s ({100 * v['frac_mfma']:.1f} % of fp16 MFMA peak)"
+                        for k, v in k5.items()))
+        del codec5, lw, lo_k, lo_v
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         base, sym64 = cpu_baseline(w, args.cpu_streams, torch)
         result["cpu_baseline"] = base

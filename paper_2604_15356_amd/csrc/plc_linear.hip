@@ -46,19 +46,18 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16 *__restrict
   const _Float16 *xg = xb + (int64_t)lrow * K + lk;
   const _Float16 *yg = yb + (int64_t)lrow * K + lk;
   const int64_t half_tile = (int64_t)64 * K;
-  uint4 px[2], py[2];
-  auto fetch = [&](int k0) {
-    px[0] = *reinterpret_cast<const uint4 *>(xg + k0);
-    px[1] = *reinterpret_cast<const uint4 *>(xg + k0 + half_tile);
-    py[0] = *reinterpret_cast<const uint4 *>(yg + k0);
-    py[1] = *reinterpret_cast<const uint4 *>(yg + k0 + half_tile);
-  };
-  auto land = [&](int buf) {
-    *reinterpret_cast<uint4 *>(&xs[buf][lrow * kLdsRow + lk]) = px[0];
-    *reinterpret_cast<uint4 *>(&xs[buf][(lrow + 64) * kLdsRow + lk]) = px[1];
-    *reinterpret_cast<uint4 *>(&ys[buf][lrow * kLdsRow + lk]) = py[0];
-    *reinterpret_cast<uint4 *>(&ys[buf][(lrow + 64) * kLdsRow + lk]) = py[1];
-  };
+  // (plain variables and macros, not arrays captured by a lambda: those would live in scratch memory)
+  uint4 px0, px1, py0, py1;
+#define PLC_FETCH(k0)                                                  \
+  px0 = *reinterpret_cast<const uint4 *>(xg + (k0));                   \
+  px1 = *reinterpret_cast<const uint4 *>(xg + (k0) + half_tile);       \
+  py0 = *reinterpret_cast<const uint4 *>(yg + (k0));                   \
+  py1 = *reinterpret_cast<const uint4 *>(yg + (k0) + half_tile)
+#define PLC_LAND(buf)                                                              \
+  *reinterpret_cast<uint4 *>(&xs[buf][lrow * kLdsRow + lk]) = px0;                 \
+  *reinterpret_cast<uint4 *>(&xs[buf][(lrow + 64) * kLdsRow + lk]) = px1;          \
+  *reinterpret_cast<uint4 *>(&ys[buf][lrow * kLdsRow + lk]) = py0;                 \
+  *reinterpret_cast<uint4 *>(&ys[buf][(lrow + 64) * kLdsRow + lk]) = py1
 
   float16v acc[2][2];
 #pragma unroll
@@ -68,14 +67,16 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16 *__restrict
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
-  fetch(0);
-  land(0);
+  PLC_FETCH(0);
+  PLC_LAND(0);
   __syncthreads();
   const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
   const int slices = K / kTileK;
   for (int s = 0; s < slices; ++s) {
     const int buf = s & 1;
-    if (s + 1 < slices) fetch((s + 1) * kTileK);
+    if (s + 1 < slices) {
+      PLC_FETCH((s + 1) * kTileK);
+    }
     const _Float16 *xa = &xs[buf][(wm * 64 + frag_row) * kLdsRow + frag_k];
     const _Float16 *ya = &ys[buf][(wn * 64 + frag_row) * kLdsRow + frag_k];
 #pragma unroll
@@ -91,9 +92,13 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16 *__restrict
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[b], acc[a][b], 0, 0, 0);
     }
-    if (s + 1 < slices) land(buf ^ 1);
+    if (s + 1 < slices) {
+      PLC_LAND(buf ^ 1);
+    }
     __syncthreads();
   }
+#undef PLC_FETCH
+#undef PLC_LAND
 
   const int row0 = tile_m * kTileM + wm * 64 + 4 * (lane >> 5);
   const int col0 = tile_n * kTileN + wn * 64 + (lane & 31);
