@@ -12,8 +12,8 @@
 // in v_mfma_f32_32x32x16_f16.  A workgroup of four wavefronts owns a 128 x 128 tile of C, each wavefront
 // a 64 x 64 quarter (2 x 2 MFMA tiles, 64 accumulator registers).  K advances in slices of 32 through two
 // LDS buffers; the next slice travels global -> registers while the current one is multiplied, and is
-// written to the other buffer afterwards, so one barrier per slice suffices.  Rows of a slice are padded
-// to 80 bytes in LDS so that the 16-byte fragment reads of 32 consecutive rows spread over the banks.
+// written to the other buffer afterwards, so one barrier per slice suffices.  The 16-byte pieces of a
+// slice row are stored swizzled so that the fragment reads of consecutive rows spread over the banks.
 #include "plc_device.h"
 
 namespace plc {
@@ -23,7 +23,11 @@ typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 
 constexpr int kTileM = 128, kTileN = 128, kTileK = 32;
-constexpr int kLdsRow = 40;  // halves per padded row (80 bytes)
+constexpr int kLdsRow = 32;  // halves per LDS row (64 bytes = four 16-byte pieces, stored swizzled)
+
+// A slice row holds four 16-byte pieces; piece g of row r is stored at position g ^ ((r >> 1) & 3), so that
+// eight consecutive rows reading the same piece touch eight different 16-byte columns of the 128-byte bank line.
+__device__ __forceinline__ int lds_piece(int row, int g) { return row * kLdsRow + ((g ^ ((row >> 1) & 3)) << 3); }
 
 // Fragment layout of v_mfma_f32_32x32x16_f16 (checked on the device): lane l holds A[l % 32][8 (l / 32) + j],
 // B[8 (l / 32) + j][l % 32], j = 0..7, and C[8 (i / 4) + 4 (l / 32) + i % 4][l % 32] in accumulator i = 0..15.
@@ -46,18 +50,20 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16 *__restrict
   const _Float16 *xg = xb + (int64_t)lrow * K + lk;
   const _Float16 *yg = yb + (int64_t)lrow * K + lk;
   const int64_t half_tile = (int64_t)64 * K;
-  // (plain variables and macros, not arrays captured by a lambda: those would live in scratch memory)
-  uint4 px0, px1, py0, py1;
-#define PLC_FETCH(k0)                                                  \
-  px0 = *reinterpret_cast<const uint4 *>(xg + (k0));                   \
-  px1 = *reinterpret_cast<const uint4 *>(xg + (k0) + half_tile);       \
-  py0 = *reinterpret_cast<const uint4 *>(yg + (k0));                   \
-  py1 = *reinterpret_cast<const uint4 *>(yg + (k0) + half_tile)
-#define PLC_LAND(buf)                                                              \
-  *reinterpret_cast<uint4 *>(&xs[buf][lrow * kLdsRow + lk]) = px0;                 \
-  *reinterpret_cast<uint4 *>(&xs[buf][(lrow + 64) * kLdsRow + lk]) = px1;          \
-  *reinterpret_cast<uint4 *>(&ys[buf][lrow * kLdsRow + lk]) = py0;                 \
-  *reinterpret_cast<uint4 *>(&ys[buf][(lrow + 64) * kLdsRow + lk]) = py1
+  // Two register sets (A, B) carry the slices two and three steps ahead, so that a global load has two
+  // multiply phases to arrive in before it is written to LDS.  (Plain variables and macros, not arrays
+  // captured by a lambda: those would live in scratch memory.)
+  uint4 ax0, ax1, ay0, ay1, bx0, bx1, by0, by1;
+#define PLC_FETCH(R, k0)                                               \
+  R##x0 = *reinterpret_cast<const uint4 *>(xg + (k0));                 \
+  R##x1 = *reinterpret_cast<const uint4 *>(xg + (k0) + half_tile);     \
+  R##y0 = *reinterpret_cast<const uint4 *>(yg + (k0));                 \
+  R##y1 = *reinterpret_cast<const uint4 *>(yg + (k0) + half_tile)
+#define PLC_LAND(R, buf)                                                           \
+  *reinterpret_cast<uint4 *>(&xs[buf][lds_piece(lrow, lk >> 3)]) = R##x0;          \
+  *reinterpret_cast<uint4 *>(&xs[buf][lds_piece(lrow + 64, lk >> 3)]) = R##x1;     \
+  *reinterpret_cast<uint4 *>(&ys[buf][lds_piece(lrow, lk >> 3)]) = R##y0;          \
+  *reinterpret_cast<uint4 *>(&ys[buf][lds_piece(lrow + 64, lk >> 3)]) = R##y1
 
   float16v acc[2][2];
 #pragma unroll
@@ -67,33 +73,49 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16 *__restrict
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
-  PLC_FETCH(0);
-  PLC_LAND(0);
-  __syncthreads();
   const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
   const int slices = K / kTileK;
-  for (int s = 0; s < slices; ++s) {
-    const int buf = s & 1;
-    if (s + 1 < slices) {
-      PLC_FETCH((s + 1) * kTileK);
-    }
-    const _Float16 *xa = &xs[buf][(wm * 64 + frag_row) * kLdsRow + frag_k];
-    const _Float16 *ya = &ys[buf][(wn * 64 + frag_row) * kLdsRow + frag_k];
+  auto multiply = [&](int buf) {
 #pragma unroll
     for (int ks = 0; ks < kTileK / 16; ++ks) {
       half8 fa[2], fb[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        fa[t] = *reinterpret_cast<const half8 *>(xa + t * 32 * kLdsRow + ks * 16);
-        fb[t] = *reinterpret_cast<const half8 *>(ya + t * 32 * kLdsRow + ks * 16);
+        fa[t] = *reinterpret_cast<const half8 *>(&xs[buf][lds_piece(wm * 64 + t * 32 + frag_row, (frag_k >> 3) + 2 * ks)]);
+        fb[t] = *reinterpret_cast<const half8 *>(&ys[buf][lds_piece(wn * 64 + t * 32 + frag_row, (frag_k >> 3) + 2 * ks)]);
       }
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[b], acc[a][b], 0, 0, 0);
     }
+  };
+
+  PLC_FETCH(a, 0);
+  PLC_LAND(a, 0);
+  if (slices > 1) {
+    PLC_FETCH(a, kTileK);
+  }
+  if (slices > 2) {
+    PLC_FETCH(b, 2 * kTileK);
+  }
+  __syncthreads();
+  for (int s = 0; s < slices; s += 2) {
+    // slice s sits in buffer 0, slice s + 1 in set A, slice s + 2 in set B
+    multiply(0);
     if (s + 1 < slices) {
-      PLC_LAND(buf ^ 1);
+      PLC_LAND(a, 1);
+      if (s + 3 < slices) {
+        PLC_FETCH(a, (s + 3) * kTileK);
+      }
+    }
+    __syncthreads();
+    if (s + 1 < slices) multiply(1);
+    if (s + 2 < slices) {
+      PLC_LAND(b, 0);
+      if (s + 4 < slices) {
+        PLC_FETCH(b, (s + 4) * kTileK);
+      }
     }
     __syncthreads();
   }
