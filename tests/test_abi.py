@@ -107,6 +107,18 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert L.plc_rans_encode_bucketed(p, 1, 1024, 0, 64, 1, None, 4, p, p, p, p, 100, p, p, None) == 1
     assert L.plc_rans_encode_bucketed(p, 1, 1024, 0, 16, 1, p, 4, p, p, p, p, 100, p, p, None) == 1
     assert L.plc_rans_decode_bucketed(p, p, p, 10, p, p, 1, 1024, 48, 64, 1, p, 4, p, p, None) == 1
+    # linear-embedding predictor: whole tiles only, 16-byte aligned operands
+    assert L.plc_expected_embedding(p, p, 100, 64, 128, p, None) == 1            # rows not a multiple of 128
+    assert L.plc_expected_embedding(p, p, 128, 50, 128, p, None) == 1            # vocabulary not a multiple of 32
+    assert L.plc_expected_embedding(p, p, 128, 64, 96, p, None) == 1             # embedding dim not a multiple of 128
+    assert L.plc_expected_embedding(C.c_void_p(4104), p, 128, 64, 128, p, None) == 1
+    lin = plc.make_dims(1, 2, 2, 128, 1, 32, 0.02)
+    lin.n = 100                                                                   # positions not a multiple of 128
+    assert L.plc_predict_residual_linear(C.byref(lin), p, 128, p, p, p, p, p, p, p, 0, p, p, p, 1 << 20, p, None) == 1
+    lin = plc.make_dims(1, 2, 1, 128, 1, 32, 0.02)                                # 2*H*d = 64: not a whole tile
+    assert L.plc_reconstruct_linear(C.byref(lin), p, 128, p, p, p, p, p, 0, p, p, p, p, 1 << 20, p, None) == 1
+    lin = plc.make_dims(1, 2, 2, 128, 1, 32, 0.02)
+    assert L.plc_reconstruct_linear(C.byref(lin), p, 100, p, p, p, p, p, 0, p, p, p, p, 1 << 20, p, None) == 1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
