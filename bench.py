@@ -54,6 +54,7 @@ def parse():
     ap.add_argument("--no-linear", action="store_true",
                     help="skip the side measurement of the linear-embedding predictor (two fp16 contractions on the "
                          "matrix cores; Llama-shaped configuration only)")
+    ap.add_argument("--no-prefix-index", action="store_true", help="skip the host-side prefix index measurement")
     ap.add_argument("--adaptive-b0", type=float, default=3.0, help="target average bit depth b0")
     ap.add_argument("--adaptive-range", type=float, default=0.32, help="quantiser range: step = range / 2^depth")
     return ap.parse_args()
@@ -478,6 +479,40 @@ def main():
                         for k, v in k5.items()))
         del codec5, lw, lo_k, lo_v
         torch.cuda.empty_cache()
+    if not args.no_prefix_index:
+        # The host-side prefix index in front of the path: 2,000 sessions of 2,048 tokens that share prefixes
+        # (each continues a random earlier session from a random depth), inserted, looked up and evicted.
+        rng = np.random.default_rng(0)
+        sessions = []
+        for i in range(2000):
+            tail = rng.integers(0, 50000, 2048).astype(np.int32)
+            if sessions and rng.random() < 0.8:
+                base = sessions[int(rng.integers(len(sessions)))]
+                cut = int(rng.integers(0, 2048))
+                tail[:cut] = base[:cut]
+            sessions.append(tail)
+        bits = np.full(2048, 3.9, dtype=np.float32)
+        trie = plc.PrefixTrie()
+        t0 = time.perf_counter()
+        for i, sess in enumerate(sessions):
+            trie.insert(sess, i, bits)
+        t1 = time.perf_counter()
+        hits = sum(trie.best_match(sess)[1] == 2048 for sess in sessions)
+        t2 = time.perf_counter()
+        nodes = trie.nodes
+        for i in range(len(sessions)):
+            trie.evict(i)
+        t3 = time.perf_counter()
+        tok = len(sessions) * 2048
+        result["prefix_index"] = {"sessions": len(sessions), "tokens_per_session": 2048, "nodes": nodes,
+                                  "insert_Mtokens_per_s": round(tok / (t1 - t0) / 1e6, 2),
+                                  "best_match_Mtokens_per_s": round(tok / (t2 - t1) / 1e6, 2),
+                                  "evict_Mtokens_per_s": round(tok / (t3 - t2) / 1e6, 2),
+                                  "exact_matches": int(hits), "empty_after_evict": trie.nodes == 1, "threads": 1}
+        log(f"  prefix index (host, 1 thread): insert {result['prefix_index']['insert_Mtokens_per_s']} M tokens/s, "
+            f"best match {result['prefix_index']['best_match_Mtokens_per_s']}, evict {result['prefix_index']['evict_Mtokens_per_s']}; "
+            f"{nodes} nodes for {tok} tokens")
+        trie.close()
     if not args.no_cpu_baseline:
         base, sym64 = cpu_baseline(w, args.cpu_streams, torch)
         result["cpu_baseline"] = base

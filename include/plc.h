@@ -383,6 +383,39 @@ int plc_reconstruct_linear(const plc_dims *dims, const void *ebar, int32_t m, co
                            void *stream);
 
 /*
+ * ---- Prefix index (host only) ---------------------------------------------------
+ * Sec. 7.3, "Trie-Based Prefix Index": the structure in front of this path that finds, for a new
+ * session, the stored session whose KV cache it can be coded against: a trie over token sequences
+ * with insert, best-match lookup and evict, each linear in the prefix length.  All arguments are
+ * HOST pointers; nothing here touches the GPU; a trie is not thread-safe.  Readings: the trie is
+ * "pruned at nodes with probability below a threshold": a prefix is stored only down to the last
+ * token at which its surprisal sum stays <= max_bits (= -log2 of that threshold); the best match is
+ * the stored prefix with the longest common prefix with the query ("follow the path of the query
+ * until it diverges from all stored paths"), for which the trie metric of Def. "PLT trie metric"
+ * d_T = -log2 P(common prefix) is returned (the text's "maximizing d_T" and "maximizing the
+ * probability of the longest common prefix" contradict each other; the traversal it describes is
+ * what is implemented).
+ *
+ *   tokens  i32 [n];  bits  fp32 [n], nullable: surprisal -log2 P(token | path) of each token, >= 0.
+ *   id      caller's handle of a stored prefix, >= 0, unique.
+ * plc_trie_insert: *stored_len (nullable) = tokens kept.  PLC_ERR_CAPACITY if another stored prefix
+ *   already ends at the same node (the two are indistinguishable to the index); nothing changes then.
+ * plc_trie_best_match: *id = a stored prefix sharing the longest common prefix with the query (-1 if
+ *   the trie is empty), *lcp = its length in tokens, *dist = sum of `bits` along it.
+ * plc_trie_evict: removes a stored prefix and the nodes no stored prefix passes through any more.
+ */
+typedef struct plc_trie plc_trie;
+plc_trie *plc_trie_create(double max_bits);
+void plc_trie_destroy(plc_trie *trie);
+int64_t plc_trie_size(const plc_trie *trie);  /* stored prefixes */
+int64_t plc_trie_nodes(const plc_trie *trie); /* nodes, the root included */
+int plc_trie_insert(plc_trie *trie, const int32_t *tokens, const float *bits, int64_t n, int64_t id,
+                    int64_t *stored_len);
+int plc_trie_best_match(const plc_trie *trie, const int32_t *tokens, int64_t n, int64_t *id,
+                        int64_t *lcp, double *dist);
+int plc_trie_evict(plc_trie *trie, int64_t id);
+
+/*
  * Instrumentation for benchmarks (not part of the coding path; process-wide,
  * not thread-safe).  While a pair of hipEvent_t (passed as void*) is set for
  * a kernel id, each later call records `start` immediately before and `stop`

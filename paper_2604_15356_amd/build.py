@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libplc.so")
-SOURCES = ["plc_api.hip", "plc_predict.hip", "plc_hist_freq.hip", "plc_rans.hip", "plc_index.hip", "plc_linear.hip"]
+SOURCES = ["plc_api.hip", "plc_predict.hip", "plc_hist_freq.hip", "plc_rans.hip", "plc_index.hip", "plc_linear.hip", "plc_trie.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

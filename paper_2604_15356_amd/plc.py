@@ -27,7 +27,9 @@ EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_
            "plc_surprisal_bits", "plc_predict_residual_adapt", "plc_reconstruct_adapt",
            "plc_histogram_bucketed", "plc_build_freq_bucketed", "plc_rans_encode_bucketed",
            "plc_rans_decode_bucketed",
-           "plc_expected_embedding", "plc_predict_residual_linear", "plc_reconstruct_linear")
+           "plc_expected_embedding", "plc_predict_residual_linear", "plc_reconstruct_linear",
+           "plc_trie_create", "plc_trie_destroy", "plc_trie_size", "plc_trie_nodes", "plc_trie_insert",
+           "plc_trie_best_match", "plc_trie_evict")
 
 MAX_BITS = 4
 
@@ -87,6 +89,17 @@ def lib() -> C.CDLL:
         L.plc_build_freq_bucketed.argtypes = [p, i64, i32, p, p, p]
         L.plc_rans_encode_bucketed.argtypes = [p, i64, i64, i32, i32, i32, p, i32, p, p, p, p, u64, p, p, p]
         L.plc_rans_decode_bucketed.argtypes = [p, p, p, u64, p, p, i64, i64, i32, i32, i32, p, i32, p, p, p]
+        L.plc_trie_create.restype = p
+        L.plc_trie_create.argtypes = [C.c_double]
+        L.plc_trie_destroy.restype = None
+        L.plc_trie_destroy.argtypes = [p]
+        L.plc_trie_size.restype = i64
+        L.plc_trie_size.argtypes = [p]
+        L.plc_trie_nodes.restype = i64
+        L.plc_trie_nodes.argtypes = [p]
+        L.plc_trie_insert.argtypes = [p, p, p, i64, i64, C.POINTER(i64)]
+        L.plc_trie_best_match.argtypes = [p, p, i64, C.POINTER(i64), C.POINTER(i64), C.POINTER(C.c_double)]
+        L.plc_trie_evict.argtypes = [p, i64]
         L.plc_expected_embedding.argtypes = [p, p, i64, i32, i32, p, p]
         L.plc_predict_residual_linear.argtypes = [dp, p, i32, p, p, p, p, p, p, p, u64, p, p, p, sz, p, p]
         L.plc_reconstruct_linear.argtypes = [dp, p, i32, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
@@ -354,6 +367,58 @@ def plc_reconstruct_linear(dims, ebar, A, bias_k, bias_v, symbols, esc_vals, esc
         _contig(esc_off, torch.int64), _ptr(out_k, torch.float16), _ptr(out_v, torch.float16),
         _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
     _check(rc, "plc_reconstruct_linear")
+
+
+class PrefixTrie:
+    """Host-side prefix index (plc_trie_*): insert / best_match / evict over token sequences (numpy int32
+    arrays; `bits` = per-token surprisal, float32, optional)."""
+
+    def __init__(self, max_bits=float("inf")):
+        import numpy as np
+        self._np = np
+        self._t = lib().plc_trie_create(float(min(max_bits, 1e300)))
+        if not self._t:
+            raise PlcError(PLC_ERR_INVALID, "plc_trie_create")
+
+    def close(self):
+        if getattr(self, "_t", None):
+            lib().plc_trie_destroy(self._t)
+            self._t = None
+
+    __del__ = close
+
+    def __len__(self):
+        return int(lib().plc_trie_size(self._t))
+
+    @property
+    def nodes(self):
+        return int(lib().plc_trie_nodes(self._t))
+
+    def _arr(self, a, dtype):
+        a = self._np.ascontiguousarray(a, dtype=dtype)
+        return a, a.ctypes.data_as(C.c_void_p)
+
+    def insert(self, tokens, ident, bits=None):
+        """Returns the number of tokens kept (the path is cut where its surprisal sum would exceed max_bits)."""
+        tok, tp = self._arr(tokens, self._np.int32)
+        bp = None
+        if bits is not None:
+            b, bp = self._arr(bits, self._np.float32)
+            assert b.size == tok.size
+        kept = C.c_int64(0)
+        _check(lib().plc_trie_insert(self._t, tp, bp, tok.size, int(ident), C.byref(kept)), "plc_trie_insert")
+        return int(kept.value)
+
+    def best_match(self, tokens):
+        """(id, lcp, dist): a stored prefix with the longest common prefix with the query (-1 if empty)."""
+        tok, tp = self._arr(tokens, self._np.int32)
+        ident, lcp, dist = C.c_int64(0), C.c_int64(0), C.c_double(0.0)
+        _check(lib().plc_trie_best_match(self._t, tp, tok.size, C.byref(ident), C.byref(lcp), C.byref(dist)),
+               "plc_trie_best_match")
+        return int(ident.value), int(lcp.value), float(dist.value)
+
+    def evict(self, ident):
+        _check(lib().plc_trie_evict(self._t, int(ident)), "plc_trie_evict")
 
 
 def plc_trace_kernel_events(kernel_id, start=None, stop=None):
