@@ -385,7 +385,11 @@ class PrefixTrie:
             lib().plc_trie_destroy(self._t)
             self._t = None
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:           # interpreter shutdown: the module globals may be gone already
+            pass
 
     def __len__(self):
         return int(lib().plc_trie_size(self._t))
