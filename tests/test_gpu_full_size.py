@@ -248,3 +248,135 @@ def test_token_conditional_full_size(oracle, name, chunk):
     assert not by_pos[ch[0] >= 0].any()
     del codec, coded, out_k, out_v, w
     torch.cuda.empty_cache()
+
+
+# --------------------------------------------------------------------------- surprisal-adaptive path, full size
+
+def test_surprisal_adaptive_full_size(oracle):
+    """The Llama-shaped configuration through the adaptive path exactly as bench.py runs it (b0 = 3, hbar =
+    log2 of the perplexity, range 0.32, whole streams).  Bit depths completely, sampled streams bit for bit
+    against the oracle (symbols, per-depth tables, rANS states and words, reconstruction), properties on all."""
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    O = oracle
+    from paper_2604_15356_amd import plc
+    dev = torch.device("cuda:0")
+    w = make_workload("llama8b", device=dev)
+    chosen = w.chosen.to(torch.int32).contiguous()
+    ch = chosen.cpu().numpy()
+    thr = plc.surprisal_thresholds(3.0, float(np.log2(np.mean(w.perplexity))))
+    step_range = 0.32
+    codec = codec_for(w)
+    print("surprisal-adaptive llama8b", flush=True)
+    coded = codec.encode_adapt(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen, thr, step_range)
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.bits.fill_(9)
+    codec.decode_adapt(w.cand_k, w.cand_v, w.probs, out_k, out_v, thr, step_range)
+    codec.check_status("surprisal-adaptive, full size")
+    probs = w.probs.cpu().numpy()
+    bits = O.surprisal_bits(probs, ch, np.array(thr, dtype=np.uint16))
+    assert np.array_equal(codec.dec_bits.cpu().numpy(), bits)
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    dm = O.make_dims(1, 1, 1, w.n, w.k, w.d, w.delta, w.qmax)
+    spp, B = 2 * w.d, plc.MAX_BITS
+    words = u16(coded.words)
+    for st in (17, 254):
+        print(f"  stream {st}", flush=True)
+        (ck, cv, p, ak, av), (s, l, h) = _stream_inputs(w, st)
+        ref = O.predict_residual(dm, ck, cv, p, ak, av, mode=O.F32, chosen=ch[s:s + 1], bits=bits[s:s + 1],
+                                 step_range=step_range)
+        sym = u8(coded.symbols[st:st + 1])
+        assert np.array_equal(sym, ref["symbols"])
+        counts = O.histogram_bucketed(sym, spp, 1, bits[s:s + 1], n_tables=B)
+        freq = O.build_freq_sparse(counts)
+        assert np.array_equal(u32(coded.counts_d[st:st + 1]), counts)
+        assert np.array_equal(u16(coded.freq_d[st:st + 1]), freq)
+        enc = O.rans_encode_bucketed(sym, freq, spp, 1, bits[s:s + 1], word_cap_per_unit=codec.word_cap)
+        nw = int(enc["n_words"][0])
+        assert int(u32(coded.n_words[st:st + 1])[0]) == nw
+        assert np.array_equal(u32(coded.states[st:st + 1]), enc["states"])
+        assert np.array_equal(words[st * codec.word_cap:st * codec.word_cap + nw], enc["words"][:nw])
+        rk, rv = O.reconstruct(dm, ck, cv, p, sym, ref["esc_vals"], np.zeros(1, dtype=np.uint64), mode=O.F32,
+                               chosen=ch[s:s + 1], bits=bits[s:s + 1], step_range=step_range)
+        assert np.array_equal(u16(out_k[s, l, h]).ravel(), rk) and np.array_equal(u16(out_v[s, l, h]).ravel(), rv)
+    # error at most half the position's own step, everywhere
+    step = torch.from_numpy(np.float32(step_range) * 2.0 ** -bits[0].astype(np.float32)).to(dev)[None, :, None]
+    esc = (coded.symbols.reshape(w.S, w.L, w.H, w.n, 2, w.d) == 255)
+    for c, (act, outp) in enumerate(((w.act_k, out_k), (w.act_v, out_v))):
+        for l in range(w.L):
+            a, o, e = act[0, l].float(), outp[0, l].float(), esc[0, l, :, :, c, :]
+            ulp = torch.clamp(o.abs(), min=2.0 ** -14) * 2.0 ** -10
+            assert bool((((a - o).abs() <= step / 2 + ulp / 2 + 1e-6) | e).all())
+    del codec, coded, out_k, out_v, w
+    torch.cuda.empty_cache()
+
+
+# --------------------------------------------------------------------------- linear-embedding predictor, full size
+
+def test_linear_predictor_full_size(oracle):
+    """The linear predictor at the size bench.py times it (m = 4096, V = 50,016).  The oracle recomputes sampled
+    rows of the expected embedding and sampled (layer, head, K/V, position) rows of the prediction from the
+    device's expected embedding; symbols may differ only by one step at rounding near-ties; round trip and
+    error bound on everything."""
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    from paper_2604_15356_amd.codec import KVDeltaCodec
+    from paper_2604_15356_amd.workloads import make_linear_workload
+    dev = torch.device("cuda:0")
+    print("linear predictor llama8b: drawing inputs", flush=True)
+    w = make_linear_workload("llama8b", device=dev)
+    codec = KVDeltaCodec(w.S, w.L, w.H, w.n, 1, w.d, w.delta, w.qmax, device=dev)
+    coded = codec.encode_linear(w.probs_full, w.embed_t, w.A, w.bias_k, w.bias_v, w.act_k, w.act_v)
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.decode_linear(w.probs_full, w.embed_t, w.A, w.bias_k, w.bias_v, out_k, out_v)
+    codec.check_status("linear predictor, full size")
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    rng = np.random.default_rng(5)
+    # expected embedding: sampled rows in fp64
+    Et = w.embed_t.cpu().numpy().astype(np.float64)
+    for r in rng.integers(0, w.S * w.n, 6):
+        want = (w.probs_full[r].cpu().numpy().astype(np.float64) @ Et.T).astype(np.float16)
+        got = codec.ebar[r].cpu().numpy()
+        ulp = np.spacing(np.maximum(np.abs(want), np.float16(2.0 ** -14))).astype(np.float64)
+        assert (np.abs(got.astype(np.float64) - want.astype(np.float64)) <= ulp).all()
+        assert (got.view(np.uint16) != want.view(np.uint16)).mean() < 0.05
+    del Et
+    # prediction / symbols: sampled rows from the device's expected embedding
+    sym = coded.symbols.reshape(w.S, w.L, w.H, w.n, 2, w.d)
+    delta = float(np.float32(w.delta))
+    n_diff = 0
+    for _ in range(48):
+        l, h, c, i = int(rng.integers(w.L)), int(rng.integers(w.H)), int(rng.integers(2)), int(rng.integers(w.n))
+        a_row = w.A[l, h, c].cpu().numpy().astype(np.float64)                       # [d, m]
+        eb = codec.ebar[i].cpu().numpy().astype(np.float64)                         # [m]
+        bias = (w.bias_v if c else w.bias_k)[0, l, h, i].cpu().numpy().astype(np.float64)
+        act = (w.act_v if c else w.act_k)[0, l, h, i].cpu().numpy()
+        pred = bias + a_row @ eb
+        u = (act.astype(np.float64) - pred) / delta
+        q = np.rint(u)
+        want = np.where(np.abs(q) > 127, 255, q + 127).astype(np.int64)
+        got = sym[0, l, h, i, c].cpu().numpy().astype(np.int64)
+        tau = (w.m + 4) * 2.0 ** -24 * (np.abs(a_row) @ np.abs(eb) + 8.0) / delta
+        differ = got != want
+        near = np.abs(u - np.floor(u) - 0.5) < tau
+        one = (np.abs(got - want) == 1) | (got == 255) | (want == 255)
+        assert (differ <= (near & one)).all()
+        n_diff += int(differ.sum())
+        out = (out_v if c else out_k)[0, l, h, i].cpu().numpy()
+        keep = got != 255
+        xhat = (pred + (got - 127.0) * delta)
+        # one fp16 step of the output plus the fp32 accumulation bound of the prediction (tau is in steps of Delta)
+        assert (np.abs(out.astype(np.float64) - xhat) <= np.maximum(np.abs(xhat), 2.0 ** -14) * 2.0 ** -10 + tau * delta)[keep].all()
+        assert np.array_equal(out.view(np.uint16)[~keep], act.view(np.uint16)[~keep])
+    print(f"  near-ties on sampled rows: {n_diff} of {48 * w.d}", flush=True)
+    assert n_diff <= 3
+    # error bound on everything
+    esc = sym == 255
+    for c, (act, outp) in enumerate(((w.act_k, out_k), (w.act_v, out_v))):
+        for l in range(w.L):
+            a, o, e = act[0, l].float(), outp[0, l].float(), esc[0, l, :, :, c, :]
+            ulp = torch.clamp(o.abs(), min=2.0 ** -14) * 2.0 ** -10
+            assert bool((((a - o).abs() <= delta / 2 + ulp + 1e-4) | e).all())
+            assert torch.equal(act[0, l].view(torch.int16)[e], outp[0, l].view(torch.int16)[e])
+    del codec, coded, out_k, out_v, w
+    torch.cuda.empty_cache()
