@@ -9,11 +9,10 @@
 //                        fused with the residual / quantiser (encode) or the add-back (decode).
 //
 // One kernel: C[M, N] = X[M, K] * Y[N, K]^T, fp16 operands with K contiguous in both, fp32 accumulation
-// in v_mfma_f32_32x32x16_f16.  A workgroup of four wavefronts owns a 128 x 128 tile of C, each wavefront
-// a 64 x 64 quarter (2 x 2 MFMA tiles, 64 accumulator registers).  K advances in slices of 32 through two
-// LDS buffers; the next slice travels global -> registers while the current one is multiplied, and is
-// written to the other buffer afterwards, so one barrier per slice suffices.  The 16-byte pieces of a
-// slice row are stored swizzled so that the fragment reads of consecutive rows spread over the banks.
+// in v_mfma_f32_32x32x16_f16.  A workgroup of WM x WN wavefronts owns a tile of C, each wavefront FM x FN
+// MFMA tiles of 32 x 32 of it.  K advances in slices of 64 through two LDS buffers: while slice s is
+// multiplied, slice s + 1 moves from registers to the other buffer and slice s + 2 from global memory
+// into those registers, one piece at a time between the products; one barrier per slice.
 #include "plc_device.h"
 
 namespace plc {
@@ -22,112 +21,169 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 
-constexpr int kTileM = 128, kTileN = 128, kTileK = 32;
-constexpr int kLdsRow = 32;  // halves per LDS row (64 bytes = four 16-byte pieces, stored swizzled)
+constexpr int kTileK = 64;
 
-// A slice row holds four 16-byte pieces; piece g of row r is stored at position g ^ ((r >> 1) & 3), so that
-// eight consecutive rows reading the same piece touch eight different 16-byte columns of the 128-byte bank line.
-__device__ __forceinline__ int lds_piece(int row, int g) { return row * kLdsRow + ((g ^ ((row >> 1) & 3)) << 3); }
+// LDS layout of one operand slice (R rows x 64 halves): eight pieces of 16 bytes along K, each piece holding
+// its R rows back to back (a multiply fragment then reads two runs of 512 contiguous bytes, which the LDS
+// serves at its full rate), with 16 bytes of padding between pieces so that the eight pieces of one row,
+// written together when the slice lands, fall on different banks.
+template <int WM_, int WN_, int FM_, int FN_>
+struct GemmShape {
+  static constexpr int kWavesM = WM_, kWavesN = WN_, kFragsM = FM_, kFragsN = FN_;
+  static constexpr int kWaves = WM_ * WN_, kThreads = 64 * kWaves;
+  static constexpr int kTileM = 32 * FM_ * WM_, kTileN = 32 * FN_ * WN_;
+  static constexpr int kStrideX = kTileM * 8 + 8, kStrideY = kTileN * 8 + 8;  // halves from piece to piece
+  static constexpr int kBufHalves = 8 * (kStrideX + kStrideY);               // both operands, one buffer
+  static constexpr size_t kLdsBytes = 2 * kBufHalves * sizeof(_Float16);
+  static constexpr int kLandX = kTileM * 8 / kThreads, kLandY = kTileN * 8 / kThreads;  // 16-byte pieces per thread
+  static_assert(kLandX * kThreads == kTileM * 8 && kLandY * kThreads == kTileN * 8, "whole pieces per thread");
+  static_assert(kTileM % 64 == 0 && kTileN % 64 == 0, "rows land in blocks of 64");
+};
+using SmallTile = GemmShape<2, 2, 2, 2>;  // 128 x 128, 256 threads, two workgroups per compute unit
+using LargeTile = GemmShape<2, 2, 4, 4>;  // 256 x 256, 256 threads, 256 accumulator registers per lane
 
 // Fragment layout of v_mfma_f32_32x32x16_f16 (checked on the device): lane l holds A[l % 32][8 (l / 32) + j],
 // B[8 (l / 32) + j][l % 32], j = 0..7, and C[8 (i / 4) + 4 (l / 32) + i % 4][l % 32] in accumulator i = 0..15.
-template <class Epilogue>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(const _Float16 *__restrict__ X, const _Float16 *__restrict__ Y,
-                                                      int64_t x_batch_stride, int64_t y_batch_stride, int32_t x_batch_div,
-                                                      int32_t y_batch_mod, int K, int tiles_n, Epilogue ep) {
-  __shared__ __attribute__((aligned(16))) _Float16 xs[2][kTileM * kLdsRow];
-  __shared__ __attribute__((aligned(16))) _Float16 ys[2][kTileN * kLdsRow];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+template <class Shape, class Epilogue>
+__global__ __launch_bounds__(Shape::kThreads) void gemm_nt_kernel(const _Float16 *__restrict__ X,
+                                                                  const _Float16 *__restrict__ Y, int64_t x_batch_stride,
+                                                                  int64_t y_batch_stride, int32_t x_batch_div,
+                                                                  int32_t y_batch_mod, int K, int tiles_n, Epilogue ep) {
+  constexpr int FM = Shape::kFragsM, FN = Shape::kFragsN;
+  constexpr int SX = Shape::kStrideX, SY = Shape::kStrideY;
+  extern __shared__ __attribute__((aligned(16))) _Float16 gemm_lds[];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // uniform: keeps what depends on it in scalar registers
+  const int wm = wave / Shape::kWavesN, wn = wave - wm * Shape::kWavesN;
   const int batch = blockIdx.y;
   const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
   // batch -> operand: X of batch b is X + (b / x_batch_div) * stride, Y is Y + (b % y_batch_mod) * stride
-  const _Float16 *xb = X + (int64_t)(batch / x_batch_div) * x_batch_stride + (int64_t)tile_m * kTileM * K;
-  const _Float16 *yb = Y + (int64_t)(batch % y_batch_mod) * y_batch_stride + (int64_t)tile_n * kTileN * K;
+  const _Float16 *xb = X + (int64_t)(batch / x_batch_div) * x_batch_stride + (int64_t)tile_m * Shape::kTileM * K;
+  const _Float16 *yb = Y + (int64_t)(batch % y_batch_mod) * y_batch_stride + (int64_t)tile_n * Shape::kTileN * K;
 
-  // global -> LDS: a slice of a tile is 128 rows x 64 bytes = 512 pieces of 16 bytes, two per thread
-  const int lrow = threadIdx.x >> 2, lk = (threadIdx.x & 3) * 8;
-  const _Float16 *xg = xb + (int64_t)lrow * K + lk;
-  const _Float16 *yg = yb + (int64_t)lrow * K + lk;
-  const int64_t half_tile = (int64_t)64 * K;
-  // Two register sets (A, B) carry the slices two and three steps ahead, so that a global load has two
-  // multiply phases to arrive in before it is written to LDS.  (Plain variables and macros, not arrays
-  // captured by a lambda: those would live in scratch memory.)
-  uint4 ax0, ax1, ay0, ay1, bx0, bx1, by0, by1;
-#define PLC_FETCH(R, k0)                                               \
-  R##x0 = *reinterpret_cast<const uint4 *>(xg + (k0));                 \
-  R##x1 = *reinterpret_cast<const uint4 *>(xg + (k0) + half_tile);     \
-  R##y0 = *reinterpret_cast<const uint4 *>(yg + (k0));                 \
-  R##y1 = *reinterpret_cast<const uint4 *>(yg + (k0) + half_tile)
-#define PLC_LAND(R, buf)                                                           \
-  *reinterpret_cast<uint4 *>(&xs[buf][lds_piece(lrow, lk >> 3)]) = R##x0;          \
-  *reinterpret_cast<uint4 *>(&xs[buf][lds_piece(lrow + 64, lk >> 3)]) = R##x1;     \
-  *reinterpret_cast<uint4 *>(&ys[buf][lds_piece(lrow, lk >> 3)]) = R##y0;          \
-  *reinterpret_cast<uint4 *>(&ys[buf][lds_piece(lrow + 64, lk >> 3)]) = R##y1
+  // global -> LDS: eight consecutive threads fetch one row's 128 bytes of the slice.  The eight rows that one
+  // wavefront fetches together lie eight apart, which spreads its LDS writes over all banks: piece i of a
+  // thread is row  row_of(i) + 8 j + wave % 8  with j = (thread / 8) % 8, where row_of(i) is the same for the
+  // whole workgroup.  A lane that would read past the end of a row re-reads the row's last piece instead.
+  const int lp = threadIdx.x & 7, lj = (threadIdx.x >> 3) & 7;
+  auto row_of = [](int i, int w) {  // w: wavefront, uniform
+    const int q = w + Shape::kWaves * i;
+    return 64 * (q >> 3) + (q & 7);
+  };
+  const int k_mine = lp * 8, k_last = K - 8;
+  const unsigned g_lane = (unsigned)(8 * lj) * (unsigned)K;  // halves; tiles stay far below 2^31 halves from xb / yb
+  const int l_lane = lj * 64;                                // halves: row 8 j of a piece
+  uint4 px[Shape::kLandX], py[Shape::kLandY];
+  auto fetch_x = [&](int i, unsigned koff) {
+    return *reinterpret_cast<const uint4 *>(xb + (int64_t)row_of(i, wave) * K + (g_lane + koff));
+  };
+  auto fetch_y = [&](int i, unsigned koff) {
+    return *reinterpret_cast<const uint4 *>(yb + (int64_t)row_of(i, wave) * K + (g_lane + koff));
+  };
 
-  float16v acc[2][2];
+  float16v acc[FM][FN];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < FM; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < FN; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
-  const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-  const int slices = K / kTileK;
-  auto multiply = [&](int buf) {
-#pragma unroll
-    for (int ks = 0; ks < kTileK / 16; ++ks) {
-      half8 fa[2], fb[2];
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        fa[t] = *reinterpret_cast<const half8 *>(&xs[buf][lds_piece(wm * 64 + t * 32 + frag_row, (frag_k >> 3) + 2 * ks)]);
-        fb[t] = *reinterpret_cast<const half8 *>(&ys[buf][lds_piece(wn * 64 + t * 32 + frag_row, (frag_k >> 3) + 2 * ks)]);
-      }
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-    }
-  };
+  // Fragments: lane l reads row (l % 32) of a 32-row block, K piece 2 ks + l / 32.
+  const int frag_x = (lane >> 5) * SX + (wm * FM * 32 + (lane & 31)) * 8;
+  const int frag_y = (lane >> 5) * SY + (wn * FN * 32 + (lane & 31)) * 8;
+  half8 fa[2][FM], fb[2][FN];
 
-  PLC_FETCH(a, 0);
-  PLC_LAND(a, 0);
-  if (slices > 1) {
-    PLC_FETCH(a, kTileK);
-  }
-  if (slices > 2) {
-    PLC_FETCH(b, 2 * kTileK);
+  // Slices: when K is an odd multiple of 32 the first slice is the short one (32 columns, its other half
+  // zero in LDS), so that every later slice is whole and the main loop needs no special case.
+  const int head = (K & (kTileK - 1)) ? kTileK / 2 : kTileK;
+  const int slices = 1 + (K - head) / kTileK;
+  {
+    _Float16 *const xs = gemm_lds, *const ys = xs + 8 * SX;
+    const bool in = k_mine < head;
+    const unsigned koff = (unsigned)min(k_mine, k_last);
+#pragma unroll
+    for (int i = 0; i < Shape::kLandX; ++i) {
+      uint4 v = fetch_x(i, koff);
+      if (!in) v = make_uint4(0u, 0u, 0u, 0u);
+      *reinterpret_cast<uint4 *>(&xs[lp * SX + l_lane + row_of(i, wave) * 8]) = v;
+    }
+#pragma unroll
+    for (int i = 0; i < Shape::kLandY; ++i) {
+      uint4 v = fetch_y(i, koff);
+      if (!in) v = make_uint4(0u, 0u, 0u, 0u);
+      *reinterpret_cast<uint4 *>(&ys[lp * SY + l_lane + row_of(i, wave) * 8]) = v;
+    }
+    const unsigned koff1 = (unsigned)min(head + k_mine, k_last);  // slice 1 (unused if there is none)
+#pragma unroll
+    for (int i = 0; i < Shape::kLandX; ++i) px[i] = fetch_x(i, koff1);
+#pragma unroll
+    for (int i = 0; i < Shape::kLandY; ++i) py[i] = fetch_y(i, koff1);
   }
   __syncthreads();
-  for (int s = 0; s < slices; s += 2) {
-    // slice s sits in buffer 0, slice s + 1 in set A, slice s + 2 in set B
-    multiply(0);
-    if (s + 1 < slices) {
-      PLC_LAND(a, 1);
-      if (s + 3 < slices) {
-        PLC_FETCH(a, (s + 3) * kTileK);
-      }
-    }
-    __syncthreads();
-    if (s + 1 < slices) multiply(1);
-    if (s + 2 < slices) {
-      PLC_LAND(b, 0);
-      if (s + 4 < slices) {
-        PLC_FETCH(b, (s + 4) * kTileK);
-      }
-    }
-    __syncthreads();
-  }
-#undef PLC_FETCH
-#undef PLC_LAND
 
-  const int row0 = tile_m * kTileM + wm * 64 + 4 * (lane >> 5);
-  const int col0 = tile_n * kTileN + wn * 64 + (lane & 31);
+  // One step per slice: slice s sits in buffer s % 2, slice s + 1 in the registers, and the fragments of
+  // the slice's first K step are already loaded.  The step has 4 * FM slots of FN products each; before the
+  // products of a slot are issued, the slot requests two fragments of the next K step and, during the first
+  // three K steps, writes register pieces of slice s + 1 to the other buffer and refills them from slice
+  // s + 2.  Memory instructions are thus spread under the products instead of queueing up in front of them.
+  // The barrier stands before the last K step: by then slice s + 1 is complete in LDS and every fragment
+  // of slice s has been read, so the last K step can already request the first fragments of slice s + 1.
+  // (Past the last slice the refill re-reads the last columns and the writes and requests touch a buffer
+  // that nobody uses: no branches in the step.)
+  constexpr int kSteps = kTileK / 16, kLandSlots = (kSteps - 1) * FM, kPieces = Shape::kLandX + Shape::kLandY;
+  static_assert(FM == FN, "two fragments per slot");
+  static_assert(kPieces <= 2 * kLandSlots, "at most two register pieces per slot");
+#define PLC_PIECE(p)                                                                            \
+  if ((p) < Shape::kLandX) {                                                                    \
+    *reinterpret_cast<uint4 *>(&xn[lp * SX + l_lane + row_of((p), wave) * 8]) = px[(p)];        \
+    px[(p)] = fetch_x((p), koff);                                                               \
+  } else if ((p) < kPieces) {                                                                   \
+    *reinterpret_cast<uint4 *>(&yn[lp * SY + l_lane + row_of((p)-Shape::kLandX, wave) * 8]) =   \
+        py[(p)-Shape::kLandX];                                                                  \
+    py[(p)-Shape::kLandX] = fetch_y((p)-Shape::kLandX, koff);                                   \
+  }
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < FM; ++a) {
+    fa[0][a] = *reinterpret_cast<const half8 *>(&gemm_lds[frag_x + a * 32 * 8]);
+    fb[0][a] = *reinterpret_cast<const half8 *>(&gemm_lds[8 * SX + frag_y + a * 32 * 8]);
+  }
+  for (int s = 0; s < slices; ++s) {
+    const int cur = s & 1;
+    const _Float16 *const xs = gemm_lds + cur * Shape::kBufHalves, *const ys = xs + 8 * SX;
+    _Float16 *const xn = gemm_lds + (cur ^ 1) * Shape::kBufHalves, *const yn = xn + 8 * SX;
+    const unsigned koff = (unsigned)min(head + (s + 1) * kTileK + k_mine, k_last);  // slice s + 2
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int ks = 0; ks < kSteps; ++ks) {
+      if (ks == kSteps - 1) __syncthreads();
+#pragma unroll
+      for (int a = 0; a < FM; ++a) {
+        const int slot = ks * FM + a;
+        if (ks + 1 < kSteps) {
+          fa[(ks + 1) & 1][a] = *reinterpret_cast<const half8 *>(&xs[frag_x + 2 * (ks + 1) * SX + a * 32 * 8]);
+          fb[(ks + 1) & 1][a] = *reinterpret_cast<const half8 *>(&ys[frag_y + 2 * (ks + 1) * SY + a * 32 * 8]);
+          PLC_PIECE(slot);
+          PLC_PIECE(slot + kLandSlots);
+        } else {
+          fa[0][a] = *reinterpret_cast<const half8 *>(&xn[frag_x + a * 32 * 8]);
+          fb[0][a] = *reinterpret_cast<const half8 *>(&yn[frag_y + a * 32 * 8]);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // memory instructions stay ahead of this slot's products
+#pragma unroll
+        for (int b = 0; b < FN; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ks & 1][a], fb[ks & 1][b], acc[a][b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  }
+#undef PLC_PIECE
+
+  const int row0 = tile_m * Shape::kTileM + wm * FM * 32 + 4 * (lane >> 5);
+  const int col0 = tile_n * Shape::kTileN + wn * FN * 32 + (lane & 31);
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) ep(batch, row0 + a * 32 + 8 * (i >> 2) + (i & 3), col0 + b * 32, acc[a][b][i]);
 }
@@ -189,13 +245,38 @@ struct DecodeLinear {  // c + A Ebar plus the dequantised residual (escaped comp
   }
 };
 
+// Launches over a (tiles, batches) grid.  The large tile is taken when the output divides into it and leaves
+// at least one workgroup per compute unit; otherwise the small one.  The LDS buffers exceed 64 KB, which a
+// kernel has to be granted before its launch.
+template <class Shape, class Epilogue>
+void launch_shape(int64_t M, int64_t N, int batches, hipStream_t st, const _Float16 *X, const _Float16 *Y, int64_t xs,
+                  int64_t ys, int32_t xdiv, int32_t ymod, int K, const Epilogue &ep) {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_kernel<Shape, Epilogue>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)Shape::kLdsBytes);
+  const int tiles_n = (int)(N / Shape::kTileN);
+  const dim3 grid((unsigned)((M / Shape::kTileM) * tiles_n), (unsigned)batches);
+  hipLaunchKernelGGL((gemm_nt_kernel<Shape, Epilogue>), grid, dim3(Shape::kThreads), Shape::kLdsBytes, st, X, Y, xs, ys,
+                     xdiv, ymod, K, tiles_n, ep);
+}
+
+template <class Epilogue>
+void launch_gemm(int64_t M, int64_t N, int batches, hipStream_t st, const _Float16 *X, const _Float16 *Y, int64_t xs,
+                 int64_t ys, int32_t xdiv, int32_t ymod, int K, const Epilogue &ep) {
+  const bool large = M % LargeTile::kTileM == 0 && N % LargeTile::kTileN == 0 &&
+                     (M / LargeTile::kTileM) * (N / LargeTile::kTileN) * batches >= 256;
+  if (large)
+    launch_shape<LargeTile>(M, N, batches, st, X, Y, xs, ys, xdiv, ymod, K, ep);
+  else
+    launch_shape<SmallTile>(M, N, batches, st, X, Y, xs, ys, xdiv, ymod, K, ep);
+}
+
 bool aligned16(const void *p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 bool linear_shapes_ok(const plc_dims *dm, int32_t m) {
   if (!dm || dm->S < 1 || dm->L < 1 || dm->H < 1) return false;
-  if (dm->n < kTileM || dm->n % kTileM) return false;                    // positions: whole tiles of rows
-  if (dm->d < 8 || dm->d % 8 || (2 * dm->H * dm->d) % kTileN) return false;  // (head, K/V, component): whole tiles
-  if (m < kTileK || m % kTileK) return false;
+  if (dm->n < SmallTile::kTileM || dm->n % SmallTile::kTileM) return false;                    // positions: whole tiles of rows
+  if (dm->d < 8 || dm->d % 8 || (2 * dm->H * dm->d) % SmallTile::kTileN) return false;  // (head, K/V, component): whole tiles
+  if (m < SmallTile::kTileN || m % SmallTile::kTileN) return false;
   if (!(dm->delta > 0.0f) || !(dm->delta < 3.0e38f) || dm->qmax < 1 || dm->qmax > 127) return false;
   for (int a = 0; a < 4; ++a)
     if (dm->act_stride[a] < 0 || dm->act_stride[a] % kChunk) return false;
@@ -220,16 +301,15 @@ using namespace plc;
 extern "C" int plc_expected_embedding(const void *probs_full, const void *embed_t, int64_t rows, int32_t V, int32_t m,
                                       void *ebar, void *stream) {
   if (!aligned16(probs_full) || !aligned16(embed_t) || !aligned16(ebar)) return PLC_ERR_INVALID;
-  if (rows < kTileM || rows % kTileM || m < kTileN || m % kTileN || V < kTileK || V % kTileK) return PLC_ERR_INVALID;
-  const int64_t tiles = (rows / kTileM) * (m / kTileN);
+  if (rows < SmallTile::kTileM || rows % SmallTile::kTileM || m < SmallTile::kTileN || m % SmallTile::kTileN || V < 32 || V % 32) return PLC_ERR_INVALID;
+  const int64_t tiles = (rows / SmallTile::kTileM) * (m / SmallTile::kTileN);
   if (tiles >= (1ll << 31)) return PLC_ERR_INVALID;
   StoreHalf ep{static_cast<_Float16 *>(ebar), m};
   hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_EXPECTED_EMBEDDING, st);
-    hipLaunchKernelGGL(gemm_nt_kernel<StoreHalf>, dim3((unsigned)tiles, 1), dim3(256), 0, st,
-                       static_cast<const _Float16 *>(probs_full), static_cast<const _Float16 *>(embed_t), (int64_t)0,
-                       (int64_t)0, 1, 1, V, m / kTileN, ep);
+    launch_gemm(rows, m, 1, st, static_cast<const _Float16 *>(probs_full), static_cast<const _Float16 *>(embed_t),
+                (int64_t)0, (int64_t)0, 1, 1, V, ep);
   }
   return launch_status();
 }
@@ -255,9 +335,8 @@ extern "C" int plc_predict_residual_linear(const plc_dims *dims, const void *eba
   hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_PREDICT_LINEAR, st);
-    hipLaunchKernelGGL(gemm_nt_kernel<EncodeLinear>, dim3((unsigned)((dims->n / kTileM) * (N / kTileN)), dims->S * dims->L),
-                       dim3(256), 0, st, static_cast<const _Float16 *>(ebar), static_cast<const _Float16 *>(A),
-                       (int64_t)dims->n * m, (int64_t)N * m, dims->L, dims->L, m, N / kTileN, ep);
+    launch_gemm(dims->n, N, dims->S * dims->L, st, static_cast<const _Float16 *>(ebar),
+                static_cast<const _Float16 *>(A), (int64_t)dims->n * m, (int64_t)N * m, dims->L, dims->L, m, ep);
   }
   if (hipGetLastError() != hipSuccess) return PLC_ERR_HIP;
   return gather_escapes(dims, act_k, act_v, symbols, esc_vals, esc_cap, esc_cnt, esc_off, ws, ws_bytes, status, st);
@@ -282,9 +361,8 @@ extern "C" int plc_reconstruct_linear(const plc_dims *dims, const void *ebar, in
   hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_RECONSTRUCT_LINEAR, st);
-    hipLaunchKernelGGL(gemm_nt_kernel<DecodeLinear>, dim3((unsigned)((dims->n / kTileM) * (N / kTileN)), dims->S * dims->L),
-                       dim3(256), 0, st, static_cast<const _Float16 *>(ebar), static_cast<const _Float16 *>(A),
-                       (int64_t)dims->n * m, (int64_t)N * m, dims->L, dims->L, m, N / kTileN, ep);
+    launch_gemm(dims->n, N, dims->S * dims->L, st, static_cast<const _Float16 *>(ebar),
+                static_cast<const _Float16 *>(A), (int64_t)dims->n * m, (int64_t)N * m, dims->L, dims->L, m, ep);
   }
   if (hipGetLastError() != hipSuccess) return PLC_ERR_HIP;
   return patch_escapes(dims, symbols, esc_vals, esc_len, esc_off, out_k, out_v, ws, ws_bytes, status, st);
