@@ -8,11 +8,14 @@
 //   prediction           pred [n, 2 H d]    = Ebar[s] [n, m] * A[l] [2 H d, m]^T + c   (K = m), per (s, l),
 //                        fused with the residual / quantiser (encode) or the add-back (decode).
 //
-// One kernel: C[M, N] = X[M, K] * Y[N, K]^T, fp16 operands with K contiguous in both, fp32 accumulation
+// Both are C[M, N] = X[M, K] * Y[N, K]^T with fp16 operands, K contiguous in both, and fp32 accumulation
 // in v_mfma_f32_32x32x16_f16.  A workgroup of WM x WN wavefronts owns a tile of C, each wavefront FM x FN
-// MFMA tiles of 32 x 32 of it.  K advances in slices of 64 through two LDS buffers: while slice s is
-// multiplied, slice s + 1 moves from registers to the other buffer and slice s + 2 from global memory
-// into those registers, one piece at a time between the products; one barrier per slice.
+// MFMA tiles of 32 x 32 of it, and K advances in slices of 64 through LDS.  Two kernels share this plan:
+//   - 256 x 256 tiles whose slices the memory system writes straight into LDS (used whenever the output
+//     divides into such tiles and there is at least one per compute unit);
+//   - 128 x 128 tiles whose slices pass through registers, for the small shapes.
+// In both, the memory instructions of the slices to come are spread between the products of the current
+// one, and the accumulators reach the epilogue through LDS, eight consecutive columns per lane.
 #include "plc_device.h"
 
 namespace plc {
@@ -23,6 +26,12 @@ typedef float float16v __attribute__((ext_vector_type(16)));
 
 constexpr int kTileK = 64;
 
+// ---- slices through registers -------------------------------------------------------------------
+//
+// While slice s is multiplied, slice s + 1 moves from registers to the other of two LDS buffers and slice
+// s + 2 from global memory into those registers, one piece at a time between the products; one barrier per
+// slice.
+//
 // LDS layout of one operand slice (R rows x 64 halves): eight pieces of 16 bytes along K, each piece holding
 // its R rows back to back (a multiply fragment then reads two runs of 512 contiguous bytes, which the LDS
 // serves at its full rate), with 16 bytes of padding between pieces so that the eight pieces of one row,
@@ -40,7 +49,35 @@ struct GemmShape {
   static_assert(kTileM % 64 == 0 && kTileN % 64 == 0, "rows land in blocks of 64");
 };
 using SmallTile = GemmShape<2, 2, 2, 2>;  // 128 x 128, 256 threads, two workgroups per compute unit
-using LargeTile = GemmShape<2, 2, 4, 4>;  // 256 x 256, 256 threads, 256 accumulator registers per lane
+
+// Hands a wavefront's accumulators to the epilogue eight consecutive columns at a time.  In the MFMA's
+// result layout a lane owns one column of a 32 x 32 tile; the values of 32 rows of the wavefront's tile go
+// through LDS (which the multiply no longer needs: the caller has passed a barrier) and come back with each
+// lane owning eight consecutive columns of one row, so that the epilogue moves 16 bytes per operand and lane.
+template <int FM, int FN, class Epilogue>
+__device__ __forceinline__ void emit_tile(float16v (&acc)[FM][FN], float *lds, int wave, int lane, int batch, int row0,
+                                          int col0, const Epilogue &ep) {
+  constexpr int W = FN * 32, RS = W + 4;       // columns of the wavefront's tile; row stride in floats
+  constexpr int kLanesPerRow = W / 8, kRowsPerPass = 64 / kLanesPerRow;
+  float *const stage = lds + wave * (32 * RS);
+  const int wr = 4 * (lane >> 5) * RS + (lane & 31);
+  const int rd_row = lane / kLanesPerRow, rd_col = (lane % kLanesPerRow) * 8;
+#pragma unroll
+  for (int a = 0; a < FM; ++a) {
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) stage[wr + (8 * (i >> 2) + (i & 3)) * RS + b * 32] = acc[a][b][i];
+#pragma unroll
+    for (int pass = 0; pass < 32 / kRowsPerPass; ++pass) {
+      const int r = pass * kRowsPerPass + rd_row;
+      const float4 lo = *reinterpret_cast<const float4 *>(&stage[r * RS + rd_col]);
+      const float4 hi = *reinterpret_cast<const float4 *>(&stage[r * RS + rd_col + 4]);
+      const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+      ep(batch, row0 + a * 32 + r, col0 + rd_col, v);
+    }
+  }
+}
 
 // Fragment layout of v_mfma_f32_32x32x16_f16 (checked on the device): lane l holds A[l % 32][8 (l / 32) + j],
 // B[8 (l / 32) + j][l % 32], j = 0..7, and C[8 (i / 4) + 4 (l / 32) + i % 4][l % 32] in accumulator i = 0..15.
@@ -178,28 +215,232 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_kernel(const _Float16
   }
 #undef PLC_PIECE
 
-  const int row0 = tile_m * Shape::kTileM + wm * FM * 32 + 4 * (lane >> 5);
-  const int col0 = tile_n * Shape::kTileN + wn * FN * 32 + (lane & 31);
+  __syncthreads();  // every wavefront is done with the slices in LDS
+  static_assert(Shape::kWaves * 32 * (FN * 32 + 4) * sizeof(float) <= Shape::kLdsBytes, "the output stage fits");
+  emit_tile<FM, FN>(acc, reinterpret_cast<float *>(gemm_lds), wave, lane, batch, tile_m * Shape::kTileM + wm * FM * 32,
+                    tile_n * Shape::kTileN + wn * FN * 32, ep);
+}
+
+// ---- the same contraction with direct global -> LDS loads ---------------------------------------
+//
+// K advances in slices of 64 through a ring of two or three LDS buffers that the memory system fills directly
+// (16 bytes per lane; lane l of a load lands at the load's LDS base + 16 l), so a slice costs neither
+// registers nor LDS write instructions.  One load moves a block of 8 rows x 128 bytes, eight consecutive
+// lanes fetching one row (whole cache lines).  Inside a block the eight 16-byte pieces of row r are stored
+// permuted, piece p in slot p ^ r (the lane of slot t fetches piece t ^ r), and the two blocks of a pair
+// lie 128 bytes further apart than their size: the 16 lanes that read one piece of 16 consecutive rows for
+// a multiply fragment then touch 16 different bank groups.
+//
+// The loop turns at its barrier, which stands before the last K step of a slice.  There every wavefront has
+// read its last fragment of slice s and has waited for its own loads of slice s + 1, so after the barrier
+// slice s + 1 is complete, and the buffer of slice s is free and starts to receive the slice that comes
+// a whole ring later.
+template <int WM_, int WN_, int FM_, int FN_, int NB_>
+struct DirectShape {
+  static constexpr int kWavesM = WM_, kWavesN = WN_, kFragsM = FM_, kFragsN = FN_;
+  static constexpr int kWaves = WM_ * WN_, kThreads = 64 * kWaves;
+  static constexpr int kTileM = 32 * FM_ * WM_, kTileN = 32 * FN_ * WN_;
+  static constexpr int kSliceK = 64, kSteps = kSliceK / 16, kBuffers = NB_;
+  static constexpr int kBlocksX = kTileM / 8, kBlocksY = kTileN / 8;  // blocks of 1 KB per slice
+  static constexpr int kLoads = (kBlocksX + kBlocksY) / kWaves;       // per wavefront and slice
+  static constexpr int kPairBytes = 2 * 1024 + 128;                   // two blocks and the padding
+  static constexpr int kBytesX = kBlocksX / 2 * kPairBytes, kBufBytes = (kBlocksX + kBlocksY) / 2 * kPairBytes;
+  static constexpr size_t kLdsBytes = (size_t)kBuffers * kBufBytes;
+  // The loads of a slice are issued from the barrier on: with three buffers spread over three K steps, with
+  // two buffers all in the first one (the slice is needed at the next barrier).
+  static constexpr int kLoadSteps = NB_ == 2 ? 1 : 3;
+  static constexpr int kLoadsPerSlot = (kLoads + kLoadSteps * FM_ - 1) / (kLoadSteps * FM_);
+  static_assert(NB_ == 2 || NB_ == 3, "ring of two or three buffers");
+  static_assert(kLoads * kWaves == kBlocksX + kBlocksY, "whole loads per wavefront");
+  static_assert((NB_ - 1) * kLoads < 64, "the loads in flight fit the counter");
+  static_assert(kLdsBytes <= 160 * 1024, "LDS of a compute unit");
+};
+using DirectTile = DirectShape<2, 2, 4, 4, 2>;  // 256 x 256, 256 threads, two buffers
+
+typedef __attribute__((address_space(3))) char lds_char;
+
+// Waits until at most N of this wavefront's loads (and none of its LDS requests) are outstanding, then
+// joins the workgroup's barrier.  The wait is written as the instruction itself so that the compiler's own
+// bookkeeping of outstanding requests sees it; nothing that touches memory moves across.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (0 << 8) | ((N >> 4) << 14));  // vmcnt(N) lgkmcnt(0)
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+template <class Shape, class Epilogue>
+__global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _Float16 *__restrict__ X,
+                                                                         const _Float16 *__restrict__ Y,
+                                                                         int64_t x_batch_stride, int64_t y_batch_stride,
+                                                                         int32_t x_batch_div, int32_t y_batch_mod, int K,
+                                                                         int tiles_n, Epilogue ep) {
+  constexpr int FM = Shape::kFragsM, FN = Shape::kFragsN, NB = Shape::kBuffers, KS = Shape::kSteps;
+  extern __shared__ __attribute__((aligned(1024))) char gemm_ring[];
+  lds_char *const ring = (lds_char *)gemm_ring;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / Shape::kWavesN, wn = wave - wm * Shape::kWavesN;
+  const int batch = blockIdx.y;
+  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x - tile_m * tiles_n;
+  const _Float16 *xb = X + (int64_t)(batch / x_batch_div) * x_batch_stride + (int64_t)tile_m * Shape::kTileM * K;
+  const _Float16 *yb = Y + (int64_t)(batch % y_batch_mod) * y_batch_stride + (int64_t)tile_n * Shape::kTileN * K;
+
+  // load j of a wavefront moves block q = wave + kWaves * j of the slice (X blocks first, then Y blocks);
+  // block q of an operand starts at (q / 2) * kPairBytes + (q % 2) * (1024 + 128)
+  const int k_lane = ((lane & 7) ^ (lane >> 3)) * 8;  // the column, within a slice, of this lane's piece
+  const unsigned g_lane = (unsigned)(lane >> 3) * (unsigned)K + (unsigned)k_lane;  // halves
+  // Lanes whose column is not below `width` stay out of the load and leave their 16 bytes of LDS alone.
+  auto request = [&](int j, int k0, int width, int buf) {
+    const int q = wave + Shape::kWaves * j;
+    const _Float16 *src = (q < Shape::kBlocksX ? xb + (int64_t)(8 * q) * K : yb + (int64_t)(8 * (q - Shape::kBlocksX)) * K);
+    const int at = buf * Shape::kBufBytes + (q >> 1) * Shape::kPairBytes + (q & 1) * 1152;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass of the compiler does not know the device's load-to-LDS builtin
+    if (k_lane < width) __builtin_amdgcn_global_load_lds(src + (k0 + g_lane), ring + at, 16, 0, 0);
+#else
+    (void)src, (void)k0, (void)width, (void)at, (void)ring;
+#endif
+  };
+
+  float16v acc[FM][FN];
 #pragma unroll
   for (int a = 0; a < FM; ++a)
 #pragma unroll
     for (int b = 0; b < FN; ++b)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) ep(batch, row0 + a * 32 + 8 * (i >> 2) + (i & 3), col0 + b * 32, acc[a][b][i]);
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+  // fragments: lane l holds row l % 32 of a group of 32 rows (four blocks, two pairs), K piece 2 ks + l / 32
+  int frag_lane[KS];
+  {
+    const int r32 = lane & 31, j = r32 >> 3, r = r32 & 7, g = lane >> 5;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+      frag_lane[ks] = (j >> 1) * Shape::kPairBytes + (j & 1) * 1152 + r * 128 + (((2 * ks + g) ^ r) << 4);
+  }
+  const int frag_x = wm * FM * 2 * Shape::kPairBytes;
+  const int frag_y = Shape::kBytesX + wn * FN * 2 * Shape::kPairBytes;
+  half8 fa[2][FM], fb[2][FN];
+
+  // Slices: when K is an odd multiple of 32 the first slice is the short one (32 columns; the other half of
+  // its LDS buffer is cleared first), so that every later slice is whole.  Requests past the last slice
+  // repeat it into ring buffers that are no longer read, which keeps the count of outstanding loads the
+  // same in every step.
+  const int head = (K & (Shape::kSliceK - 1)) ? Shape::kSliceK / 2 : Shape::kSliceK;
+  const int slices = 1 + (K - head) / Shape::kSliceK;
+  auto k_of = [&](int t) {
+    const int c = min(t, slices - 1);
+    return c == 0 ? 0 : head + (c - 1) * Shape::kSliceK;
+  };
+  auto width_of = [&](int t) { return min(t, slices - 1) == 0 ? head : Shape::kSliceK; };
+  if (head != Shape::kSliceK) {
+    for (int i = threadIdx.x * 16; i < Shape::kBufBytes; i += Shape::kThreads * 16)
+      *reinterpret_cast<uint4 *>(gemm_ring + i) = make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int t = 0; t < NB; ++t)
+#pragma unroll
+    for (int j = 0; j < Shape::kLoads; ++j) request(j, k_of(t), width_of(t), t);
+  wait_loads_and_barrier<(NB - 1) * Shape::kLoads>();
+
+  // A K step has FM slots of FN products.  The fragments of the next K step are requested around the first
+  // slot's products -- half of them right after, half before the second slot's -- so that they are several
+  // slots old when the next step starts, and the wait in front of a step's first products covers no request
+  // younger than that.  A slot may also issue loads of the slice a whole ring ahead.
+  constexpr int kHalf = (FM + FN + 1) / 2;
+  static_assert(FM >= 2, "two slots carry the fragment requests");
+#define PLC_REQUEST_FRAGS(set, base, ks, e0, e1)                                                                  \
+  _Pragma("unroll") for (int e = (e0); e < (e1); ++e) {                                                           \
+    if (e < FN)                                                                                                   \
+      fb[set][e] = *reinterpret_cast<const half8 *>((base) + frag_y + frag_lane[ks] + e * 2 * Shape::kPairBytes);  \
+    else                                                                                                          \
+      fa[set][e - FN] =                                                                                           \
+          *reinterpret_cast<const half8 *>((base) + frag_x + frag_lane[ks] + (e - FN) * 2 * Shape::kPairBytes);    \
+  }
+  // K step ks of a slice: products of fragment set ks % 2; requests the fragments of step ks_next of the
+  // slice in buffer `from` and, as the order-th step after the barrier (order < 0: none), its share of the
+  // loads of slice fill_slice
+#define PLC_LOADS(order, a, fill_slice)                                                                 \
+  if ((order) >= 0 && (order) < Shape::kLoadSteps) {                                                    \
+    _Pragma("unroll") for (int i = 0; i < Shape::kLoadsPerSlot; ++i) {                                  \
+      const int idx = ((order)*FM + (a)) * Shape::kLoadsPerSlot + i;                                    \
+      if (idx < Shape::kLoads) request(idx, k_of(fill_slice), width_of(fill_slice), (fill_slice) % NB); \
+    }                                                                                                   \
+  }
+#define PLC_KSTEP(ks, from, ks_next, order, fill_slice)                                                 \
+  _Pragma("unroll") for (int a = 0; a < FM; ++a) {                                                      \
+    if (a == 1) {                                                                                       \
+      PLC_REQUEST_FRAGS(((ks) + 1) & 1, from, ks_next, kHalf, FM + FN);                                 \
+    }                                                                                                   \
+    if (a > 0) {                                                                                        \
+      PLC_LOADS(order, a, fill_slice);                                                                  \
+    }                                                                                                   \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    _Pragma("unroll") for (int b = 0; b < FN; ++b) acc[a][b] =                                          \
+        __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[(ks)&1][a], fb[(ks)&1][b], acc[a][b], 0, 0, 0);       \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
+    if (a == 0) {                                                                                       \
+      PLC_REQUEST_FRAGS(((ks) + 1) & 1, from, ks_next, 0, kHalf);                                       \
+      PLC_LOADS(order, a, fill_slice);                                                                  \
+    }                                                                                                   \
+  }
+  static_assert(KS == 4, "the steps are written out below");
+  {
+    const char *const cur = gemm_ring;
+    PLC_REQUEST_FRAGS(0, cur, 0, 0, FM + FN);
+    PLC_KSTEP(0, cur, 1, -1, 0);
+    PLC_KSTEP(1, cur, 2, -1, 0);
+    PLC_KSTEP(2, cur, 3, -1, 0);
+  }
+  wait_loads_and_barrier<(NB - 2) * Shape::kLoads>();  // slice 1 has landed
+  for (int s = 0; s + 1 < slices; ++s) {
+    const char *const nxt = gemm_ring + ((s + 1) % NB) * Shape::kBufBytes;
+    PLC_KSTEP(3, nxt, 0, 0, s + NB);
+    PLC_KSTEP(0, nxt, 1, 1, s + NB);
+    PLC_KSTEP(1, nxt, 2, 2, s + NB);
+    PLC_KSTEP(2, nxt, 3, 3, s + NB);
+    wait_loads_and_barrier<(NB - 2) * Shape::kLoads>();  // slice s + 2 has landed
+  }
+  {
+    const char *const nxt = gemm_ring + (slices % NB) * Shape::kBufBytes;  // read, never used
+    PLC_KSTEP(3, nxt, 0, -1, 0);
+  }
+#undef PLC_KSTEP
+#undef PLC_LOADS
+#undef PLC_REQUEST_FRAGS
+  // nothing may still be writing this workgroup's LDS when it ends
+  __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));  // vmcnt(0)
+
+  __syncthreads();  // ... and every wavefront is done with the slices in LDS
+  static_assert(Shape::kWaves * 32 * (FN * 32 + 4) * sizeof(float) <= Shape::kLdsBytes, "the output stage fits");
+  emit_tile<FM, FN>(acc, reinterpret_cast<float *>(gemm_ring), wave, lane, batch, tile_m * Shape::kTileM + wm * FM * 32,
+                    tile_n * Shape::kTileN + wn * FN * 32, ep);
 }
 
 // ---- epilogues --------------------------------------------------------------------------------
 
+// An epilogue receives eight consecutive columns (col a multiple of 8) of one row of C.
+
+typedef uint8_t byte8 __attribute__((ext_vector_type(8)));
+
 struct StoreHalf {  // Ebar[row, col] = fp16(acc)
   _Float16 *out;
   int64_t ld;
-  __device__ void operator()(int, int row, int col, float v) const { out[(int64_t)row * ld + col] = (_Float16)v; }
+  __device__ void operator()(int, int row, int col, const float (&v)[8]) const {
+    half8 h;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) h[j] = (_Float16)v[j];
+    *reinterpret_cast<half8 *>(out + (int64_t)row * ld + col) = h;
+  }
 };
 
 struct LinearCoord {
   int32_t L, H, n, d;
   int64_t as[4];
-  // batch = s * L + l; col = (h * 2 + c) * d + e
+  // batch = s * L + l; col = (h * 2 + c) * d + e; d is a multiple of 8, so eight columns share (h, c)
   __device__ void locate(int batch, int row, int col, int *c, int64_t *act_off, int64_t *sym_off) const {
     const int s = batch / L, l = batch - s * L;
     const int hc = col / d, e = col - hc * d;
@@ -215,15 +456,22 @@ struct EncodeLinear {  // residual against c + A Ebar, quantised (escapes are ga
   const _Float16 *bias_k, *bias_v, *act_k, *act_v;
   uint8_t *symbols;
   float delta, qmax;
-  __device__ void operator()(int batch, int row, int col, float v) const {
+  __device__ void operator()(int batch, int row, int col, const float (&v)[8]) const {
     int c;
     int64_t ao, so;
     g.locate(batch, row, col, &c, &ao, &so);
-    const float pred = v + (float)(c ? bias_v : bias_k)[ao];
-    const float r = (float)(c ? act_v : act_k)[ao] - pred;
-    const float u = r / delta;
-    const float qf = __builtin_rintf(u);
-    symbols[so] = __builtin_fabsf(qf) <= qmax ? (uint8_t)((int)qf + (int)kZeroSymbol) : (uint8_t)PLC_ESCAPE;
+    const half8 bias = *reinterpret_cast<const half8 *>((c ? bias_v : bias_k) + ao);
+    const half8 act = *reinterpret_cast<const half8 *>((c ? act_v : act_k) + ao);
+    byte8 sym;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float pred = v[j] + (float)bias[j];
+      const float r = (float)act[j] - pred;
+      const float u = r / delta;
+      const float qf = __builtin_rintf(u);
+      sym[j] = __builtin_fabsf(qf) <= qmax ? (uint8_t)((int)qf + (int)kZeroSymbol) : (uint8_t)PLC_ESCAPE;
+    }
+    *reinterpret_cast<byte8 *>(symbols + so) = sym;
   }
 };
 
@@ -233,15 +481,22 @@ struct DecodeLinear {  // c + A Ebar plus the dequantised residual (escaped comp
   _Float16 *out_k, *out_v;
   const uint8_t *symbols;
   float delta;
-  __device__ void operator()(int batch, int row, int col, float v) const {
+  __device__ void operator()(int batch, int row, int col, const float (&v)[8]) const {
     int c;
     int64_t ao, so;
     g.locate(batch, row, col, &c, &ao, &so);
-    const float pred = v + (float)(c ? bias_v : bias_k)[ao];
-    const float qf = (float)((int)symbols[so] - (int)kZeroSymbol);
-    float x = __builtin_fmaf(qf, delta, pred);
-    asm("" : "+v"(x));  // round to fp32, then to fp16
-    (c ? out_v : out_k)[ao] = (_Float16)x;
+    const half8 bias = *reinterpret_cast<const half8 *>((c ? bias_v : bias_k) + ao);
+    const byte8 sym = *reinterpret_cast<const byte8 *>(symbols + so);
+    half8 out;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float pred = v[j] + (float)bias[j];
+      const float qf = (float)((int)sym[j] - (int)kZeroSymbol);
+      float x = __builtin_fmaf(qf, delta, pred);
+      asm("" : "+v"(x));  // round to fp32, then to fp16
+      out[j] = (_Float16)x;
+    }
+    *reinterpret_cast<half8 *>((c ? out_v : out_k) + ao) = out;
   }
 };
 
@@ -259,13 +514,24 @@ void launch_shape(int64_t M, int64_t N, int batches, hipStream_t st, const _Floa
                      xdiv, ymod, K, tiles_n, ep);
 }
 
+template <class Shape, class Epilogue>
+void launch_direct(int64_t M, int64_t N, int batches, hipStream_t st, const _Float16 *X, const _Float16 *Y, int64_t xs,
+                   int64_t ys, int32_t xdiv, int32_t ymod, int K, const Epilogue &ep) {
+  (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_direct_kernel<Shape, Epilogue>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)Shape::kLdsBytes);
+  const int tiles_n = (int)(N / Shape::kTileN);
+  const dim3 grid((unsigned)((M / Shape::kTileM) * tiles_n), (unsigned)batches);
+  hipLaunchKernelGGL((gemm_nt_direct_kernel<Shape, Epilogue>), grid, dim3(Shape::kThreads), Shape::kLdsBytes, st, X, Y, xs,
+                     ys, xdiv, ymod, K, tiles_n, ep);
+}
+
 template <class Epilogue>
 void launch_gemm(int64_t M, int64_t N, int batches, hipStream_t st, const _Float16 *X, const _Float16 *Y, int64_t xs,
                  int64_t ys, int32_t xdiv, int32_t ymod, int K, const Epilogue &ep) {
-  const bool large = M % LargeTile::kTileM == 0 && N % LargeTile::kTileN == 0 &&
-                     (M / LargeTile::kTileM) * (N / LargeTile::kTileN) * batches >= 256;
+  const bool large = M % DirectTile::kTileM == 0 && N % DirectTile::kTileN == 0 &&
+                     (M / DirectTile::kTileM) * (N / DirectTile::kTileN) * batches >= 256;
   if (large)
-    launch_shape<LargeTile>(M, N, batches, st, X, Y, xs, ys, xdiv, ymod, K, ep);
+    launch_direct<DirectTile>(M, N, batches, st, X, Y, xs, ys, xdiv, ymod, K, ep);
   else
     launch_shape<SmallTile>(M, N, batches, st, X, Y, xs, ys, xdiv, ymod, K, ep);
 }
@@ -321,7 +587,7 @@ extern "C" int plc_predict_residual_linear(const plc_dims *dims, const void *eba
                                            uint32_t *status, void *stream) {
   if (!linear_shapes_ok(dims, m)) return PLC_ERR_INVALID;
   if (!aligned16(ebar) || !aligned16(A) || !aligned16(bias_k) || !aligned16(bias_v) || !aligned16(act_k) ||
-      !aligned16(act_v) || !symbols)
+      !aligned16(act_v) || !aligned16(symbols))
     return PLC_ERR_INVALID;
   const int N = 2 * dims->H * dims->d;
   EncodeLinear ep{coord_of(dims),
@@ -348,7 +614,7 @@ extern "C" int plc_reconstruct_linear(const plc_dims *dims, const void *ebar, in
                                       void *out_v, void *ws, size_t ws_bytes, uint32_t *status, void *stream) {
   if (!linear_shapes_ok(dims, m)) return PLC_ERR_INVALID;
   if (!aligned16(ebar) || !aligned16(A) || !aligned16(bias_k) || !aligned16(bias_v) || !aligned16(out_k) ||
-      !aligned16(out_v) || !symbols)
+      !aligned16(out_v) || !aligned16(symbols))
     return PLC_ERR_INVALID;
   const int N = 2 * dims->H * dims->d;
   DecodeLinear ep{coord_of(dims),
