@@ -466,7 +466,7 @@ def main():
             "workload": f"S={lw.S} L={lw.L} H={lw.H} d={lw.d} n={lw.n} m={lw.m} V={lw.V}", "steps": lin_steps,
             "value": round(lw.kv_bytes / (dt5 / lin_steps) / 1e9, 2), "unit": "GB/s",
             "ms_per_step": round(dt5 / lin_steps * 1e3, 4),
-            "roofline": dict(bound="mfma", kernel="gemm_nt_kernel<EncodeLinear>", achieved=dom5["TFLOPs"],
+            "roofline": dict(bound="mfma", kernel="gemm_nt_direct_kernel<EncodeLinear>", achieved=dom5["TFLOPs"],
                              peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=dom5["frac_mfma"], traffic=None),
             "kernels": k5, "kernels_ms": {k: round(v, 4) for k, v in ms5.items()},
             "payload_bits_per_symbol": round((16 * int(nw5.sum()) + 16 * esc5) / E5, 4),
