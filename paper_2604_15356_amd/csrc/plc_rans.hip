@@ -756,10 +756,20 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
 // mirrored at 2048..2591 so that q + r never needs a wrap inside a batch.
 constexpr int kRingWords = 2048, kBlockWords = 512, kRingMirror = kBlockWords + 32;
 
-template <bool MASKED>
+// COMPACT: the slot table is split in two, slot -> symbol (one byte per slot) and symbol -> f - 1 | cum << 16,
+// 5 KB instead of 16 KB per stream at the price of a second dependent lookup.
+template <bool MASKED, bool COMPACT = false>
 __device__ __forceinline__ void dec_step(uint32_t &x, const uint32_t *lut, const uint16_t *&top, uint8_t *sym_slot,
                                          uint32_t below, bool on, uint32_t table_off = 0) {
-  const uint32_t e = lut[(x & (kScale - 1)) + table_off];
+  uint32_t e;
+  if (COMPACT) {
+    const uint32_t slot = x & (kScale - 1);
+    const uint32_t s = reinterpret_cast<const uint8_t *>(lut + 256)[slot];
+    const uint32_t fc = lut[s];
+    e = s | ((fc & 0xfffu) << 8) | ((slot - (fc >> 16)) << 20);
+  } else {
+    e = lut[(x & (kScale - 1)) + table_off];
+  }
   const uint32_t xh = x >> kScaleBits;
   uint32_t xn = __umul24((e >> 8) & 0xfffu, xh) + (xh + (e >> 20));  // f * (x >> 12) + slot - cum
   uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
@@ -786,9 +796,10 @@ __device__ __forceinline__ void dec_step(uint32_t &x, const uint32_t *lut, const
   }
 }
 
-template <int W, bool ADAPT>
+template <int W, bool ADAPT, bool COMPACT = false>
 __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
-  __shared__ uint32_t lut_one[ADAPT ? 1 : kScale];
+  static_assert(!(ADAPT && COMPACT), "the split table is for the single-table streams");
+  __shared__ uint32_t lut_one[ADAPT ? 1 : (COMPACT ? 256 + kScale / 4 : kScale)];
   extern __shared__ uint32_t lut_per_depth[];  // ADAPT: n_tables slot tables, sized at launch
   uint32_t *lut = ADAPT ? lut_per_depth : lut_one;
   __shared__ uint16_t table_of_group[ADAPT ? W : 1][2][kBatch];  // ADAPT: table offset of each group of a batch
@@ -810,7 +821,12 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
       for (int r = 0; r < 4; ++r) {
         const int s = lane * 4 + r;
         if ((s & (W - 1)) == wave) {
-          for (uint32_t o = 0; o < f[r]; ++o) lut[cum + o] = (uint32_t)s | ((f[r] - 1u) << 8) | (o << 20);
+          if (COMPACT) {
+            lut[s] = ((f[r] - 1u) & 0xfffu) | (cum << 16);  // a symbol that does not occur is never looked up
+            for (uint32_t o = 0; o < f[r]; ++o) reinterpret_cast<uint8_t *>(lut + 256)[cum + o] = (uint8_t)s;
+          } else {
+            for (uint32_t o = 0; o < f[r]; ++o) lut[cum + o] = (uint32_t)s | ((f[r] - 1u) << 8) | (o << 20);
+          }
         }
         cum += f[r];
       }
@@ -939,10 +955,12 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
     const uint16_t *wtop = wtop0;
     if (tail) {
       for (int32_t j = 0; j < cnt_groups; ++j)
-        dec_step<true>(x, lut, wtop, sb + kLanes * j, below, j != cnt_groups - 1 || top_active, ADAPT ? gt[j] : 0u);
+        dec_step<true, COMPACT>(x, lut, wtop, sb + kLanes * j, below, j != cnt_groups - 1 || top_active,
+                                ADAPT ? gt[j] : 0u);
     } else {
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) dec_step<false>(x, lut, wtop, sb + kLanes * j, below, true, ADAPT ? gt[j] : 0u);
+      for (int j = 0; j < kBatch; ++j)
+        dec_step<false, COMPACT>(x, lut, wtop, sb + kLanes * j, below, true, ADAPT ? gt[j] : 0u);
     }
     if (ADAPT) {
       if (lane < kBatch) table_of_group[wave][gbuf ^ 1][lane] = (uint16_t)ngt;
@@ -1233,7 +1251,9 @@ struct LaunchDecode {
     } else if (W == 1 && a.n_units <= 512) {
       hipLaunchKernelGGL(rans_decode_chain_kernel, dim3(grid), dim3(64), 0, st, a);
     } else {
-      hipLaunchKernelGGL((rans_decode_kernel<W, false>), dim3(grid), dim3(W * 64), 0, st, a);
+      // Many units: LDS decides how many wavefronts fit a compute unit, and the split table lets more in
+      // (twice as many where every one-wavefront workgroup has a table of its own).
+      hipLaunchKernelGGL((rans_decode_kernel<W, false, true>), dim3(grid), dim3(W * 64), 0, st, a);
     }
   }
 };
