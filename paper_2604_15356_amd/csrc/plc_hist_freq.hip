@@ -65,7 +65,8 @@ __global__ __launch_bounds__(kBlock) void histogram_bucketed_kernel(const uint8_
                                                                     int64_t syms_per_stream, uint32_t segs_per_stream,
                                                                     uint32_t syms_per_pos, uint32_t streams_per_session,
                                                                     const uint8_t *__restrict__ bits, int n_tables,
-                                                                    uint32_t *__restrict__ counts, uint32_t *status) {
+                                                                    uint32_t pos_lanes, uint32_t *__restrict__ counts,
+                                                                    uint32_t *status) {
   __shared__ uint32_t hist[kBlock / 64][PLC_MAX_BITS][256];
   const uint32_t stream = blockIdx.x / segs_per_stream;
   const uint32_t seg = blockIdx.x - stream * segs_per_stream;
@@ -89,11 +90,25 @@ __global__ __launch_bounds__(kBlock) void histogram_bucketed_kernel(const uint8_
     uint32_t *h = hist[wave][b - 1];
     const uint4 v = load16_stream(base + t0);
     const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+    // At coarse steps most residuals quantise to zero, and every lane would queue at that one counter: the
+    // zeros are counted apart and summed over the `pos_lanes` neighbouring lanes that share the position
+    // (a power of two, at most 16) before one lane adds them.
+    uint32_t zeros = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) atomicAdd(&h[(wds[j] >> (8 * q)) & 255u], 1u);
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t sym = (wds[j] >> (8 * q)) & 255u;
+        if (sym == kZeroSymbol)
+          ++zeros;
+        else
+          atomicAdd(&h[sym], 1u);
+      }
     }
+#pragma unroll
+    for (uint32_t m = 1; m < 16; m <<= 1)
+      if (m < pos_lanes) zeros += __shfl_xor(zeros, (int)m);
+    if ((threadIdx.x & (pos_lanes - 1)) == 0 && zeros) atomicAdd(&h[kZeroSymbol], zeros);
   }
   __syncthreads();
   for (int t = 0; t < n_tables; ++t) {
@@ -241,10 +256,13 @@ extern "C" int plc_histogram_bucketed(const uint8_t *symbols, int64_t n_streams,
   if (n_streams * segs >= (1ll << 31) || n_streams >= (1ll << 31) / (256 * PLC_MAX_BITS)) return PLC_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int64_t n = n_streams * n_tables * 256;
+  // neighbouring lanes (16 symbols each) that always share a position: a power of two dividing syms_per_pos / 16
+  uint32_t pos_lanes = 2;
+  while (pos_lanes < 16 && (syms_per_pos / 16) % (2 * pos_lanes) == 0) pos_lanes *= 2;
   hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, counts, n);
   hipLaunchKernelGGL(histogram_bucketed_kernel, dim3((unsigned)(n_streams * segs)), dim3(kBlock), 0, st, symbols,
                      syms_per_stream, (uint32_t)segs, (uint32_t)syms_per_pos, (uint32_t)streams_per_session, bits,
-                     n_tables, counts, status);
+                     n_tables, pos_lanes, counts, status);
   return launch_status();
 }
 
