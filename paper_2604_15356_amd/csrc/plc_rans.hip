@@ -958,9 +958,13 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
         dec_step<true, COMPACT>(x, lut, wtop, sb + kLanes * j, below, j != cnt_groups - 1 || top_active,
                                 ADAPT ? gt[j] : 0u);
     } else {
+      // the batch's table offsets are read before its first symbol is stored (the compiler cannot tell
+      // the two LDS arrays apart, and a read inside a step would queue behind the previous step's store)
+      uint32_t off[kBatch];
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j)
-        dec_step<false, COMPACT>(x, lut, wtop, sb + kLanes * j, below, true, ADAPT ? gt[j] : 0u);
+      for (int j = 0; j < kBatch; ++j) off[j] = ADAPT ? (uint32_t)__builtin_amdgcn_readfirstlane(gt[j]) : 0u;
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) dec_step<false, COMPACT>(x, lut, wtop, sb + kLanes * j, below, true, off[j]);
     }
     if (ADAPT) {
       if (lane < kBatch) table_of_group[wave][gbuf ^ 1][lane] = (uint16_t)ngt;
