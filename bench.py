@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--also-chunked", type=int, default=4096,
                     help="when the headline run codes whole streams (chunk_syms 0), also time the same workload with "
                          "rANS units of this many symbols and report it beside the headline (0 = skip)")
+    ap.add_argument("--no-pipeline", action="store_true",
+                    help="skip the measurement with the steps dealt to several streams")
+    ap.add_argument("--pipeline-streams", type=int, default=3, help="streams of that measurement")
     ap.add_argument("--no-conditional", action="store_true",
                     help="skip the side measurement of the token-conditional path (prediction = the true token's "
                          "candidate, its index coded in a stream of its own)")
@@ -290,6 +293,51 @@ def main():
         log(f"  with rANS units of {args.also_chunked} symbols: step {dt2 / args.steps * 1e3:.4f} ms "
             f"({result['chunked']['value']} GB/s), rans_encode {ms2['rans_encode']:.4f} ms, rans_decode {ms2['rans_decode']:.4f} ms")
         del codec2
+    if not args.no_pipeline:
+        # The same steps dealt in turn to a few HIP streams (default priority), each with a codec and output
+        # buffers of its own: a step is sequential inside, but the entropy coder keeps only a few wavefronts
+        # per compute unit busy, so the neighbouring step's memory-bound kernels run beside it.  What a
+        # serving loop that codes independent sessions gets; reported beside the headline, not as it (the
+        # headline and its per-kernel durations are those of one step at a time).
+        NS = max(2, args.pipeline_streams)
+        lanes = [(torch.cuda.Stream(device=dev), codec, out_k, out_v)]
+        for _ in range(NS - 1):
+            lanes.append((torch.cuda.Stream(device=dev),
+                          KVDeltaCodec(w.S, w.L, w.H, w.n, w.k, w.d, w.delta, w.qmax, chunk_syms=args.chunk_syms,
+                                       device=dev, cand_stride=w.cand_k.stride()[:5], act_stride=w.act_k.stride()[:4]),
+                          torch.zeros_like(out_k), torch.zeros_like(out_v)))
+
+        def run_pipelined(count):
+            for st, _, _, _ in lanes:
+                st.wait_stream(torch.cuda.current_stream())
+            for i in range(count):
+                st, cd, ok_, ov_ = lanes[i % NS]
+                with torch.cuda.stream(st):
+                    cd.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+                    cd.decode(w.cand_k, w.cand_v, w.probs, ok_, ov_)
+            for st, _, _, _ in lanes:
+                torch.cuda.current_stream().wait_stream(st)
+
+        run_pipelined(NS * max(1, args.warmup))
+        torch.cuda.synchronize()
+        steps_p = ((args.steps + NS - 1) // NS) * NS
+        t0 = time.perf_counter()
+        run_pipelined(steps_p)
+        torch.cuda.synchronize()
+        dtp = time.perf_counter() - t0
+        same = True
+        for _, cd, ok_, ov_ in lanes:
+            cd.check_status("pipelined steps")
+            same = same and bool(torch.equal(cd.dec_symbols, cd.symbols)) and bool(torch.equal(ok_, out_k)) and \
+                bool(torch.equal(ov_, out_v)) and bool(torch.equal(cd.n_words, codec.n_words)) and \
+                bool(torch.equal(cd.states, codec.states))
+        result["stream_pipeline"] = {
+            "streams": NS, "steps": steps_p, "value": round(w.kv_bytes / (dtp / steps_p) / 1e9, 2), "unit": "GB/s",
+            "ms_per_step": round(dtp / steps_p * 1e3, 4), "outputs_identical": same,
+        }
+        log(f"  steps dealt to {NS} streams: {dtp / steps_p * 1e3:.4f} ms per step "
+            f"({result['stream_pipeline']['value']} GB/s), outputs identical: {same}")
+        del lanes
     if not args.no_conditional:
         # Token-conditional path on the same workload and in the same format (whole streams unless --chunk-syms):
         # every position is predicted by the candidate of its true token (given, as the serving loop knows it),
