@@ -1008,51 +1008,55 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 // Decoder for streams coded as one unit (one wavefront per workgroup)
 // ---------------------------------------------------------------------------
 // With one unit per stream there are only as many wavefronts as streams, so what counts is the
-// length of the dependent chain of one step.  In the kernel above that chain holds two LDS round
-// trips: slot table, then -- for the lanes that renormalise -- the word.  Here they are folded into
-// one.  Every entry, of the slot table and of the word ring alike, is 8 bytes
-//     .x = f | (slot - cum) << 16        .y = sym | word << 16
-// and a ring entry carries, next to its word, the slot-table entry that the state will select once
-// that word has been shifted in (its low 12 bits are the word's).  A lane that renormalises reads
-// its ring entry, a lane that does not reads the slot table at its new state -- one read either
-// way, at an address chosen per lane, both tables living in one LDS array.  The ring entries are
-// formed when a block of words is staged, off the chain.
+// length of the dependent chain of one step: a lone wavefront waits out the full latency of every
+// instruction whose result the next one needs (measured: with the table lookup replaced by arithmetic a
+// step still took 130 of its 180 cycles).  In the kernel above that chain holds two LDS round trips --
+// slot table, then, for the lanes that renormalise, the word -- and some ten dependent vector
+// instructions.  Here the round trips are folded into one and the instructions behind it cut to five.
+//
+// Every entry, of the slot table and of the word ring alike, is 8 bytes
+//     .x = f | sym << 24        .y = f * w4 + slot - cum
+// A ring entry stands for a word w = w4 << 12 | slot: it is the slot-table entry that the state will
+// select once the word has been shifted in (the state's low 12 bits are then the word's, which is all
+// they are needed for), with the word's top four bits w4 already multiplied in; in the slot table itself
+// w4 = 0.  A lane that renormalises reads its ring entry, a lane that does not reads the slot table at
+// its new state -- one read either way, at an address chosen per lane, both tables living in one LDS
+// array; the ring entries are formed when a block of words is staged, off the chain.  The state is
+// carried as xc = x >> 12 without the bits the word supplies: from the previous step's value v,
+// xc = v << 4 if the lane renormalised and v >> 12 if not (ready long before the entry arrives), so
+// that f * (x >> 12) + slot - cum = f * (xc + w4) + slot - cum = f * xc + .y: one multiply-add, whose
+// 24-bit multiplicand ignores the symbol in the top byte of .x.
 constexpr int kRing2Entries = kRingWords + kRingMirror;
 
 template <bool MASKED>
-__device__ __forceinline__ void dec_chain_step(uint32_t &x, uint2 &e, const uint2 *tab, uint32_t &q,
-                                               uint8_t *sym_slot, uint32_t below, bool on) {
-  const uint32_t xh = x >> kScaleBits;
-  const uint32_t xn = __umul24(e.x & 0xffffu, xh) + (e.x >> 16);  // f * (x >> 12) + slot - cum
+__device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uint2 *tab, uint32_t &q,
+                                               uint8_t *sym_slot, bool on) {
+  const uint32_t xn = __umul24(e.x, xc) + e.y;  // f * (x >> 12) + slot - cum
   uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
   bool need = xn < kLow;
   if (MASKED) {
     need = need && on;
     m32 = (uint32_t)__builtin_amdgcn_ballot_w64(need);
   }
-  // ring entry of the rank-th word from the top (lane 0 is served first), or slot-table entry of xn
-  uint32_t idx_ring = (uint32_t)kScale + q + (uint32_t)__builtin_popcount(m32 & below);
+  // ring entry of the rank-th word from the top (lane 0 is served first: the rank is the number of
+  // renormalising lanes below this one), or slot-table entry of xn
+  uint32_t idx_ring = __builtin_amdgcn_mbcnt_lo(m32, (uint32_t)kScale + q);
   uint32_t idx_slot = xn & (kScale - 1);
   asm volatile("" : "+v"(idx_ring), "+v"(idx_slot));  // both in registers: the choice is one select, not a branch
   const uint2 en = tab[need ? idx_ring : idx_slot];
+  __builtin_amdgcn_sched_barrier(0);  // what follows is issued in the shadow of the read
   q += (uint32_t)__builtin_popcount(m32);
-  const uint32_t xw = (xn << 16) | (en.y >> 16);
-  if (MASKED) {
-    if (on) {
-      *sym_slot = (uint8_t)e.y;
-      x = need ? xw : xn;
-      e = en;
-    }
-  } else {
-    *sym_slot = (uint8_t)e.y;
-    x = need ? xw : xn;
+  const uint32_t next = need ? (xn << 4) : (xn >> kScaleBits);
+  if (!MASKED || on) {
+    *sym_slot = (uint8_t)(e.x >> 24);
+    xc = next;
     e = en;
   }
 }
 
 __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a) {
   __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing2Entries];  // slot table, then the ring
-  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[kBatchSyms];
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2 * kBatchSyms];  // second half: lanes 32..63
   __shared__ uint32_t fc[256];
   const int lane = threadIdx.x;
   const int64_t stream = blockIdx.x / a.wgs_per_stream;
@@ -1075,7 +1079,7 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
     for (int s = 0; s < 256; ++s) {
       const uint32_t v = fc[s];
       const uint32_t fs = v & 0xffffu, cs = v >> 16;
-      for (uint32_t o = lane; o < fs; o += 64) tab[cs + o] = make_uint2(fs | (o << 16), (uint32_t)s);
+      for (uint32_t o = lane; o < fs; o += 64) tab[cs + o] = make_uint2(fs | ((uint32_t)s << 24), o);
     }
     wave_sync();
   }
@@ -1109,7 +1113,7 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
     if (take) v = *reinterpret_cast<const uint4 *>(aligned_base + first);
     return take;
   };
-  // Word i goes to ring position (~i) mod 2048, together with the slot-table entry of its low 12 bits.
+  // Word i goes to ring position (~i) mod 2048: its top four bits and the slot-table entry of its low 12.
   auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
     if (take) {
       const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
@@ -1119,7 +1123,7 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
 #pragma unroll
       for (int i = 0; i < 8; ++i) en[i] = tab[w[7 - i] & (kScale - 1)];  // en[i] belongs at pos + i
 #pragma unroll
-      for (int i = 0; i < 8; ++i) en[i].y = (en[i].y & 0xffu) | (w[7 - i] << 16);
+      for (int i = 0; i < 8; ++i) en[i].y += __umul24(en[i].x, w[7 - i] >> kScaleBits);  // f * w4 <= 4096 * 15
 #pragma unroll
       for (int i = 0; i < 8; ++i) ring[pos + i] = en[i];
       if (pos < (uint32_t)kRingMirror) {
@@ -1140,17 +1144,20 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
   }
   wave_sync();
 
+  // Lanes 0..31 decode.  Lanes 32..63 start as their copies and run the same instructions, so that no step
+  // needs a lane mask; their ranks count all 32 decoding lanes, so their states go astray -- whatever they
+  // read lies inside the tables, and what they store goes to a spare half of the stage.
   const bool coder = lane < kLanes;
   const int rl = lane & (kLanes - 1);
-  const uint32_t below = (1u << rl) - 1u;
   const bool top_active = (uint32_t)rl < top_syms;
-  uint32_t x = a.states_in[unit * kLanes + rl];
-  uint2 e = tab[x & (kScale - 1)];
+  const uint32_t x0 = a.states_in[unit * kLanes + rl];
+  uint32_t xc = x0 >> kScaleBits;
+  uint2 e = tab[x0 & (kScale - 1)];
 
   int32_t tail_groups = G % kBatch;
   if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
   const int32_t g_tail = G - tail_groups;
-  uint8_t *sb = &sym_stage[rl];
+  uint8_t *sb = &sym_stage[coder ? rl : kBatchSyms + rl];
 
   for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
     const bool tail = g0 >= g_tail;
@@ -1167,10 +1174,10 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
     uint32_t q = q0;
     if (tail) {
       for (int32_t j = 0; j < cnt_groups; ++j)
-        dec_chain_step<true>(x, e, tab, q, sb + kLanes * j, below, j != cnt_groups - 1 || top_active);
+        dec_chain_step<true>(xc, e, tab, q, sb + kLanes * j, j != cnt_groups - 1 || top_active);
     } else {
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) dec_chain_step<false>(x, e, tab, q, sb + kLanes * j, below, true);
+      for (int j = 0; j < kBatch; ++j) dec_chain_step<false>(xc, e, tab, q, sb + kLanes * j, true);
     }
     ptr -= (int32_t)__builtin_amdgcn_readfirstlane(q - q0);
     if (ptr < lo) {  // ran out of words: the stream is damaged
@@ -1199,8 +1206,12 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
     }
     wave_sync();
   }
-  // integrity: every word consumed, every lane back at the initial state
-  if (ptr != lo || (coder && x != kLow)) bad = true;
+  // integrity: every word consumed, every lane back at the initial state: x >> 12 as carried, and the entry
+  // in hand that of the initial state's slot with w4 = 0 (entries of different slots differ in .y, and
+  // f * w4 > 0 otherwise)
+  const uint2 e0 = tab[kLow & (kScale - 1)];
+  const bool home = xc == (kLow >> kScaleBits) && e.x == e0.x && e.y == e0.y;
+  if (ptr != lo || (coder && !home)) bad = true;
   if (bad) raise(a.status, PLC_ERR_CORRUPT);
 }
 
