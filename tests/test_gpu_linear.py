@@ -36,6 +36,10 @@ CASES = {
     "wide_heads": dict(S=2, L=1, H=4, d=32, n=128, m=256, V=96, seed=52),
     "d128": dict(L=2, H=1, d=128, n=256, m=384, V=2048, seed=53),
     "noisy": dict(L=1, H=2, d=64, n=128, m=128, V=512, sigma=3.0, seed=54),       # escapes
+    # 256 (session, layer) pairs of one 256 x 256 tile each: the second contraction takes the large-tile
+    # kernel (slices loaded straight into LDS); K = m = 128 is two slices, 384 six
+    "large_tiles": dict(L=256, H=1, d=128, n=256, m=128, V=64, seed=55),
+    "large_tiles_k384": dict(S=2, L=128, H=2, d=64, n=256, m=384, V=96, seed=56),
 }
 
 
@@ -126,3 +130,29 @@ def test_linear_predictor_is_deterministic_and_rejects_bad_shapes(dev):
         plc.plc_expected_embedding(w.probs_full[:, :1000].contiguous(), w.embed_t[:, :1000].contiguous(), codec.ebar)
     with pytest.raises(plc.PlcError):                      # rows not a multiple of 128
         plc.plc_expected_embedding(w.probs_full[:100].contiguous(), w.embed_t, codec.ebar[:100].contiguous())
+
+
+@pytest.mark.parametrize("V", [32, 64, 96, 416])
+def test_expected_embedding_large_tiles(dev, V):
+    """The first contraction at an output that divides into 256 x 256 tiles, one per compute unit (the kernel
+    whose slices are loaded straight into LDS), with K one short slice, one whole slice, a short and a whole
+    one, and several: against numpy in fp64 (numpy.matmul is the oracle's own step here)."""
+    from paper_2604_15356_amd import plc
+    rows, m = 4096, 4096
+    g = torch.Generator(device="cpu").manual_seed(900 + V)
+    P = torch.rand((rows, V), generator=g).to(torch.float16)
+    P = (P / P.float().sum(dim=1, keepdim=True)).to(torch.float16)
+    E = torch.randn((m, V), generator=g).to(torch.float16)
+    out = torch.zeros((rows, m), dtype=torch.float16, device=dev)
+    print(f"expected embedding {rows} x {m}, V {V}", flush=True)
+    plc.plc_expected_embedding(P.to(dev), E.to(dev), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    want64 = OL.expected_embedding(P.numpy(), E.numpy()).astype(np.float64)
+    exact = P.numpy().astype(np.float64) @ E.numpy().astype(np.float64).T
+    assert np.array_equal(want64, exact.astype(np.float16).astype(np.float64))
+    # fp32 accumulation of V terms, then one rounding to fp16
+    tol = np.spacing(np.maximum(np.abs(want64), 2.0 ** -14).astype(np.float16)).astype(np.float64) \
+        + (V + 2) * 2.0 ** -24 * (np.abs(P.numpy().astype(np.float64)) @ np.abs(E.numpy().astype(np.float64)).T)
+    assert (np.abs(got.astype(np.float64) - want64) <= tol).all()
+    assert (got.view(np.uint16) != want64.astype(np.float16).view(np.uint16)).mean() < 0.02
