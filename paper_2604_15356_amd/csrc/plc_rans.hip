@@ -1054,34 +1054,48 @@ __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uin
   }
 }
 
-__global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a) {
+// Two wavefronts per unit.  What a step does not need stays off the decoding wavefront: a helper, on
+// another SIMD of the compute unit, stages the words (forming the ring entries costs eight table lookups
+// and up to sixteen LDS writes per lane and block) and moves the decoded symbols to global memory.  The
+// two meet at one workgroup barrier per batch of 16 steps:
+//   decoder  batch b: 16 steps into symbol stage b % 2; publishes the word pointer; barrier b
+//   helper   while batch b runs: stages every block down to 1024 words below the pointer published at
+//            barrier b - 1 (a batch consumes at most 512, so batch b + 1 finds its words); barrier b;
+//            then moves the symbols of batch b out while batch b + 1 runs.
+// The blocks the helper writes lie at least one block below those the running batch reads, and the ring
+// slots they take belonged to blocks above the pointer.
+__global__ __launch_bounds__(128) void rans_decode_chain_kernel(const RansArgs a) {
   __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing2Entries];  // slot table, then the ring
-  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2 * kBatchSyms];  // second half: lanes 32..63
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
   __shared__ uint32_t fc[256];
-  const int lane = threadIdx.x;
+  __shared__ int32_t ptr_pub;
+  const int lane = threadIdx.x & 63;
+  const bool helper = threadIdx.x >= 64;  // uniform per wavefront
   const int64_t stream = blockIdx.x / a.wgs_per_stream;
   const int64_t chunk = blockIdx.x - stream * a.wgs_per_stream;
   bool bad = false;
 
-  {  // slot table: symbols one after the other, 64 slots per pass
+  {  // slot table: symbols one after the other, 128 slots per pass
     uint32_t f[4], cum;
     const uint32_t total = load_freq4(a.freq + stream * 256, lane, f, &cum);
-    if (total != kScale) {  // not a table: nothing can be decoded
-      if (lane == 0) raise(a.status, PLC_ERR_CORRUPT);
+    if (total != kScale) {  // not a table: nothing can be decoded (both wavefronts leave, before any barrier)
+      if (threadIdx.x == 0) raise(a.status, PLC_ERR_CORRUPT);
       return;
     }
+    if (!helper) {
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      fc[lane * 4 + r] = f[r] | (cum << 16);
-      cum += f[r];
+      for (int r = 0; r < 4; ++r) {
+        fc[lane * 4 + r] = f[r] | (cum << 16);
+        cum += f[r];
+      }
     }
-    wave_sync();
+    __syncthreads();
     for (int s = 0; s < 256; ++s) {
       const uint32_t v = fc[s];
       const uint32_t fs = v & 0xffffu, cs = v >> 16;
-      for (uint32_t o = lane; o < fs; o += 64) tab[cs + o] = make_uint2(fs | ((uint32_t)s << 24), o);
+      for (uint32_t o = threadIdx.x; o < fs; o += 128) tab[cs + o] = make_uint2(fs | ((uint32_t)s << 24), o);
     }
-    wave_sync();
+    __syncthreads();
   }
   uint2 *ring = tab + kScale;
 
@@ -1097,8 +1111,8 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
   // ---- word list geometry, relative to a 1 KiB-aligned address at or below the unit's first word
   const uint64_t off = a.word_off[unit];
   const uint32_t n = a.n_words_in[unit];
-  if (off > a.words_len || (uint64_t)n > a.words_len - off) {
-    if (lane == 0) raise(a.status, PLC_ERR_CORRUPT);
+  if (off > a.words_len || (uint64_t)n > a.words_len - off) {  // uniform: both wavefronts leave
+    if (threadIdx.x == 0) raise(a.status, PLC_ERR_CORRUPT);
     return;
   }
   const uint16_t *first_word = a.words_in + off;
@@ -1106,44 +1120,80 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
   const uint16_t *aligned_base = first_word - lo;  // pointer arithmetic keeps the loads global, not flat
   const int32_t hi = lo + (int32_t)n;
 
-  // one 16-byte piece (eight words) of block blk per lane, if the piece holds a word of this unit
-  auto block_load = [&](int32_t blk, uint4 &v) -> bool {
-    const int32_t first = blk * kBlockWords + lane * 8;
-    const bool take = blk >= 0 && hi > lo && first + 8 > lo && first < hi;
-    if (take) v = *reinterpret_cast<const uint4 *>(aligned_base + first);
-    return take;
-  };
-  // Word i goes to ring position (~i) mod 2048: its top four bits and the slot-table entry of its low 12.
-  auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
-    if (take) {
-      const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
-      const uint32_t w[8] = {v.x & 0xffffu, v.x >> 16, v.y & 0xffffu, v.y >> 16,
-                             v.z & 0xffffu, v.z >> 16, v.w & 0xffffu, v.w >> 16};
-      uint2 en[8];
+  int32_t tail_groups = G % kBatch;
+  if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
+  const int32_t g_tail = G - tail_groups;
+
+  if (helper) {
+    // one 16-byte piece (eight words) of block blk per lane, if the piece holds a word of this unit
+    auto block_load = [&](int32_t blk, uint4 &v) -> bool {
+      const int32_t first = blk * kBlockWords + lane * 8;
+      const bool take = blk >= 0 && hi > lo && first + 8 > lo && first < hi;
+      if (take) v = *reinterpret_cast<const uint4 *>(aligned_base + first);
+      return take;
+    };
+    // Word i goes to ring position (~i) mod 2048: the slot-table entry of its low 12 bits, its top four
+    // bits multiplied in.
+    auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
+      if (take) {
+        const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
+        const uint32_t w[8] = {v.x & 0xffffu, v.x >> 16, v.y & 0xffffu, v.y >> 16,
+                               v.z & 0xffffu, v.z >> 16, v.w & 0xffffu, v.w >> 16};
+        uint2 en[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) en[i] = tab[w[7 - i] & (kScale - 1)];  // en[i] belongs at pos + i
+        for (int i = 0; i < 8; ++i) en[i] = tab[w[7 - i] & (kScale - 1)];  // en[i] belongs at pos + i
 #pragma unroll
-      for (int i = 0; i < 8; ++i) en[i].y += __umul24(en[i].x, w[7 - i] >> kScaleBits);  // f * w4 <= 4096 * 15
+        for (int i = 0; i < 8; ++i) en[i].y += __umul24(en[i].x, w[7 - i] >> kScaleBits);  // f * w4 <= 4096 * 15
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ring[pos + i] = en[i];
-      if (pos < (uint32_t)kRingMirror) {
+        for (int i = 0; i < 8; i += 2)
+          *reinterpret_cast<uint4 *>(&ring[pos + i]) = make_uint4(en[i].x, en[i].y, en[i + 1].x, en[i + 1].y);
+        if (pos < (uint32_t)kRingMirror) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ring[kRingWords + pos + i] = en[i];
+          for (int i = 0; i < 8; i += 2)
+            *reinterpret_cast<uint4 *>(&ring[kRingWords + pos + i]) =
+                make_uint4(en[i].x, en[i].y, en[i + 1].x, en[i + 1].y);
+        }
+      }
+    };
+    // stages every block that holds a word at or above `down_to` and is not staged yet
+    int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already staged (none yet)
+    auto stage_down_to = [&](int32_t down_to) {
+      const int32_t last = down_to > 0 ? down_to >> 9 : 0;
+      while (lowest > last) {  // uniform; at most two rounds after the first call
+        uint4 v;
+        const int32_t blk = lowest - 1;
+        const bool take = block_load(blk, v);
+        block_store(blk, take, v);
+        lowest = blk;
+      }
+    };
+    stage_down_to(hi - 2 * kBlockWords);  // the words of the first two batches
+    __syncthreads();                      // barrier "start"
+    int32_t ptr_before = hi;  // the pointer as it stood before the batch now running
+    for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
+      stage_down_to(ptr_before - 2 * kBlockWords);
+      __syncthreads();  // barrier of this batch: its symbols are in the stage, the pointer is published
+      ptr_before = ptr_pub;  // read at once: the decoder writes it again only at the end of its next batch
+      const bool tail = g0 >= g_tail;
+      const int32_t cnt_groups = tail ? tail_groups : kBatch;
+      const uint8_t *stage = sym_stage[(g0 / kBatch) & 1];
+      const uint32_t done = (uint32_t)g0 * kLanes;
+      const uint32_t room = (uint32_t)cnt_groups * kLanes;
+      const uint32_t nsym = (len - done) < room ? (len - done) : room;
+      if (out_aligned) {
+        const uint32_t full = nsym / 16;
+        if ((uint32_t)lane < full)
+          *reinterpret_cast<uint4 *>(ubase + done + lane * 16) = *reinterpret_cast<const uint4 *>(&stage[lane * 16]);
+        const uint32_t rest_at = full * 16 + (uint32_t)lane;
+        if (rest_at < nsym) ubase[done + rest_at] = stage[rest_at];
+      } else {
+        for (uint32_t i = lane; i < nsym; i += 64) ubase[done + i] = stage[i];
       }
     }
-  };
-
-  int32_t ptr = hi;
-  int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already staged (none yet)
-  for (int r = 0; r < 2; ++r) {          // the two top blocks
-    uint4 v;
-    const int32_t blk = lowest - 1;
-    const bool take = block_load(blk, v);
-    block_store(blk, take, v);
-    lowest = blk;
+    return;
   }
-  wave_sync();
 
+  // ---- the decoding wavefront
   // Lanes 0..31 decode.  Lanes 32..63 start as their copies and run the same instructions, so that no step
   // needs a lane mask; their ranks count all 32 decoding lanes, so their states go astray -- whatever they
   // read lies inside the tables, and what they store goes to a spare half of the stage.
@@ -1153,23 +1203,12 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
   const uint32_t x0 = a.states_in[unit * kLanes + rl];
   uint32_t xc = x0 >> kScaleBits;
   uint2 e = tab[x0 & (kScale - 1)];
-
-  int32_t tail_groups = G % kBatch;
-  if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
-  const int32_t g_tail = G - tail_groups;
-  uint8_t *sb = &sym_stage[coder ? rl : kBatchSyms + rl];
-
+  int32_t ptr = hi;
+  __syncthreads();  // barrier "start": the first words are staged
   for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
     const bool tail = g0 >= g_tail;
     const int32_t cnt_groups = tail ? tail_groups : kBatch;
-    // stage one more block below if the coming batches may reach it
-    const int32_t top = (ptr - 1) >> 9;
-    const bool fetch = lowest > top - 2;
-    const int32_t blk = lowest - 1;
-    uint4 pre;
-    bool ptake = false;
-    if (fetch) ptake = block_load(blk, pre);
-
+    uint8_t *sb = &sym_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
     const uint32_t q0 = (uint32_t)(-ptr) & (kRingWords - 1);
     uint32_t q = q0;
     if (tail) {
@@ -1184,27 +1223,8 @@ __global__ __launch_bounds__(64) void rans_decode_chain_kernel(const RansArgs a)
       bad = true;
       ptr = lo;
     }
-    // the prefetched block goes to the ring BEFORE this batch's symbols are stored: waiting for the load
-    // then does not also wait for freshly issued stores (loads and stores share one counter)
-    if (fetch) {
-      block_store(blk, ptake, pre);
-      lowest = blk;
-    }
-    wave_sync();
-    // drain the batch's symbols
-    const uint32_t done = (uint32_t)g0 * kLanes;
-    const uint32_t room = (uint32_t)cnt_groups * kLanes;
-    const uint32_t nsym = (len - done) < room ? (len - done) : room;
-    if (out_aligned) {
-      const uint32_t full = nsym / 16;
-      if ((uint32_t)lane < full)
-        *reinterpret_cast<uint4 *>(ubase + done + lane * 16) = *reinterpret_cast<const uint4 *>(&sym_stage[lane * 16]);
-      const uint32_t rest_at = full * 16 + (uint32_t)lane;
-      if (rest_at < nsym) ubase[done + rest_at] = sym_stage[rest_at];
-    } else {
-      for (uint32_t i = lane; i < nsym; i += 64) ubase[done + i] = sym_stage[i];
-    }
-    wave_sync();
+    if (lane == 0) ptr_pub = ptr;
+    __syncthreads();  // barrier of this batch
   }
   // integrity: every word consumed, every lane back at the initial state: x >> 12 as carried, and the entry
   // in hand that of the initial state's slot with w4 = 0 (entries of different slots differ in .y, and
@@ -1264,7 +1284,7 @@ struct LaunchDecode {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipLaunchKernelGGL((rans_decode_kernel<W, true>), dim3(grid), dim3(W * 64), lds, st, a);
     } else if (W == 1 && a.n_units <= 512) {
-      hipLaunchKernelGGL(rans_decode_chain_kernel, dim3(grid), dim3(64), 0, st, a);
+      hipLaunchKernelGGL(rans_decode_chain_kernel, dim3(grid), dim3(128), 0, st, a);
     } else {
       // Many units: LDS decides how many wavefronts fit a compute unit, and the split table lets more in
       // (twice as many where every one-wavefront workgroup has a table of its own).
