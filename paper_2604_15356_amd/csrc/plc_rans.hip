@@ -514,7 +514,7 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
   __shared__ uint4 entry_ring[kEntrySlots][kBatch][kLanes];
   __shared__ uint32_t state_ring[kStateSlots][kBatch][kLanes];
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][kSymStage];
-  __shared__ __attribute__((aligned(16))) uint16_t word_stage[2 * kBatchSyms + 8];
+  __shared__ __attribute__((aligned(16))) uint16_t word_stage[2 * kBatchSyms + 8 + 64];  // list, carry, idle slots
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t unit = blockIdx.x;  // one unit per stream, one workgroup per unit
 
@@ -671,21 +671,31 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
         // hardware lane h of a half carries rANS lane 31 - h, which the encoder visits first
         const uint32_t *xs = &state_ring[sslot_pack][lane >> 5][31 - (lane & 31)];
         const uint32_t *ts = &entry_ring[eslot_pack][lane >> 5][31 - (lane & 31)].y;
-        uint32_t xps[kBatch / 2], thrs[kBatch / 2];
+        // In phases, each over all eight step pairs, so that the instructions of a phase do not wait for one
+        // another (a lone wavefront waits out the latency of every dependent instruction): reads, emit
+        // masks, ranks, list positions, stores.  A lane without a word stores into a slot of its own
+        // behind the list instead of sitting out the store.
+        uint32_t xps[kBatch / 2], thrs[kBatch / 2], rank[kBatch / 2], base[kBatch / 2];
+        uint64_t mask[kBatch / 2];
 #pragma unroll
         for (int p = 0; p < kBatch / 2; ++p) {
           xps[p] = xs[2 * p * kLanes];
           thrs[p] = ts[2 * p * kLanes * 4];
         }
 #pragma unroll
+        for (int p = 0; p < kBatch / 2; ++p) mask[p] = __ballot(xps[p] > thrs[p]);
+#pragma unroll
+        for (int p = 0; p < kBatch / 2; ++p)
+          rank[p] = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask[p] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask[p], 0u));
+#pragma unroll
         for (int p = 0; p < kBatch / 2; ++p) {
-          const uint32_t xp = xps[p];
-          const bool emit = xp > thrs[p];
-          const uint64_t mask = __ballot(emit);
-          const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
-                                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-          if (emit) word_stage[top_fill + rank] = (uint16_t)xp;
-          top_fill += (uint32_t)__builtin_popcountll(mask);
+          base[p] = top_fill;
+          top_fill += (uint32_t)__builtin_popcountll(mask[p]);
+        }
+#pragma unroll
+        for (int p = 0; p < kBatch / 2; ++p) {
+          const bool emit = xps[p] > thrs[p];
+          word_stage[emit ? base[p] + rank[p] : (uint32_t)(2 * kBatchSyms + 8) + (uint32_t)lane] = (uint16_t)xps[p];
         }
         eslot_pack = eslot_pack == kEntrySlots - 1 ? 0 : eslot_pack + 1;
         sslot_pack ^= 1;
