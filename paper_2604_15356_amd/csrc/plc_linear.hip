@@ -300,7 +300,7 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _
 #if defined(__HIP_DEVICE_COMPILE__)  // the host pass of the compiler does not know the device's load-to-LDS builtin
     if (k_lane < width) __builtin_amdgcn_global_load_lds(src + (k0 + g_lane), ring + at, 16, 0, 0);
 #else
-    (void)src, (void)k0, (void)width, (void)at, (void)ring;
+    (void)src, (void)k0, (void)width, (void)at, (void)ring, (void)g_lane;
 #endif
   };
 
