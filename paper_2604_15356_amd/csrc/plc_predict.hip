@@ -334,22 +334,30 @@ __global__ __launch_bounds__(kBlock) void predict_residual_cond_kernel(const Cod
   }
 }
 
-// Count the escape symbols of each tile (decode side).
-__global__ __launch_bounds__(kBlock) void count_escapes_kernel(const CodecArgs a) {
-  __shared__ uint32_t wave_cnt[kBlock / 64];
-  const Coord q = locate(a);
+// Count the escape symbols of each tile (decode side).  One wavefront per tile, 32 bytes per lane: a tile per
+// workgroup would spend its time starting workgroups, this way the pass runs at memory speed.
+__global__ __launch_bounds__(kBlock) void count_escapes_kernel(const CodecArgs a, uint32_t n_tiles) {
+  const uint32_t t = blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);  // tile, uniform per wavefront
+  if (t >= n_tiles) return;
+  const int lane = threadIdx.x & 63;
+  const uint32_t stream = t / a.tiles_per_stream;
+  const uint32_t tile = t - stream * a.tiles_per_stream;
+  const uint32_t chunk0 = tile * kBlock + lane * 4;  // this lane's four chunks of 8 symbols
+  const uint8_t *p = a.symbols + (int64_t)stream * a.syms_per_stream + (int64_t)chunk0 * kChunk;
   uint32_t n_esc = 0;
-  if (q.valid) {
-    const uint2 sv = *reinterpret_cast<const uint2 *>(a.symbols + q.sym);
 #pragma unroll
-    for (int e = 0; e < kChunk; ++e) n_esc += (((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u) == PLC_ESCAPE;
+  for (int c = 0; c < 4; ++c) {  // 8-byte loads: that is the alignment the symbols are promised to have
+    if (chunk0 + c < a.chunks_per_stream) {
+      const uint2 v = *reinterpret_cast<const uint2 *>(p + kChunk * c);
+      // a byte is 0xff iff its low seven bits carry into bit 7 when 1 is added and bit 7 is set
+      n_esc += (uint32_t)__builtin_popcount(((v.x & 0x7f7f7f7fu) + 0x01010101u) & v.x & 0x80808080u);
+      n_esc += (uint32_t)__builtin_popcount(((v.y & 0x7f7f7f7fu) + 0x01010101u) & v.y & 0x80808080u);
+    }
   }
-  uint32_t wsum = n_esc;
+  static_assert(PLC_ESCAPE == 255, "the byte test above");
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) wsum += __shfl_xor(wsum, off, 64);
-  if ((threadIdx.x & 63) == 0) wave_cnt[threadIdx.x >> 6] = wsum;
-  __syncthreads();
-  if (threadIdx.x == 0) a.tile_cnt[blockIdx.x] = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+  for (int off = 32; off > 0; off >>= 1) n_esc += __shfl_xor(n_esc, off, 64);
+  if (lane == 0) a.tile_cnt[t] = n_esc;
 }
 
 // Exclusive prefix sum of the tile counts inside each stream; one workgroup per stream.
@@ -736,7 +744,8 @@ int decode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
 
   hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
                      weights, p.rows, dims->k, status);
-  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
+  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))), dim3(kBlock), 0, st,
+                     a, (uint32_t)p.n_tiles);
   hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
                      (uint32_t)p.tiles_per_stream, (uint32_t *)nullptr);
   {
@@ -765,7 +774,8 @@ int plc::gather_escapes(const plc_dims *dims, const void *act_k, const void *act
   a.symbols = const_cast<uint8_t *>(symbols);
   a.status = status;
   uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
-  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
+  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))), dim3(kBlock), 0, st,
+                     a, (uint32_t)p.n_tiles);
   hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
                      (uint32_t)p.tiles_per_stream, esc_cnt);
   hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
@@ -794,7 +804,8 @@ int plc::patch_escapes(const plc_dims *dims, const uint8_t *symbols, const uint1
   a.esc_off = esc_off;
   a.status = status;
   uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
-  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
+  hipLaunchKernelGGL(count_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))), dim3(kBlock), 0, st,
+                     a, (uint32_t)p.n_tiles);
   hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)p.n_streams), dim3(kBlock), 0, st, a.tile_cnt, tile_off,
                      (uint32_t)p.tiles_per_stream, (uint32_t *)nullptr);
   hipLaunchKernelGGL(patch_escapes_kernel, dim3((unsigned)p.n_tiles), dim3(kBlock), 0, st, a);
