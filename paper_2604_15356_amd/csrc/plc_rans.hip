@@ -1245,6 +1245,238 @@ __global__ __launch_bounds__(128) void rans_decode_chain_kernel(const RansArgs a
   if (bad) raise(a.status, PLC_ERR_CORRUPT);
 }
 
+// ---------------------------------------------------------------------------
+// Decoder for streams coded as one unit with one table per bit depth
+// ---------------------------------------------------------------------------
+// The table changes from position to position, so a ring entry cannot carry the slot-table entry its word
+// will select (it would need to know the step that consumes it), and a step keeps two LDS round trips:
+// the ring, then the table.  What the kernel above teaches still applies: few dependent instructions
+// between the round trips, and everything that is not the recurrence on a helper wavefront.
+//   slot tables   per depth, 8 bytes per slot: .x = f | sym << 24, .y = slot - cum   (32 KB each)
+//   ring          4 bytes per word w: (w & 0xfff) * 8 | (w >> 12) << 16 -- the byte offset of the word's
+//                 slot in a table, and the four bits the state takes from it
+//   state         x >> 12 with the word's top bits already in; f * (x >> 12) + slot - cum is one
+//                 multiply-add on the entry's arrival
+//   step          multiply-add, compare, rank, shift | ring read | mask-or-in the next table's offset,
+//                 select | table read: six dependent instructions and two round trips
+// The helper stages the words, looks up the table of each group of the next batch, and moves the symbols
+// out; one workgroup barrier per batch, as above.
+constexpr uint32_t kDepthTableBytes = kScale * sizeof(uint2);
+
+template <bool MASKED>
+__device__ __forceinline__ void dec_depth_step(uint32_t &xh, uint2 &e, uint32_t &at, const char *tabs,
+                                               const uint32_t *ring, uint32_t &q, uint8_t *sym_slot,
+                                               uint32_t next_table, uint32_t low16, bool on) {
+  const uint32_t xn = __umul24(e.x, xh) + e.y;  // f * (x >> 12) + slot - cum
+  uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
+  bool need = xn < kLow;
+  if (MASKED) {
+    need = need && on;
+    m32 = (uint32_t)__builtin_amdgcn_ballot_w64(need);
+  }
+  const uint32_t r = ring[__builtin_amdgcn_mbcnt_lo(m32, q)];  // the rank-th word from the top
+  __builtin_amdgcn_sched_barrier(0);                           // what does not need it is issued in its shadow
+  const uint32_t at_stay = (((xn & (kScale - 1)) << 3) | next_table);
+  const uint32_t xh_stay = xn >> kScaleBits, xh_base = xn << 4;
+  q += (uint32_t)__builtin_popcount(m32);
+  if (!MASKED || on) *sym_slot = (uint8_t)(e.x >> 24);
+  __builtin_amdgcn_sched_barrier(0);
+  const uint32_t at_word = (r & low16) | next_table;
+  const uint32_t at_next = need ? at_word : at_stay;
+  const uint2 en = *reinterpret_cast<const uint2 *>(tabs + at_next);
+  const uint32_t xh_next = need ? (xh_base | (r >> 16)) : xh_stay;
+  if (!MASKED || on) {
+    xh = xh_next;
+    e = en;
+    at = at_next;
+  }
+}
+
+__global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char depth_lds[];  // n_tables slot tables, then the ring
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
+  __shared__ uint32_t fc[256];
+  __shared__ uint32_t table_of_group[2][kBatch];  // byte offset of the table of groups g0 + 1 .. g0 + 16
+  __shared__ uint32_t first_table;
+  __shared__ int32_t ptr_pub;
+  __shared__ uint32_t tables_ok;
+  const int lane = threadIdx.x & 63;
+  const bool helper = threadIdx.x >= 64;  // uniform per wavefront
+  const int64_t stream = blockIdx.x / a.wgs_per_stream;
+  const int64_t chunk = blockIdx.x - stream * a.wgs_per_stream;
+  uint2 *tabs2 = reinterpret_cast<uint2 *>(depth_lds);
+  uint32_t *ring = reinterpret_cast<uint32_t *>(depth_lds + (size_t)a.n_tables * kDepthTableBytes);
+  bool bad = false;
+
+  // slot tables, one after the other; an all-zero table (a depth the stream does not use) stays zero
+  if (threadIdx.x == 0) tables_ok = 1u;
+  __syncthreads();
+  for (int t = 0; t < a.n_tables; ++t) {
+    uint32_t f[4], cum;
+    const uint32_t total = load_freq4(a.freq + (stream * a.n_tables + t) * 256, lane, f, &cum);
+    if (total != kScale && total != 0 && threadIdx.x == 0) tables_ok = 0u;
+    if (!helper) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        fc[lane * 4 + r] = f[r] | (cum << 16);
+        cum += f[r];
+      }
+    }
+    __syncthreads();
+    uint2 *tt = tabs2 + (size_t)t * kScale;
+    if (total == kScale) {
+      for (int sy = 0; sy < 256; ++sy) {
+        const uint32_t v = fc[sy];
+        const uint32_t fs = v & 0xffffu, cs = v >> 16;
+        for (uint32_t o = threadIdx.x; o < fs; o += 128) tt[cs + o] = make_uint2(fs | ((uint32_t)sy << 24), o);
+      }
+    } else {
+      for (uint32_t o = threadIdx.x; o < (uint32_t)kScale; o += 128) tt[o] = make_uint2(0u, 0u);
+    }
+    __syncthreads();
+  }
+  if (!tables_ok) {  // not a table: nothing can be decoded (uniform: both wavefronts leave)
+    if (threadIdx.x == 0) raise(a.status, PLC_ERR_CORRUPT);
+    return;
+  }
+
+  const int64_t unit = stream * a.units_per_stream + chunk;
+  const int64_t begin = chunk * a.unit_syms;
+  const int64_t rest = a.syms_per_stream - begin;
+  const uint32_t len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
+  uint8_t *ubase = a.sym_out + stream * a.syms_per_stream + begin;
+  const bool out_aligned = (reinterpret_cast<uintptr_t>(ubase) & 15u) == 0;
+  const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
+  const uint32_t top_syms = len - (uint32_t)(G - 1) * kLanes;
+
+  const uint64_t off = a.word_off[unit];
+  const uint32_t n = a.n_words_in[unit];
+  if (off > a.words_len || (uint64_t)n > a.words_len - off) {  // uniform: both wavefronts leave
+    if (threadIdx.x == 0) raise(a.status, PLC_ERR_CORRUPT);
+    return;
+  }
+  const uint16_t *first_word = a.words_in + off;
+  const int32_t lo = (int32_t)((reinterpret_cast<uintptr_t>(first_word) & (uintptr_t)(kBlockWords * 2 - 1)) >> 1);
+  const uint16_t *aligned_base = first_word - lo;
+  const int32_t hi = lo + (int32_t)n;
+
+  int32_t tail_groups = G % kBatch;
+  if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
+  const int32_t g_tail = G - tail_groups;
+
+  if (helper) {
+    bool bad_depth = false;
+    auto block_load = [&](int32_t blk, uint4 &v) -> bool {
+      const int32_t first = blk * kBlockWords + lane * 8;
+      const bool take = blk >= 0 && hi > lo && first + 8 > lo && first < hi;
+      if (take) v = *reinterpret_cast<const uint4 *>(aligned_base + first);
+      return take;
+    };
+    auto entry = [](uint32_t w) { return ((w & (kScale - 1)) << 3) | ((w >> kScaleBits) << 16); };
+    auto block_store = [&](int32_t blk, bool take, const uint4 &v) {  // word i goes to ring position (~i) mod 2048
+      if (take) {
+        const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
+        const uint4 r0 = make_uint4(entry(v.w >> 16), entry(v.w & 0xffffu), entry(v.z >> 16), entry(v.z & 0xffffu));
+        const uint4 r1 = make_uint4(entry(v.y >> 16), entry(v.y & 0xffffu), entry(v.x >> 16), entry(v.x & 0xffffu));
+        *reinterpret_cast<uint4 *>(&ring[pos]) = r0;
+        *reinterpret_cast<uint4 *>(&ring[pos + 4]) = r1;
+        if (pos < (uint32_t)kRingMirror) {
+          *reinterpret_cast<uint4 *>(&ring[kRingWords + pos]) = r0;
+          *reinterpret_cast<uint4 *>(&ring[kRingWords + pos + 4]) = r1;
+        }
+      }
+    };
+    int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already staged (none yet)
+    auto stage_down_to = [&](int32_t down_to) {
+      const int32_t last = down_to > 0 ? down_to >> 9 : 0;
+      while (lowest > last) {
+        uint4 v;
+        const int32_t blk = lowest - 1;
+        const bool take = block_load(blk, v);
+        block_store(blk, take, v);
+        lowest = blk;
+      }
+    };
+    // tables of groups g0 + 1 .. g0 + 16 (past the last group: the first table, whose entry is never used)
+    auto tables_for = [&](int32_t g0, int buf) {
+      if (lane < kBatch) {
+        const int32_t g = g0 + 1 + lane;
+        table_of_group[buf][lane] = g < G ? group_table(a, stream, begin, g, kDepthTableBytes, &bad_depth) : 0u;
+      }
+    };
+    stage_down_to(hi - 2 * kBlockWords);
+    if (lane == 0) first_table = group_table(a, stream, begin, 0, kDepthTableBytes, &bad_depth);
+    tables_for(0, 0);
+    __syncthreads();  // barrier "start"
+    int32_t ptr_before = hi;
+    for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
+      stage_down_to(ptr_before - 2 * kBlockWords);
+      tables_for(g0 + kBatch, ((g0 / kBatch) + 1) & 1);
+      __syncthreads();  // barrier of this batch
+      ptr_before = ptr_pub;
+      const bool tail = g0 >= g_tail;
+      const int32_t cnt_groups = tail ? tail_groups : kBatch;
+      const uint8_t *stage = sym_stage[(g0 / kBatch) & 1];
+      const uint32_t done = (uint32_t)g0 * kLanes;
+      const uint32_t room = (uint32_t)cnt_groups * kLanes;
+      const uint32_t nsym = (len - done) < room ? (len - done) : room;
+      if (out_aligned) {
+        const uint32_t full = nsym / 16;
+        if ((uint32_t)lane < full)
+          *reinterpret_cast<uint4 *>(ubase + done + lane * 16) = *reinterpret_cast<const uint4 *>(&stage[lane * 16]);
+        const uint32_t rest_at = full * 16 + (uint32_t)lane;
+        if (rest_at < nsym) ubase[done + rest_at] = stage[rest_at];
+      } else {
+        for (uint32_t i = lane; i < nsym; i += 64) ubase[done + i] = stage[i];
+      }
+    }
+    if (bad_depth) raise(a.status, PLC_ERR_INVALID);
+    return;
+  }
+
+  // ---- the decoding wavefront (lanes 32..63 ride along, as in the kernel above)
+  const bool coder = lane < kLanes;
+  const int rl = lane & (kLanes - 1);
+  const bool top_active = (uint32_t)rl < top_syms;
+  const uint32_t x0 = a.states_in[unit * kLanes + rl];
+  const uint32_t low16 = 0x7ff8u;  // a ring entry's slot offset; also keeps a stray entry inside a table
+  int32_t ptr = hi;
+  __syncthreads();  // barrier "start": the first words are staged, the first tables known
+  uint32_t xh = x0 >> kScaleBits;
+  uint32_t at = ((x0 & (kScale - 1)) << 3) | first_table;
+  uint2 e = *reinterpret_cast<const uint2 *>(depth_lds + at);
+  for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
+    const bool tail = g0 >= g_tail;
+    const int32_t cnt_groups = tail ? tail_groups : kBatch;
+    const uint32_t *tg = table_of_group[(g0 / kBatch) & 1];
+    uint8_t *sb = &sym_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
+    const uint32_t q0 = (uint32_t)(-ptr) & (kRingWords - 1);
+    uint32_t q = q0;
+    if (tail) {
+      for (int32_t j = 0; j < cnt_groups; ++j)
+        dec_depth_step<true>(xh, e, at, depth_lds, ring, q, sb + kLanes * j,
+                             (uint32_t)__builtin_amdgcn_readfirstlane(tg[j]), low16, j != cnt_groups - 1 || top_active);
+    } else {
+      uint32_t nt[kBatch];
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) nt[j] = (uint32_t)__builtin_amdgcn_readfirstlane(tg[j]);
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) dec_depth_step<false>(xh, e, at, depth_lds, ring, q, sb + kLanes * j, nt[j], low16, true);
+    }
+    ptr -= (int32_t)__builtin_amdgcn_readfirstlane(q - q0);
+    if (ptr < lo) {
+      bad = true;
+      ptr = lo;
+    }
+    if (lane == 0) ptr_pub = ptr;
+    __syncthreads();  // barrier of this batch
+  }
+  // integrity: every word consumed, every lane back at the initial state (x >> 12 as carried, slot 0 in hand)
+  const bool home = xh == (kLow >> kScaleBits) && (at & (kDepthTableBytes - 1)) == 0;
+  if (ptr != lo || (coder && !home)) bad = true;
+  if (bad) raise(a.status, PLC_ERR_CORRUPT);
+}
+
 int check_common(int64_t n_streams, int64_t syms_per_stream, int32_t chunk_syms, RansArgs *a, int *waves) {
   if (n_streams < 1 || syms_per_stream < 1) return PLC_ERR_INVALID;
   if (syms_per_stream >= (1ll << 31) - 1024) return PLC_ERR_INVALID;
@@ -1288,7 +1520,12 @@ struct LaunchDecode {
     // One unit per stream and no more units than the chip has compute-unit halves: time is the length of one
     // unit's chain, so take the variant with the shortest step.  With more units its 60 KB of LDS per
     // wavefront would cost more in occupancy than the shorter step gains.
-    if (a.bits) {
+    if (a.bits && W == 1 && a.n_units <= 512) {
+      const size_t lds = (size_t)a.n_tables * kDepthTableBytes + (size_t)(kRingWords + kRingMirror) * sizeof(uint32_t);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipLaunchKernelGGL(rans_decode_depths_kernel, dim3(grid), dim3(128), lds, st, a);
+    } else if (a.bits) {
       const size_t lds = (size_t)a.n_tables * kScale * sizeof(uint32_t);
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_kernel<W, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
