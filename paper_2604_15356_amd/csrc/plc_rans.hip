@@ -449,9 +449,10 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
 // Encoder for few, long units: three wavefronts per unit
 // ---------------------------------------------------------------------------
 // When there are no more units than compute units, time is the length of one unit's chain of steps,
-// and a lone wavefront issues one vector instruction every ~4.3 cycles and one LDS instruction every
-// ~16.  So everything that is not the state recurrence moves to two helper wavefronts of the same
-// workgroup, which run on other SIMDs of the compute unit:
+// and a lone wavefront issues in order: an independent vector instruction every ~4.3 cycles, one that needs
+// the previous result after ~9, an LDS instruction every 8-16.  So everything that is not the state
+// recurrence moves to two helper wavefronts of the same workgroup, which run on other SIMDs of the compute
+// unit:
 //   feeder  stages the symbols (64 groups ahead, as above) and turns every (group, lane) of the next
 //           batch into its 16-byte table entry at a fixed place of an LDS ring; a lane without a symbol
 //           (ragged top group, or a step past the unit's first group) gets an identity entry;
