@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain elementwise kernel that reads and writes 256 MiB, as the known-size "
                          "reference for scaling HBM byte counters in a profiler run")
-    ap.add_argument("--cpu-streams", type=int, default=64, help="streams the CPU oracle is timed on")
+    ap.add_argument("--cpu-streams", type=int, default=128, help="streams the CPU oracle is timed on")
     ap.add_argument("--also-chunked", type=int, default=4096,
                     help="when the headline run codes whole streams (chunk_syms 0), also time the same workload with "
                          "rANS units of this many symbols and report it beside the headline (0 = skip)")
@@ -99,6 +99,15 @@ class KernelTimer:
     def mean_ms(self):
         return {name: sum(a.elapsed_time(b) for a, b in pairs) / len(pairs) for name, pairs in self.ev.items()}
 
+    def spread_ms(self):
+        """(median, min) of the launch durations of each kernel."""
+        out = {}
+        for name, pairs in self.ev.items():
+            t = sorted(a.elapsed_time(b) for a, b in pairs)
+            mid = len(t) // 2
+            out[name] = (t[mid] if len(t) % 2 else 0.5 * (t[mid - 1] + t[mid]), t[0])
+        return out
+
 
 def measured_traffic(kernel, config_name, k):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when there
@@ -148,10 +157,18 @@ def cpu_baseline(w, n_sample, torch):
     with ThreadPoolExecutor(threads) as ex:
         syms = list(ex.map(one, jobs))
     dt = time.perf_counter() - t0
-    kv_bytes = n_sample * 2 * w.n * w.d * 2
+    n_single = min(4, n_sample)
+    t1 = time.perf_counter()
+    for j in jobs[:n_single]:
+        one(j)
+    dt1 = time.perf_counter() - t1
+    stream_bytes = 2 * w.n * w.d * 2
+    kv_bytes = n_sample * stream_bytes
     return dict(value=kv_bytes / dt / 1e9, unit="GB/s", cores=threads, kind="oracle",
                 sample=f"first {n_sample} of {w.n_streams} streams ({kv_bytes / 1e6:.0f} MB of fp16 KV), "
-                       f"encode+decode, fp64, {dt:.1f} s wall"), np.concatenate(syms, axis=0)
+                       f"encode+decode, fp64, {dt:.1f} s wall",
+                one_thread=dict(value=n_single * stream_bytes / dt1 / 1e9, unit="GB/s", cores=1,
+                                sample=f"first {n_single} streams, {dt1:.1f} s wall")), np.concatenate(syms, axis=0)
 
 
 def main():
@@ -227,9 +244,11 @@ def main():
     alg_bytes = {"predict_residual": (2 * w.k + 3) * E, "reconstruct": (2 * w.k + 3) * E, "histogram": 1.0 * E,
                  "rans_encode": E + word_bytes, "rans_decode": E + word_bytes}
     kernels = {}
+    spread = timer.spread_ms()
     for name, t in ms.items():
         gbs = alg_bytes[name] / (t * 1e-3) / 1e9
-        kernels[name] = dict(ms=round(t, 4), GBs=round(gbs, 1), frac_hbm=round(gbs / HBM_PEAK_GBS, 4))
+        kernels[name] = dict(ms=round(t, 4), median_ms=round(spread[name][0], 4), min_ms=round(spread[name][1], 4),
+                             GBs=round(gbs, 1), frac_hbm=round(gbs / HBM_PEAK_GBS, 4))
         log(f"  {name:18s} {t:9.4f} ms  {gbs:8.1f} GB/s algorithmic  {100 * gbs / HBM_PEAK_GBS:5.1f} % of HBM peak")
     log(f"  step (encode+decode) {ms_per_step:9.4f} ms   kernels sum {sum(ms.values()):.4f} ms")
     dom = kernels["predict_residual"]
@@ -566,7 +585,8 @@ def main():
         result["cpu_baseline"] = base
         got = codec.symbols[:sym64.shape[0]].cpu().numpy()
         result["near_ties_vs_fp64_oracle"] = dict(count=int((got != sym64).sum()), of=int(sym64.size))
-        log(f"  cpu oracle: {base['value']:.4f} GB/s on {base['cores']} threads ({base['sample']})")
+        log(f"  cpu oracle: {base['value']:.4f} GB/s on {base['cores']} threads ({base['sample']}); "
+            f"{base['one_thread']['value']:.4f} GB/s on one thread ({base['one_thread']['sample']})")
     print(json.dumps(result), flush=True)
 
 
