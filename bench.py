@@ -57,6 +57,9 @@ def parse():
     ap.add_argument("--no-linear", action="store_true",
                     help="skip the side measurement of the linear-embedding predictor (two fp16 contractions on the "
                          "matrix cores; Llama-shaped configuration only)")
+    ap.add_argument("--two-call-decode", action="store_true",
+                    help="decode with plc_rans_decode then plc_reconstruct instead of the single call that "
+                         "reconstructs inside the entropy decoder")
     ap.add_argument("--no-prefix-index", action="store_true", help="skip the host-side prefix index measurement")
     ap.add_argument("--adaptive-b0", type=float, default=3.0, help="target average bit depth b0")
     ap.add_argument("--adaptive-range", type=float, default=0.32, help="quantiser range: step = range / 2^depth")
@@ -66,10 +69,13 @@ def parse():
 class KernelTimer:
     """HIP event pairs recorded by libplc around the main kernel of each call."""
 
-    def __init__(self, plc, torch, steps, conditional=False, linear=False):
+    def __init__(self, plc, torch, steps, conditional=False, linear=False, fused=False):
         self.plc, self.ids = plc, {"predict_residual": plc.TRACE_PREDICT, "reconstruct": plc.TRACE_RECONSTRUCT,
                                    "histogram": plc.TRACE_HISTOGRAM, "rans_encode": plc.TRACE_RANS_ENCODE,
                                    "rans_decode": plc.TRACE_RANS_DECODE}
+        if fused:       # one kernel decodes and reconstructs
+            del self.ids["reconstruct"], self.ids["rans_decode"]
+            self.ids["rans_decode_reconstruct"] = plc.TRACE_RANS_DECODE
         if conditional:
             del self.ids["predict_residual"], self.ids["reconstruct"]
             self.ids.update(predict_residual_cond=plc.TRACE_PREDICT_COND, reconstruct_cond=plc.TRACE_RECONSTRUCT_COND)
@@ -197,9 +203,13 @@ def main():
                          cand_stride=w.cand_k.stride()[:5], act_stride=w.act_k.stride()[:4])
     out_k, out_v = torch.empty_like(w.act_k), torch.empty_like(w.act_v)
 
+    fused = not args.two_call_decode
+    # whether the single decode call runs its one-kernel form for this shape (see include/plc.h)
+    one_kernel = fused and args.chunk_syms == 0 and w.k <= 8 and w.n_streams <= 512
+
     def step():
         codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
-        codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+        codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v, fused=fused)
 
     for _ in range(args.warmup):
         step()
@@ -211,7 +221,7 @@ def main():
         torch.add(src, 1, out=dst)      # 256 MiB read + 256 MiB written by one elementwise kernel
         torch.cuda.synchronize()
         del src, dst
-    timer = KernelTimer(plc, torch, args.steps)
+    timer = KernelTimer(plc, torch, args.steps, fused=one_kernel)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -242,7 +252,9 @@ def main():
     ms = timer.mean_ms()
     word_bytes = 2.0 * n_words.sum()
     alg_bytes = {"predict_residual": (2 * w.k + 3) * E, "reconstruct": (2 * w.k + 3) * E, "histogram": 1.0 * E,
-                 "rans_encode": E + word_bytes, "rans_decode": E + word_bytes}
+                 "rans_encode": E + word_bytes, "rans_decode": E + word_bytes,
+                 # words in, symbols out, 2k bytes of candidates in and 2 bytes of KV out per component
+                 "rans_decode_reconstruct": (2 * w.k + 3) * E + word_bytes}
     kernels = {}
     spread = timer.spread_ms()
     for name, t in ms.items():
@@ -264,7 +276,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.config}: S={w.S} L={w.L} H={w.H} d={w.d} n={w.n} k={w.k} delta={w.delta} "
                                f"qmax=127, candidates {args.layout}", "chunk_syms": args.chunk_syms,
-                   "rans_units": codec.n_units},
+                   "rans_units": codec.n_units,
+                   "decode": "one kernel (reconstruction inside the entropy decoder)" if one_kernel else "two kernels"},
         "roofline": roofline,
         "kernels": kernels,
         "coded_bits_per_token": round(total_bits / (w.S * w.n), 1),
@@ -283,7 +296,7 @@ def main():
 
         def step2():
             codec2.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
-            codec2.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+            codec2.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v, fused=fused)
 
         for _ in range(args.warmup):
             step2()
@@ -333,7 +346,7 @@ def main():
                 st, cd, ok_, ov_ = lanes[i % NS]
                 with torch.cuda.stream(st):
                     cd.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
-                    cd.decode(w.cand_k, w.cand_v, w.probs, ok_, ov_)
+                    cd.decode(w.cand_k, w.cand_v, w.probs, ok_, ov_, fused=fused)
             for st, _, _, _ in lanes:
                 torch.cuda.current_stream().wait_stream(st)
 

@@ -126,9 +126,16 @@ class KVDeltaCodec:
         self.rans_encode()
         return self.coded()
 
-    def decode(self, cand_k, cand_v, probs, out_k, out_v):
-        self.rans_decode()
-        self.reconstruct(cand_k, cand_v, probs, out_k, out_v)
+    def decode(self, cand_k, cand_v, probs, out_k, out_v, fused=True):
+        """fused: one call that reconstructs inside the entropy decoder where the shape allows it (the
+        results are the same either way); False makes the two calls one after the other."""
+        if fused:
+            plc.plc_rans_decode_reconstruct(self.dims, self.freq, self.states, self.words, self.word_off,
+                                            self.n_words, self.chunk_syms, cand_k, cand_v, probs, self.esc_vals,
+                                            self.esc_off, self.dec_symbols, out_k, out_v, self.ws, self.status)
+        else:
+            self.rans_decode()
+            self.reconstruct(cand_k, cand_v, probs, out_k, out_v)
 
     # -- linear-embedding predictor ------------------------------------------------------------
     def encode_linear(self, probs_full, embed_t, A, bias_k, bias_v, act_k, act_v) -> Coded:

@@ -17,6 +17,7 @@ constexpr int kTileSyms = kBlock * kChunk;
 constexpr uint32_t kZeroSymbol = 127;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
 // 16-byte load of data that is read once: keep it from displacing cache lines that are reused.
 __device__ __forceinline__ uint4 load16_stream(const void *p) {
@@ -52,6 +53,67 @@ __device__ __forceinline__ void store16_stream(void *p, uint4 a) {
   const u32x4 v = {a.x, a.y, a.z, a.w};
   __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(p));
 }
+
+// One candidate's term of a chunk's prediction: pred[e] = fma(w, cand[e], pred[e]) in fp32.
+__device__ __forceinline__ void accumulate8(float w, uint4 cv, float pred[kChunk]) {
+  const half8 c = __builtin_bit_cast(half8, cv);
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) pred[e] = __builtin_fmaf(w, (float)c[e], pred[e]);
+}
+
+// Dequantised residual added back to the prediction, for the 8 symbols of a chunk (packed low byte
+// first); counts the escapes among them, whose components the caller replaces.
+__device__ __forceinline__ half8 add_back8(uint2 sv, float step, const float pred[kChunk], uint32_t *n_esc) {
+  half8 out;
+#pragma unroll
+  for (int e = 0; e < kChunk; ++e) {
+    const uint32_t sym = ((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u;
+    *n_esc += sym == PLC_ESCAPE;
+    const float qf = (float)((int)sym - (int)kZeroSymbol);
+    float v = __builtin_fmaf(qf, step, pred[e]);
+    // Two roundings are the contract: to fp32 here, then to fp16 (nearest even).  Left to itself the
+    // compiler may merge both into one fused multiply-add with an fp16 result, which rounds once and
+    // lands on the other neighbour when the fp32 value is an exact fp16 tie.
+    asm("" : "+v"(v));
+    out[e] = (_Float16)v;
+  }
+  return out;
+}
+
+// Number of escapes in the lanes below this one, from the per-lane counts 0..8, by bit planes.
+__device__ __forceinline__ uint32_t wave_escape_prefix(uint32_t n_esc, uint32_t *wave_total) {
+  uint32_t prefix = 0, total = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const uint64_t plane = __ballot((n_esc >> b) & 1u);
+    prefix += __builtin_amdgcn_mbcnt_hi((uint32_t)(plane >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)plane, 0u)) << b;
+    total += (uint32_t)__builtin_popcountll(plane) << b;
+  }
+  *wave_total = total;
+  return prefix;
+}
+
+// What a reconstruction that runs inside the entropy decoder (plc_rans.hip) needs to know; filled in by
+// plc_predict.hip, which owns the workspace layout.
+struct ReconView {
+  const uint16_t *cand_k, *cand_v;
+  uint16_t *out_k, *out_v;
+  const float *weights;  // [S, n, k] renormalised
+  int64_t cs[5], as[4];  // element strides of the candidates [S,L,H,n,k] and of the output [S,L,H,n]
+  int32_t L, H, n, k, d8;
+  float delta;
+  const uint16_t *esc_in;   // the escape lists, as for plc_reconstruct
+  uint64_t esc_len;
+  const uint64_t *esc_off;
+};
+// Whether plc_rans.hip has a decoder that reconstructs as it goes for this many streams and candidates.
+bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k);
+// That decoder: plc_rans_decode with one unit per stream, plus out = prediction + symbol * delta for every
+// component, escapes from their lists.  The weights must be in place on `st`.
+int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16_t *words, uint64_t words_len,
+                      const uint64_t *word_off, const uint32_t *n_words, int64_t n_streams,
+                      int64_t syms_per_stream, uint8_t *symbols, const ReconView &recon, uint32_t *status,
+                      hipStream_t st);
 
 // Escape bookkeeping for callers that produce or consume symbols outside the tile-structured kernels
 // (plc_predict.hip): collect the escaped components' raw fp16 values of `act` into the per-stream lists /

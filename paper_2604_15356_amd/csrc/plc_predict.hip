@@ -15,8 +15,6 @@
 namespace plc {
 namespace {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-
 // Escapes of a tile are first parked in a per-tile staging row of this many entries (a tile has 2048
 // symbols; the synthetic workloads escape 0.7 % of them).  A tile with more escapes than that is
 // gathered again from its symbols by the compaction pass.
@@ -87,19 +85,6 @@ __device__ __forceinline__ Coord locate(const CodecArgs &a) {
   return locate_chunk(a, stream, blockIdx.x - stream * a.tiles_per_stream, threadIdx.x);
 }
 
-// Number of escapes in the lanes below this one, from the per-lane counts 0..8, by bit planes.
-__device__ __forceinline__ uint32_t wave_escape_prefix(uint32_t n_esc, uint32_t *wave_total) {
-  uint32_t prefix = 0, total = 0;
-#pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const uint64_t plane = __ballot((n_esc >> b) & 1u);
-    prefix += __builtin_amdgcn_mbcnt_hi((uint32_t)(plane >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)plane, 0u)) << b;
-    total += (uint32_t)__builtin_popcountll(plane) << b;
-  }
-  *wave_total = total;
-  return prefix;
-}
-
 // pred[e] = sum_j w[j] * cand_j[e], fp32 fused multiply-add, j ascending from 0.
 template <int K>
 __device__ __forceinline__ void predict8(const uint16_t *cand, int64_t sj, const float *w, int k,
@@ -114,19 +99,10 @@ __device__ __forceinline__ void predict8(const uint16_t *cand, int64_t sj, const
 #pragma unroll
     for (int j = 0; j < K; ++j) wv[j] = w[j];
 #pragma unroll
-    for (int j = 0; j < K; ++j) {
-      const half8 c = __builtin_bit_cast(half8, cv[j]);
-#pragma unroll
-      for (int e = 0; e < kChunk; ++e) pred[e] = __builtin_fmaf(wv[j], (float)c[e], pred[e]);
-    }
+    for (int j = 0; j < K; ++j) accumulate8(wv[j], cv[j], pred);
   } else {
 #pragma unroll 4
-    for (int j = 0; j < k; ++j) {
-      const half8 c = __builtin_bit_cast(half8, load16_stream(cand + j * sj));
-      const float wj = w[j];
-#pragma unroll
-      for (int e = 0; e < kChunk; ++e) pred[e] = __builtin_fmaf(wj, (float)c[e], pred[e]);
-    }
+    for (int j = 0; j < k; ++j) accumulate8(w[j], load16_stream(cand + j * sj), pred);
   }
 }
 
@@ -459,18 +435,7 @@ __global__ __launch_bounds__(kBlock) void reconstruct_kernel(const CodecArgs a) 
     float pred[kChunk];
     predict_chunk<K, COND>(a, q, cand, pred);
     const float step = COND ? position_step(a, q.row) : a.delta;
-#pragma unroll
-    for (int e = 0; e < kChunk; ++e) {
-      const uint32_t sym = ((e < 4 ? sv.x : sv.y) >> (8 * (e & 3))) & 255u;
-      n_esc += sym == PLC_ESCAPE;
-      const float qf = (float)((int)sym - (int)kZeroSymbol);
-      float v = __builtin_fmaf(qf, step, pred[e]);
-      // Two roundings are the contract: to fp32 here, then to fp16 (nearest even).  Left to itself the
-      // compiler may merge both into one fused multiply-add with an fp16 result, which rounds once and
-      // lands on the other neighbour when the fp32 value is an exact fp16 tie.
-      asm("" : "+v"(v));
-      out[e] = (_Float16)v;
-    }
+    out = add_back8(sv, step, pred, &n_esc);
   }
   if (tile_has_escapes) {
     uint32_t total;
@@ -837,6 +802,58 @@ extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const v
                                uint32_t *status, void *stream) {
   return decode_floats(dims, cand_k, cand_v, probs, nullptr, nullptr, 0.0f, PLC_TRACE_RECONSTRUCT, symbols, esc_vals, esc_len,
                        esc_off, out_k, out_v, ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
+                                           const uint16_t *words, uint64_t words_len, const uint64_t *word_off,
+                                           const uint32_t *n_words, int32_t chunk_syms, const void *cand_k,
+                                           const void *cand_v, const float *probs, const uint16_t *esc_vals,
+                                           uint64_t esc_len, const uint64_t *esc_off, uint8_t *symbols,
+                                           void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
+                                           void *stream) {
+  Plan p;
+  if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  if (chunk_syms != 0 || !decode_fused_supported(p.n_streams, p.syms_per_stream, dims->k)) {
+    const int rc = plc_rans_decode(freq, states, words, words_len, word_off, n_words, p.n_streams,
+                                   p.syms_per_stream, chunk_syms, symbols, status, stream);
+    if (rc) return rc;
+    return plc_reconstruct(dims, cand_k, cand_v, probs, symbols, esc_vals, esc_len, esc_off, out_k, out_v, ws,
+                           ws_bytes, status, stream);
+  }
+  if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(out_k, 16) || !aligned(out_v, 16))
+    return PLC_ERR_INVALID;
+  if (!aligned(symbols, 8) || !aligned(probs, 4) || !aligned(esc_off, 8)) return PLC_ERR_INVALID;
+  if (!aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total) return PLC_ERR_INVALID;
+  if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  CodecArgs a = {};
+  fill_args(dims, p, ws, &a);
+  a.out_k = static_cast<uint16_t *>(out_k);
+  a.out_v = static_cast<uint16_t *>(out_v);
+  a.symbols = symbols;
+  a.esc_in = esc_vals;
+  a.esc_len = esc_len;
+  a.esc_off = esc_off;
+  a.status = status;
+  ReconView r = {};
+  r.cand_k = static_cast<const uint16_t *>(cand_k);
+  r.cand_v = static_cast<const uint16_t *>(cand_v);
+  r.out_k = a.out_k;
+  r.out_v = a.out_v;
+  r.weights = a.weights;
+  for (int i = 0; i < 5; ++i) r.cs[i] = a.cs[i];
+  for (int i = 0; i < 4; ++i) r.as[i] = a.as[i];
+  r.L = a.L, r.H = a.H, r.n = a.n, r.k = a.k, r.d8 = a.d8;
+  r.delta = a.delta;
+  r.esc_in = esc_vals;
+  r.esc_len = esc_len;
+  r.esc_off = esc_off;
+
+  hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
+                     const_cast<float *>(a.weights), p.rows, dims->k, status);
+  return rans_decode_fused(freq, states, words, words_len, word_off, n_words, p.n_streams, p.syms_per_stream,
+                           symbols, r, status, st);
 }
 
 extern "C" int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,

@@ -54,6 +54,8 @@ struct RansArgs {
   // one table per bit depth (the *_bucketed calls): symbol t of a stream uses table bits[...] - 1 of its position
   const uint8_t *bits;
   int32_t syms_per_pos, streams_per_session, n_tables;
+  // reconstruction inside the decoder (rans_decode_chain_kernel with candidates)
+  ReconView recon;
 };
 
 // Offset (in table entries of `stride` each) of the table that the 32 symbols from unit-relative group g on use.
@@ -1074,14 +1076,31 @@ __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uin
 //            barrier b - 1 (a batch consumes at most 512, so batch b + 1 finds its words); barrier b;
 //            then moves the symbols of batch b out while batch b + 1 runs.
 // The blocks the helper writes lie at least one block below those the running batch reads, and the ring
-// slots they take belonged to blocks above the pointer.
-__global__ __launch_bounds__(128) void rans_decode_chain_kernel(const RansArgs a) {
+// slots they take belonged to blocks above the pointer (four blocks of ring: the pointer's block and the
+// three below it).
+//
+// RK > 0 adds a third wavefront that reconstructs the KV components of each batch from its symbols while
+// the next batches are decoded: out = prediction over RK candidates + symbol * step (the arithmetic of
+// plc_reconstruct).  A batch is 512 symbols = 64 chunks of 8 components, one chunk per lane.  The
+// candidates and weights of a chunk do not depend on its symbols, so they are requested kRecDepth batches
+// ahead and are in registers when the symbols arrive; the wavefront joins the batch barrier through the
+// bare instruction, which unlike __syncthreads does not first wait for its outstanding loads.  Loads are
+// issued by every lane in every batch (past the end of the stream: chunk 0 again, nothing stored), so
+// that the number of loads behind any given one is the same on every path and the wait before a use
+// leaves the later requests in flight (the few loads and stores that escapes add are issued only where
+// there are escapes and cost at most their own number in that count).
+constexpr int kRecDepth = 3;
+
+template <int RK>
+__global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const RansArgs a) {
   __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing2Entries];  // slot table, then the ring
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
   __shared__ uint32_t fc[256];
   __shared__ int32_t ptr_pub;
+  constexpr int kThreads = RK ? 192 : 128;
   const int lane = threadIdx.x & 63;
-  const bool helper = threadIdx.x >= 64;  // uniform per wavefront
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const bool helper = wave == 1;
   const int64_t stream = blockIdx.x / a.wgs_per_stream;
   const int64_t chunk = blockIdx.x - stream * a.wgs_per_stream;
   bool bad = false;
@@ -1093,7 +1112,7 @@ __global__ __launch_bounds__(128) void rans_decode_chain_kernel(const RansArgs a
       if (threadIdx.x == 0) raise(a.status, PLC_ERR_CORRUPT);
       return;
     }
-    if (!helper) {
+    if (wave == 0) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         fc[lane * 4 + r] = f[r] | (cum << 16);
@@ -1104,7 +1123,7 @@ __global__ __launch_bounds__(128) void rans_decode_chain_kernel(const RansArgs a
     for (int s = 0; s < 256; ++s) {
       const uint32_t v = fc[s];
       const uint32_t fs = v & 0xffffu, cs = v >> 16;
-      for (uint32_t o = threadIdx.x; o < fs; o += 128) tab[cs + o] = make_uint2(fs | ((uint32_t)s << 24), o);
+      for (uint32_t o = threadIdx.x; o < fs; o += kThreads) tab[cs + o] = make_uint2(fs | ((uint32_t)s << 24), o);
     }
     __syncthreads();
   }
@@ -1134,6 +1153,185 @@ __global__ __launch_bounds__(128) void rans_decode_chain_kernel(const RansArgs a
   int32_t tail_groups = G % kBatch;
   if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
   const int32_t g_tail = G - tail_groups;
+
+  if constexpr (RK > 0) {
+    if (wave == 2) {
+      const ReconView &r = a.recon;
+      const uint32_t lh = (uint32_t)(r.L * r.H);
+      const uint32_t s = (uint32_t)stream / lh, rem = (uint32_t)stream - s * lh;
+      const uint32_t l = rem / (uint32_t)r.H, h = rem - l * (uint32_t)r.H;
+      const int64_t cand0 = s * r.cs[0] + l * r.cs[1] + h * r.cs[2];
+      const int64_t out0 = s * r.as[0] + l * r.as[1] + h * r.as[2];
+      const float *w0 = r.weights + (int64_t)s * r.n * r.k;
+      const uint32_t n_chunks = len / kChunk;
+      const uint32_t d8 = (uint32_t)r.d8, adv_row = 64u / d8, adv_e8 = 64u - adv_row * d8;
+      // The chunk this lane requests next: row = position * 2 + (0 = K, 1 = V), e8 = chunk inside the row,
+      // and where its candidates, weights and output are.  From batch to batch a lane moves on by 64
+      // chunks; where that is a whole, even number of rows (d = 8, 16, ... 256) it is the same position
+      // step in the same half every time, and the three pointers advance by constants.
+      uint32_t chunk = (uint32_t)lane, row = (uint32_t)lane / d8, e8 = (uint32_t)lane - row * d8;
+      const bool steady = adv_e8 == 0u && (adv_row & 1u) == 0u;
+      const int64_t cand_step = (int64_t)(adv_row / 2u) * r.cs[3], out_step = (int64_t)(adv_row / 2u) * r.as[3];
+      const uint32_t w_step = (adv_row / 2u) * (uint32_t)RK;
+      const uint16_t *cand_p;
+      const float *w_p;
+      uint16_t *out_p;
+      auto point = [&](uint32_t rr, uint32_t ee) {
+        const uint32_t i = rr >> 1;
+        cand_p = ((rr & 1u) ? r.cand_v : r.cand_k) + cand0 + (int64_t)i * r.cs[3] + ee * kChunk;
+        w_p = w0 + (int64_t)i * RK;
+        out_p = ((rr & 1u) ? r.out_v : r.out_k) + out0 + (int64_t)i * r.as[3] + ee * kChunk;
+      };
+      if (chunk < n_chunks) {
+        point(row, e8);
+      } else {
+        point(0u, 0u);
+      }
+      uint4 cv[kRecDepth][RK];
+      float wv[kRecDepth][RK];
+      typedef __attribute__((address_space(1))) u32x4 *global_u32x4;  // named global: kept through the loop
+      typedef __attribute__((address_space(1))) uint16_t *global_u16;
+      global_u32x4 dst[kRecDepth];
+      bool live[kRecDepth];  // whether the lane's chunk exists (a flag of its own: the pointer stays a global one)
+      // Escapes.  This wavefront sees every chunk of the stream in order, so the number of escapes in front
+      // of a chunk is a running count plus a prefix over the lanes.  The raw values are requested from the
+      // stream's list when the chunk is stored and written over its escaped components the next time the
+      // same registers come round, kRecDepth batches later (memory operations of a wavefront complete in
+      // the order of issue, so by the time a value has arrived the chunk's own store has landed).
+      uint32_t esc_bits[kRecDepth];  // which components of the chunk at esc_dst await their raw value
+      uint32_t esc_raw[kRecDepth][kChunk];
+      global_u32x4 esc_dst[kRecDepth];
+      const uint64_t esc_base = r.esc_off[stream];
+      uint32_t esc_seen = 0;  // escapes of the stream so far
+#pragma unroll
+      for (int j = 0; j < kRecDepth; ++j) esc_bits[j] = 0u, esc_dst[j] = nullptr;
+      // Loads of the lane's next chunk (of chunk 0 again once the stream is at its end, so that every
+      // batch issues the same loads), then on to the chunk after it.
+      auto request = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok) {
+#pragma unroll
+        for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + j * r.cs[4]);
+        if constexpr (RK % 4 == 0) {
+#pragma unroll
+          for (int j = 0; j < RK; j += 4) {
+            const float4 t = *reinterpret_cast<const float4 *>(w_p + j);
+            w[j] = t.x, w[j + 1] = t.y, w[j + 2] = t.z, w[j + 3] = t.w;
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < RK; ++j) w[j] = w_p[j];
+        }
+        out = (global_u32x4)out_p;
+        ok = chunk < n_chunks;
+        chunk += 64u;
+        if (steady) {  // uniform
+          if (chunk < n_chunks) cand_p += cand_step, w_p += w_step, out_p += out_step;
+        } else {
+          row += adv_row;
+          e8 += adv_e8;
+          if (e8 >= d8) {
+            e8 -= d8;
+            ++row;
+          }
+          if (chunk < n_chunks) point(row, e8);
+        }
+      };
+      // the raw values that have arrived for the chunk at `out`: over its escaped components, lowest first
+      auto patch = [&](global_u32x4 out, uint32_t &bits, const uint32_t (&raw)[kChunk]) {
+        if (__ballot(bits != 0u) == 0) return;  // uniform
+        global_u16 comp = (global_u16)out;
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+          if (i > 0 && __ballot(bits != 0u) == 0) break;  // uniform; seldom more than one per chunk
+          if (bits) {
+            const int e = __builtin_ctz(bits);
+            bits &= bits - 1u;
+            comp[e] = (uint16_t)raw[i];
+          }
+        }
+      };
+#pragma unroll
+      for (int j = 0; j < kRecDepth; ++j) request(cv[j], wv[j], dst[j], live[j]);
+      asm volatile("" ::: "memory");
+      __builtin_amdgcn_s_barrier();  // barrier "start"
+      asm volatile("" ::: "memory");
+      const int32_t n_batches = (G + kBatch - 1) / kBatch;
+      const int32_t n_full = (int32_t)(n_chunks / 64u);  // batches all of whose chunks exist
+      // One batch: join its barrier, take its symbols from the stage, finish the chunk, request the chunk
+      // of the batch kRecDepth later into the registers just freed.
+      auto turn = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, uint32_t &bits,
+                      uint32_t(&raw)[kChunk], global_u32x4 &late, int32_t b, bool whole) {
+        // (the scheduler would otherwise start on the predictions of all kRecDepth batches at the top of a
+        // pass, and so wait there for requests that have only just gone out)
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();  // barrier of batch b: its symbols are in the stage
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        const uint2 sv = *reinterpret_cast<const uint2 *>(&sym_stage[b & 1][lane * kChunk]);
+        patch(late, bits, raw);
+        float pred[kChunk];
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) pred[e] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < RK; ++j) accumulate8(w[j], c[j], pred);
+        uint32_t unused = 0;
+        const half8 v = add_back8(sv, r.delta, pred, &unused);
+        const bool mine = whole || ok;
+        if (mine) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), out);
+        // a byte is 0xff iff its low seven bits carry into bit 7 when 1 is added and bit 7 is set
+        const uint32_t hx = ((sv.x & 0x7f7f7f7fu) + 0x01010101u) & sv.x & 0x80808080u;
+        const uint32_t hy = ((sv.y & 0x7f7f7f7fu) + 0x01010101u) & sv.y & 0x80808080u;
+        const bool has = mine && (hx | hy) != 0u;
+        const uint64_t lanes = __ballot(has);
+        if (lanes != 0) {  // uniform
+          // bit 7 of byte e to bit e
+          const uint32_t mx = ((hx >> 7) * 0x00204081u) >> 21 & 0xfu, my = ((hy >> 7) * 0x00204081u) >> 21 & 0xfu;
+          bits = has ? (mx | (my << 4)) : 0u;
+          late = out;
+          const uint32_t n_esc = (uint32_t)__builtin_popcount(bits);
+          const bool several = __ballot(n_esc > 1u) != 0;  // uniform; seldom
+          uint32_t total, before;
+          if (!several) {
+            before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lanes >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lanes, 0u));
+            total = (uint32_t)__builtin_popcountll(lanes);
+          } else {
+            before = wave_escape_prefix(n_esc, &total);
+          }
+          const uint64_t src = esc_base + esc_seen + before;
+          esc_seen += total;
+#pragma unroll
+          for (int i = 0; i < kChunk; ++i) {
+            if (i > 0 && (!several || __ballot(n_esc > (uint32_t)i) == 0)) break;  // uniform
+            if (n_esc > (uint32_t)i) {
+              if (src + i < r.esc_len) {
+                raw[i] = r.esc_in[src + i];
+              } else {
+                raise(a.status, PLC_ERR_CORRUPT);
+                raw[i] = 0u;
+              }
+            }
+          }
+        }
+        request(c, w, out, ok);
+      };
+      // Whole batches, kRecDepth at a time and free of branches: every pass issues the same loads and
+      // stores in the same order.
+      int32_t b0 = 0;
+      for (; b0 + kRecDepth <= n_full; b0 += kRecDepth) {
+#pragma unroll
+        for (int j = 0; j < kRecDepth; ++j)
+          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], b0 + j, true);
+      }
+      // What is left: fewer than kRecDepth whole batches and possibly a partial one.
+#pragma unroll
+      for (int j = 0; j < kRecDepth; ++j)
+        if (b0 + j < n_batches)  // uniform
+          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], b0 + j, false);
+#pragma unroll
+      for (int j = 0; j < kRecDepth; ++j) patch(esc_dst[j], esc_bits[j], esc_raw[j]);
+      return;
+    }
+  }
 
   if (helper) {
     // one 16-byte piece (eight words) of block blk per lane, if the piece holds a word of this unit
@@ -1166,23 +1364,41 @@ __global__ __launch_bounds__(128) void rans_decode_chain_kernel(const RansArgs a
         }
       }
     };
-    // stages every block that holds a word at or above `down_to` and is not staged yet
-    int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already staged (none yet)
-    auto stage_down_to = [&](int32_t down_to) {
+    // Stages every block that holds a word at or above `down_to` and is not staged yet.  The last of them
+    // may be left on its way (`ahead`): its words go to the ring at the next call, a batch later, so that
+    // the wavefront does not sit out the load's latency in front of the barrier.
+    int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already requested (none yet)
+    uint4 ahead_v;
+    int32_t ahead_blk = 0;
+    bool ahead = false, ahead_take = false;
+    auto stage_down_to = [&](int32_t down_to, bool leave_one) {
+      if (ahead) {  // uniform
+        block_store(ahead_blk, ahead_take, ahead_v);
+        ahead = false;
+      }
       const int32_t last = down_to > 0 ? down_to >> 9 : 0;
-      while (lowest > last) {  // uniform; at most two rounds after the first call
-        uint4 v;
+      while (lowest > last) {  // uniform; one round per batch after the first call
         const int32_t blk = lowest - 1;
-        const bool take = block_load(blk, v);
-        block_store(blk, take, v);
         lowest = blk;
+        if (leave_one && blk == last) {
+          ahead_take = block_load(blk, ahead_v);
+          ahead_blk = blk;
+          ahead = true;
+        } else {
+          uint4 v;
+          const bool take = block_load(blk, v);
+          block_store(blk, take, v);
+        }
       }
     };
-    stage_down_to(hi - 2 * kBlockWords);  // the words of the first two batches
-    __syncthreads();                      // barrier "start"
+    // A batch consumes at most one block of words.  While batch b runs, the pointer p_b it started from is
+    // known here: the words down to p_b - 3 blocks are requested and those down to p_(b-1) - 3 blocks, at
+    // or below p_b - 2 blocks, are in the ring -- batch b + 1 reads no further down than that.
+    stage_down_to(hi - 3 * kBlockWords, false);
+    __syncthreads();  // barrier "start"
     int32_t ptr_before = hi;  // the pointer as it stood before the batch now running
     for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
-      stage_down_to(ptr_before - 2 * kBlockWords);
+      stage_down_to(ptr_before - 3 * kBlockWords, true);
       __syncthreads();  // barrier of this batch: its symbols are in the stage, the pointer is published
       ptr_before = ptr_pub;  // read at once: the decoder writes it again only at the end of its next batch
       const bool tail = g0 >= g_tail;
@@ -1532,7 +1748,7 @@ struct LaunchDecode {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipLaunchKernelGGL((rans_decode_kernel<W, true>), dim3(grid), dim3(W * 64), lds, st, a);
     } else if (W == 1 && a.n_units <= 512) {
-      hipLaunchKernelGGL(rans_decode_chain_kernel, dim3(grid), dim3(128), 0, st, a);
+      hipLaunchKernelGGL(rans_decode_chain_kernel<0>, dim3(grid), dim3(128), 0, st, a);
     } else {
       // Many units: LDS decides how many wavefronts fit a compute unit, and the split table lets more in
       // (twice as many where every one-wavefront workgroup has a table of its own).
@@ -1629,6 +1845,53 @@ int decode_impl(const uint16_t *freq, const uint32_t *states, const uint16_t *wo
 }
 
 }  // namespace
+
+bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k) {
+  // the chain decoder's own condition (no more units than compute-unit halves), candidates that fit the
+  // registers of one wavefront kRecDepth batches deep, and whole chunks
+  return n_streams >= 1 && n_streams <= 512 && k >= 1 && k <= 8 && syms_per_stream >= kChunk &&
+         syms_per_stream % kChunk == 0;
+}
+
+int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16_t *words, uint64_t words_len,
+                      const uint64_t *word_off, const uint32_t *n_words, int64_t n_streams,
+                      int64_t syms_per_stream, uint8_t *symbols, const ReconView &recon, uint32_t *status,
+                      hipStream_t st) {
+  RansArgs a = {};
+  int waves = 1;
+  const int rc = check_common(n_streams, syms_per_stream, 0, &a, &waves);
+  if (rc) return rc;
+  if (!decode_fused_supported(n_streams, syms_per_stream, recon.k)) return PLC_ERR_INVALID;
+  if (!symbols || !freq || !states || !word_off || !n_words || !status) return PLC_ERR_INVALID;
+  if (words_len > 0 && !words) return PLC_ERR_INVALID;
+  if (reinterpret_cast<uintptr_t>(freq) % 8 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
+  if ((int64_t)recon.L * recon.H < 1 || n_streams % ((int64_t)recon.L * recon.H)) return PLC_ERR_INVALID;
+  if (syms_per_stream != 2ll * recon.n * recon.d8 * kChunk) return PLC_ERR_INVALID;
+  a.sym_out = symbols;
+  a.freq = freq;
+  a.states_in = states;
+  a.words_in = words;
+  a.words_len = words_len;
+  a.word_off = word_off;
+  a.n_words_in = n_words;
+  a.status = status;
+  a.recon = recon;
+  {
+    TraceScope trace(PLC_TRACE_RANS_DECODE, st);
+    const dim3 grid((unsigned)n_streams), block(192);
+    switch (recon.k) {
+#define PLC_CASE(K) \
+  case K:           \
+    hipLaunchKernelGGL(rans_decode_chain_kernel<K>, grid, block, 0, st, a); \
+    break;
+      PLC_CASE(1) PLC_CASE(2) PLC_CASE(3) PLC_CASE(4) PLC_CASE(5) PLC_CASE(6) PLC_CASE(7) PLC_CASE(8)
+#undef PLC_CASE
+      default: return PLC_ERR_INVALID;
+    }
+  }
+  return launch_status();
+}
+
 }  // namespace plc
 
 extern "C" int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stream,

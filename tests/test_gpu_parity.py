@@ -105,6 +105,14 @@ def test_encode_decode_matches_oracle(oracle, dev, case):
     rk32, rv32 = O.reconstruct(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v),
                                w.probs.cpu().numpy(), sym, ref32["esc_vals"], ref32["esc_off"], mode=O.F32)
     assert np.array_equal(u16(out_k).ravel(), rk32) and np.array_equal(u16(out_v).ravel(), rv32)
+    # decode() is the single call that reconstructs inside the entropy decoder where the shape allows it;
+    # the two calls one after the other must give the same bits
+    two_k, two_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.dec_symbols.zero_()
+    codec.decode(w.cand_k, w.cand_v, w.probs, two_k, two_v, fused=False)
+    codec.check_status("decode in two calls")
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    assert np.array_equal(u16(two_k), u16(out_k)) and np.array_equal(u16(two_v), u16(out_v))
     rk64, rv64 = O.reconstruct(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v),
                                w.probs.cpu().numpy(), sym, ref32["esc_vals"], ref32["esc_off"], mode=O.F64)
     for got, want in ((u16(out_k).ravel(), rk64), (u16(out_v).ravel(), rv64)):
@@ -330,9 +338,26 @@ def test_data_dependent_errors_are_reported_not_fatal(oracle, dev):
     with pytest.raises(plc.PlcError) as e:
         codec.check_status()
     assert e.value.code == plc.PLC_ERR_CORRUPT
+    # the same damage through the single decode call, whose reconstructing wavefront must still meet the
+    # others at every barrier
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+    with pytest.raises(plc.PlcError) as e:
+        codec.check_status()
+    assert e.value.code == plc.PLC_ERR_CORRUPT
     # a word count that points outside the buffer is refused
     codec.n_words[1] = 2 ** 31 - 1
     codec.rans_decode()
+    with pytest.raises(plc.PlcError) as e:
+        codec.check_status()
+    assert e.value.code == plc.PLC_ERR_CORRUPT
+    codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
+    with pytest.raises(plc.PlcError) as e:
+        codec.check_status()
+    assert e.value.code == plc.PLC_ERR_CORRUPT
+    # a table that does not sum to 2^12 is refused as well
+    codec.freq[0, 3] += 1
+    codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
     with pytest.raises(plc.PlcError) as e:
         codec.check_status()
     assert e.value.code == plc.PLC_ERR_CORRUPT
