@@ -109,11 +109,12 @@ struct ReconView {
 // Whether plc_rans.hip has a decoder that reconstructs as it goes for this many streams and candidates.
 bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k);
 // That decoder: plc_rans_decode with one unit per stream, plus out = prediction + symbol * delta for every
-// component, escapes from their lists.  The weights must be in place on `st`.
+// component, escapes from their lists.  The weights must be in place on `st`.  With launch = false the
+// arguments are checked and nothing is enqueued.
 int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16_t *words, uint64_t words_len,
                       const uint64_t *word_off, const uint32_t *n_words, int64_t n_streams,
                       int64_t syms_per_stream, uint8_t *symbols, const ReconView &recon, uint32_t *status,
-                      hipStream_t st);
+                      hipStream_t st, bool launch);
 
 // Escape bookkeeping for callers that produce or consume symbols outside the tile-structured kernels
 // (plc_predict.hip): collect the escaped components' raw fp16 values of `act` into the per-stream lists /

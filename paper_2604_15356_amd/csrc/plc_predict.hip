@@ -813,6 +813,12 @@ extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t 
                                            void *stream) {
   Plan p;
   if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  // the checks of plc_reconstruct first, so that a refusal leaves nothing enqueued
+  if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(out_k, 16) || !aligned(out_v, 16))
+    return PLC_ERR_INVALID;
+  if (!aligned(symbols, 8) || !aligned(probs, 4) || !aligned(esc_off, 8)) return PLC_ERR_INVALID;
+  if (!aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total) return PLC_ERR_INVALID;
+  if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
   if (chunk_syms != 0 || !decode_fused_supported(p.n_streams, p.syms_per_stream, dims->k)) {
     const int rc = plc_rans_decode(freq, states, words, words_len, word_off, n_words, p.n_streams,
                                    p.syms_per_stream, chunk_syms, symbols, status, stream);
@@ -820,11 +826,6 @@ extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t 
     return plc_reconstruct(dims, cand_k, cand_v, probs, symbols, esc_vals, esc_len, esc_off, out_k, out_v, ws,
                            ws_bytes, status, stream);
   }
-  if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(out_k, 16) || !aligned(out_v, 16))
-    return PLC_ERR_INVALID;
-  if (!aligned(symbols, 8) || !aligned(probs, 4) || !aligned(esc_off, 8)) return PLC_ERR_INVALID;
-  if (!aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total) return PLC_ERR_INVALID;
-  if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   CodecArgs a = {};
@@ -850,10 +851,13 @@ extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t 
   r.esc_len = esc_len;
   r.esc_off = esc_off;
 
+  const int rc = rans_decode_fused(freq, states, words, words_len, word_off, n_words, p.n_streams,
+                                   p.syms_per_stream, symbols, r, status, st, false);
+  if (rc) return rc;  // nothing enqueued
   hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
                      const_cast<float *>(a.weights), p.rows, dims->k, status);
   return rans_decode_fused(freq, states, words, words_len, word_off, n_words, p.n_streams, p.syms_per_stream,
-                           symbols, r, status, st);
+                           symbols, r, status, st, true);
 }
 
 extern "C" int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,

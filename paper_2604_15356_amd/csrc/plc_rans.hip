@@ -1856,7 +1856,7 @@ bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k) {
 int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16_t *words, uint64_t words_len,
                       const uint64_t *word_off, const uint32_t *n_words, int64_t n_streams,
                       int64_t syms_per_stream, uint8_t *symbols, const ReconView &recon, uint32_t *status,
-                      hipStream_t st) {
+                      hipStream_t st, bool launch) {
   RansArgs a = {};
   int waves = 1;
   const int rc = check_common(n_streams, syms_per_stream, 0, &a, &waves);
@@ -1867,6 +1867,7 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
   if (reinterpret_cast<uintptr_t>(freq) % 8 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
   if ((int64_t)recon.L * recon.H < 1 || n_streams % ((int64_t)recon.L * recon.H)) return PLC_ERR_INVALID;
   if (syms_per_stream != 2ll * recon.n * recon.d8 * kChunk) return PLC_ERR_INVALID;
+  if (!launch) return PLC_OK;
   a.sym_out = symbols;
   a.freq = freq;
   a.states_in = states;

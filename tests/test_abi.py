@@ -74,6 +74,17 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert L.plc_rans_encode(p, 1, 100, -32, p, p, p, p, 100, p, p, None) == 1
     assert L.plc_rans_decode(p, p, p, 10, p, p, 1, 0, 0, p, p, None) == 1
     assert L.plc_rans_decode(p, p, p, 10, p, p, 1, 1 << 31, 0, p, p, None) == 1
+    # the single decode call: its own checks, and those of the two calls it stands for
+    dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
+    dec = L.plc_rans_decode_reconstruct
+    assert dec(C.byref(dm), p, p, p, 10, p, p, 0, odd, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert dec(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, p, 0, p, p, p, odd, p, 1 << 20, p, None) == 1
+    assert dec(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, p, 0, p, p, p, p, p, 16, p, None) == 1       # ws too small
+    assert dec(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, C.c_void_p(4097), 8, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert dec(C.byref(dm), p, p, p, 10, p, p, 48, p, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1  # chunk not a multiple of 32
+    assert dec(C.byref(dm), None, p, p, 10, p, p, 0, p, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    bad = plc.make_dims(1, 2, 2, 16, 0, 64, 0.02)
+    assert dec(C.byref(bad), p, p, p, 10, p, p, 0, p, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
     # token-conditional calls
     dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
     odd4 = C.c_void_p(4098)
