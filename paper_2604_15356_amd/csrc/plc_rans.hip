@@ -1603,15 +1603,29 @@ __global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs 
         }
       }
     };
-    int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already staged (none yet)
-    auto stage_down_to = [&](int32_t down_to) {
+    // as in the kernel above: the newest block stays on its way for a batch
+    int32_t lowest = ((hi - 1) >> 9) + 1;  // lowest block already requested (none yet)
+    uint4 ahead_v;
+    int32_t ahead_blk = 0;
+    bool ahead = false, ahead_take = false;
+    auto stage_down_to = [&](int32_t down_to, bool leave_one) {
+      if (ahead) {  // uniform
+        block_store(ahead_blk, ahead_take, ahead_v);
+        ahead = false;
+      }
       const int32_t last = down_to > 0 ? down_to >> 9 : 0;
       while (lowest > last) {
-        uint4 v;
         const int32_t blk = lowest - 1;
-        const bool take = block_load(blk, v);
-        block_store(blk, take, v);
         lowest = blk;
+        if (leave_one && blk == last) {
+          ahead_take = block_load(blk, ahead_v);
+          ahead_blk = blk;
+          ahead = true;
+        } else {
+          uint4 v;
+          const bool take = block_load(blk, v);
+          block_store(blk, take, v);
+        }
       }
     };
     // tables of groups g0 + 1 .. g0 + 16 (past the last group: the first table, whose entry is never used)
@@ -1621,13 +1635,13 @@ __global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs 
         table_of_group[buf][lane] = g < G ? group_table(a, stream, begin, g, kDepthTableBytes, &bad_depth) : 0u;
       }
     };
-    stage_down_to(hi - 2 * kBlockWords);
+    stage_down_to(hi - 3 * kBlockWords, false);
     if (lane == 0) first_table = group_table(a, stream, begin, 0, kDepthTableBytes, &bad_depth);
     tables_for(0, 0);
     __syncthreads();  // barrier "start"
     int32_t ptr_before = hi;
     for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
-      stage_down_to(ptr_before - 2 * kBlockWords);
+      stage_down_to(ptr_before - 3 * kBlockWords, true);
       tables_for(g0 + kBatch, ((g0 / kBatch) + 1) & 1);
       __syncthreads();  // barrier of this batch
       ptr_before = ptr_pub;
