@@ -42,6 +42,10 @@ CASES = {
     "escape_heavy_ragged": ("tiny", dict(L=1, H=3, n=37, k=5, d=24, sigma=2.0, seed=19), "lnkhd", True),
     # k = 20 with positions whose true vector is none of the candidates
     "k20_with_misses": ("miss20", dict(L=1, H=2, n=300, seed=20), "lhnkd", False),
+    # rows longer than a batch of the decoder that reconstructs (64 chunks), and as long as one
+    "wide_rows_d1024_k3": ("tiny", dict(L=1, H=2, n=9, k=3, d=1024, seed=21), "lhnkd", True),
+    "rows_of_a_batch_d512_k7": ("tiny", dict(L=1, H=1, n=33, k=7, d=512, seed=22), "lnkhd", True),
+    "two_sessions_k6": ("tiny", dict(S=2, L=3, H=1, n=130, k=6, d=64, sigma=0.5, seed=23), "lhnkd", True),
 }
 
 
