@@ -1085,7 +1085,8 @@ __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uin
 // candidates and weights of a chunk do not depend on its symbols, so they are requested kRecDepth batches
 // ahead and are in registers when the symbols arrive; the wavefront joins the batch barrier through the
 // bare instruction, which unlike __syncthreads does not first wait for its outstanding loads.  Loads are
-// issued by every lane in every batch (past the end of the stream: chunk 0 again, nothing stored), so
+// issued by every lane in every batch (past the end of the stream a lane stays on its last chunk and
+// stores nothing), so
 // that the number of loads behind any given one is the same on every path and the wait before a use
 // leaves the later requests in flight (the few loads and stores that escapes add are issued only where
 // there are escapes and cost at most their own number in that count).
@@ -1169,7 +1170,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
       // and where its candidates, weights and output are.  From batch to batch a lane moves on by 64
       // chunks; where that is a whole, even number of rows (d = 8, 16, ... 256) it is the same position
       // step in the same half every time, and the three pointers advance by constants.
-      uint32_t chunk = (uint32_t)lane, row = (uint32_t)lane / d8, e8 = (uint32_t)lane - row * d8;
+      uint32_t at_chunk = (uint32_t)lane, row = (uint32_t)lane / d8, e8 = (uint32_t)lane - row * d8;
       const bool steady = adv_e8 == 0u && (adv_row & 1u) == 0u;
       const int64_t cand_step = (int64_t)(adv_row / 2u) * r.cs[3], out_step = (int64_t)(adv_row / 2u) * r.as[3];
       const uint32_t w_step = (adv_row / 2u) * (uint32_t)RK;
@@ -1182,7 +1183,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
         w_p = w0 + (int64_t)i * RK;
         out_p = ((rr & 1u) ? r.out_v : r.out_k) + out0 + (int64_t)i * r.as[3] + ee * kChunk;
       };
-      if (chunk < n_chunks) {
+      if (at_chunk < n_chunks) {
         point(row, e8);
       } else {
         point(0u, 0u);
@@ -1205,7 +1206,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
       uint32_t esc_seen = 0;  // escapes of the stream so far
 #pragma unroll
       for (int j = 0; j < kRecDepth; ++j) esc_bits[j] = 0u, esc_dst[j] = nullptr;
-      // Loads of the lane's next chunk (of chunk 0 again once the stream is at its end, so that every
+      // Loads of the lane's next chunk (of its last one again once the stream is at its end, so that every
       // batch issues the same loads), then on to the chunk after it.
       auto request = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok) {
 #pragma unroll
@@ -1221,10 +1222,10 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
           for (int j = 0; j < RK; ++j) w[j] = w_p[j];
         }
         out = (global_u32x4)out_p;
-        ok = chunk < n_chunks;
-        chunk += 64u;
+        ok = at_chunk < n_chunks;
+        at_chunk += 64u;
         if (steady) {  // uniform
-          if (chunk < n_chunks) cand_p += cand_step, w_p += w_step, out_p += out_step;
+          if (at_chunk < n_chunks) cand_p += cand_step, w_p += w_step, out_p += out_step;
         } else {
           row += adv_row;
           e8 += adv_e8;
@@ -1232,7 +1233,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
             e8 -= d8;
             ++row;
           }
-          if (chunk < n_chunks) point(row, e8);
+          if (at_chunk < n_chunks) point(row, e8);
         }
       };
       // the raw values that have arrived for the chunk at `out`: over its escaped components, lowest first
