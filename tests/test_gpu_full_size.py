@@ -32,6 +32,17 @@ def run():
         out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
         codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v)
         codec.check_status("full size")
+        # every stream, not only the sampled ones: the single decode call (one kernel that also
+        # reconstructs when chunk = 0) against the two calls one after the other
+        sym_one = codec.dec_symbols.clone()
+        two_k, two_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+        codec.dec_symbols.zero_()
+        codec.decode(w.cand_k, w.cand_v, w.probs, two_k, two_v, fused=False)
+        codec.check_status("full size, two calls")
+        assert torch.equal(codec.dec_symbols, sym_one)
+        assert torch.equal(two_k.view(torch.int16), out_k.view(torch.int16))
+        assert torch.equal(two_v.view(torch.int16), out_v.view(torch.int16))
+        del two_k, two_v, sym_one
         out[chunk] = (codec, coded, out_k, out_v)
     return w, out
 
