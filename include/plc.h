@@ -252,6 +252,22 @@ int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *c
                          void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
                          void *stream);
 
+/* plc_rans_decode followed by plc_reconstruct_cond as one call, the way
+ * plc_rans_decode_reconstruct stands for plc_rans_decode and plc_reconstruct:
+ * same results, and under the same conditions one kernel, whose reconstructing
+ * wavefront fetches each position's chosen index a round before it requests
+ * that candidate (all k of them where a position has none).  chosen must be in
+ * place on `stream` (plc_index_decode) before the call. */
+int plc_rans_decode_reconstruct_cond(const plc_dims *dims, const uint16_t *freq,
+                                     const uint32_t *states, const uint16_t *words,
+                                     uint64_t words_len, const uint64_t *word_off,
+                                     const uint32_t *n_words, int32_t chunk_syms,
+                                     const void *cand_k, const void *cand_v, const float *probs,
+                                     const int32_t *chosen, const uint16_t *esc_vals,
+                                     uint64_t esc_len, const uint64_t *esc_off, uint8_t *symbols,
+                                     void *out_k, void *out_v, void *ws, size_t ws_bytes,
+                                     uint32_t *status, void *stream);
+
 /*
  * `chosen` from the vectors alone, for an encoder that is not told the token:
  * by the same lemma one row identifies it.  Per (s, i): D_j = sum_e (act[e] -

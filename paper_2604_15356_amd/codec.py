@@ -228,12 +228,18 @@ class KVDeltaCodec:
                              self.idx_word_off, self.idx_word_cap, self.idx_n_words, self.status)
         return self.coded(cond=True)
 
-    def decode_cond(self, cand_k, cand_v, probs, out_k, out_v):
+    def decode_cond(self, cand_k, cand_v, probs, out_k, out_v, fused=True):
         plc.plc_index_decode(probs, self.idx_states, self.idx_words, self.idx_word_off, self.idx_n_words,
                              self.S, self.n, self.k, self.dec_chosen, self.status)
-        self.rans_decode()
-        plc.plc_reconstruct_cond(self.dims, cand_k, cand_v, probs, self.dec_chosen, self.dec_symbols,
-                                 self.esc_vals, self.esc_off, out_k, out_v, self.ws, self.status)
+        if fused:
+            plc.plc_rans_decode_reconstruct_cond(self.dims, self.freq, self.states, self.words, self.word_off,
+                                                 self.n_words, self.chunk_syms, cand_k, cand_v, probs,
+                                                 self.dec_chosen, self.esc_vals, self.esc_off, self.dec_symbols,
+                                                 out_k, out_v, self.ws, self.status)
+        else:
+            self.rans_decode()
+            plc.plc_reconstruct_cond(self.dims, cand_k, cand_v, probs, self.dec_chosen, self.dec_symbols,
+                                     self.esc_vals, self.esc_off, out_k, out_v, self.ws, self.status)
 
     def coded(self, cond=False) -> Coded:
         if cond:

@@ -99,6 +99,7 @@ struct ReconView {
   const uint16_t *cand_k, *cand_v;
   uint16_t *out_k, *out_v;
   const float *weights;  // [S, n, k] renormalised
+  const int32_t *chosen;  // [S, n] index of each position's true candidate or -1; null: always the weighted mean
   int64_t cs[5], as[4];  // element strides of the candidates [S,L,H,n,k] and of the output [S,L,H,n]
   int32_t L, H, n, k, d8;
   float delta;

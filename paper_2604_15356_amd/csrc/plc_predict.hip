@@ -804,13 +804,16 @@ extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const v
                        esc_off, out_k, out_v, ws, ws_bytes, status, stream);
 }
 
-extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
-                                           const uint16_t *words, uint64_t words_len, const uint64_t *word_off,
-                                           const uint32_t *n_words, int32_t chunk_syms, const void *cand_k,
-                                           const void *cand_v, const float *probs, const uint16_t *esc_vals,
-                                           uint64_t esc_len, const uint64_t *esc_off, uint8_t *symbols,
-                                           void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
-                                           void *stream) {
+namespace plc {
+namespace {
+
+// plc_rans_decode_reconstruct (chosen = null) and plc_rans_decode_reconstruct_cond
+int decode_and_reconstruct(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
+                           const uint16_t *words, uint64_t words_len, const uint64_t *word_off,
+                           const uint32_t *n_words, int32_t chunk_syms, const void *cand_k, const void *cand_v,
+                           const float *probs, const int32_t *chosen, const uint16_t *esc_vals, uint64_t esc_len,
+                           const uint64_t *esc_off, uint8_t *symbols, void *out_k, void *out_v, void *ws,
+                           size_t ws_bytes, uint32_t *status, void *stream) {
   Plan p;
   if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
   // the checks of plc_reconstruct first, so that a refusal leaves nothing enqueued
@@ -823,8 +826,9 @@ extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t 
     const int rc = plc_rans_decode(freq, states, words, words_len, word_off, n_words, p.n_streams,
                                    p.syms_per_stream, chunk_syms, symbols, status, stream);
     if (rc) return rc;
-    return plc_reconstruct(dims, cand_k, cand_v, probs, symbols, esc_vals, esc_len, esc_off, out_k, out_v, ws,
-                           ws_bytes, status, stream);
+    return decode_floats(dims, cand_k, cand_v, probs, chosen, nullptr, 0.0f,
+                         chosen ? PLC_TRACE_RECONSTRUCT_COND : PLC_TRACE_RECONSTRUCT, symbols, esc_vals, esc_len,
+                         esc_off, out_k, out_v, ws, ws_bytes, status, stream);
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
 
@@ -843,6 +847,7 @@ extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t 
   r.out_k = a.out_k;
   r.out_v = a.out_v;
   r.weights = a.weights;
+  r.chosen = chosen;
   for (int i = 0; i < 5; ++i) r.cs[i] = a.cs[i];
   for (int i = 0; i < 4; ++i) r.as[i] = a.as[i];
   r.L = a.L, r.H = a.H, r.n = a.n, r.k = a.k, r.d8 = a.d8;
@@ -858,6 +863,35 @@ extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t 
                      const_cast<float *>(a.weights), p.rows, dims->k, status);
   return rans_decode_fused(freq, states, words, words_len, word_off, n_words, p.n_streams, p.syms_per_stream,
                            symbols, r, status, st, true);
+}
+
+}  // namespace
+}  // namespace plc
+
+extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
+                                           const uint16_t *words, uint64_t words_len, const uint64_t *word_off,
+                                           const uint32_t *n_words, int32_t chunk_syms, const void *cand_k,
+                                           const void *cand_v, const float *probs, const uint16_t *esc_vals,
+                                           uint64_t esc_len, const uint64_t *esc_off, uint8_t *symbols,
+                                           void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
+                                           void *stream) {
+  return decode_and_reconstruct(dims, freq, states, words, words_len, word_off, n_words, chunk_syms, cand_k, cand_v,
+                                probs, nullptr, esc_vals, esc_len, esc_off, symbols, out_k, out_v, ws, ws_bytes,
+                                status, stream);
+}
+
+extern "C" int plc_rans_decode_reconstruct_cond(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
+                                                const uint16_t *words, uint64_t words_len,
+                                                const uint64_t *word_off, const uint32_t *n_words,
+                                                int32_t chunk_syms, const void *cand_k, const void *cand_v,
+                                                const float *probs, const int32_t *chosen,
+                                                const uint16_t *esc_vals, uint64_t esc_len, const uint64_t *esc_off,
+                                                uint8_t *symbols, void *out_k, void *out_v, void *ws,
+                                                size_t ws_bytes, uint32_t *status, void *stream) {
+  if (!aligned(chosen, 4)) return PLC_ERR_INVALID;
+  return decode_and_reconstruct(dims, freq, states, words, words_len, word_off, n_words, chunk_syms, cand_k, cand_v,
+                                probs, chosen, esc_vals, esc_len, esc_off, symbols, out_k, out_v, ws, ws_bytes,
+                                status, stream);
 }
 
 extern "C" int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,

@@ -1092,7 +1092,7 @@ __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uin
 // there are escapes and cost at most their own number in that count).
 constexpr int kRecDepth = 3;
 
-template <int RK>
+template <int RK, bool COND>
 __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const RansArgs a) {
   __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing2Entries];  // slot table, then the ring
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
@@ -1188,6 +1188,15 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
       } else {
         point(0u, 0u);
       }
+      // COND: the position names its true candidate (plc_reconstruct_cond), whose vector then is the
+      // prediction; which candidate to request is itself a load, so it runs one round further ahead: a
+      // second cursor walks the chunks 2 * kRecDepth batches in front and fetches their chosen index.
+      uint32_t far_chunk = at_chunk, far_row = row, far_e8 = e8;
+      const int32_t *pick_p = nullptr;
+      if constexpr (COND) pick_p = r.chosen + (int64_t)s * r.n + (at_chunk < n_chunks ? row >> 1 : 0u);
+      int32_t pick_next[kRecDepth];  // chosen index of the chunk the stage requests next
+      int32_t pick_used[kRecDepth];  // and of the chunk whose candidates it holds (-1: the weighted mean)
+      bool mean_path[kRecDepth];     // uniform: some lane of the stage's request needed all candidates
       uint4 cv[kRecDepth][RK];
       float wv[kRecDepth][RK];
       typedef __attribute__((address_space(1))) u32x4 *global_u32x4;  // named global: kept through the loop
@@ -1208,9 +1217,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
       for (int j = 0; j < kRecDepth; ++j) esc_bits[j] = 0u, esc_dst[j] = nullptr;
       // Loads of the lane's next chunk (of its last one again once the stream is at its end, so that every
       // batch issues the same loads), then on to the chunk after it.
-      auto request = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok) {
-#pragma unroll
-        for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + j * r.cs[4]);
+      auto load_weights = [&](float(&w)[RK]) {
         if constexpr (RK % 4 == 0) {
 #pragma unroll
           for (int j = 0; j < RK; j += 4) {
@@ -1220,6 +1227,45 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
         } else {
 #pragma unroll
           for (int j = 0; j < RK; ++j) w[j] = w_p[j];
+        }
+      };
+      auto fetch_pick = [&](int32_t &pick) {  // COND: the far cursor's chosen index, then one batch on
+        pick = *pick_p;
+        far_chunk += 64u;
+        if (steady) {  // uniform
+          if (far_chunk < n_chunks) pick_p += adv_row / 2u;
+        } else {
+          far_row += adv_row;
+          far_e8 += adv_e8;
+          if (far_e8 >= d8) {
+            far_e8 -= d8;
+            ++far_row;
+          }
+          if (far_chunk < n_chunks) pick_p = r.chosen + (int64_t)s * r.n + (far_row >> 1);
+        }
+      };
+      auto request = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, int32_t &pick_nx,
+                         int32_t &pick_us, bool &mean) {
+        if constexpr (COND) {
+          int32_t pick = pick_nx;
+          if (pick < -1 || pick >= RK) {
+            raise(a.status, PLC_ERR_INVALID);
+            pick = -1;
+          }
+          mean = __ballot(pick < 0) != 0;  // uniform
+          if (!mean) {
+            c[0] = load16_stream(cand_p + pick * r.cs[4]);
+          } else {  // a lane that has its candidate takes it RK times: every lane issues the same loads
+#pragma unroll
+            for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + (pick >= 0 ? pick : j) * r.cs[4]);
+            load_weights(w);
+          }
+          pick_us = pick;
+          fetch_pick(pick_nx);
+        } else {
+#pragma unroll
+          for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + j * r.cs[4]);
+          load_weights(w);
         }
         out = (global_u32x4)out_p;
         ok = at_chunk < n_chunks;
@@ -1250,8 +1296,13 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
           }
         }
       };
+      if constexpr (COND) {
 #pragma unroll
-      for (int j = 0; j < kRecDepth; ++j) request(cv[j], wv[j], dst[j], live[j]);
+        for (int j = 0; j < kRecDepth; ++j) fetch_pick(pick_next[j]);
+      }
+#pragma unroll
+      for (int j = 0; j < kRecDepth; ++j)
+        request(cv[j], wv[j], dst[j], live[j], pick_next[j], pick_used[j], mean_path[j]);
       asm volatile("" ::: "memory");
       __builtin_amdgcn_s_barrier();  // barrier "start"
       asm volatile("" ::: "memory");
@@ -1260,7 +1311,8 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
       // One batch: join its barrier, take its symbols from the stage, finish the chunk, request the chunk
       // of the batch kRecDepth later into the registers just freed.
       auto turn = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, uint32_t &bits,
-                      uint32_t(&raw)[kChunk], global_u32x4 &late, int32_t b, bool whole) {
+                      uint32_t(&raw)[kChunk], global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
+                      int32_t b, bool whole) {
         // (the scheduler would otherwise start on the predictions of all kRecDepth batches at the top of a
         // pass, and so wait there for requests that have only just gone out)
         __builtin_amdgcn_sched_barrier(0);
@@ -1271,10 +1323,17 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
         const uint2 sv = *reinterpret_cast<const uint2 *>(&sym_stage[b & 1][lane * kChunk]);
         patch(late, bits, raw);
         float pred[kChunk];
+        if (!COND || mean) {  // uniform
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) pred[e] = 0.0f;
+          for (int e = 0; e < kChunk; ++e) pred[e] = 0.0f;
 #pragma unroll
-        for (int j = 0; j < RK; ++j) accumulate8(w[j], c[j], pred);
+          for (int j = 0; j < RK; ++j) accumulate8(w[j], c[j], pred);
+        }
+        if constexpr (COND) {
+          const half8 own = __builtin_bit_cast(half8, c[0]);
+#pragma unroll
+          for (int e = 0; e < kChunk; ++e) pred[e] = (!mean || pick_us >= 0) ? (float)own[e] : pred[e];
+        }
         uint32_t unused = 0;
         const half8 v = add_back8(sv, r.delta, pred, &unused);
         const bool mine = whole || ok;
@@ -1313,7 +1372,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
             }
           }
         }
-        request(c, w, out, ok);
+        request(c, w, out, ok, pick_nx, pick_us, mean);
       };
       // Whole batches, kRecDepth at a time and free of branches: every pass issues the same loads and
       // stores in the same order.
@@ -1321,13 +1380,15 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
       for (; b0 + kRecDepth <= n_full; b0 += kRecDepth) {
 #pragma unroll
         for (int j = 0; j < kRecDepth; ++j)
-          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], b0 + j, true);
+          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
+               mean_path[j], b0 + j, true);
       }
       // What is left: fewer than kRecDepth whole batches and possibly a partial one.
 #pragma unroll
       for (int j = 0; j < kRecDepth; ++j)
         if (b0 + j < n_batches)  // uniform
-          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], b0 + j, false);
+          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
+               mean_path[j], b0 + j, false);
 #pragma unroll
       for (int j = 0; j < kRecDepth; ++j) patch(esc_dst[j], esc_bits[j], esc_raw[j]);
       return;
@@ -1763,7 +1824,7 @@ struct LaunchDecode {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipLaunchKernelGGL((rans_decode_kernel<W, true>), dim3(grid), dim3(W * 64), lds, st, a);
     } else if (W == 1 && a.n_units <= 512) {
-      hipLaunchKernelGGL(rans_decode_chain_kernel<0>, dim3(grid), dim3(128), 0, st, a);
+      hipLaunchKernelGGL((rans_decode_chain_kernel<0, false>), dim3(grid), dim3(128), 0, st, a);
     } else {
       // Many units: LDS decides how many wavefronts fit a compute unit, and the split table lets more in
       // (twice as many where every one-wavefront workgroup has a table of its own).
@@ -1896,9 +1957,13 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
     TraceScope trace(PLC_TRACE_RANS_DECODE, st);
     const dim3 grid((unsigned)n_streams), block(192);
     switch (recon.k) {
-#define PLC_CASE(K) \
-  case K:           \
-    hipLaunchKernelGGL(rans_decode_chain_kernel<K>, grid, block, 0, st, a); \
+#define PLC_CASE(K)                                                                       \
+  case K:                                                                                 \
+    if (recon.chosen) {                                                                   \
+      hipLaunchKernelGGL((rans_decode_chain_kernel<K, true>), grid, block, 0, st, a);     \
+    } else {                                                                              \
+      hipLaunchKernelGGL((rans_decode_chain_kernel<K, false>), grid, block, 0, st, a);    \
+    }                                                                                     \
     break;
       PLC_CASE(1) PLC_CASE(2) PLC_CASE(3) PLC_CASE(4) PLC_CASE(5) PLC_CASE(6) PLC_CASE(7) PLC_CASE(8)
 #undef PLC_CASE

@@ -21,7 +21,8 @@ PLC_ESCAPE = 255
 
 EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_stream",
            "plc_predict_residual", "plc_histogram", "plc_build_freq", "plc_rans_encode",
-           "plc_rans_decode", "plc_reconstruct", "plc_rans_decode_reconstruct", "plc_trace_kernel_events",
+           "plc_rans_decode", "plc_reconstruct", "plc_rans_decode_reconstruct", "plc_rans_decode_reconstruct_cond",
+           "plc_trace_kernel_events",
            "plc_predict_residual_cond", "plc_reconstruct_cond", "plc_select_candidate",
            "plc_index_encode", "plc_index_decode",
            "plc_surprisal_bits", "plc_predict_residual_adapt", "plc_reconstruct_adapt",
@@ -78,6 +79,8 @@ def lib() -> C.CDLL:
         L.plc_reconstruct.argtypes = [dp, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
         L.plc_rans_decode_reconstruct.argtypes = [dp, p, p, p, u64, p, p, i32, p, p, p, p, u64, p, p, p, p, p, sz,
                                                   p, p]
+        L.plc_rans_decode_reconstruct_cond.argtypes = [dp, p, p, p, u64, p, p, i32, p, p, p, p, p, u64, p, p, p, p, p,
+                                                       sz, p, p]
         L.plc_trace_kernel_events.argtypes = [C.c_int, p, p]
         L.plc_predict_residual_cond.argtypes = [dp, p, p, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
         L.plc_reconstruct_cond.argtypes = [dp, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
@@ -231,6 +234,18 @@ def plc_rans_decode_reconstruct(dims, freq, states, words, word_off, n_words, ch
         _ptr(out_k, torch.float16), _ptr(out_v, torch.float16), _contig(ws, torch.uint8), ws.numel(),
         _contig(status, torch.int32), _stream())
     _check(rc, "plc_rans_decode_reconstruct")
+
+
+def plc_rans_decode_reconstruct_cond(dims, freq, states, words, word_off, n_words, chunk_syms, cand_k, cand_v,
+                                     probs, chosen, esc_vals, esc_off, symbols, out_k, out_v, ws, status):
+    rc = lib().plc_rans_decode_reconstruct_cond(
+        C.byref(dims), _contig(freq, torch.int16), _contig(states, torch.int32), _contig(words, torch.int16),
+        words.numel(), _contig(word_off, torch.int64), _contig(n_words, torch.int32), chunk_syms,
+        _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16), _contig(probs, torch.float32),
+        _contig(chosen, torch.int32), _contig(esc_vals, None), esc_vals.numel(), _contig(esc_off, torch.int64),
+        _contig(symbols, torch.uint8), _ptr(out_k, torch.float16), _ptr(out_v, torch.float16),
+        _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_rans_decode_reconstruct_cond")
 
 
 def plc_predict_residual_cond(dims, cand_k, cand_v, probs, chosen, act_k, act_v, symbols, esc_vals,

@@ -85,6 +85,11 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert dec(C.byref(dm), None, p, p, 10, p, p, 0, p, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
     bad = plc.make_dims(1, 2, 2, 16, 0, 64, 0.02)
     assert dec(C.byref(bad), p, p, p, 10, p, p, 0, p, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    decc = L.plc_rans_decode_reconstruct_cond
+    assert decc(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, None, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert decc(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, C.c_void_p(4098), p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert decc(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, p, p, 0, p, p, p, odd, p, 1 << 20, p, None) == 1
+    assert decc(C.byref(dm), p, None, p, 10, p, p, 0, p, p, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
     # token-conditional calls
     dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
     odd4 = C.c_void_p(4098)

@@ -127,6 +127,14 @@ def test_conditional_encode_decode_matches_oracle(oracle, dev, case):
     rk32, rv32 = O.reconstruct(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v), probs, sym,
                                ref32["esc_vals"], ref32["esc_off"], mode=O.F32, chosen=ch_np)
     assert np.array_equal(u16(out_k).ravel(), rk32) and np.array_equal(u16(out_v).ravel(), rv32)
+    # decode_cond() is the single call that reconstructs inside the entropy decoder where the shape allows
+    # it; the two calls one after the other must give the same bits
+    two_k, two_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.dec_symbols.zero_()
+    codec.decode_cond(w.cand_k, w.cand_v, w.probs, two_k, two_v, fused=False)
+    codec.check_status("decode_cond in two calls")
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    assert np.array_equal(u16(two_k), u16(out_k)) and np.array_equal(u16(two_v), u16(out_v))
     # recovery error is the quantiser's: |act - out| <= Delta/2 (+ half an fp16 ulp of the output)
     esc = sym.reshape(codec.n_streams, w.n, 2, w.d) == 255
     delta = float(np.float32(w.delta))
@@ -197,6 +205,26 @@ def test_error_statuses_of_the_conditional_calls(oracle, dev):
     plc.plc_index_encode(bad, ch, w.S, w.n, w.k, codec.idx_states, codec.idx_words, codec.idx_word_off,
                          codec.idx_word_cap, codec.idx_n_words, status)
     assert int(status.item()) == plc.PLC_ERR_INVALID
+    # a chosen index out of range handed to the decode side: reported, and no candidate is read through it
+    codec = codec_for(w)
+    codec.encode_cond(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen=ch)
+    codec.check_status()
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    for wrong in (w.k, 1 << 20, -2, -(1 << 30)):
+        broken = ch.clone()
+        broken[0, 11] = wrong
+        for call in ("one", "two"):
+            if call == "one":
+                plc.plc_rans_decode_reconstruct_cond(codec.dims, codec.freq, codec.states, codec.words,
+                                                     codec.word_off, codec.n_words, 0, w.cand_k, w.cand_v, w.probs,
+                                                     broken, codec.esc_vals, codec.esc_off, codec.dec_symbols,
+                                                     out_k, out_v, codec.ws, codec.status)
+            else:
+                plc.plc_reconstruct_cond(codec.dims, w.cand_k, w.cand_v, w.probs, broken, codec.dec_symbols,
+                                         codec.esc_vals, codec.esc_off, out_k, out_v, codec.ws, codec.status)
+            with pytest.raises(plc.PlcError) as e:
+                codec.check_status()
+            assert e.value.code == plc.PLC_ERR_INVALID, (wrong, call)
 
 
 @pytest.mark.parametrize("layout", ["lhnkd", "lnkhd"])
