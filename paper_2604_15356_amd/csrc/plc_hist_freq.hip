@@ -13,19 +13,24 @@ __global__ __launch_bounds__(kBlock) void zero_u32_kernel(uint32_t *p, int64_t n
   if (i < n) p[i] = 0u;
 }
 
-// Each workgroup counts one segment of one stream into four per-wavefront LDS
-// histograms (so that wavefronts do not contend with each other), then adds
-// the non-empty bins to the stream's global counts.
+// Each workgroup counts one segment of one stream into LDS histograms, then adds the non-empty bins to
+// the stream's global counts.  Lanes that hit the same counter in one instruction are served one after
+// the other, and quantised residuals crowd into a few symbols (a dozen on the token-conditional path),
+// so every wavefront has kHistCopies histograms, a lane using copy lane mod kHistCopies; the copies
+// start 8 banks apart, so that equal symbols in different copies do not share a bank either.
+constexpr int kHistCopies = 8;
+constexpr int kHistStride = 256 + 8;
+
 __global__ __launch_bounds__(kBlock) void histogram_kernel(const uint8_t *__restrict__ symbols,
                                                            int64_t syms_per_stream, uint32_t segs_per_stream,
                                                            uint32_t *__restrict__ counts) {
-  __shared__ uint32_t hist[kBlock / 64][256];
+  __shared__ uint32_t hist[kBlock / 64][kHistCopies][kHistStride];
   const uint32_t stream = blockIdx.x / segs_per_stream;
   const uint32_t seg = blockIdx.x - stream * segs_per_stream;
   const int wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int w = 0; w < kBlock / 64; ++w) hist[w][threadIdx.x] = 0u;
+  for (int i = threadIdx.x; i < (kBlock / 64) * kHistCopies * kHistStride; i += kBlock) (&hist[0][0][0])[i] = 0u;
   __syncthreads();
+  uint32_t *mine = hist[wave][threadIdx.x & (kHistCopies - 1)];
 
   const int64_t seg_begin = (int64_t)seg * kHistSegment;
   const int64_t seg_end = seg_begin + kHistSegment < syms_per_stream ? seg_begin + kHistSegment : syms_per_stream;
@@ -36,7 +41,7 @@ __global__ __launch_bounds__(kBlock) void histogram_kernel(const uint8_t *__rest
   const uintptr_t mis = reinterpret_cast<uintptr_t>(p) & 15u;
   int64_t head = mis ? 16 - (int64_t)mis : 0;
   if (head > end - p) head = end - p;
-  if ((int64_t)threadIdx.x < head) atomicAdd(&hist[wave][p[threadIdx.x]], 1u);
+  if ((int64_t)threadIdx.x < head) atomicAdd(&mine[p[threadIdx.x]], 1u);
   p += head;
   const int64_t n_vec = (end - p) / 16;
   const uint4 *pv = reinterpret_cast<const uint4 *>(p);
@@ -46,16 +51,18 @@ __global__ __launch_bounds__(kBlock) void histogram_kernel(const uint8_t *__rest
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
 #pragma unroll
-      for (int b = 0; b < 4; ++b) atomicAdd(&hist[wave][(wds[j] >> (8 * b)) & 255u], 1u);
+      for (int b = 0; b < 4; ++b) atomicAdd(&mine[(wds[j] >> (8 * b)) & 255u], 1u);
     }
   }
   p += n_vec * 16;
-  if ((int64_t)threadIdx.x < end - p) atomicAdd(&hist[wave][p[threadIdx.x]], 1u);
+  if ((int64_t)threadIdx.x < end - p) atomicAdd(&mine[p[threadIdx.x]], 1u);
   __syncthreads();
 
   uint32_t c = 0;
 #pragma unroll
-  for (int w = 0; w < kBlock / 64; ++w) c += hist[w][threadIdx.x];
+  for (int w = 0; w < kBlock / 64; ++w)
+#pragma unroll
+    for (int r = 0; r < kHistCopies; ++r) c += hist[w][r][threadIdx.x];
   if (c) atomicAdd(&counts[(int64_t)stream * 256 + threadIdx.x], c);
 }
 
