@@ -55,6 +55,7 @@ __device__ bool index_table(const float *__restrict__ p, int k, uint32_t f[kMaxK
 constexpr int kTileGroups = 6;
 constexpr int kTilePos = kTileGroups * kLanes;  // 192 = the three helper wavefronts
 constexpr int kRow = kMaxK + 2;                 // k + 1 frequencies or k + 2 cumulative values, padded
+constexpr int kIdxStageWords = 8192;            // decoder: index streams up to this many words are read from LDS
 
 // Frequencies of one row into an LDS row (same arithmetic as index_table).
 __device__ __forceinline__ bool index_table_lds(const float *__restrict__ p, int k, uint16_t *f) {
@@ -165,7 +166,9 @@ __global__ __launch_bounds__(256) void index_decode_kernel(const float *__restri
                                                            const uint64_t *__restrict__ word_off,
                                                            const uint32_t *__restrict__ n_words, int n, int k,
                                                            int32_t *__restrict__ chosen, uint32_t *status) {
-  __shared__ uint16_t cums[2][kTilePos][kRow];  // cumulative frequencies cum[0..k+1] of every position of a tile
+  // cumulative frequencies cum[0..k+1] of every position of a tile (rows of 68 bytes, read as words)
+  __shared__ __attribute__((aligned(4))) uint16_t cums[2][kTilePos][kRow];
+  __shared__ uint16_t wstage[kIdxStageWords];
   const int s = blockIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bool rans_lane = lane < kLanes;
@@ -173,9 +176,15 @@ __global__ __launch_bounds__(256) void index_decode_kernel(const float *__restri
   uint64_t ptr = n_words[s];  // uniform
   bool corrupt = base > words_len || ptr > words_len - base;
   if (corrupt) ptr = 0;
+  // A session's index stream is short (a few bits per position): it is copied to LDS first, so that a
+  // renormalising lane does not wait for HBM inside the chain of steps.  A longer one is read in place.
+  const bool staged = ptr <= (uint64_t)kIdxStageWords;  // uniform
+  if (staged)
+    for (uint32_t i = threadIdx.x; i < (uint32_t)ptr; i += 256) wstage[i] = words[base + i];
   uint32_t x = rans_lane ? states[(int64_t)s * kLanes + lane] : kLow;
   const int groups = (n + kLanes - 1) / kLanes;
   const int tiles = (groups + kTileGroups - 1) / kTileGroups;
+  __syncthreads();
   for (int it = 0; it <= tiles; ++it) {
     if (wave > 0) {
       if (it < tiles) {
@@ -204,8 +213,31 @@ __global__ __launch_bounds__(256) void index_decode_kernel(const float *__restri
           const uint16_t *row = cums[t & 1][gi * kLanes + lane];
           const uint32_t slot = x & (kScale - 1);
           int sym = 0;
-          while (sym < k && row[sym + 1] <= slot) ++sym;  // the symbol whose interval holds the slot
-          const uint32_t cs = row[sym], fs = (uint32_t)row[sym + 1] - cs;
+          uint32_t cs, fs;
+          if (k <= 8) {  // uniform
+            // the row's ten values in one LDS round trip, then the search in registers: the symbol is the
+            // number of interval starts cum[1..k] at or below the slot, its start the largest value at
+            // or below the slot and its end the smallest above (cum[k+1] = 4096 always is)
+            const uint32_t *r32 = reinterpret_cast<const uint32_t *>(row);
+            const uint32_t v[5] = {r32[0], r32[1], r32[2], r32[3], r32[4]};
+            cs = 0;
+            uint32_t next = kScale;
+#pragma unroll
+            for (int m = 1; m <= 9; ++m) {
+              const uint32_t c = (m & 1) ? v[m >> 1] >> 16 : v[m >> 1] & 0xffffu;
+              const bool in = m <= k + 1;  // uniform
+              if (in && c <= slot) {
+                cs = c > cs ? c : cs;
+                sym += m <= k;
+              }
+              if (in && c > slot) next = c < next ? c : next;
+            }
+            fs = next - cs;
+          } else {
+            while (sym < k && row[sym + 1] <= slot) ++sym;  // the symbol whose interval holds the slot
+            cs = row[sym];
+            fs = (uint32_t)row[sym + 1] - cs;
+          }
           chosen[(int64_t)s * n + i] = sym == k ? -1 : sym;
           x = fs * (x >> 12) + slot - cs;
         }
@@ -217,7 +249,7 @@ __global__ __launch_bounds__(256) void index_decode_kernel(const float *__restri
           const uint64_t rank = (uint32_t)__builtin_popcount(below);
           uint32_t word = 0;
           if (rank < ptr) {
-            word = words[base + ptr - 1 - rank];
+            word = staged ? wstage[ptr - 1 - rank] : words[base + ptr - 1 - rank];
           } else {
             corrupt = true;
           }
