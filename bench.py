@@ -208,9 +208,15 @@ def main():
     # whether the single decode call runs its one-kernel form for this shape (see include/plc.h)
     one_kernel = fused and args.chunk_syms == 0 and w.k <= 8 and w.n_streams <= 512
 
-    def step():
+    def step(marks=None):
+        if marks:
+            marks[0].record()
         codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+        if marks:
+            marks[1].record()
         codec.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v, fused=fused)
+        if marks:
+            marks[2].record()
 
     for _ in range(args.warmup):
         step()
@@ -223,17 +229,21 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     timer = KernelTimer(plc, torch, args.steps, fused=one_kernel)
+    # events at the start, between encode and decode, and at the end of every step: the two directions apart
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         timer.arm(i)
-        step()
+        step(marks[i])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     timer.disarm()
     codec.check_status("timed steps")
     ms_per_step = dt / args.steps * 1e3
     value = w.kv_bytes / (dt / args.steps) / 1e9
+    encode_ms = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
+    decode_ms = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps
 
     # ---- what was produced
     E = w.n_streams * w.syms_per_stream
@@ -263,7 +273,8 @@ def main():
         kernels[name] = dict(ms=round(t, 4), median_ms=round(spread[name][0], 4), min_ms=round(spread[name][1], 4),
                              GBs=round(gbs, 1), frac_hbm=round(gbs / HBM_PEAK_GBS, 4))
         log(f"  {name:18s} {t:9.4f} ms  {gbs:8.1f} GB/s algorithmic  {100 * gbs / HBM_PEAK_GBS:5.1f} % of HBM peak")
-    log(f"  step (encode+decode) {ms_per_step:9.4f} ms   kernels sum {sum(ms.values()):.4f} ms")
+    log(f"  step (encode+decode) {ms_per_step:9.4f} ms   kernels sum {sum(ms.values()):.4f} ms;  encode {encode_ms:.4f} ms "
+        f"({w.kv_bytes / encode_ms / 1e6:.1f} GB/s of KV), decode {decode_ms:.4f} ms ({w.kv_bytes / decode_ms / 1e6:.1f} GB/s)")
     dom = kernels["predict_residual"]
     roofline = dict(bound="hbm", kernel="predict_residual_kernel", achieved=dom["GBs"], peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=dom["frac_hbm"],
@@ -281,6 +292,8 @@ def main():
                    "decode": "one kernel (reconstruction inside the entropy decoder)" if one_kernel else "two kernels"},
         "roofline": roofline,
         "kernels": kernels,
+        "directions": {"encode_ms": round(encode_ms, 4), "encode_GBs": round(w.kv_bytes / encode_ms / 1e6, 1),
+                       "decode_ms": round(decode_ms, 4), "decode_GBs": round(w.kv_bytes / decode_ms / 1e6, 1)},
         "coded_bits_per_token": round(total_bits / (w.S * w.n), 1),
         "payload_bits_per_symbol": round(payload / E, 4),
         "fp16_bits_per_token": 2 * w.L * w.H * w.d * 16,
