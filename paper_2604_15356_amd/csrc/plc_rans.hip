@@ -1018,6 +1018,264 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// Reconstruction inside the decoder for units coded as whole streams
+// ---------------------------------------------------------------------------
+// A further wavefront of the unit's workgroup that turns each batch of decoded symbols into KV components
+// while the next batches are decoded: out = prediction over RK candidates + symbol * step (the arithmetic
+// of plc_reconstruct; COND: of plc_reconstruct_cond).  A batch is 512 symbols = 64 chunks of 8 components,
+// one chunk per lane.  The candidates and weights of a chunk do not depend on its symbols, so they are
+// requested kRecDepth batches ahead and are in registers when the symbols arrive.  The wavefront meets the
+// decoder at every batch barrier -- one "start" barrier, then one per batch, in step with the other
+// wavefronts of the workgroup -- through the bare instruction, which unlike __syncthreads does not first
+// wait for its outstanding loads.  Loads are issued by every lane in every batch (past the end of the stream
+// a lane stays on its last chunk and stores nothing), so that the number of loads behind any given one is the
+// same on every path and the wait before a use leaves the later requests in flight (the few loads and
+// stores that escapes add are issued only where there are escapes and cost at most their own number in
+// that count).
+//   stream, len, G   the unit's stream, its symbols and groups of 32
+//   sym_stage        the decoder's two symbol stages: batch b is in stage b mod 2 from its barrier to the next
+constexpr int kRecDepth = 3;
+
+template <int RK, bool COND>
+__device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t stream, uint32_t len, int32_t G,
+                                                    const uint8_t (&sym_stage)[2][2 * kBatchSyms], int lane) {
+  const ReconView &r = a.recon;
+  const uint32_t lh = (uint32_t)(r.L * r.H);
+  const uint32_t s = (uint32_t)stream / lh, rem = (uint32_t)stream - s * lh;
+  const uint32_t l = rem / (uint32_t)r.H, h = rem - l * (uint32_t)r.H;
+  const int64_t cand0 = s * r.cs[0] + l * r.cs[1] + h * r.cs[2];
+  const int64_t out0 = s * r.as[0] + l * r.as[1] + h * r.as[2];
+  const float *w0 = r.weights + (int64_t)s * r.n * r.k;
+  const uint32_t n_chunks = len / kChunk;
+  const uint32_t d8 = (uint32_t)r.d8, adv_row = 64u / d8, adv_e8 = 64u - adv_row * d8;
+  // The chunk this lane requests next: row = position * 2 + (0 = K, 1 = V), e8 = chunk inside the row,
+  // and where its candidates, weights and output are.  From batch to batch a lane moves on by 64
+  // chunks; where that is a whole, even number of rows (d = 8, 16, ... 256) it is the same position
+  // step in the same half every time, and the three pointers advance by constants.
+  uint32_t at_chunk = (uint32_t)lane, row = (uint32_t)lane / d8, e8 = (uint32_t)lane - row * d8;
+  const bool steady = adv_e8 == 0u && (adv_row & 1u) == 0u;
+  const int64_t cand_step = (int64_t)(adv_row / 2u) * r.cs[3], out_step = (int64_t)(adv_row / 2u) * r.as[3];
+  const uint32_t w_step = (adv_row / 2u) * (uint32_t)RK;
+  const uint16_t *cand_p;
+  const float *w_p;
+  uint16_t *out_p;
+  auto point = [&](uint32_t rr, uint32_t ee) {
+    const uint32_t i = rr >> 1;
+    cand_p = ((rr & 1u) ? r.cand_v : r.cand_k) + cand0 + (int64_t)i * r.cs[3] + ee * kChunk;
+    w_p = w0 + (int64_t)i * RK;
+    out_p = ((rr & 1u) ? r.out_v : r.out_k) + out0 + (int64_t)i * r.as[3] + ee * kChunk;
+  };
+  if (at_chunk < n_chunks) {
+    point(row, e8);
+  } else {
+    point(0u, 0u);
+  }
+  // COND: the position names its true candidate (plc_reconstruct_cond), whose vector then is the
+  // prediction; which candidate to request is itself a load, so it runs one round further ahead: a
+  // second cursor walks the chunks 2 * kRecDepth batches in front and fetches their chosen index.
+  uint32_t far_chunk = at_chunk, far_row = row, far_e8 = e8;
+  const int32_t *pick_p = nullptr;
+  if constexpr (COND) pick_p = r.chosen + (int64_t)s * r.n + (at_chunk < n_chunks ? row >> 1 : 0u);
+  int32_t pick_next[kRecDepth];  // chosen index of the chunk the stage requests next
+  int32_t pick_used[kRecDepth];  // and of the chunk whose candidates it holds (-1: the weighted mean)
+  bool mean_path[kRecDepth];     // uniform: some lane of the stage's request needed all candidates
+  uint4 cv[kRecDepth][RK];
+  float wv[kRecDepth][RK];
+  typedef __attribute__((address_space(1))) u32x4 *global_u32x4;  // named global: kept through the loop
+  typedef __attribute__((address_space(1))) uint16_t *global_u16;
+  global_u32x4 dst[kRecDepth];
+  bool live[kRecDepth];  // whether the lane's chunk exists (a flag of its own: the pointer stays a global one)
+  // Escapes.  This wavefront sees every chunk of the stream in order, so the number of escapes in front
+  // of a chunk is a running count plus a prefix over the lanes.  The raw values are requested from the
+  // stream's list when the chunk is stored and written over its escaped components the next time the
+  // same registers come round, kRecDepth batches later (memory operations of a wavefront complete in
+  // the order of issue, so by the time a value has arrived the chunk's own store has landed).
+  uint32_t esc_bits[kRecDepth];  // which components of the chunk at esc_dst await their raw value
+  uint32_t esc_raw[kRecDepth][kChunk];
+  global_u32x4 esc_dst[kRecDepth];
+  const uint64_t esc_base = r.esc_off[stream];
+  uint32_t esc_seen = 0;  // escapes of the stream so far
+#pragma unroll
+  for (int j = 0; j < kRecDepth; ++j) esc_bits[j] = 0u, esc_dst[j] = nullptr;
+  // Loads of the lane's next chunk (of its last one again once the stream is at its end, so that every
+  // batch issues the same loads), then on to the chunk after it.
+  auto load_weights = [&](float(&w)[RK]) {
+    if constexpr (RK % 4 == 0) {
+#pragma unroll
+      for (int j = 0; j < RK; j += 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(w_p + j);
+        w[j] = t.x, w[j + 1] = t.y, w[j + 2] = t.z, w[j + 3] = t.w;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < RK; ++j) w[j] = w_p[j];
+    }
+  };
+  auto fetch_pick = [&](int32_t &pick) {  // COND: the far cursor's chosen index, then one batch on
+    pick = *pick_p;
+    far_chunk += 64u;
+    if (steady) {  // uniform
+      if (far_chunk < n_chunks) pick_p += adv_row / 2u;
+    } else {
+      far_row += adv_row;
+      far_e8 += adv_e8;
+      if (far_e8 >= d8) {
+        far_e8 -= d8;
+        ++far_row;
+      }
+      if (far_chunk < n_chunks) pick_p = r.chosen + (int64_t)s * r.n + (far_row >> 1);
+    }
+  };
+  auto request = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, int32_t &pick_nx,
+                     int32_t &pick_us, bool &mean) {
+    if constexpr (COND) {
+      int32_t pick = pick_nx;
+      if (pick < -1 || pick >= RK) {
+        raise(a.status, PLC_ERR_INVALID);
+        pick = -1;
+      }
+      mean = __ballot(pick < 0) != 0;  // uniform
+      if (!mean) {
+        c[0] = load16_stream(cand_p + pick * r.cs[4]);
+      } else {  // a lane that has its candidate takes it RK times: every lane issues the same loads
+#pragma unroll
+        for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + (pick >= 0 ? pick : j) * r.cs[4]);
+        load_weights(w);
+      }
+      pick_us = pick;
+      fetch_pick(pick_nx);
+    } else {
+#pragma unroll
+      for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + j * r.cs[4]);
+      load_weights(w);
+    }
+    out = (global_u32x4)out_p;
+    ok = at_chunk < n_chunks;
+    at_chunk += 64u;
+    if (steady) {  // uniform
+      if (at_chunk < n_chunks) cand_p += cand_step, w_p += w_step, out_p += out_step;
+    } else {
+      row += adv_row;
+      e8 += adv_e8;
+      if (e8 >= d8) {
+        e8 -= d8;
+        ++row;
+      }
+      if (at_chunk < n_chunks) point(row, e8);
+    }
+  };
+  // the raw values that have arrived for the chunk at `out`: over its escaped components, lowest first
+  auto patch = [&](global_u32x4 out, uint32_t &bits, const uint32_t (&raw)[kChunk]) {
+    if (__ballot(bits != 0u) == 0) return;  // uniform
+    global_u16 comp = (global_u16)out;
+#pragma unroll
+    for (int i = 0; i < kChunk; ++i) {
+      if (i > 0 && __ballot(bits != 0u) == 0) break;  // uniform; seldom more than one per chunk
+      if (bits) {
+        const int e = __builtin_ctz(bits);
+        bits &= bits - 1u;
+        comp[e] = (uint16_t)raw[i];
+      }
+    }
+  };
+  if constexpr (COND) {
+#pragma unroll
+    for (int j = 0; j < kRecDepth; ++j) fetch_pick(pick_next[j]);
+  }
+#pragma unroll
+  for (int j = 0; j < kRecDepth; ++j)
+    request(cv[j], wv[j], dst[j], live[j], pick_next[j], pick_used[j], mean_path[j]);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();  // barrier "start"
+  asm volatile("" ::: "memory");
+  const int32_t n_batches = (G + kBatch - 1) / kBatch;
+  const int32_t n_full = (int32_t)(n_chunks / 64u);  // batches all of whose chunks exist
+  // One batch: join its barrier, take its symbols from the stage, finish the chunk, request the chunk
+  // of the batch kRecDepth later into the registers just freed.
+  auto turn = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, uint32_t &bits,
+                  uint32_t(&raw)[kChunk], global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
+                  int32_t b, bool whole) {
+    // (the scheduler would otherwise start on the predictions of all kRecDepth batches at the top of a
+    // pass, and so wait there for requests that have only just gone out)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // barrier of batch b: its symbols are in the stage
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+    const uint2 sv = *reinterpret_cast<const uint2 *>(&sym_stage[b & 1][lane * kChunk]);
+    patch(late, bits, raw);
+    float pred[kChunk];
+    if (!COND || mean) {  // uniform
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) pred[e] = 0.0f;
+#pragma unroll
+      for (int j = 0; j < RK; ++j) accumulate8(w[j], c[j], pred);
+    }
+    if constexpr (COND) {
+      const half8 own = __builtin_bit_cast(half8, c[0]);
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) pred[e] = (!mean || pick_us >= 0) ? (float)own[e] : pred[e];
+    }
+    uint32_t unused = 0;
+    const half8 v = add_back8(sv, r.delta, pred, &unused);
+    const bool mine = whole || ok;
+    if (mine) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), out);
+    // a byte is 0xff iff its low seven bits carry into bit 7 when 1 is added and bit 7 is set
+    const uint32_t hx = ((sv.x & 0x7f7f7f7fu) + 0x01010101u) & sv.x & 0x80808080u;
+    const uint32_t hy = ((sv.y & 0x7f7f7f7fu) + 0x01010101u) & sv.y & 0x80808080u;
+    const bool has = mine && (hx | hy) != 0u;
+    const uint64_t lanes = __ballot(has);
+    if (lanes != 0) {  // uniform
+      // bit 7 of byte e to bit e
+      const uint32_t mx = ((hx >> 7) * 0x00204081u) >> 21 & 0xfu, my = ((hy >> 7) * 0x00204081u) >> 21 & 0xfu;
+      bits = has ? (mx | (my << 4)) : 0u;
+      late = out;
+      const uint32_t n_esc = (uint32_t)__builtin_popcount(bits);
+      const bool several = __ballot(n_esc > 1u) != 0;  // uniform; seldom
+      uint32_t total, before;
+      if (!several) {
+        before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lanes >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lanes, 0u));
+        total = (uint32_t)__builtin_popcountll(lanes);
+      } else {
+        before = wave_escape_prefix(n_esc, &total);
+      }
+      const uint64_t src = esc_base + esc_seen + before;
+      esc_seen += total;
+#pragma unroll
+      for (int i = 0; i < kChunk; ++i) {
+        if (i > 0 && (!several || __ballot(n_esc > (uint32_t)i) == 0)) break;  // uniform
+        if (n_esc > (uint32_t)i) {
+          if (src + i < r.esc_len) {
+            raw[i] = r.esc_in[src + i];
+          } else {
+            raise(a.status, PLC_ERR_CORRUPT);
+            raw[i] = 0u;
+          }
+        }
+      }
+    }
+    request(c, w, out, ok, pick_nx, pick_us, mean);
+  };
+  // Whole batches, kRecDepth at a time and free of branches: every pass issues the same loads and
+  // stores in the same order.
+  int32_t b0 = 0;
+  for (; b0 + kRecDepth <= n_full; b0 += kRecDepth) {
+#pragma unroll
+    for (int j = 0; j < kRecDepth; ++j)
+      turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
+           mean_path[j], b0 + j, true);
+  }
+  // What is left: fewer than kRecDepth whole batches and possibly a partial one.
+#pragma unroll
+  for (int j = 0; j < kRecDepth; ++j)
+    if (b0 + j < n_batches)  // uniform
+      turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
+           mean_path[j], b0 + j, false);
+#pragma unroll
+  for (int j = 0; j < kRecDepth; ++j) patch(esc_dst[j], esc_bits[j], esc_raw[j]);
+}
+
+// ---------------------------------------------------------------------------
 // Decoder for streams coded as one unit (one wavefront per workgroup)
 // ---------------------------------------------------------------------------
 // With one unit per stream there are only as many wavefronts as streams, so what counts is the
@@ -1079,19 +1337,8 @@ __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uin
 // slots they take belonged to blocks above the pointer (four blocks of ring: the pointer's block and the
 // three below it).
 //
-// RK > 0 adds a third wavefront that reconstructs the KV components of each batch from its symbols while
-// the next batches are decoded: out = prediction over RK candidates + symbol * step (the arithmetic of
-// plc_reconstruct).  A batch is 512 symbols = 64 chunks of 8 components, one chunk per lane.  The
-// candidates and weights of a chunk do not depend on its symbols, so they are requested kRecDepth batches
-// ahead and are in registers when the symbols arrive; the wavefront joins the batch barrier through the
-// bare instruction, which unlike __syncthreads does not first wait for its outstanding loads.  Loads are
-// issued by every lane in every batch (past the end of the stream a lane stays on its last chunk and
-// stores nothing), so
-// that the number of loads behind any given one is the same on every path and the wait before a use
-// leaves the later requests in flight (the few loads and stores that escapes add are issued only where
-// there are escapes and cost at most their own number in that count).
-constexpr int kRecDepth = 3;
-
+// RK > 0 adds a third wavefront that reconstructs the KV components of each batch while the next batches are
+// decoded (reconstruct_batches above).
 template <int RK, bool COND>
 __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const RansArgs a) {
   __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing2Entries];  // slot table, then the ring
@@ -1157,240 +1404,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
 
   if constexpr (RK > 0) {
     if (wave == 2) {
-      const ReconView &r = a.recon;
-      const uint32_t lh = (uint32_t)(r.L * r.H);
-      const uint32_t s = (uint32_t)stream / lh, rem = (uint32_t)stream - s * lh;
-      const uint32_t l = rem / (uint32_t)r.H, h = rem - l * (uint32_t)r.H;
-      const int64_t cand0 = s * r.cs[0] + l * r.cs[1] + h * r.cs[2];
-      const int64_t out0 = s * r.as[0] + l * r.as[1] + h * r.as[2];
-      const float *w0 = r.weights + (int64_t)s * r.n * r.k;
-      const uint32_t n_chunks = len / kChunk;
-      const uint32_t d8 = (uint32_t)r.d8, adv_row = 64u / d8, adv_e8 = 64u - adv_row * d8;
-      // The chunk this lane requests next: row = position * 2 + (0 = K, 1 = V), e8 = chunk inside the row,
-      // and where its candidates, weights and output are.  From batch to batch a lane moves on by 64
-      // chunks; where that is a whole, even number of rows (d = 8, 16, ... 256) it is the same position
-      // step in the same half every time, and the three pointers advance by constants.
-      uint32_t at_chunk = (uint32_t)lane, row = (uint32_t)lane / d8, e8 = (uint32_t)lane - row * d8;
-      const bool steady = adv_e8 == 0u && (adv_row & 1u) == 0u;
-      const int64_t cand_step = (int64_t)(adv_row / 2u) * r.cs[3], out_step = (int64_t)(adv_row / 2u) * r.as[3];
-      const uint32_t w_step = (adv_row / 2u) * (uint32_t)RK;
-      const uint16_t *cand_p;
-      const float *w_p;
-      uint16_t *out_p;
-      auto point = [&](uint32_t rr, uint32_t ee) {
-        const uint32_t i = rr >> 1;
-        cand_p = ((rr & 1u) ? r.cand_v : r.cand_k) + cand0 + (int64_t)i * r.cs[3] + ee * kChunk;
-        w_p = w0 + (int64_t)i * RK;
-        out_p = ((rr & 1u) ? r.out_v : r.out_k) + out0 + (int64_t)i * r.as[3] + ee * kChunk;
-      };
-      if (at_chunk < n_chunks) {
-        point(row, e8);
-      } else {
-        point(0u, 0u);
-      }
-      // COND: the position names its true candidate (plc_reconstruct_cond), whose vector then is the
-      // prediction; which candidate to request is itself a load, so it runs one round further ahead: a
-      // second cursor walks the chunks 2 * kRecDepth batches in front and fetches their chosen index.
-      uint32_t far_chunk = at_chunk, far_row = row, far_e8 = e8;
-      const int32_t *pick_p = nullptr;
-      if constexpr (COND) pick_p = r.chosen + (int64_t)s * r.n + (at_chunk < n_chunks ? row >> 1 : 0u);
-      int32_t pick_next[kRecDepth];  // chosen index of the chunk the stage requests next
-      int32_t pick_used[kRecDepth];  // and of the chunk whose candidates it holds (-1: the weighted mean)
-      bool mean_path[kRecDepth];     // uniform: some lane of the stage's request needed all candidates
-      uint4 cv[kRecDepth][RK];
-      float wv[kRecDepth][RK];
-      typedef __attribute__((address_space(1))) u32x4 *global_u32x4;  // named global: kept through the loop
-      typedef __attribute__((address_space(1))) uint16_t *global_u16;
-      global_u32x4 dst[kRecDepth];
-      bool live[kRecDepth];  // whether the lane's chunk exists (a flag of its own: the pointer stays a global one)
-      // Escapes.  This wavefront sees every chunk of the stream in order, so the number of escapes in front
-      // of a chunk is a running count plus a prefix over the lanes.  The raw values are requested from the
-      // stream's list when the chunk is stored and written over its escaped components the next time the
-      // same registers come round, kRecDepth batches later (memory operations of a wavefront complete in
-      // the order of issue, so by the time a value has arrived the chunk's own store has landed).
-      uint32_t esc_bits[kRecDepth];  // which components of the chunk at esc_dst await their raw value
-      uint32_t esc_raw[kRecDepth][kChunk];
-      global_u32x4 esc_dst[kRecDepth];
-      const uint64_t esc_base = r.esc_off[stream];
-      uint32_t esc_seen = 0;  // escapes of the stream so far
-#pragma unroll
-      for (int j = 0; j < kRecDepth; ++j) esc_bits[j] = 0u, esc_dst[j] = nullptr;
-      // Loads of the lane's next chunk (of its last one again once the stream is at its end, so that every
-      // batch issues the same loads), then on to the chunk after it.
-      auto load_weights = [&](float(&w)[RK]) {
-        if constexpr (RK % 4 == 0) {
-#pragma unroll
-          for (int j = 0; j < RK; j += 4) {
-            const float4 t = *reinterpret_cast<const float4 *>(w_p + j);
-            w[j] = t.x, w[j + 1] = t.y, w[j + 2] = t.z, w[j + 3] = t.w;
-          }
-        } else {
-#pragma unroll
-          for (int j = 0; j < RK; ++j) w[j] = w_p[j];
-        }
-      };
-      auto fetch_pick = [&](int32_t &pick) {  // COND: the far cursor's chosen index, then one batch on
-        pick = *pick_p;
-        far_chunk += 64u;
-        if (steady) {  // uniform
-          if (far_chunk < n_chunks) pick_p += adv_row / 2u;
-        } else {
-          far_row += adv_row;
-          far_e8 += adv_e8;
-          if (far_e8 >= d8) {
-            far_e8 -= d8;
-            ++far_row;
-          }
-          if (far_chunk < n_chunks) pick_p = r.chosen + (int64_t)s * r.n + (far_row >> 1);
-        }
-      };
-      auto request = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, int32_t &pick_nx,
-                         int32_t &pick_us, bool &mean) {
-        if constexpr (COND) {
-          int32_t pick = pick_nx;
-          if (pick < -1 || pick >= RK) {
-            raise(a.status, PLC_ERR_INVALID);
-            pick = -1;
-          }
-          mean = __ballot(pick < 0) != 0;  // uniform
-          if (!mean) {
-            c[0] = load16_stream(cand_p + pick * r.cs[4]);
-          } else {  // a lane that has its candidate takes it RK times: every lane issues the same loads
-#pragma unroll
-            for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + (pick >= 0 ? pick : j) * r.cs[4]);
-            load_weights(w);
-          }
-          pick_us = pick;
-          fetch_pick(pick_nx);
-        } else {
-#pragma unroll
-          for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + j * r.cs[4]);
-          load_weights(w);
-        }
-        out = (global_u32x4)out_p;
-        ok = at_chunk < n_chunks;
-        at_chunk += 64u;
-        if (steady) {  // uniform
-          if (at_chunk < n_chunks) cand_p += cand_step, w_p += w_step, out_p += out_step;
-        } else {
-          row += adv_row;
-          e8 += adv_e8;
-          if (e8 >= d8) {
-            e8 -= d8;
-            ++row;
-          }
-          if (at_chunk < n_chunks) point(row, e8);
-        }
-      };
-      // the raw values that have arrived for the chunk at `out`: over its escaped components, lowest first
-      auto patch = [&](global_u32x4 out, uint32_t &bits, const uint32_t (&raw)[kChunk]) {
-        if (__ballot(bits != 0u) == 0) return;  // uniform
-        global_u16 comp = (global_u16)out;
-#pragma unroll
-        for (int i = 0; i < kChunk; ++i) {
-          if (i > 0 && __ballot(bits != 0u) == 0) break;  // uniform; seldom more than one per chunk
-          if (bits) {
-            const int e = __builtin_ctz(bits);
-            bits &= bits - 1u;
-            comp[e] = (uint16_t)raw[i];
-          }
-        }
-      };
-      if constexpr (COND) {
-#pragma unroll
-        for (int j = 0; j < kRecDepth; ++j) fetch_pick(pick_next[j]);
-      }
-#pragma unroll
-      for (int j = 0; j < kRecDepth; ++j)
-        request(cv[j], wv[j], dst[j], live[j], pick_next[j], pick_used[j], mean_path[j]);
-      asm volatile("" ::: "memory");
-      __builtin_amdgcn_s_barrier();  // barrier "start"
-      asm volatile("" ::: "memory");
-      const int32_t n_batches = (G + kBatch - 1) / kBatch;
-      const int32_t n_full = (int32_t)(n_chunks / 64u);  // batches all of whose chunks exist
-      // One batch: join its barrier, take its symbols from the stage, finish the chunk, request the chunk
-      // of the batch kRecDepth later into the registers just freed.
-      auto turn = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, uint32_t &bits,
-                      uint32_t(&raw)[kChunk], global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
-                      int32_t b, bool whole) {
-        // (the scheduler would otherwise start on the predictions of all kRecDepth batches at the top of a
-        // pass, and so wait there for requests that have only just gone out)
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_s_barrier();  // barrier of batch b: its symbols are in the stage
-        asm volatile("" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-        const uint2 sv = *reinterpret_cast<const uint2 *>(&sym_stage[b & 1][lane * kChunk]);
-        patch(late, bits, raw);
-        float pred[kChunk];
-        if (!COND || mean) {  // uniform
-#pragma unroll
-          for (int e = 0; e < kChunk; ++e) pred[e] = 0.0f;
-#pragma unroll
-          for (int j = 0; j < RK; ++j) accumulate8(w[j], c[j], pred);
-        }
-        if constexpr (COND) {
-          const half8 own = __builtin_bit_cast(half8, c[0]);
-#pragma unroll
-          for (int e = 0; e < kChunk; ++e) pred[e] = (!mean || pick_us >= 0) ? (float)own[e] : pred[e];
-        }
-        uint32_t unused = 0;
-        const half8 v = add_back8(sv, r.delta, pred, &unused);
-        const bool mine = whole || ok;
-        if (mine) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), out);
-        // a byte is 0xff iff its low seven bits carry into bit 7 when 1 is added and bit 7 is set
-        const uint32_t hx = ((sv.x & 0x7f7f7f7fu) + 0x01010101u) & sv.x & 0x80808080u;
-        const uint32_t hy = ((sv.y & 0x7f7f7f7fu) + 0x01010101u) & sv.y & 0x80808080u;
-        const bool has = mine && (hx | hy) != 0u;
-        const uint64_t lanes = __ballot(has);
-        if (lanes != 0) {  // uniform
-          // bit 7 of byte e to bit e
-          const uint32_t mx = ((hx >> 7) * 0x00204081u) >> 21 & 0xfu, my = ((hy >> 7) * 0x00204081u) >> 21 & 0xfu;
-          bits = has ? (mx | (my << 4)) : 0u;
-          late = out;
-          const uint32_t n_esc = (uint32_t)__builtin_popcount(bits);
-          const bool several = __ballot(n_esc > 1u) != 0;  // uniform; seldom
-          uint32_t total, before;
-          if (!several) {
-            before = __builtin_amdgcn_mbcnt_hi((uint32_t)(lanes >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)lanes, 0u));
-            total = (uint32_t)__builtin_popcountll(lanes);
-          } else {
-            before = wave_escape_prefix(n_esc, &total);
-          }
-          const uint64_t src = esc_base + esc_seen + before;
-          esc_seen += total;
-#pragma unroll
-          for (int i = 0; i < kChunk; ++i) {
-            if (i > 0 && (!several || __ballot(n_esc > (uint32_t)i) == 0)) break;  // uniform
-            if (n_esc > (uint32_t)i) {
-              if (src + i < r.esc_len) {
-                raw[i] = r.esc_in[src + i];
-              } else {
-                raise(a.status, PLC_ERR_CORRUPT);
-                raw[i] = 0u;
-              }
-            }
-          }
-        }
-        request(c, w, out, ok, pick_nx, pick_us, mean);
-      };
-      // Whole batches, kRecDepth at a time and free of branches: every pass issues the same loads and
-      // stores in the same order.
-      int32_t b0 = 0;
-      for (; b0 + kRecDepth <= n_full; b0 += kRecDepth) {
-#pragma unroll
-        for (int j = 0; j < kRecDepth; ++j)
-          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
-               mean_path[j], b0 + j, true);
-      }
-      // What is left: fewer than kRecDepth whole batches and possibly a partial one.
-#pragma unroll
-      for (int j = 0; j < kRecDepth; ++j)
-        if (b0 + j < n_batches)  // uniform
-          turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
-               mean_path[j], b0 + j, false);
-#pragma unroll
-      for (int j = 0; j < kRecDepth; ++j) patch(esc_dst[j], esc_bits[j], esc_raw[j]);
+      reconstruct_batches<RK, COND>(a, stream, len, G, sym_stage, lane);
       return;
     }
   }
