@@ -461,12 +461,12 @@ def main():
 
         def step4():
             codec4.encode_adapt(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen4, thr, args.adaptive_range)
-            codec4.decode_adapt(w.cand_k, w.cand_v, w.probs, out_k, out_v, thr, args.adaptive_range)
+            codec4.decode_adapt(w.cand_k, w.cand_v, w.probs, out_k, out_v, thr, args.adaptive_range, fused=fused)
 
         for _ in range(args.warmup):
             step4()
         torch.cuda.synchronize()
-        timer4 = KernelTimer(plc, torch, args.steps, conditional=True)
+        timer4 = KernelTimer(plc, torch, args.steps, conditional=True, fused=one_kernel)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(args.steps):
@@ -503,12 +503,13 @@ def main():
             "roundtrip_symbols_exact": bool(torch.equal(codec4.dec_symbols, codec4.symbols)),
             "roundtrip_depths_exact": bool(torch.equal(codec4.dec_bits, codec4.bits)),
             "kernels_ms": {k: round(v, 4) for k, v in ms4.items() if k != "histogram"},
+            "decode": "one kernel (reconstruction inside the entropy decoder)" if one_kernel else "two kernels",
         }
         r4 = result["surprisal_adaptive"]
         log(f"  surprisal-adaptive (b0 {args.adaptive_b0}, range {args.adaptive_range}): step {r4['ms_per_step']} ms "
             f"({r4['value']} GB/s), mean depth {r4['mean_depth']}, {r4['payload_bits_per_symbol']} bits/component, "
             f"mse {r4['mean_square_error']:.3e} (fixed step: {r4['fixed_step_mean_square_error']:.3e}); "
-            f"rans_encode {ms4['rans_encode']:.3f} ms, rans_decode {ms4['rans_decode']:.3f} ms")
+            + ", ".join(f"{k} {ms4[k]:.3f} ms" for k in ("rans_encode", "rans_decode", "rans_decode_reconstruct") if k in ms4))
         del codec4
     if not args.no_linear and args.config == "llama8b" and not args.sessions:
         # Linear-embedding predictor on a workload of the same KV shape: prediction = c + A * Ebar with

@@ -384,6 +384,22 @@ int plc_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const
                              int32_t syms_per_pos, int32_t streams_per_session, const uint8_t *bits,
                              int32_t n_tables, uint8_t *symbols, uint32_t *status, void *stream);
 
+/* plc_rans_decode_bucketed (syms_per_pos = 2d, streams_per_session = L*H) followed by
+ * plc_reconstruct_adapt as one call, the way plc_rans_decode_reconstruct stands for
+ * plc_rans_decode and plc_reconstruct: same results, and under the same conditions one kernel,
+ * whose reconstructing wavefront fetches each position's depth with its chosen index.  chosen and
+ * bits must be in place on `stream` before the call. */
+int plc_rans_decode_reconstruct_adapt(const plc_dims *dims, const uint16_t *freq,
+                                      const uint32_t *states, const uint16_t *words,
+                                      uint64_t words_len, const uint64_t *word_off,
+                                      const uint32_t *n_words, int32_t chunk_syms, int32_t n_tables,
+                                      const void *cand_k, const void *cand_v, const float *probs,
+                                      const int32_t *chosen, const uint8_t *bits, float range,
+                                      const uint16_t *esc_vals, uint64_t esc_len,
+                                      const uint64_t *esc_off, uint8_t *symbols, void *out_k,
+                                      void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
+                                      void *stream);
+
 /*
  * ---- Linear-embedding predictor ------------------------------------------------
  * Sec. 7.1, "Linear embedding approximation": per layer the KV vector is taken as linear in the

@@ -192,12 +192,18 @@ class KVDeltaCodec:
         c.bits, c.counts_d, c.freq_d = self.bits, self.counts_d, self.freq_d
         return c
 
-    def decode_adapt(self, cand_k, cand_v, probs, out_k, out_v, thr, step_range):
+    def decode_adapt(self, cand_k, cand_v, probs, out_k, out_v, thr, step_range, fused=True):
         """From the coded artefacts alone: the index stream gives the tokens, the tokens the bit depths."""
         B, spp, sps = plc.MAX_BITS, 2 * self.d, self.L * self.H
         plc.plc_index_decode(probs, self.idx_states, self.idx_words, self.idx_word_off, self.idx_n_words,
                              self.S, self.n, self.k, self.dec_chosen, self.status)
         plc.plc_surprisal_bits(probs, self.dec_chosen, self.S, self.n, self.k, thr, self.dec_bits, self.status)
+        if fused:
+            plc.plc_rans_decode_reconstruct_adapt(self.dims, self.freq_d, self.states, self.words, self.word_off,
+                                                  self.n_words, self.chunk_syms, B, cand_k, cand_v, probs,
+                                                  self.dec_chosen, self.dec_bits, step_range, self.esc_vals,
+                                                  self.esc_off, self.dec_symbols, out_k, out_v, self.ws, self.status)
+            return
         plc.plc_rans_decode_bucketed(self.freq_d, self.states, self.words, self.word_off, self.n_words,
                                      self.n_streams, self.N, self.chunk_syms, spp, sps, self.dec_bits, B,
                                      self.dec_symbols, self.status)

@@ -100,6 +100,8 @@ struct ReconView {
   uint16_t *out_k, *out_v;
   const float *weights;  // [S, n, k] renormalised
   const int32_t *chosen;  // [S, n] index of each position's true candidate or -1; null: always the weighted mean
+  const uint8_t *bits;    // [S, n] bit depth of each position (step = range * 2^-bits); null: the step is delta
+  float range;
   int64_t cs[5], as[4];  // element strides of the candidates [S,L,H,n,k] and of the output [S,L,H,n]
   int32_t L, H, n, k, d8;
   float delta;
@@ -110,12 +112,13 @@ struct ReconView {
 // Whether plc_rans.hip has a decoder that reconstructs as it goes for this many streams and candidates.
 bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k);
 // That decoder: plc_rans_decode with one unit per stream, plus out = prediction + symbol * delta for every
-// component, escapes from their lists.  The weights must be in place on `st`.  With launch = false the
-// arguments are checked and nothing is enqueued.
+// component, escapes from their lists.  With recon.bits: plc_rans_decode_bucketed with n_tables tables per
+// stream instead.  The weights must be in place on `st`.  With launch = false the arguments are checked and
+// nothing is enqueued.
 int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16_t *words, uint64_t words_len,
                       const uint64_t *word_off, const uint32_t *n_words, int64_t n_streams,
-                      int64_t syms_per_stream, uint8_t *symbols, const ReconView &recon, uint32_t *status,
-                      hipStream_t st, bool launch);
+                      int64_t syms_per_stream, int32_t n_tables, uint8_t *symbols, const ReconView &recon,
+                      uint32_t *status, hipStream_t st, bool launch);
 
 // Escape bookkeeping for callers that produce or consume symbols outside the tile-structured kernels
 // (plc_predict.hip): collect the escaped components' raw fp16 values of `act` into the per-stream lists /

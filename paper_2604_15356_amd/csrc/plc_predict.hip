@@ -807,11 +807,13 @@ extern "C" int plc_reconstruct(const plc_dims *dims, const void *cand_k, const v
 namespace plc {
 namespace {
 
-// plc_rans_decode_reconstruct (chosen = null) and plc_rans_decode_reconstruct_cond
+// plc_rans_decode_reconstruct (chosen = null), plc_rans_decode_reconstruct_cond and, with bits and n_tables
+// tables per stream, plc_rans_decode_reconstruct_adapt
 int decode_and_reconstruct(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
                            const uint16_t *words, uint64_t words_len, const uint64_t *word_off,
                            const uint32_t *n_words, int32_t chunk_syms, const void *cand_k, const void *cand_v,
-                           const float *probs, const int32_t *chosen, const uint16_t *esc_vals, uint64_t esc_len,
+                           const float *probs, const int32_t *chosen, const uint8_t *bits, float range,
+                           int32_t n_tables, const uint16_t *esc_vals, uint64_t esc_len,
                            const uint64_t *esc_off, uint8_t *symbols, void *out_k, void *out_v, void *ws,
                            size_t ws_bytes, uint32_t *status, void *stream) {
   Plan p;
@@ -823,10 +825,13 @@ int decode_and_reconstruct(const plc_dims *dims, const uint16_t *freq, const uin
   if (!aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total) return PLC_ERR_INVALID;
   if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
   if (chunk_syms != 0 || !decode_fused_supported(p.n_streams, p.syms_per_stream, dims->k)) {
-    const int rc = plc_rans_decode(freq, states, words, words_len, word_off, n_words, p.n_streams,
-                                   p.syms_per_stream, chunk_syms, symbols, status, stream);
+    const int rc = bits ? plc_rans_decode_bucketed(freq, states, words, words_len, word_off, n_words, p.n_streams,
+                                                   p.syms_per_stream, chunk_syms, 2 * dims->d, dims->L * dims->H,
+                                                   bits, n_tables, symbols, status, stream)
+                        : plc_rans_decode(freq, states, words, words_len, word_off, n_words, p.n_streams,
+                                          p.syms_per_stream, chunk_syms, symbols, status, stream);
     if (rc) return rc;
-    return decode_floats(dims, cand_k, cand_v, probs, chosen, nullptr, 0.0f,
+    return decode_floats(dims, cand_k, cand_v, probs, chosen, bits, range,
                          chosen ? PLC_TRACE_RECONSTRUCT_COND : PLC_TRACE_RECONSTRUCT, symbols, esc_vals, esc_len,
                          esc_off, out_k, out_v, ws, ws_bytes, status, stream);
   }
@@ -848,6 +853,8 @@ int decode_and_reconstruct(const plc_dims *dims, const uint16_t *freq, const uin
   r.out_v = a.out_v;
   r.weights = a.weights;
   r.chosen = chosen;
+  r.bits = bits;
+  r.range = range;
   for (int i = 0; i < 5; ++i) r.cs[i] = a.cs[i];
   for (int i = 0; i < 4; ++i) r.as[i] = a.as[i];
   r.L = a.L, r.H = a.H, r.n = a.n, r.k = a.k, r.d8 = a.d8;
@@ -857,12 +864,12 @@ int decode_and_reconstruct(const plc_dims *dims, const uint16_t *freq, const uin
   r.esc_off = esc_off;
 
   const int rc = rans_decode_fused(freq, states, words, words_len, word_off, n_words, p.n_streams,
-                                   p.syms_per_stream, symbols, r, status, st, false);
+                                   p.syms_per_stream, n_tables, symbols, r, status, st, false);
   if (rc) return rc;  // nothing enqueued
   hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
                      const_cast<float *>(a.weights), p.rows, dims->k, status);
   return rans_decode_fused(freq, states, words, words_len, word_off, n_words, p.n_streams, p.syms_per_stream,
-                           symbols, r, status, st, true);
+                           n_tables, symbols, r, status, st, true);
 }
 
 }  // namespace
@@ -876,8 +883,8 @@ extern "C" int plc_rans_decode_reconstruct(const plc_dims *dims, const uint16_t 
                                            void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
                                            void *stream) {
   return decode_and_reconstruct(dims, freq, states, words, words_len, word_off, n_words, chunk_syms, cand_k, cand_v,
-                                probs, nullptr, esc_vals, esc_len, esc_off, symbols, out_k, out_v, ws, ws_bytes,
-                                status, stream);
+                                probs, nullptr, nullptr, 0.0f, 0, esc_vals, esc_len, esc_off, symbols, out_k, out_v,
+                                ws, ws_bytes, status, stream);
 }
 
 extern "C" int plc_rans_decode_reconstruct_cond(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
@@ -890,8 +897,24 @@ extern "C" int plc_rans_decode_reconstruct_cond(const plc_dims *dims, const uint
                                                 size_t ws_bytes, uint32_t *status, void *stream) {
   if (!aligned(chosen, 4)) return PLC_ERR_INVALID;
   return decode_and_reconstruct(dims, freq, states, words, words_len, word_off, n_words, chunk_syms, cand_k, cand_v,
-                                probs, chosen, esc_vals, esc_len, esc_off, symbols, out_k, out_v, ws, ws_bytes,
-                                status, stream);
+                                probs, chosen, nullptr, 0.0f, 0, esc_vals, esc_len, esc_off, symbols, out_k, out_v,
+                                ws, ws_bytes, status, stream);
+}
+
+extern "C" int plc_rans_decode_reconstruct_adapt(const plc_dims *dims, const uint16_t *freq, const uint32_t *states,
+                                                 const uint16_t *words, uint64_t words_len,
+                                                 const uint64_t *word_off, const uint32_t *n_words,
+                                                 int32_t chunk_syms, int32_t n_tables, const void *cand_k,
+                                                 const void *cand_v, const float *probs, const int32_t *chosen,
+                                                 const uint8_t *bits, float range, const uint16_t *esc_vals,
+                                                 uint64_t esc_len, const uint64_t *esc_off, uint8_t *symbols,
+                                                 void *out_k, void *out_v, void *ws, size_t ws_bytes,
+                                                 uint32_t *status, void *stream) {
+  if (!aligned(chosen, 4) || !bits || !(range > 0.0f) || !(range < 3.0e38f)) return PLC_ERR_INVALID;
+  if (n_tables < 1 || n_tables > PLC_MAX_BITS) return PLC_ERR_INVALID;
+  return decode_and_reconstruct(dims, freq, states, words, words_len, word_off, n_words, chunk_syms, cand_k, cand_v,
+                                probs, chosen, bits, range, n_tables, esc_vals, esc_len, esc_off, symbols, out_k,
+                                out_v, ws, ws_bytes, status, stream);
 }
 
 extern "C" int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,

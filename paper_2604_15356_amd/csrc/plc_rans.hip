@@ -1022,7 +1022,7 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 // ---------------------------------------------------------------------------
 // A further wavefront of the unit's workgroup that turns each batch of decoded symbols into KV components
 // while the next batches are decoded: out = prediction over RK candidates + symbol * step (the arithmetic
-// of plc_reconstruct; COND: of plc_reconstruct_cond).  A batch is 512 symbols = 64 chunks of 8 components,
+// of plc_reconstruct; COND: of plc_reconstruct_cond; ADAPT: of plc_reconstruct_adapt).  A batch is 512 symbols = 64 chunks of 8 components,
 // one chunk per lane.  The candidates and weights of a chunk do not depend on its symbols, so they are
 // requested kRecDepth batches ahead and are in registers when the symbols arrive.  The wavefront meets the
 // decoder at every batch barrier -- one "start" barrier, then one per batch, in step with the other
@@ -1036,9 +1036,10 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 //   sym_stage        the decoder's two symbol stages: batch b is in stage b mod 2 from its barrier to the next
 constexpr int kRecDepth = 3;
 
-template <int RK, bool COND>
+template <int RK, bool COND, bool ADAPT>
 __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t stream, uint32_t len, int32_t G,
                                                     const uint8_t (&sym_stage)[2][2 * kBatchSyms], int lane) {
+  static_assert(COND || !ADAPT, "the adaptive quantiser lives on the token-conditional path");
   const ReconView &r = a.recon;
   const uint32_t lh = (uint32_t)(r.L * r.H);
   const uint32_t s = (uint32_t)stream / lh, rem = (uint32_t)stream - s * lh;
@@ -1073,12 +1074,13 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   // COND: the position names its true candidate (plc_reconstruct_cond), whose vector then is the
   // prediction; which candidate to request is itself a load, so it runs one round further ahead: a
   // second cursor walks the chunks 2 * kRecDepth batches in front and fetches their chosen index.
+  // ADAPT: the position's bit depth, which sets its step, is fetched with the chosen index.
   uint32_t far_chunk = at_chunk, far_row = row, far_e8 = e8;
-  const int32_t *pick_p = nullptr;
-  if constexpr (COND) pick_p = r.chosen + (int64_t)s * r.n + (at_chunk < n_chunks ? row >> 1 : 0u);
+  int64_t far_pos = (int64_t)s * r.n + (at_chunk < n_chunks ? row >> 1 : 0u);  // entry in chosen and bits
   int32_t pick_next[kRecDepth];  // chosen index of the chunk the stage requests next
   int32_t pick_used[kRecDepth];  // and of the chunk whose candidates it holds (-1: the weighted mean)
   bool mean_path[kRecDepth];     // uniform: some lane of the stage's request needed all candidates
+  uint32_t depth_next[kRecDepth], depth_used[kRecDepth];  // bit depths, the same way
   uint4 cv[kRecDepth][RK];
   float wv[kRecDepth][RK];
   typedef __attribute__((address_space(1))) u32x4 *global_u32x4;  // named global: kept through the loop
@@ -1111,11 +1113,12 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
       for (int j = 0; j < RK; ++j) w[j] = w_p[j];
     }
   };
-  auto fetch_pick = [&](int32_t &pick) {  // COND: the far cursor's chosen index, then one batch on
-    pick = *pick_p;
+  auto fetch_pick = [&](int32_t &pick, uint32_t &depth) {  // COND: the far cursor's position, then one batch on
+    pick = r.chosen[far_pos];
+    if constexpr (ADAPT) depth = r.bits[far_pos];
     far_chunk += 64u;
     if (steady) {  // uniform
-      if (far_chunk < n_chunks) pick_p += adv_row / 2u;
+      if (far_chunk < n_chunks) far_pos += adv_row / 2u;
     } else {
       far_row += adv_row;
       far_e8 += adv_e8;
@@ -1123,16 +1126,24 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
         far_e8 -= d8;
         ++far_row;
       }
-      if (far_chunk < n_chunks) pick_p = r.chosen + (int64_t)s * r.n + (far_row >> 1);
+      if (far_chunk < n_chunks) far_pos = (int64_t)s * r.n + (far_row >> 1);
     }
   };
   auto request = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, int32_t &pick_nx,
-                     int32_t &pick_us, bool &mean) {
+                     int32_t &pick_us, bool &mean, uint32_t &depth_nx, uint32_t &depth_us) {
     if constexpr (COND) {
       int32_t pick = pick_nx;
       if (pick < -1 || pick >= RK) {
         raise(a.status, PLC_ERR_INVALID);
         pick = -1;
+      }
+      if constexpr (ADAPT) {
+        uint32_t b = depth_nx;
+        if (b < 1u || b > (uint32_t)PLC_MAX_BITS) {
+          raise(a.status, PLC_ERR_INVALID);
+          b = 1u;
+        }
+        depth_us = b;
       }
       mean = __ballot(pick < 0) != 0;  // uniform
       if (!mean) {
@@ -1143,7 +1154,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
         load_weights(w);
       }
       pick_us = pick;
-      fetch_pick(pick_nx);
+      fetch_pick(pick_nx, depth_nx);
     } else {
 #pragma unroll
       for (int j = 0; j < RK; ++j) c[j] = load16_stream(cand_p + j * r.cs[4]);
@@ -1180,11 +1191,11 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   };
   if constexpr (COND) {
 #pragma unroll
-    for (int j = 0; j < kRecDepth; ++j) fetch_pick(pick_next[j]);
+    for (int j = 0; j < kRecDepth; ++j) fetch_pick(pick_next[j], depth_next[j]);
   }
 #pragma unroll
   for (int j = 0; j < kRecDepth; ++j)
-    request(cv[j], wv[j], dst[j], live[j], pick_next[j], pick_used[j], mean_path[j]);
+    request(cv[j], wv[j], dst[j], live[j], pick_next[j], pick_used[j], mean_path[j], depth_next[j], depth_used[j]);
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();  // barrier "start"
   asm volatile("" ::: "memory");
@@ -1194,7 +1205,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   // of the batch kRecDepth later into the registers just freed.
   auto turn = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, uint32_t &bits,
                   uint32_t(&raw)[kChunk], global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
-                  int32_t b, bool whole) {
+                  uint32_t &depth_nx, uint32_t &depth_us, int32_t b, bool whole) {
     // (the scheduler would otherwise start on the predictions of all kRecDepth batches at the top of a
     // pass, and so wait there for requests that have only just gone out)
     __builtin_amdgcn_sched_barrier(0);
@@ -1217,7 +1228,8 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
       for (int e = 0; e < kChunk; ++e) pred[e] = (!mean || pick_us >= 0) ? (float)own[e] : pred[e];
     }
     uint32_t unused = 0;
-    const half8 v = add_back8(sv, r.delta, pred, &unused);
+    const float step = ADAPT ? __builtin_ldexpf(r.range, -(int)depth_us) : r.delta;
+    const half8 v = add_back8(sv, step, pred, &unused);
     const bool mine = whole || ok;
     if (mine) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), out);
     // a byte is 0xff iff its low seven bits carry into bit 7 when 1 is added and bit 7 is set
@@ -1254,7 +1266,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
         }
       }
     }
-    request(c, w, out, ok, pick_nx, pick_us, mean);
+    request(c, w, out, ok, pick_nx, pick_us, mean, depth_nx, depth_us);
   };
   // Whole batches, kRecDepth at a time and free of branches: every pass issues the same loads and
   // stores in the same order.
@@ -1263,14 +1275,14 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
 #pragma unroll
     for (int j = 0; j < kRecDepth; ++j)
       turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
-           mean_path[j], b0 + j, true);
+           mean_path[j], depth_next[j], depth_used[j], b0 + j, true);
   }
   // What is left: fewer than kRecDepth whole batches and possibly a partial one.
 #pragma unroll
   for (int j = 0; j < kRecDepth; ++j)
     if (b0 + j < n_batches)  // uniform
       turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
-           mean_path[j], b0 + j, false);
+           mean_path[j], depth_next[j], depth_used[j], b0 + j, false);
 #pragma unroll
   for (int j = 0; j < kRecDepth; ++j) patch(esc_dst[j], esc_bits[j], esc_raw[j]);
 }
@@ -1404,7 +1416,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
 
   if constexpr (RK > 0) {
     if (wave == 2) {
-      reconstruct_batches<RK, COND>(a, stream, len, G, sym_stage, lane);
+      reconstruct_batches<RK, COND, false>(a, stream, len, G, sym_stage, lane);
       return;
     }
   }
@@ -1585,7 +1597,8 @@ __device__ __forceinline__ void dec_depth_step(uint32_t &xh, uint2 &e, uint32_t 
   }
 }
 
-__global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs a) {
+template <int RK>
+__global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(const RansArgs a) {
   extern __shared__ __attribute__((aligned(16))) char depth_lds[];  // n_tables slot tables, then the ring
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
   __shared__ uint32_t fc[256];
@@ -1593,8 +1606,10 @@ __global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs 
   __shared__ uint32_t first_table;
   __shared__ int32_t ptr_pub;
   __shared__ uint32_t tables_ok;
+  constexpr int kThreads = RK ? 192 : 128;
   const int lane = threadIdx.x & 63;
-  const bool helper = threadIdx.x >= 64;  // uniform per wavefront
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const bool helper = wave == 1;
   const int64_t stream = blockIdx.x / a.wgs_per_stream;
   const int64_t chunk = blockIdx.x - stream * a.wgs_per_stream;
   uint2 *tabs2 = reinterpret_cast<uint2 *>(depth_lds);
@@ -1608,7 +1623,7 @@ __global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs 
     uint32_t f[4], cum;
     const uint32_t total = load_freq4(a.freq + (stream * a.n_tables + t) * 256, lane, f, &cum);
     if (total != kScale && total != 0 && threadIdx.x == 0) tables_ok = 0u;
-    if (!helper) {
+    if (wave == 0) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         fc[lane * 4 + r] = f[r] | (cum << 16);
@@ -1621,10 +1636,10 @@ __global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs 
       for (int sy = 0; sy < 256; ++sy) {
         const uint32_t v = fc[sy];
         const uint32_t fs = v & 0xffffu, cs = v >> 16;
-        for (uint32_t o = threadIdx.x; o < fs; o += 128) tt[cs + o] = make_uint2(fs | ((uint32_t)sy << 24), o);
+        for (uint32_t o = threadIdx.x; o < fs; o += kThreads) tt[cs + o] = make_uint2(fs | ((uint32_t)sy << 24), o);
       }
     } else {
-      for (uint32_t o = threadIdx.x; o < (uint32_t)kScale; o += 128) tt[o] = make_uint2(0u, 0u);
+      for (uint32_t o = threadIdx.x; o < (uint32_t)kScale; o += kThreads) tt[o] = make_uint2(0u, 0u);
     }
     __syncthreads();
   }
@@ -1656,6 +1671,13 @@ __global__ __launch_bounds__(128) void rans_decode_depths_kernel(const RansArgs 
   int32_t tail_groups = G % kBatch;
   if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
   const int32_t g_tail = G - tail_groups;
+
+  if constexpr (RK > 0) {  // the wavefront that reconstructs, as in the kernel above
+    if (wave == 2) {
+      reconstruct_batches<RK, true, true>(a, stream, len, G, sym_stage, lane);
+      return;
+    }
+  }
 
   if (helper) {
     bool bad_depth = false;
@@ -1829,9 +1851,9 @@ struct LaunchDecode {
     // wavefront would cost more in occupancy than the shorter step gains.
     if (a.bits && W == 1 && a.n_units <= 512) {
       const size_t lds = (size_t)a.n_tables * kDepthTableBytes + (size_t)(kRingWords + kRingMirror) * sizeof(uint32_t);
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel),
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      hipLaunchKernelGGL(rans_decode_depths_kernel, dim3(grid), dim3(128), lds, st, a);
+      hipLaunchKernelGGL(rans_decode_depths_kernel<0>, dim3(grid), dim3(128), lds, st, a);
     } else if (a.bits) {
       const size_t lds = (size_t)a.n_tables * kScale * sizeof(uint32_t);
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_kernel<W, true>),
@@ -1945,11 +1967,11 @@ bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k) {
 
 int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16_t *words, uint64_t words_len,
                       const uint64_t *word_off, const uint32_t *n_words, int64_t n_streams,
-                      int64_t syms_per_stream, uint8_t *symbols, const ReconView &recon, uint32_t *status,
-                      hipStream_t st, bool launch) {
+                      int64_t syms_per_stream, int32_t n_tables, uint8_t *symbols, const ReconView &recon,
+                      uint32_t *status, hipStream_t st, bool launch) {
   RansArgs a = {};
   int waves = 1;
-  const int rc = check_common(n_streams, syms_per_stream, 0, &a, &waves);
+  int rc = check_common(n_streams, syms_per_stream, 0, &a, &waves);
   if (rc) return rc;
   if (!decode_fused_supported(n_streams, syms_per_stream, recon.k)) return PLC_ERR_INVALID;
   if (!symbols || !freq || !states || !word_off || !n_words || !status) return PLC_ERR_INVALID;
@@ -1957,6 +1979,11 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
   if (reinterpret_cast<uintptr_t>(freq) % 8 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
   if ((int64_t)recon.L * recon.H < 1 || n_streams % ((int64_t)recon.L * recon.H)) return PLC_ERR_INVALID;
   if (syms_per_stream != 2ll * recon.n * recon.d8 * kChunk) return PLC_ERR_INVALID;
+  if (recon.bits) {  // one table per bit depth: a position is the 2 * d symbols of its K and V rows
+    if (!recon.chosen || !(recon.range > 0.0f)) return PLC_ERR_INVALID;
+    rc = check_depths(syms_per_stream, 0, 2 * recon.d8 * kChunk, recon.L * recon.H, recon.bits, n_tables, &a);
+    if (rc) return rc;
+  }
   if (!launch) return PLC_OK;
   a.sym_out = symbols;
   a.freq = freq;
@@ -1970,14 +1997,19 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
   {
     TraceScope trace(PLC_TRACE_RANS_DECODE, st);
     const dim3 grid((unsigned)n_streams), block(192);
+    const size_t lds = (size_t)a.n_tables * kDepthTableBytes + (size_t)(kRingWords + kRingMirror) * sizeof(uint32_t);
     switch (recon.k) {
-#define PLC_CASE(K)                                                                       \
-  case K:                                                                                 \
-    if (recon.chosen) {                                                                   \
-      hipLaunchKernelGGL((rans_decode_chain_kernel<K, true>), grid, block, 0, st, a);     \
-    } else {                                                                              \
-      hipLaunchKernelGGL((rans_decode_chain_kernel<K, false>), grid, block, 0, st, a);    \
-    }                                                                                     \
+#define PLC_CASE(K)                                                                              \
+  case K:                                                                                        \
+    if (recon.bits) {                                                                            \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<K>),   \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
+      hipLaunchKernelGGL(rans_decode_depths_kernel<K>, grid, block, lds, st, a);                 \
+    } else if (recon.chosen) {                                                                   \
+      hipLaunchKernelGGL((rans_decode_chain_kernel<K, true>), grid, block, 0, st, a);            \
+    } else {                                                                                     \
+      hipLaunchKernelGGL((rans_decode_chain_kernel<K, false>), grid, block, 0, st, a);           \
+    }                                                                                            \
     break;
       PLC_CASE(1) PLC_CASE(2) PLC_CASE(3) PLC_CASE(4) PLC_CASE(5) PLC_CASE(6) PLC_CASE(7) PLC_CASE(8)
 #undef PLC_CASE

@@ -22,6 +22,7 @@ PLC_ESCAPE = 255
 EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_stream",
            "plc_predict_residual", "plc_histogram", "plc_build_freq", "plc_rans_encode",
            "plc_rans_decode", "plc_reconstruct", "plc_rans_decode_reconstruct", "plc_rans_decode_reconstruct_cond",
+           "plc_rans_decode_reconstruct_adapt",
            "plc_trace_kernel_events",
            "plc_predict_residual_cond", "plc_reconstruct_cond", "plc_select_candidate",
            "plc_index_encode", "plc_index_decode",
@@ -81,6 +82,8 @@ def lib() -> C.CDLL:
                                                   p, p]
         L.plc_rans_decode_reconstruct_cond.argtypes = [dp, p, p, p, u64, p, p, i32, p, p, p, p, p, u64, p, p, p, p, p,
                                                        sz, p, p]
+        L.plc_rans_decode_reconstruct_adapt.argtypes = [dp, p, p, p, u64, p, p, i32, i32, p, p, p, p, p, C.c_float, p,
+                                                        u64, p, p, p, p, p, sz, p, p]
         L.plc_trace_kernel_events.argtypes = [C.c_int, p, p]
         L.plc_predict_residual_cond.argtypes = [dp, p, p, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
         L.plc_reconstruct_cond.argtypes = [dp, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
@@ -366,6 +369,20 @@ def plc_rans_decode_bucketed(freq, states, words, word_off, n_words, n_streams, 
                                         streams_per_session, _contig(bits, torch.uint8), n_tables,
                                         _contig(symbols, torch.uint8), _contig(status, torch.int32), _stream())
     _check(rc, "plc_rans_decode_bucketed")
+
+
+def plc_rans_decode_reconstruct_adapt(dims, freq, states, words, word_off, n_words, chunk_syms, n_tables, cand_k,
+                                      cand_v, probs, chosen, bits, step_range, esc_vals, esc_off, symbols, out_k,
+                                      out_v, ws, status):
+    rc = lib().plc_rans_decode_reconstruct_adapt(
+        C.byref(dims), _contig(freq, torch.int16), _contig(states, torch.int32), _contig(words, torch.int16),
+        words.numel(), _contig(word_off, torch.int64), _contig(n_words, torch.int32), chunk_syms, n_tables,
+        _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16), _contig(probs, torch.float32),
+        _contig(chosen, torch.int32), _contig(bits, torch.uint8), float(step_range), _contig(esc_vals, None),
+        esc_vals.numel(), _contig(esc_off, torch.int64), _contig(symbols, torch.uint8),
+        _ptr(out_k, torch.float16), _ptr(out_v, torch.float16), _contig(ws, torch.uint8), ws.numel(),
+        _contig(status, torch.int32), _stream())
+    _check(rc, "plc_rans_decode_reconstruct_adapt")
 
 
 def plc_expected_embedding(probs_full, embed_t, ebar):

@@ -90,6 +90,13 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert decc(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, C.c_void_p(4098), p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
     assert decc(C.byref(dm), p, p, p, 10, p, p, 0, p, p, p, p, p, 0, p, p, p, odd, p, 1 << 20, p, None) == 1
     assert decc(C.byref(dm), p, None, p, 10, p, p, 0, p, p, p, p, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    deca = L.plc_rans_decode_reconstruct_adapt
+    r03 = C.c_float(0.3)
+    assert deca(C.byref(dm), p, p, p, 10, p, p, 0, 4, p, p, p, p, None, r03, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert deca(C.byref(dm), p, p, p, 10, p, p, 0, 4, p, p, p, p, p, C.c_float(0.0), p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert deca(C.byref(dm), p, p, p, 10, p, p, 0, 5, p, p, p, p, p, r03, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert deca(C.byref(dm), p, p, p, 10, p, p, 0, 4, p, p, p, None, p, r03, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
+    assert deca(C.byref(dm), p, p, p, 10, p, p, 0, 4, odd, p, p, p, p, r03, p, 0, p, p, p, p, p, 1 << 20, p, None) == 1
     # token-conditional calls
     dm = plc.make_dims(1, 2, 2, 16, 4, 64, 0.02)
     odd4 = C.c_void_p(4098)

@@ -103,6 +103,14 @@ def test_adaptive_encode_decode_matches_oracle(oracle, dev, case):
                            ref32["esc_vals"], ref32["esc_off"], mode=O.F32, chosen=ch, bits=bits,
                            step_range=step_range)
     assert np.array_equal(u16(out_k).ravel(), rk) and np.array_equal(u16(out_v).ravel(), rv)
+    # decode_adapt() ends in the single call that reconstructs inside the entropy decoder where the shape
+    # allows it; the two calls one after the other must give the same bits
+    two_k, two_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    codec.dec_symbols.zero_()
+    codec.decode_adapt(w.cand_k, w.cand_v, w.probs, two_k, two_v, thr, step_range, fused=False)
+    codec.check_status("decode_adapt in two calls")
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    assert np.array_equal(u16(two_k), u16(out_k)) and np.array_equal(u16(two_v), u16(out_v))
     # recovery error: half the position's own step (+ half an fp16 ulp of the output); escapes exact
     esc = sym.reshape(codec.n_streams, w.n, 2, w.d) == 255
     step = float(np.float32(step_range)) * 2.0 ** -bits.astype(np.float64)                  # [S, n]
