@@ -106,9 +106,12 @@ __device__ __forceinline__ void wave_sync() {
 //     stays below 2^(32+s) as long as f^2 <= 2^(12+s), i.e. s <= 10.  For f = 1 the multiplier
 //     2^32 - 1 yields x - 1, and the missing 4095 is added to the entry's cum.
 //       .x = m   .y = thr   .z = (4096 - f) | s << 24   .w = cum (+4095 if f = 1)
-//   long form, for tables with an f > 2048 (round-up reciprocal of 33 bits, exact for any x):
-//       t = mulhi(m, x);  q = (t + ((x - t) >> sh1)) >> sh2
-//       .x = m   .y = thr   .z = (4096 - f) | sh2 << 24   .w = cum | sh1 << 24
+//   long form, for tables with an f > 2048: a reciprocal of 33 bits, 2^32 + m = floor(2^(32+l) / f) + 1 with
+//   l = ceil(log2 f), whose leading bit is implied:
+//       q = (mulhi(m, x) + x) >> l
+//     Exact because the error term x * ((2^32 + m) * f - 2^(32+l)) <= x * f < f^2 * 2^20 <= 2^(32+l) for
+//     l <= 12; and x * (2^32 + m) stays below 2^64 (x / f < 2^20), so the sum does not overflow.
+//       .x = m   .y = thr   .z = (4096 - f) | l << 24   .w = cum
 // A symbol with f = 0 gets .w = 1 << 31, which is collected and reported if it occurs in the data.
 template <bool LONG>
 __device__ __forceinline__ uint4 make_enc_entry(uint32_t f, uint32_t cum) {
@@ -120,8 +123,7 @@ __device__ __forceinline__ uint4 make_enc_entry(uint32_t f, uint32_t cum) {
     const uint32_t n = (1u << l) - f;
     const uint32_t q1 = (n << 16) / f, r1 = (n << 16) - q1 * f;
     const uint32_t m = (q1 << 16) + (r1 << 16) / f + 1u;
-    const uint32_t sh1 = l < 1 ? l : 1u, sh2 = l > 1 ? l - 1u : 0u;
-    return make_uint4(m, thr, (kScale - f) | (sh2 << 24), (cum & 0xfffu) | (sh1 << 24));
+    return make_uint4(m, thr, (kScale - f) | (l << 24), cum & 0xfffu);
   }
   if (f == 1) return make_uint4(0xffffffffu, thr, kScale - 1u, (cum & 0xfffu) + (kScale - 1u));
   // ceil(2^(32+s) / f), s = l - 1, as 2^32 * 2^s / f: again two divisions with small numerators
@@ -154,10 +156,8 @@ __device__ __forceinline__ void enc_step(uint32_t &x, const uint4 e, uint16_t *&
   wtop += __builtin_popcount(m32);
   uint32_t xn;
   if (LONG) {
-    const uint32_t t1 = __umulhi(e.x, x);
-    const uint32_t d = (x - t1) >> ((e.w >> 24) & 31u);
-    const uint32_t q = (t1 + d) >> (e.z >> 24);
-    xn = __umul24(q, e.z) + (x + (e.w & 0xffffu));
+    const uint32_t q = (__umulhi(e.x, x) + x) >> (e.z >> 24);
+    xn = __umul24(q, e.z) + (x + e.w);
   } else {
     const uint32_t q = __umulhi(e.x, x) >> (e.z >> 24);
     xn = __umul24(q, e.z) + (x + e.w);
@@ -198,13 +198,11 @@ __device__ __forceinline__ void enc_step_pinned(uint32_t &x, const uint4 e, uint
   PLC_PIN();
   uint32_t q, xc;
   if (LONG) {
-    const uint32_t d = (xr - t1) >> ((e.w >> 24) & 31u);
-    q = (t1 + d) >> (e.z >> 24);
-    xc = xr + (e.w & 0xffffu);
+    q = (t1 + xr) >> (e.z >> 24);
   } else {
     q = t1 >> (e.z >> 24);
-    xc = xr + e.w;
   }
+  xc = xr + e.w;
   PLC_PIN();
   slot = emit ? slot : scratch;
   PLC_PIN();
@@ -473,16 +471,8 @@ __device__ __forceinline__ void pipe_step(uint32_t &x, const uint4 e) {
   const bool emit = x > e.y;
   const uint32_t xr = emit ? x >> 16 : x;
   const uint32_t t1 = __umulhi(e.x, xr);
-  uint32_t q, xc;
-  if (LONG) {
-    const uint32_t d = (xr - t1) >> ((e.w >> 24) & 31u);
-    q = (t1 + d) >> (e.z >> 24);
-    xc = xr + (e.w & 0xffffu);
-  } else {
-    q = t1 >> (e.z >> 24);
-    xc = xr + e.w;
-  }
-  x = __umul24(q, e.z) + xc;
+  const uint32_t q = (LONG ? t1 + xr : t1) >> (e.z >> 24);
+  x = __umul24(q, e.z) + (xr + e.w);
 }
 
 // One batch of the coder.  Entries are fetched kAhead steps before their use, so that the LDS round
