@@ -206,7 +206,7 @@ def main():
 
     fused = not args.two_call_decode
     # whether the single decode call runs its one-kernel form for this shape (see include/plc.h)
-    one_kernel = fused and args.chunk_syms == 0 and w.k <= 8 and w.n_streams <= 512
+    one_kernel = fused and args.chunk_syms == 0 and w.k <= 8
 
     def step(marks=None):
         if marks:

@@ -201,13 +201,13 @@ int plc_reconstruct(const plc_dims *dims, const void *cand_k, const void *cand_v
  * plc_rans_decode followed by plc_reconstruct, as one call (the decode side of
  * Sec. 7.2 as a whole: entropy-decode the residual symbols, dequantise, add back
  * the prediction).  Results -- symbols, out_k, out_v, status -- are those of the
- * two calls, bit for bit.  With one rANS unit per stream (chunk_syms = 0), at
- * most 512 streams and k <= 8 the reconstruction runs inside the entropy
- * decoder: a unit's symbols come out in stream order, so a further wavefront
- * of the unit's workgroup turns each batch of them into KV components while
- * the next batch is being decoded, with the candidates it needs requested
- * ahead of time; the escaped components are then overwritten from the escape
- * lists.  For every other shape the call simply makes the two calls.
+ * two calls, bit for bit.  With one rANS unit per stream (chunk_syms = 0) and
+ * k <= 8 the reconstruction runs inside the entropy decoder: a unit's symbols
+ * come out in stream order, so a further wavefront of the unit's workgroup
+ * turns each batch of them into KV components while the next batch is being
+ * decoded, with the candidates it needs requested ahead of time and the
+ * escaped components taken from the escape lists.  For every other shape the
+ * call simply makes the two calls.
  * Arguments as in plc_rans_decode (n_streams = S*L*H and syms_per_stream =
  * 2*n*d follow from dims) and plc_reconstruct; symbols is an output here.
  */

@@ -464,7 +464,11 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
 constexpr int kEntrySlots = 3;  // feeder writes b+1, coder reads b, packer reads b-1
 constexpr int kStateSlots = 2;  // coder writes b, packer reads b-1
 constexpr int kIdentity = PLC_MAX_BITS * 256;  // table index of the entry that leaves a state unchanged
-constexpr int64_t kPipeMaxUnits = 512;
+// These kernels hold two units per compute unit (LDS), 512 at a time, and a unit's time is that of its chain:
+// up to two rounds they beat the many-unit kernels (768 units: encode 1.7 against 2.8 ms, decode 3.3 against
+// 4.9 ms), at three they tie with them.
+constexpr int64_t kPipeMaxUnits = 1024;
+constexpr int64_t kChainMaxUnits = 1024;  // the same bound for the decoders of whole-stream units
 
 template <bool LONG>
 __device__ __forceinline__ void pipe_step(uint32_t &x, const uint4 e) {
@@ -1836,10 +1840,10 @@ struct LaunchEncode {
 template <int W>
 struct LaunchDecode {
   static void run(const RansArgs &a, unsigned grid, hipStream_t st) {
-    // One unit per stream and no more units than the chip has compute-unit halves: time is the length of one
-    // unit's chain, so take the variant with the shortest step.  With more units its 60 KB of LDS per
-    // wavefront would cost more in occupancy than the shorter step gains.
-    if (a.bits && W == 1 && a.n_units <= 512) {
+    // One unit per stream and few enough units (kChainMaxUnits): time is the length of one unit's chain,
+    // so take the variant with the shortest step.  With more units its 60 KB of LDS per workgroup would
+    // cost more in occupancy than the shorter step gains.
+    if (a.bits && W == 1 && a.n_units <= kChainMaxUnits) {
       const size_t lds = (size_t)a.n_tables * kDepthTableBytes + (size_t)(kRingWords + kRingMirror) * sizeof(uint32_t);
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1849,7 +1853,7 @@ struct LaunchDecode {
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_kernel<W, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipLaunchKernelGGL((rans_decode_kernel<W, true>), dim3(grid), dim3(W * 64), lds, st, a);
-    } else if (W == 1 && a.n_units <= 512) {
+    } else if (W == 1 && a.n_units <= kChainMaxUnits) {
       hipLaunchKernelGGL((rans_decode_chain_kernel<0, false>), dim3(grid), dim3(128), 0, st, a);
     } else {
       // Many units: LDS decides how many wavefronts fit a compute unit, and the split table lets more in
@@ -1906,9 +1910,8 @@ int encode_impl(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stre
   {
     TraceScope trace(PLC_TRACE_RANS_ENCODE, st);
     if (a.units_per_stream == 1 && a.n_units <= kPipeMaxUnits) {
-      // no more units than compute-unit halves: the chain of one unit is the time, so give each unit three
-      // wavefronts (with more units, three wavefronts per unit cost more in occupancy than the shorter
-      // chain gains)
+      // few units (kPipeMaxUnits): the chain of one unit is the time, so give each unit three wavefronts
+      // (with more units, three wavefronts per unit cost more in occupancy than the shorter chain gains)
       if (a.bits) {
         hipLaunchKernelGGL(rans_encode_pipe_kernel<true>, dim3((unsigned)a.n_units), dim3(192), 0, st, a);
       } else {
@@ -1949,9 +1952,12 @@ int decode_impl(const uint16_t *freq, const uint32_t *states, const uint16_t *wo
 }  // namespace
 
 bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k) {
-  // the chain decoder's own condition (no more units than compute-unit halves), candidates that fit the
-  // registers of one wavefront kRecDepth batches deep, and whole chunks
-  return n_streams >= 1 && n_streams <= 512 && k >= 1 && k <= 8 && syms_per_stream >= kChunk &&
+  // Candidates that fit the registers of one wavefront kRecDepth batches deep, and whole chunks.  Any
+  // number of streams: a round of 512 workgroups takes its chain's time or the HBM time of its
+  // reconstruction, whichever is longer, and the two are of a size, so the kernel keeps up with the
+  // many-unit decoder followed by the reconstruction kernel however many rounds there are (5120 streams:
+  // 9.1 against 10.9 ms; 16,384 streams with k = 8: 32 against 42 ms).
+  return n_streams >= 1 && k >= 1 && k <= 8 && syms_per_stream >= kChunk &&
          syms_per_stream % kChunk == 0;
 }
 
