@@ -109,8 +109,9 @@ struct ReconView {
   uint64_t esc_len;
   const uint64_t *esc_off;
 };
-// Whether plc_rans.hip has a decoder that reconstructs as it goes for this many streams and candidates.
-bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k);
+// Whether plc_rans.hip has a decoder that reconstructs as it goes for this many streams and candidates
+// (cond: token-conditional prediction; per_depth: with one table per bit depth besides).
+bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k, bool cond, bool per_depth);
 // That decoder: plc_rans_decode with one unit per stream, plus out = prediction + symbol * delta for every
 // component, escapes from their lists.  With recon.bits: plc_rans_decode_bucketed with n_tables tables per
 // stream instead.  The weights must be in place on `st`.  With launch = false the arguments are checked and

@@ -824,7 +824,8 @@ int decode_and_reconstruct(const plc_dims *dims, const uint16_t *freq, const uin
   if (!aligned(symbols, 8) || !aligned(probs, 4) || !aligned(esc_off, 8)) return PLC_ERR_INVALID;
   if (!aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total) return PLC_ERR_INVALID;
   if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
-  if (chunk_syms != 0 || !decode_fused_supported(p.n_streams, p.syms_per_stream, dims->k)) {
+  if (chunk_syms != 0 ||
+      !decode_fused_supported(p.n_streams, p.syms_per_stream, dims->k, chosen != nullptr, bits != nullptr)) {
     const int rc = bits ? plc_rans_decode_bucketed(freq, states, words, words_len, word_off, n_words, p.n_streams,
                                                    p.syms_per_stream, chunk_syms, 2 * dims->d, dims->L * dims->H,
                                                    bits, n_tables, symbols, status, stream)

@@ -468,7 +468,10 @@ constexpr int kIdentity = PLC_MAX_BITS * 256;  // table index of the entry that 
 // up to two rounds they beat the many-unit kernels (768 units: encode 1.7 against 2.8 ms, decode 3.3 against
 // 4.9 ms), at three they tie with them.
 constexpr int64_t kPipeMaxUnits = 1024;
-constexpr int64_t kChainMaxUnits = 1024;  // the same bound for the decoders of whole-stream units
+constexpr int64_t kChainMaxUnits = 1024;  // the same bound for the decoder of whole-stream units
+// The decoder with one table per depth holds one unit per compute unit (its tables take 128 KB of LDS): two
+// rounds of 256 are what it may take before the many-unit decoder is as fast.
+constexpr int64_t kDepthsMaxUnits = 512;
 
 template <bool LONG>
 __device__ __forceinline__ void pipe_step(uint32_t &x, const uint4 e) {
@@ -1843,7 +1846,7 @@ struct LaunchDecode {
     // One unit per stream and few enough units (kChainMaxUnits): time is the length of one unit's chain,
     // so take the variant with the shortest step.  With more units its 60 KB of LDS per workgroup would
     // cost more in occupancy than the shorter step gains.
-    if (a.bits && W == 1 && a.n_units <= kChainMaxUnits) {
+    if (a.bits && W == 1 && a.n_units <= kDepthsMaxUnits) {
       const size_t lds = (size_t)a.n_tables * kDepthTableBytes + (size_t)(kRingWords + kRingMirror) * sizeof(uint32_t);
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1951,13 +1954,17 @@ int decode_impl(const uint16_t *freq, const uint32_t *states, const uint16_t *wo
 
 }  // namespace
 
-bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k) {
-  // Candidates that fit the registers of one wavefront kRecDepth batches deep, and whole chunks.  Any
-  // number of streams: a round of 512 workgroups takes its chain's time or the HBM time of its
-  // reconstruction, whichever is longer, and the two are of a size, so the kernel keeps up with the
-  // many-unit decoder followed by the reconstruction kernel however many rounds there are (5120 streams:
-  // 9.1 against 10.9 ms; 16,384 streams with k = 8: 32 against 42 ms).
-  return n_streams >= 1 && k >= 1 && k <= 8 && syms_per_stream >= kChunk &&
+bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k, bool cond, bool per_depth) {
+  // Candidates that fit the registers of one wavefront kRecDepth batches deep, and whole chunks.  As to
+  // the number of streams: 512 workgroups run at a time, and a round takes its chain's time or the HBM time
+  // of its reconstruction, whichever is longer.  With the weighted mean the two are of a size, so the kernel
+  // beats the many-unit decoder followed by the reconstruction kernel however many rounds there are (5120
+  // streams: 9.1 against 10.9 ms; 16,384 streams with k = 8: 32 against 42 ms).  The token-conditional
+  // reconstruction moves a quarter of the bytes, so there is little to hide and from some eight rounds on
+  // the many-unit decoder's shorter total wins (5120 streams: 8.2 against 6.6 ms): four rounds at most.
+  // With one table per depth a round is 256 workgroups, and the bound of that decoder applies.
+  const int64_t most = per_depth ? kDepthsMaxUnits : cond ? 2048 : INT64_MAX;
+  return n_streams >= 1 && n_streams <= most && k >= 1 && k <= 8 && syms_per_stream >= kChunk &&
          syms_per_stream % kChunk == 0;
 }
 
@@ -1969,7 +1976,8 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
   int waves = 1;
   int rc = check_common(n_streams, syms_per_stream, 0, &a, &waves);
   if (rc) return rc;
-  if (!decode_fused_supported(n_streams, syms_per_stream, recon.k)) return PLC_ERR_INVALID;
+  if (!decode_fused_supported(n_streams, syms_per_stream, recon.k, recon.chosen != nullptr, recon.bits != nullptr))
+    return PLC_ERR_INVALID;
   if (!symbols || !freq || !states || !word_off || !n_words || !status) return PLC_ERR_INVALID;
   if (words_len > 0 && !words) return PLC_ERR_INVALID;
   if (reinterpret_cast<uintptr_t>(freq) % 8 || reinterpret_cast<uintptr_t>(words) % 2) return PLC_ERR_INVALID;
