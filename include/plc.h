@@ -254,10 +254,11 @@ int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *c
 
 /* plc_rans_decode followed by plc_reconstruct_cond as one call, the way
  * plc_rans_decode_reconstruct stands for plc_rans_decode and plc_reconstruct:
- * same results, and under the same conditions one kernel, whose reconstructing
- * wavefront fetches each position's chosen index a round before it requests
- * that candidate (all k of them where a position has none).  chosen must be in
- * place on `stream` (plc_index_decode) before the call. */
+ * same results, and under the same conditions -- here also: at most 2048
+ * streams, beyond which the two calls are the faster -- one kernel, whose
+ * reconstructing wavefront fetches each position's chosen index a round before
+ * it requests that candidate (all k of them where a position has none).
+ * chosen must be in place on `stream` (plc_index_decode) before the call. */
 int plc_rans_decode_reconstruct_cond(const plc_dims *dims, const uint16_t *freq,
                                      const uint32_t *states, const uint16_t *words,
                                      uint64_t words_len, const uint64_t *word_off,
@@ -386,9 +387,9 @@ int plc_rans_decode_bucketed(const uint16_t *freq, const uint32_t *states, const
 
 /* plc_rans_decode_bucketed (syms_per_pos = 2d, streams_per_session = L*H) followed by
  * plc_reconstruct_adapt as one call, the way plc_rans_decode_reconstruct stands for
- * plc_rans_decode and plc_reconstruct: same results, and under the same conditions one kernel,
- * whose reconstructing wavefront fetches each position's depth with its chosen index.  chosen and
- * bits must be in place on `stream` before the call. */
+ * plc_rans_decode and plc_reconstruct: same results, and under the same conditions (here also: at
+ * most 512 streams) one kernel, whose reconstructing wavefront fetches each position's depth with
+ * its chosen index.  chosen and bits must be in place on `stream` before the call. */
 int plc_rans_decode_reconstruct_adapt(const plc_dims *dims, const uint16_t *freq,
                                       const uint32_t *states, const uint16_t *words,
                                       uint64_t words_len, const uint64_t *word_off,
