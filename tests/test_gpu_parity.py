@@ -460,3 +460,49 @@ def test_reconstruct_rounds_to_fp32_then_to_fp16(oracle, dev, k, cond):
     with np.errstate(over="ignore"):
         once = exact.astype(np.float16).view(np.uint16).ravel()
     assert (once != rk).all()
+
+
+def test_one_call_decode_equals_two_calls_on_random_shapes(dev):
+    """The decoder that reconstructs against the two kernels it replaces, on seeded random shapes: head
+    dimensions with whole, half and several rows per batch of 64 chunks, ragged ends, few and many
+    escapes, both candidate layouts, and with and without a chosen candidate per position."""
+    rng = np.random.default_rng(20241)
+    for trial in range(14):
+        k = int(rng.integers(1, 9))
+        d = int(rng.choice([8, 16, 24, 40, 64, 72, 128, 256, 264, 512, 520]))
+        n = int(rng.integers(1, max(2, 6000 // d)))
+        S, L, H = int(rng.integers(1, 3)), int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        layout = "lhnkd" if trial % 2 == 0 else "lnkhd"
+        sigma = float(rng.choice([0.02, 0.05, 0.6, 2.5]))
+        print(f"trial {trial}: S{S} L{L} H{H} n{n} k{k} d{d} {layout} sigma {sigma}", flush=True)
+        w = make_workload("tiny", device=dev, layout=layout, random_rows=True,
+                          overrides=dict(S=S, L=L, H=H, n=n, k=k, d=d, sigma=sigma, seed=1000 + trial))
+        codec = codec_for(w, esc_frac=1.0)
+        ones = [torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)]
+        twos = [torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)]
+        # weighted mean
+        coded = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v)
+        codec.check_status("encode")
+        codec.decode(w.cand_k, w.cand_v, w.probs, *ones)
+        codec.check_status("decode")
+        assert torch.equal(codec.dec_symbols, coded.symbols)
+        codec.dec_symbols.zero_()
+        codec.decode(w.cand_k, w.cand_v, w.probs, *twos, fused=False)
+        codec.check_status("decode in two calls")
+        assert torch.equal(codec.dec_symbols, coded.symbols)
+        for a, b in zip(ones, twos):
+            assert np.array_equal(u16(a), u16(b)), f"trial {trial}"
+        # token-conditional, a fifth of the positions without a candidate
+        ch = w.chosen.to(torch.int32).clone()
+        g = torch.Generator(device=ch.device).manual_seed(trial)
+        ch[torch.rand(ch.shape, generator=g, device=ch.device) < 0.2] = -1
+        coded = codec.encode_cond(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen=ch.contiguous())
+        codec.check_status("encode_cond")
+        codec.decode_cond(w.cand_k, w.cand_v, w.probs, *ones)
+        codec.check_status("decode_cond")
+        assert torch.equal(codec.dec_symbols, coded.symbols)
+        codec.dec_symbols.zero_()
+        codec.decode_cond(w.cand_k, w.cand_v, w.probs, *twos, fused=False)
+        codec.check_status("decode_cond in two calls")
+        for a, b in zip(ones, twos):
+            assert np.array_equal(u16(a), u16(b)), f"trial {trial} (token-conditional)"
