@@ -116,21 +116,22 @@ class KernelTimer:
         return out
 
 
-def measured_traffic(kernel, config_name, k):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when there
-    is none for this workload or the kernel's sources have changed since the counters were taken."""
+def measured_traffic(kernel, config_name):
+    """HBM bytes per launch of `kernel` (its name as the profiler prints it, template arguments included)
+    from the committed rocprofv3 counter summary, or None when there is none for this workload or the
+    kernels' sources have changed since the counters were taken."""
     import hashlib
     import re
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{config_name}.txt")
     if not os.path.exists(path):
         return None
     h = hashlib.sha256()
-    for f in ("plc_predict.hip", "plc_device.h"):
+    for f in ("plc_predict.hip", "plc_rans.hip", "plc_hist_freq.hip", "plc_device.h"):
         with open(os.path.join(ROOT, "paper_2604_15356_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     for line in open(path):
-        m = re.match(r"machine-readable: kernel=(\S+) traffic_bytes_per_launch=(\d+) source_sha256=(\w+)", line)
-        if m and m.group(1) == f"{kernel}<{k}>" and m.group(3) == h.hexdigest():
+        m = re.match(r"machine-readable: kernel=(.+) traffic_bytes_per_launch=(\d+) source_sha256=(\w+)", line)
+        if m and m.group(1) == kernel and m.group(3) == h.hexdigest():
             return int(m.group(2))
     return None
 
@@ -275,12 +276,21 @@ def main():
         log(f"  {name:18s} {t:9.4f} ms  {gbs:8.1f} GB/s algorithmic  {100 * gbs / HBM_PEAK_GBS:5.1f} % of HBM peak")
     log(f"  step (encode+decode) {ms_per_step:9.4f} ms   kernels sum {sum(ms.values()):.4f} ms;  encode {encode_ms:.4f} ms "
         f"({w.kv_bytes / encode_ms / 1e6:.1f} GB/s of KV), decode {decode_ms:.4f} ms ({w.kv_bytes / decode_ms / 1e6:.1f} GB/s)")
-    dom = kernels["predict_residual"]
-    roofline = dict(bound="hbm", kernel="predict_residual_kernel", achieved=dom["GBs"], peak=HBM_PEAK_GBS,
+    # The roofline object describes the kernel a step spends most time in.  All of them are priced against
+    # HBM: the step holds no contraction, and the entropy coder's chains have no tighter ceiling to name.
+    symbol = {"predict_residual": f"predict_residual_kernel<{w.k}>", "reconstruct": f"reconstruct_kernel<{w.k}, false>",
+              "histogram": "histogram_kernel", "rans_encode": "rans_encode_pipe_kernel<false>",
+              "rans_decode": "rans_decode_chain_kernel<0, false>",
+              "rans_decode_reconstruct": f"rans_decode_chain_kernel<{w.k}, false>"}
+    dom_name = max(ms, key=ms.get)
+    dom = kernels[dom_name]
+    whole_streams = args.layout == "lhnkd" and not args.sessions and args.chunk_syms == 0
+    roofline = dict(bound="hbm", kernel=symbol[dom_name], achieved=dom["GBs"], peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=dom["frac_hbm"],
-                    traffic=measured_traffic("predict_residual_kernel", args.config, w.k)
-                    if (args.layout == "lhnkd" and not args.sessions) else None,
-                    bytes_per_component=2 * w.k + 3, components=E)
+                    traffic=measured_traffic(symbol[dom_name], args.config) if whole_streams else None,
+                    bytes_per_launch=int(alg_bytes[dom_name]), components=E)
+    for name, kd in kernels.items():
+        kd["traffic"] = measured_traffic(symbol[name], args.config) if whole_streams else None
 
     result = {
         "metric": "fp16 KV GB/s delta-coded (encode+decode)", "value": round(value, 2), "unit": "GB/s",
