@@ -1081,21 +1081,21 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   uint4 cv[kRecDepth][RK];
   float wv[kRecDepth][RK];
   typedef __attribute__((address_space(1))) u32x4 *global_u32x4;  // named global: kept through the loop
-  typedef __attribute__((address_space(1))) uint16_t *global_u16;
   global_u32x4 dst[kRecDepth];
   bool live[kRecDepth];  // whether the lane's chunk exists (a flag of its own: the pointer stays a global one)
   // Escapes.  This wavefront sees every chunk of the stream in order, so the number of escapes in front
-  // of a chunk is a running count plus a prefix over the lanes.  The raw values are requested from the
-  // stream's list when the chunk is stored and written over its escaped components the next time the
-  // same registers come round, kRecDepth batches later (memory operations of a wavefront complete in
-  // the order of issue, so by the time a value has arrived the chunk's own store has landed).
-  uint32_t esc_bits[kRecDepth];  // which components of the chunk at esc_dst await their raw value
+  // of a chunk is a running count plus a prefix over the lanes.  A chunk with escapes is not stored when
+  // its symbols arrive: its raw values are requested from the stream's list, the chunk is held, and the
+  // next time the same registers come round, kRecDepth batches later, the values that have arrived are
+  // put over its escaped components and the chunk is stored, once and whole.
+  uint32_t esc_bits[kRecDepth];  // which components of the chunk held for esc_dst await their raw value
   uint32_t esc_raw[kRecDepth][kChunk];
+  u32x4 esc_held[kRecDepth];
   global_u32x4 esc_dst[kRecDepth];
   const uint64_t esc_base = r.esc_off[stream];
   uint32_t esc_seen = 0;  // escapes of the stream so far
 #pragma unroll
-  for (int j = 0; j < kRecDepth; ++j) esc_bits[j] = 0u, esc_dst[j] = nullptr;
+  for (int j = 0; j < kRecDepth; ++j) esc_bits[j] = 0u, esc_dst[j] = nullptr, esc_held[j] = u32x4{0u, 0u, 0u, 0u};
   // Loads of the lane's next chunk (of its last one again once the stream is at its end, so that every
   // batch issues the same loads), then on to the chunk after it.
   auto load_weights = [&](float(&w)[RK]) {
@@ -1172,19 +1172,24 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
       if (at_chunk < n_chunks) point(row, e8);
     }
   };
-  // the raw values that have arrived for the chunk at `out`: over its escaped components, lowest first
-  auto patch = [&](global_u32x4 out, uint32_t &bits, const uint32_t (&raw)[kChunk]) {
+  // the raw values that have arrived for the chunk held for `out`: over its escaped components, lowest
+  // first (component e is half e & 1 of word e >> 1), then the chunk goes out
+  auto patch = [&](global_u32x4 out, uint32_t &bits, const uint32_t (&raw)[kChunk], u32x4 &held) {
     if (__ballot(bits != 0u) == 0) return;  // uniform
-    global_u16 comp = (global_u16)out;
+    const bool pending = bits != 0u;
 #pragma unroll
     for (int i = 0; i < kChunk; ++i) {
       if (i > 0 && __ballot(bits != 0u) == 0) break;  // uniform; seldom more than one per chunk
       if (bits) {
-        const int e = __builtin_ctz(bits);
+        const uint32_t e = (uint32_t)__builtin_ctz(bits);
         bits &= bits - 1u;
-        comp[e] = (uint16_t)raw[i];
+        const uint32_t shift = (e & 1u) * 16u, keep = ~(0xffffu << shift), value = (raw[i] & 0xffffu) << shift;
+#pragma unroll
+        for (uint32_t word = 0; word < 4; ++word)
+          held[word] = (e >> 1) == word ? (held[word] & keep) | value : held[word];
       }
     }
+    if (pending) __builtin_nontemporal_store(held, out);
   };
   if constexpr (COND) {
 #pragma unroll
@@ -1201,7 +1206,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   // One batch: join its barrier, take its symbols from the stage, finish the chunk, request the chunk
   // of the batch kRecDepth later into the registers just freed.
   auto turn = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, uint32_t &bits,
-                  uint32_t(&raw)[kChunk], global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
+                  uint32_t(&raw)[kChunk], u32x4 &held, global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
                   uint32_t &depth_nx, uint32_t &depth_us, int32_t b, bool whole) {
     // (the scheduler would otherwise start on the predictions of all kRecDepth batches at the top of a
     // pass, and so wait there for requests that have only just gone out)
@@ -1211,7 +1216,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
     const uint2 sv = *reinterpret_cast<const uint2 *>(&sym_stage[b & 1][lane * kChunk]);
-    patch(late, bits, raw);
+    patch(late, bits, raw, held);
     float pred[kChunk];
     if (!COND || mean) {  // uniform
 #pragma unroll
@@ -1228,16 +1233,17 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
     const float step = ADAPT ? __builtin_ldexpf(r.range, -(int)depth_us) : r.delta;
     const half8 v = add_back8(sv, step, pred, &unused);
     const bool mine = whole || ok;
-    if (mine) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), out);
     // a byte is 0xff iff its low seven bits carry into bit 7 when 1 is added and bit 7 is set
     const uint32_t hx = ((sv.x & 0x7f7f7f7fu) + 0x01010101u) & sv.x & 0x80808080u;
     const uint32_t hy = ((sv.y & 0x7f7f7f7fu) + 0x01010101u) & sv.y & 0x80808080u;
     const bool has = mine && (hx | hy) != 0u;
+    if (mine && !has) __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), out);
     const uint64_t lanes = __ballot(has);
     if (lanes != 0) {  // uniform
       // bit 7 of byte e to bit e
       const uint32_t mx = ((hx >> 7) * 0x00204081u) >> 21 & 0xfu, my = ((hy >> 7) * 0x00204081u) >> 21 & 0xfu;
       bits = has ? (mx | (my << 4)) : 0u;
+      held = __builtin_bit_cast(u32x4, v);
       late = out;
       const uint32_t n_esc = (uint32_t)__builtin_popcount(bits);
       const bool several = __ballot(n_esc > 1u) != 0;  // uniform; seldom
@@ -1271,17 +1277,17 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   for (; b0 + kRecDepth <= n_full; b0 += kRecDepth) {
 #pragma unroll
     for (int j = 0; j < kRecDepth; ++j)
-      turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
+      turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_held[j], esc_dst[j], pick_next[j], pick_used[j],
            mean_path[j], depth_next[j], depth_used[j], b0 + j, true);
   }
   // What is left: fewer than kRecDepth whole batches and possibly a partial one.
 #pragma unroll
   for (int j = 0; j < kRecDepth; ++j)
     if (b0 + j < n_batches)  // uniform
-      turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_dst[j], pick_next[j], pick_used[j],
+      turn(cv[j], wv[j], dst[j], live[j], esc_bits[j], esc_raw[j], esc_held[j], esc_dst[j], pick_next[j], pick_used[j],
            mean_path[j], depth_next[j], depth_used[j], b0 + j, false);
 #pragma unroll
-  for (int j = 0; j < kRecDepth; ++j) patch(esc_dst[j], esc_bits[j], esc_raw[j]);
+  for (int j = 0; j < kRecDepth; ++j) patch(esc_dst[j], esc_bits[j], esc_raw[j], esc_held[j]);
 }
 
 // ---------------------------------------------------------------------------
