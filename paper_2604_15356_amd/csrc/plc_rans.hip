@@ -767,15 +767,17 @@ __global__ __launch_bounds__(192) void rans_encode_pipe_kernel(const RansArgs a)
 constexpr int kRingWords = 2048, kBlockWords = 512, kRingMirror = kBlockWords + 32;
 
 // COMPACT: the slot table is split in two, slot -> symbol (one byte per slot) and symbol -> f - 1 | cum << 16,
-// 5 KB instead of 16 KB per stream at the price of a second dependent lookup.
+// 5 KB instead of 16 KB per table at the price of a second dependent lookup.
+constexpr uint32_t kCompactTable = 256 + kScale / 4;  // in 32-bit words
 template <bool MASKED, bool COMPACT = false>
 __device__ __forceinline__ void dec_step(uint32_t &x, const uint32_t *lut, const uint16_t *&top, uint8_t *sym_slot,
                                          uint32_t below, bool on, uint32_t table_off = 0) {
   uint32_t e;
   if (COMPACT) {
     const uint32_t slot = x & (kScale - 1);
-    const uint32_t s = reinterpret_cast<const uint8_t *>(lut + 256)[slot];
-    const uint32_t fc = lut[s];
+    const uint32_t *mine = lut + table_off;
+    const uint32_t s = reinterpret_cast<const uint8_t *>(mine + 256)[slot];
+    const uint32_t fc = mine[s];
     e = s | ((fc & 0xfffu) << 8) | ((slot - (fc >> 16)) << 20);
   } else {
     e = lut[(x & (kScale - 1)) + table_off];
@@ -808,8 +810,7 @@ __device__ __forceinline__ void dec_step(uint32_t &x, const uint32_t *lut, const
 
 template <int W, bool ADAPT, bool COMPACT = false>
 __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
-  static_assert(!(ADAPT && COMPACT), "the split table is for the single-table streams");
-  __shared__ uint32_t lut_one[ADAPT ? 1 : (COMPACT ? 256 + kScale / 4 : kScale)];
+  __shared__ uint32_t lut_one[ADAPT ? 1 : (COMPACT ? kCompactTable : kScale)];
   extern __shared__ uint32_t lut_per_depth[];  // ADAPT: n_tables slot tables, sized at launch
   uint32_t *lut = ADAPT ? lut_per_depth : lut_one;
   __shared__ uint16_t table_of_group[ADAPT ? W : 1][2][kBatch];  // ADAPT: table offset of each group of a batch
@@ -847,18 +848,23 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
       uint32_t f[4], cum;
       const uint32_t total = load_freq4(a.freq + (stream * a.n_tables + t) * 256, lane, f, &cum);
       ok = ok && (total == kScale || total == 0);
-      uint32_t *lt = lut + t * kScale;
+      uint32_t *lt = lut + t * (COMPACT ? kCompactTable : (uint32_t)kScale);
       if (total == kScale) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int s = lane * 4 + r;
           if ((s & (W - 1)) == wave) {
-            for (uint32_t o = 0; o < f[r]; ++o) lt[cum + o] = (uint32_t)s | ((f[r] - 1u) << 8) | (o << 20);
+            if (COMPACT) {
+              lt[s] = ((f[r] - 1u) & 0xfffu) | (cum << 16);
+              for (uint32_t o = 0; o < f[r]; ++o) reinterpret_cast<uint8_t *>(lt + 256)[cum + o] = (uint8_t)s;
+            } else {
+              for (uint32_t o = 0; o < f[r]; ++o) lt[cum + o] = (uint32_t)s | ((f[r] - 1u) << 8) | (o << 20);
+            }
           }
           cum += f[r];
         }
       } else {
-        for (uint32_t o = threadIdx.x; o < kScale; o += W * 64) lt[o] = 0u;
+        for (uint32_t o = threadIdx.x; o < (COMPACT ? kCompactTable : (uint32_t)kScale); o += W * 64) lt[o] = 0u;
       }
     }
     if (threadIdx.x == 0) table_ok = ok;
@@ -939,7 +945,7 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
   auto group_load = [&](int32_t g0) -> uint32_t {
     const int32_t g = g0 + lane;
     if (!ADAPT || lane >= kBatch || g >= G) return 0u;
-    return group_table(a, stream, begin, g, kScale, &bad_depth);
+    return group_table(a, stream, begin, g, COMPACT ? kCompactTable : (uint32_t)kScale, &bad_depth);
   };
   if (ADAPT) {
     const uint32_t gt0 = group_load(0);
@@ -1858,10 +1864,11 @@ struct LaunchDecode {
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       hipLaunchKernelGGL(rans_decode_depths_kernel<0>, dim3(grid), dim3(128), lds, st, a);
     } else if (a.bits) {
-      const size_t lds = (size_t)a.n_tables * kScale * sizeof(uint32_t);
-      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_kernel<W, true>),
+      // (the split tables here too: 5 KB per depth instead of 16 lets three times the wavefronts in)
+      const size_t lds = (size_t)a.n_tables * kCompactTable * sizeof(uint32_t);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_kernel<W, true, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      hipLaunchKernelGGL((rans_decode_kernel<W, true>), dim3(grid), dim3(W * 64), lds, st, a);
+      hipLaunchKernelGGL((rans_decode_kernel<W, true, true>), dim3(grid), dim3(W * 64), lds, st, a);
     } else if (W == 1 && a.n_units <= kChainMaxUnits) {
       hipLaunchKernelGGL((rans_decode_chain_kernel<0, false>), dim3(grid), dim3(128), 0, st, a);
     } else {
