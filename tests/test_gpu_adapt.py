@@ -176,3 +176,52 @@ def test_bucketed_byte_streams_bit_exact(oracle, dev):
     bad[0, 5] = 7
     plc.plc_histogram_bucketed(sym, n_streams, N, spp, sps, bad, B, counts, status)
     assert int(status.item()) == plc.PLC_ERR_INVALID
+
+
+def test_bucketed_more_whole_streams_than_the_chain_decoder_takes(oracle, dev):
+    """Whole-stream units beyond the bound of the per-depth chain decoder: the many-unit kernels, one
+    wavefront per workgroup, with their split per-depth tables."""
+    O = oracle
+    from paper_2604_15356_amd import plc
+    rng = np.random.default_rng(13)
+    S, sps, n, spp = 41, 16, 21, 64                           # 656 streams of 1344 symbols
+    n_streams, N = S * sps, n * spp
+    bits_np = rng.integers(1, 5, (S, n)).astype(np.uint8)
+    bits_np[7] = 3                                            # a session with a single depth
+    bits_np[8, :] = np.where(np.arange(n) % 2 == 0, 1, 4)     # and one without the middle depths
+    width = 1.5 * 2.0 ** np.repeat(bits_np, spp, axis=1)
+    sym_np = np.empty((n_streams, N), dtype=np.uint8)
+    for st in range(n_streams):
+        sym_np[st] = np.clip(np.round(rng.standard_normal(N) * width[st // sps] + 127), 0, 254)
+    sym_np[5, ::97] = 255
+    sym = torch.from_numpy(sym_np).to(dev)
+    bits = torch.from_numpy(bits_np).to(dev)
+    B = plc.MAX_BITS
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    counts = torch.empty((n_streams, B, 256), dtype=torch.int32, device=dev)
+    freq = torch.empty((n_streams, B, 256), dtype=torch.int16, device=dev)
+    plc.plc_histogram_bucketed(sym, n_streams, N, spp, sps, bits, B, counts, status)
+    plc.plc_build_freq_bucketed(counts, n_streams, B, freq, status)
+    ref_freq = O.build_freq_sparse(O.histogram_bucketed(sym_np, spp, sps, bits_np, n_tables=B))
+    assert np.array_equal(u16(freq), ref_freq)
+    cap = (N + 7) // 8 * 8
+    states = torch.empty((n_streams, 32), dtype=torch.int32, device=dev)
+    words = torch.zeros(n_streams * cap, dtype=torch.int16, device=dev)
+    woff = torch.arange(n_streams, dtype=torch.int64, device=dev) * cap
+    nw = torch.empty(n_streams, dtype=torch.int32, device=dev)
+    dec = torch.zeros_like(sym)
+    print(f"  {n_streams} whole-stream units", flush=True)
+    plc.plc_rans_encode_bucketed(sym, n_streams, N, 0, spp, sps, bits, B, freq, states, words, woff, cap, nw, status)
+    plc.plc_rans_decode_bucketed(freq, states, words, woff, nw, n_streams, N, 0, spp, sps, bits, B, dec, status)
+    assert int(status.item()) == 0
+    assert torch.equal(dec, sym)
+    enc = O.rans_encode_bucketed(sym_np, ref_freq, spp, sps, bits_np, chunk_syms=0, word_cap_per_unit=cap)
+    assert np.array_equal(u32(nw), enc["n_words"]) and np.array_equal(u32(states), enc["states"])
+    wd = u16(words)
+    for unit in range(n_streams):
+        o, k_ = unit * cap, int(enc["n_words"][unit])
+        assert np.array_equal(wd[o:o + k_], enc["words"][o:o + k_]), f"unit {unit}"
+    # a damaged word list is reported, and decoding ends
+    words[woff[300] + 3] ^= 0x1555
+    plc.plc_rans_decode_bucketed(freq, states, words, woff, nw, n_streams, N, 0, spp, sps, bits, B, dec, status)
+    assert int(status.item()) == plc.PLC_ERR_CORRUPT
