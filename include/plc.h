@@ -336,6 +336,14 @@ int plc_index_decode(const float *probs, const uint32_t *states, const uint16_t 
  * or 1.  Integer comparisons only: encoder and decoder agree bit for bit.
  *   bits  out, u8 [S,n].
  */
+/* The thresholds of that comparison from the definition's two parameters (Def. "Surprisal-adaptive
+ * quantizer", Sec. 5.3: b0 the base depth, hbar the average surprisal in bits): thr[m] =
+ * floor(4096 * 2^(-m * hbar / b0)) in double precision for m = 2..bmax, thr[0] = thr[1] = 0.  Host call;
+ * thr is a HOST array of bmax + 1 entries.  PLC_ERR_INVALID unless b0, hbar > 0 and finite and
+ * 1 <= bmax <= PLC_MAX_BITS (the definition puts no upper limit on b_i; this library codes at most
+ * PLC_MAX_BITS depths and refuses more). */
+int plc_surprisal_thresholds(double b0, double hbar, int32_t bmax, uint16_t *thr /* host */);
+
 int plc_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n, int32_t k,
                        const uint16_t *thr /* host */, int32_t bmax, uint8_t *bits,
                        uint32_t *status, void *stream);

@@ -713,7 +713,21 @@ int plco_index_decode(const float *probs, const uint32_t *states, const uint16_t
  * for a miss).  floor(b0 * h / hbar) >= m  <=>  f <= 4096 * 2^(-m * hbar / b0),
  * so the depth is a count of integer comparisons against the thresholds
  * thr[m] = floor(4096 * 2^(-m * hbar / b0)), m = 2..bmax (thr[0], thr[1] unused),
- * which the caller derives from b0 and hbar. */
+ * which plco_surprisal_thresholds derives from b0 and hbar.  The definition has no
+ * upper limit on b_i; bmax is the caller's, up to what this file's arrays hold
+ * (PLCO_MAX_BITS). */
+int plco_surprisal_thresholds(double b0, double hbar, int32_t bmax, uint16_t *thr) {
+  if (!(b0 > 0.0) || !(hbar > 0.0) || bmax < 1 || bmax > PLCO_MAX_BITS || !thr) return PLCO_ERR_INVALID;
+  thr[0] = thr[1] = 0;
+  for (int m = 2; m <= bmax; ++m) {
+    double t = floor(4096.0 * pow(2.0, -(double)m * hbar / b0));
+    if (t < 0.0) t = 0.0;
+    if (t > 4096.0) t = 4096.0;
+    thr[m] = (uint16_t)t;
+  }
+  return PLCO_OK;
+}
+
 int plco_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n,
                         int32_t k, const uint16_t *thr, int32_t bmax, uint8_t *bits) {
   if (S < 0 || n < 1 || k < 1 || k > PLCO_MAX_K || bmax < 1 || bmax > PLCO_MAX_BITS)

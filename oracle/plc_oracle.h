@@ -204,7 +204,7 @@ int plco_index_decode(const float *probs, const uint32_t *states, const uint16_t
  * range * 2^-b_i (range: fp32 > 0, scaled exactly).  chosen as above (all -1
  * = weighted mean everywhere).  Symbols of positions with depth b are counted
  * and coded with the stream's table number b - 1. */
-#define PLCO_MAX_BITS 4
+#define PLCO_MAX_BITS 16 /* bound of this file's per-depth arrays; the definition itself has none */
 
 int plco_predict_residual_adapt(const plco_dims *dm, int mode,
                                 const uint16_t *cand_k, const uint16_t *cand_v,
@@ -224,6 +224,10 @@ int plco_reconstruct_adapt(const plco_dims *dm, int mode,
 
 /* Bit depth per position from the token's coded surprisal and integer
  * thresholds thr[2..bmax] (non-increasing): b = the largest m with f <= thr[m], else 1. */
+/* thr[m] = floor(4096 * 2^(-m * hbar / b0)) for m = 2..bmax; thr[0] = thr[1] = 0 (host array of
+ * bmax + 1 entries).  b0, hbar > 0. */
+int plco_surprisal_thresholds(double b0, double hbar, int32_t bmax, uint16_t *thr);
+
 int plco_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n,
                         int32_t k, const uint16_t *thr, int32_t bmax, uint8_t *bits);
 

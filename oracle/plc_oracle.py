@@ -96,6 +96,7 @@ def lib():
         L.plco_predict_residual_adapt.argtypes = [C.POINTER(Dims), C.c_int, p, p, p, p, p, C.c_float, p, p, p, p,
                                                   C.c_uint64, p, p, p, p]
         L.plco_reconstruct_adapt.argtypes = [C.POINTER(Dims), C.c_int, p, p, p, p, p, C.c_float, p, p, p, p, p, p]
+        L.plco_surprisal_thresholds.argtypes = [C.c_double, C.c_double, C.c_int32, p]
         L.plco_surprisal_bits.argtypes = [p, p, C.c_int32, C.c_int32, C.c_int32, p, C.c_int32, p]
         L.plco_histogram_bucketed.argtypes = [p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, p, C.c_int32, p]
         L.plco_build_freq_sparse.argtypes = [p, C.c_int64, p]
@@ -328,14 +329,15 @@ def index_decode(probs, states, words, word_off, n_words):
     return chosen
 
 
-MAX_BITS = 4
+MAX_BITS = 4          # default number of depths, the one the GPU library supports
+MAX_BITS_ORACLE = 16  # what the oracle's own per-depth arrays hold (the definition has no limit)
 
 
 def surprisal_thresholds(b0, hbar, bmax=MAX_BITS):
     """thr[m] = floor(4096 * 2^(-m * hbar / b0)) for m = 2..bmax (entries 0 and 1 unused)."""
     thr = np.zeros(bmax + 1, dtype=np.uint16)
-    for m in range(2, bmax + 1):
-        thr[m] = int(np.floor(4096.0 * 2.0 ** (-m * float(hbar) / float(b0))))
+    _check(lib().plco_surprisal_thresholds(C.c_double(float(b0)), C.c_double(float(hbar)), int(bmax), _ptr(thr)),
+           "surprisal_thresholds")
     return thr
 
 

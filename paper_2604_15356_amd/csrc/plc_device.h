@@ -124,12 +124,13 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
 // Escape bookkeeping for callers that produce or consume symbols outside the tile-structured kernels
 // (plc_predict.hip): collect the escaped components' raw fp16 values of `act` into the per-stream lists /
 // overwrite the escaped components of `out` from the lists.  dims->k and the candidate strides are not used.
+// With launch = false the arguments are checked and nothing is enqueued.
 int gather_escapes(const plc_dims *dims, const void *act_k, const void *act_v, const uint8_t *symbols,
                    uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, void *ws,
-                   size_t ws_bytes, uint32_t *status, hipStream_t st);
+                   size_t ws_bytes, uint32_t *status, hipStream_t st, bool launch = true);
 int patch_escapes(const plc_dims *dims, const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
                   const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes, uint32_t *status,
-                  hipStream_t st);
+                  hipStream_t st, bool launch = true);
 
 inline int launch_status() { return hipGetLastError() == hipSuccess ? PLC_OK : PLC_ERR_HIP; }
 

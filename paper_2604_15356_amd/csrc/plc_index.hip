@@ -6,6 +6,8 @@
 // The stream is tiny next to the residuals (one symbol per position against 2*L*H*d of them), but with
 // one session it is a single chain of n / 32 steps, so the per-position tables are prepared off the
 // chain; words go straight to global memory at positions ranked from the emission mask.
+#include <cmath>
+
 #include "plc_device.h"
 
 namespace plc {
@@ -328,6 +330,18 @@ extern "C" int plc_index_decode(const float *probs, const uint32_t *states, cons
   hipLaunchKernelGGL(index_decode_kernel, dim3((unsigned)S), dim3(256), 0, static_cast<hipStream_t>(stream), probs,
                      states, words, words_len, word_off, n_words, n, k, chosen, status);
   return launch_status();
+}
+
+extern "C" int plc_surprisal_thresholds(double b0, double hbar, int32_t bmax, uint16_t *thr) {
+  if (!(b0 > 0.0) || !(hbar > 0.0) || !(b0 < 1e300) || !(hbar < 1e300)) return PLC_ERR_INVALID;
+  if (bmax < 1 || bmax > PLC_MAX_BITS || !thr) return PLC_ERR_INVALID;
+  thr[0] = thr[1] = 0;
+  for (int m = 2; m <= bmax; ++m) {
+    // 4096 * 2^(-m * hbar / b0): the power of two scales the exponential exactly
+    const double t = std::floor(std::ldexp(std::exp2(-((double)m * hbar) / b0), 12 /* log2 of the probability scale */));
+    thr[m] = (uint16_t)(t < 0.0 ? 0.0 : t > 4096.0 ? 4096.0 : t);
+  }
+  return PLC_OK;
 }
 
 extern "C" int plc_surprisal_bits(const float *probs, const int32_t *chosen, int32_t S, int32_t n, int32_t k,

@@ -589,6 +589,11 @@ extern "C" int plc_predict_residual_linear(const plc_dims *dims, const void *eba
   if (!aligned16(ebar) || !aligned16(A) || !aligned16(bias_k) || !aligned16(bias_v) || !aligned16(act_k) ||
       !aligned16(act_v) || !aligned16(symbols))
     return PLC_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // the escape pass's own checks (lists, workspace, status) before the contraction is enqueued
+  if (int rc = gather_escapes(dims, act_k, act_v, symbols, esc_vals, esc_cap, esc_cnt, esc_off, ws, ws_bytes, status,
+                              st, false))
+    return rc;
   const int N = 2 * dims->H * dims->d;
   EncodeLinear ep{coord_of(dims),
                   static_cast<const _Float16 *>(bias_k),
@@ -598,7 +603,6 @@ extern "C" int plc_predict_residual_linear(const plc_dims *dims, const void *eba
                   symbols,
                   dims->delta,
                   (float)dims->qmax};
-  hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_PREDICT_LINEAR, st);
     launch_gemm(dims->n, N, dims->S * dims->L, st, static_cast<const _Float16 *>(ebar),
@@ -616,6 +620,9 @@ extern "C" int plc_reconstruct_linear(const plc_dims *dims, const void *ebar, in
   if (!aligned16(ebar) || !aligned16(A) || !aligned16(bias_k) || !aligned16(bias_v) || !aligned16(out_k) ||
       !aligned16(out_v) || !aligned16(symbols))
     return PLC_ERR_INVALID;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (int rc = patch_escapes(dims, symbols, esc_vals, esc_len, esc_off, out_k, out_v, ws, ws_bytes, status, st, false))
+    return rc;
   const int N = 2 * dims->H * dims->d;
   DecodeLinear ep{coord_of(dims),
                   static_cast<const _Float16 *>(bias_k),
@@ -624,7 +631,6 @@ extern "C" int plc_reconstruct_linear(const plc_dims *dims, const void *ebar, in
                   static_cast<_Float16 *>(out_v),
                   symbols,
                   dims->delta};
-  hipStream_t st = static_cast<hipStream_t>(stream);
   {
     TraceScope trace(PLC_TRACE_RECONSTRUCT_LINEAR, st);
     launch_gemm(dims->n, N, dims->S * dims->L, st, static_cast<const _Float16 *>(ebar),

@@ -725,13 +725,14 @@ int decode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
 
 int plc::gather_escapes(const plc_dims *dims, const void *act_k, const void *act_v, const uint8_t *symbols,
                         uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, void *ws,
-                        size_t ws_bytes, uint32_t *status, hipStream_t st) {
+                        size_t ws_bytes, uint32_t *status, hipStream_t st, bool launch) {
   Plan p;
   if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
   if (!aligned(act_k, 16) || !aligned(act_v, 16) || !aligned(symbols, 8) || !aligned(esc_cnt, 4) ||
       !aligned(esc_off, 8) || !aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total)
     return PLC_ERR_INVALID;
   if (esc_cap > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
+  if (!launch) return PLC_OK;
   CodecArgs a = {};
   fill_args(dims, p, ws, &a);
   a.act_k = static_cast<const uint16_t *>(act_k);
@@ -752,13 +753,14 @@ int plc::gather_escapes(const plc_dims *dims, const void *act_k, const void *act
 
 int plc::patch_escapes(const plc_dims *dims, const uint8_t *symbols, const uint16_t *esc_vals, uint64_t esc_len,
                        const uint64_t *esc_off, void *out_k, void *out_v, void *ws, size_t ws_bytes,
-                       uint32_t *status, hipStream_t st) {
+                       uint32_t *status, hipStream_t st, bool launch) {
   Plan p;
   if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
   if (!aligned(out_k, 16) || !aligned(out_v, 16) || !aligned(symbols, 8) || !aligned(esc_off, 8) ||
       !aligned(status, 4) || !aligned(ws, 256) || ws_bytes < p.total)
     return PLC_ERR_INVALID;
   if (esc_len > 0 && !aligned(esc_vals, 2)) return PLC_ERR_INVALID;
+  if (!launch) return PLC_OK;
   CodecArgs a = {};
   fill_args(dims, p, ws, &a);
   a.out_k = static_cast<uint16_t *>(out_k);

@@ -26,7 +26,7 @@ EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_
            "plc_trace_kernel_events",
            "plc_predict_residual_cond", "plc_reconstruct_cond", "plc_select_candidate",
            "plc_index_encode", "plc_index_decode",
-           "plc_surprisal_bits", "plc_predict_residual_adapt", "plc_reconstruct_adapt",
+           "plc_surprisal_thresholds", "plc_surprisal_bits", "plc_predict_residual_adapt", "plc_reconstruct_adapt",
            "plc_histogram_bucketed", "plc_build_freq_bucketed", "plc_rans_encode_bucketed",
            "plc_rans_decode_bucketed",
            "plc_expected_embedding", "plc_predict_residual_linear", "plc_reconstruct_linear",
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         L.plc_select_candidate.argtypes = [dp, p, p, C.c_float, p, p]
         L.plc_index_encode.argtypes = [p, p, i32, i32, i32, p, p, p, u64, p, p, p]
         L.plc_index_decode.argtypes = [p, p, p, u64, p, p, i32, i32, i32, p, p, p]
+        L.plc_surprisal_thresholds.argtypes = [C.c_double, C.c_double, i32, C.POINTER(C.c_uint16)]
         L.plc_surprisal_bits.argtypes = [p, p, i32, i32, i32, C.POINTER(C.c_uint16), i32, p, p, p]
         L.plc_predict_residual_adapt.argtypes = [dp, p, p, p, p, p, C.c_float, p, p, p, p, u64, p, p, p, p, sz, p, p]
         L.plc_reconstruct_adapt.argtypes = [dp, p, p, p, p, p, C.c_float, p, p, u64, p, p, p, p, sz, p, p]
@@ -297,10 +298,14 @@ def plc_index_decode(probs, states, words, word_off, n_words, S, n, k, chosen, s
     _check(rc, "plc_index_decode")
 
 
-def surprisal_thresholds(b0, hbar, bmax=MAX_BITS):
-    """Host helper: thr[m] = floor(4096 * 2^(-m * hbar / b0)), m = 2..bmax (entries 0, 1 unused)."""
-    import math
-    return [0, 0] + [int(math.floor(4096.0 * 2.0 ** (-m * float(hbar) / float(b0)))) for m in range(2, bmax + 1)]
+def plc_surprisal_thresholds(b0, hbar, bmax=MAX_BITS):
+    """Host call: the bmax + 1 thresholds (entries 0, 1 unused) that plc_surprisal_bits compares with."""
+    arr = (C.c_uint16 * (int(bmax) + 1))()
+    _check(lib().plc_surprisal_thresholds(float(b0), float(hbar), int(bmax), arr), "plc_surprisal_thresholds")
+    return list(arr)
+
+
+surprisal_thresholds = plc_surprisal_thresholds
 
 
 def plc_surprisal_bits(probs, chosen, S, n, k, thr, bits, status):

@@ -142,6 +142,38 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert L.plc_reconstruct_linear(C.byref(lin), p, 128, p, p, p, p, p, 0, p, p, p, p, 1 << 20, p, None) == 1
     lin = plc.make_dims(1, 2, 2, 128, 1, 32, 0.02)
     assert L.plc_reconstruct_linear(C.byref(lin), p, 100, p, p, p, p, p, 0, p, p, p, p, 1 << 20, p, None) == 1
+    # null pointers anywhere, a missing status word or a workspace that is too small: refused on the host,
+    # before the contraction is enqueued
+    pl, rl = L.plc_predict_residual_linear, L.plc_reconstruct_linear
+    assert L.plc_expected_embedding(None, p, 128, 64, 128, p, None) == 1
+    assert L.plc_expected_embedding(p, None, 128, 64, 128, p, None) == 1
+    assert L.plc_expected_embedding(p, p, 128, 64, 128, None, None) == 1
+    big = 1 << 24
+    for hole in range(1, 15):
+        if hole in (2, 10, 14):                 # m, esc_cap, ws_bytes: not pointers
+            continue
+        args = [C.byref(lin), p, 128, p, p, p, p, p, p, p, 0, p, p, p, big, p]
+        args[hole] = None
+        want = 0 if hole == 9 else 1             # an empty escape list needs no storage
+        if want:
+            assert pl(*args, None) == 1, hole
+    assert pl(C.byref(lin), p, 128, p, p, p, p, p, p, p, 0, p, p, p, big, None, None) == 1      # no status word
+    assert pl(C.byref(lin), p, 128, p, p, p, p, p, p, p, 0, p, p, p, 16, p, None) == 1          # workspace too small
+    assert pl(C.byref(lin), p, 128, p, p, p, p, p, p, None, 8, p, p, p, big, p, None) == 1      # list without storage
+    for hole in (1, 3, 4, 5, 6, 9, 10, 11, 12):
+        args = [C.byref(lin), p, 128, p, p, p, p, p, 0, p, p, p, p, big, p]
+        args[hole] = None
+        assert rl(*args, None) == 1, hole
+    assert rl(C.byref(lin), p, 128, p, p, p, p, p, 0, p, p, p, p, big, None, None) == 1
+    assert rl(C.byref(lin), p, 128, p, p, p, p, p, 0, p, p, p, p, 16, p, None) == 1
+    assert rl(C.byref(lin), p, 128, p, p, p, p, None, 8, p, p, p, p, big, p, None) == 1
+    # thresholds of the adaptive quantiser (host call)
+    out = (C.c_uint16 * 5)()
+    assert L.plc_surprisal_thresholds(3.0, 3.9, 4, out) == 0 and list(out)[:2] == [0, 0]
+    assert L.plc_surprisal_thresholds(0.0, 3.9, 4, out) == 1
+    assert L.plc_surprisal_thresholds(3.0, float("nan"), 4, out) == 1
+    assert L.plc_surprisal_thresholds(3.0, 3.9, 5, out) == 1                     # beyond PLC_MAX_BITS
+    assert L.plc_surprisal_thresholds(3.0, 3.9, 4, None) == 1
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):

@@ -46,8 +46,9 @@ def test_adaptive_encode_decode_matches_oracle(oracle, dev, case):
     chosen = w.chosen.to(torch.int32).clone()
     chosen[:, 3::11] = -1                                   # some declared misses on top of the generator's
     ch = chosen.cpu().numpy()
-    thr = plc.surprisal_thresholds(b0, hbar)
-    assert list(thr) == list(O.surprisal_thresholds(b0, hbar))
+    thr = plc.plc_surprisal_thresholds(b0, hbar)
+    thr_oracle = O.surprisal_thresholds(b0, hbar)
+    assert list(thr) == list(thr_oracle)
     codec = codec_for(w, want_pred=True, esc_frac=1.0, chunk_syms=chunk)
     print(f"case {case}: S{w.S} L{w.L} H{w.H} n{w.n} k{w.k} d{w.d} chunk {chunk} thr {thr}", flush=True)
     coded = codec.encode_adapt(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, chosen, thr, step_range)
@@ -56,7 +57,7 @@ def test_adaptive_encode_decode_matches_oracle(oracle, dev, case):
     spp, sps, B = 2 * w.d, w.L * w.H, plc.MAX_BITS
 
     # ---- bit depths
-    bits = O.surprisal_bits(probs, ch, np.array(thr, dtype=np.uint16))
+    bits = O.surprisal_bits(probs, ch, thr_oracle)
     assert np.array_equal(coded.bits.cpu().numpy(), bits)
     assert len(set(bits.ravel())) >= 2                      # the case really mixes depths
 

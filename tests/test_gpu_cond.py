@@ -41,6 +41,9 @@ CASES = {
     "three_sessions": ("tiny", dict(S=3, L=1, H=2, n=100, seed=28), "lhnkd", True, 0.15),
     # the generator's own misses (fresh vectors where the token is none of the k = 20 candidates)
     "k20_with_misses": ("miss20", dict(L=1, H=2, n=300, seed=29), "lhnkd", False, 0.0),
+    # more streams than the one-kernel decode takes on this path (2048): the single call then runs the
+    # many-unit entropy decoder, one wavefront per workgroup, followed by the reconstruction kernel
+    "many_streams": ("tiny", dict(S=3, L=24, H=32, n=7, k=4, d=16, seed=30), "lhnkd", True, 0.2),
 }
 
 

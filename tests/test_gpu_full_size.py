@@ -275,7 +275,10 @@ def test_surprisal_adaptive_full_size(oracle):
     w = make_workload("llama8b", device=dev)
     chosen = w.chosen.to(torch.int32).contiguous()
     ch = chosen.cpu().numpy()
-    thr = plc.surprisal_thresholds(3.0, float(np.log2(np.mean(w.perplexity))))
+    hbar = float(np.log2(np.mean(w.perplexity)))
+    thr = plc.plc_surprisal_thresholds(3.0, hbar)
+    thr_oracle = O.surprisal_thresholds(3.0, hbar)            # the oracle's own, from its own arithmetic
+    assert list(thr) == list(thr_oracle)
     step_range = 0.32
     codec = codec_for(w)
     print("surprisal-adaptive llama8b", flush=True)
@@ -285,7 +288,7 @@ def test_surprisal_adaptive_full_size(oracle):
     codec.decode_adapt(w.cand_k, w.cand_v, w.probs, out_k, out_v, thr, step_range)
     codec.check_status("surprisal-adaptive, full size")
     probs = w.probs.cpu().numpy()
-    bits = O.surprisal_bits(probs, ch, np.array(thr, dtype=np.uint16))
+    bits = O.surprisal_bits(probs, ch, thr_oracle)
     assert np.array_equal(codec.dec_bits.cpu().numpy(), bits)
     assert torch.equal(codec.dec_symbols, coded.symbols)
     dm = O.make_dims(1, 1, 1, w.n, w.k, w.d, w.delta, w.qmax)

@@ -46,6 +46,9 @@ CASES = {
     "wide_rows_d1024_k3": ("tiny", dict(L=1, H=2, n=9, k=3, d=1024, seed=21), "lhnkd", True),
     "rows_of_a_batch_d512_k7": ("tiny", dict(L=1, H=1, n=33, k=7, d=512, seed=22), "lnkhd", True),
     "two_sessions_k6": ("tiny", dict(S=2, L=3, H=1, n=130, k=6, d=64, sigma=0.5, seed=23), "lhnkd", True),
+    # more streams than the whole-stream encoder and decoder kernels take (1024): the many-unit kernels with one
+    # wavefront per workgroup code them, and the one-kernel decode runs in several rounds of workgroups
+    "many_streams": ("tiny", dict(S=2, L=20, H=32, n=9, k=4, d=24, seed=24), "lhnkd", True),
 }
 
 
@@ -189,7 +192,9 @@ def test_special_values_escape_bit_exactly(oracle, dev):
 
 # --------------------------------------------------------------------------- byte-stream calls on their own
 
-BYTE_CASES = [(600, 1000, "gauss"),        # more single-unit streams than the chain decoder takes
+BYTE_CASES = [(600, 1000, "gauss"),        # several hundred whole-stream units: the three-wavefront encoder, the chain decoder
+              (1500, 1000, "gauss"),       # more whole-stream units than those kernels take: the many-unit kernels, one
+                                           # wavefront per workgroup (the shape of the 70B-shaped and 64-session runs)
               (1, 1, "gauss"), (3, 5, "gauss"), (2, 33, "uniform"), (5, 1000, "gauss"), (2, 4097, "two"),
               (3, 70001, "gauss"), (2, 200000, "constant"), (4, 131072, "uniform"), (1, 262144 + 17, "gauss")]
 
@@ -239,6 +244,55 @@ def test_histogram_table_rans_bit_exact(oracle, dev, n_streams, N, kind, chunk):
     plc.plc_rans_decode(freq, o_states, o_words, word_off, o_nw, n_streams, N, chunk, dec, status)
     assert int(status.item()) == 0
     assert torch.equal(dec, sym_t)
+
+
+def test_more_whole_stream_units_than_the_chain_kernels_take(oracle, dev):
+    """Whole-stream units beyond the bound of the three-wavefront encoder and the chain decoder
+    (plc_rans_encode / plc_rans_decode then run the many-unit kernels with one wavefront per workgroup):
+    ragged streams, bit-exact both ways against the oracle, one damaged unit reported."""
+    from paper_2604_15356_amd import plc
+    O = oracle
+    n_streams, N = 1100, 2000 + 13                     # 63 groups: three full batches and a ragged tail
+    sym_t = random_bytes(n_streams, N, seed=4242, kind="gauss", device=dev)
+    sym_t[17] = 127                                    # a one-symbol stream (f = 4096, no words)
+    sym_t[18, ::5] = 255
+    sym = sym_t.cpu().numpy()
+    cap = (N + 7) // 8 * 8
+    i32, i16 = torch.int32, torch.int16
+    counts = torch.empty((n_streams, 256), dtype=i32, device=dev)
+    freq = torch.empty((n_streams, 256), dtype=i16, device=dev)
+    states = torch.empty((n_streams, 32), dtype=i32, device=dev)
+    words = torch.zeros(n_streams * cap, dtype=i16, device=dev)
+    word_off = torch.arange(n_streams, dtype=torch.int64, device=dev) * cap
+    n_words = torch.empty(n_streams, dtype=i32, device=dev)
+    status = torch.zeros(1, dtype=i32, device=dev)
+    print(f"  {n_streams} whole-stream units of {N} symbols", flush=True)
+    plc.plc_histogram(sym_t, n_streams, N, counts)
+    plc.plc_build_freq(counts, n_streams, freq, None, status)
+    plc.plc_rans_encode(sym_t, n_streams, N, 0, freq, states, words, word_off, cap, n_words, status)
+    dec = torch.zeros_like(sym_t)
+    plc.plc_rans_decode(freq, states, words, word_off, n_words, n_streams, N, 0, dec, status)
+    assert int(status.item()) == 0
+    assert torch.equal(dec, sym_t)
+    ref_freq, _ = O.build_freq(O.histogram(sym))
+    enc = O.rans_encode(sym, ref_freq, word_cap_per_unit=cap)
+    assert np.array_equal(u16(freq), ref_freq)
+    assert np.array_equal(u32(n_words), enc["n_words"]) and np.array_equal(u32(states), enc["states"])
+    got = u16(words)
+    for unit in range(n_streams):
+        o, nw = unit * cap, int(enc["n_words"][unit])
+        assert np.array_equal(got[o:o + nw], enc["words"][o:o + nw]), f"unit {unit}"
+    # the oracle decodes the GPU's streams, the GPU the oracle's
+    assert np.array_equal(O.rans_decode(u16(freq), u32(states), got, u64(word_off), u32(n_words), n_streams, N), sym)
+    dec.zero_()
+    plc.plc_rans_decode(freq, torch.from_numpy(enc["states"].view(np.int32)).to(dev),
+                        torch.from_numpy(enc["words"].view(np.int16)).to(dev), word_off,
+                        torch.from_numpy(enc["n_words"].view(np.int32)).to(dev), n_streams, N, 0, dec, status)
+    assert int(status.item()) == 0 and torch.equal(dec, sym_t)
+    # one damaged unit is reported, and decoding ends
+    words[int(word_off[700]) + 3] ^= 0x1555
+    plc.plc_rans_decode(freq, states, words, word_off, n_words, n_streams, N, 0, dec, status)
+    assert int(status.item()) == plc.PLC_ERR_CORRUPT
 
 
 def test_word_list_at_odd_addresses(oracle, dev):

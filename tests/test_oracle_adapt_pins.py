@@ -53,6 +53,27 @@ def test_bit_depth_is_the_definitions_formula_on_every_frequency(oracle):
             assert (np.abs(got[~clear].astype(float) - want[~clear]) <= 1).all()
 
 
+def test_thresholds_are_the_closed_form_and_depths_have_no_cap_of_four(oracle):
+    """thr[m] = floor(4096 * 2^(-m hbar / b0)) where that is clear of an integer; where hbar / b0 is a whole
+    number the thresholds are exact powers of two; and with twelve depths allowed the depth of a frequency
+    is the definition's floor(b0 h / hbar) beyond four as well."""
+    assert list(oracle.surprisal_thresholds(3.0, 3.0, 6)) == [0, 0, 1024, 512, 256, 128, 64]
+    assert list(oracle.surprisal_thresholds(1.0, 2.0, 7)) == [0, 0, 256, 64, 16, 4, 1, 0]
+    for b0, hbar in ((3.0, np.log2(15.0)), (2.0, 3.3), (5.0, 2.1)):
+        thr = oracle.surprisal_thresholds(b0, hbar, 12)
+        for m in range(2, 13):
+            v = 4096.0 * 2.0 ** (-m * hbar / b0)
+            if abs(v - round(v)) > 1e-6:
+                assert thr[m] == int(np.floor(v))
+        f = np.arange(1, 4096)
+        probs = (f / 4096.0).astype(np.float32).reshape(1, -1, 1)
+        got = oracle.surprisal_bits(probs, np.zeros((1, f.size), np.int32), thr)[0]
+        v = b0 * np.log2(4096.0 / f) / hbar
+        clear = np.abs(v - np.round(v)) > 1e-9
+        assert np.array_equal(got[clear], np.clip(np.floor(v), 1, 12)[clear].astype(np.uint8))
+        assert got.max() > 4
+
+
 def test_bit_depths_of_the_synthetic_row(oracle):
     """Llama-shaped row (perplexity 15, top 8): likely tokens get one bit, the tail four."""
     w = make_workload("llama8b", overrides=dict(L=1, H=1, d=8, n=2000))
@@ -110,7 +131,7 @@ def test_error_is_half_the_positions_own_step(oracle):
         assert (err[narrow] ** 2).mean() <= 1.02 * min((step_range * 2.0 ** -b) ** 2 / 12,
                                                        float(w.sigma[0]) ** 2 + 1e-6)
     assert np.array_equal(pre[~keep], act[~keep])
-    for bad in (0, 5):
+    for bad in (0, oracle.MAX_BITS_ORACLE + 1):       # no depth, and more depths than the oracle's arrays hold
         bits2 = bits.copy()
         bits2[0, 7] = bad
         with pytest.raises(oracle.OracleError):
