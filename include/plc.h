@@ -60,6 +60,8 @@ extern "C" {
 #define PLC_ERR_CORRUPT 3  /* decoder integrity check failed                                 */
 #define PLC_ERR_HIP 4      /* the HIP runtime refused a launch                               */
 
+#define PLC_ERR_SCRATCH 5  /* the shape needs more scratch than the library's own buffer has  */
+
 #define PLC_ESCAPE 255     /* escape symbol                                                  */
 #define PLC_RANS_LANES 32
 #define PLC_RANS_SCALE 4096
@@ -119,6 +121,29 @@ int plc_predict_residual(const plc_dims *dims, const void *cand_k, const void *c
                          uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
                          uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
                          void *ws, size_t ws_bytes, uint32_t *status, void *stream);
+
+/*
+ * plc_predict_residual for callers that cannot allocate device memory or have a workspace handed to
+ * them: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results, bit for bit, but the workspace is a buffer inside the library itself
+ * (a static device array of PLC_STATIC_SCRATCH_BYTES bytes; every GPU the library runs on holds its own
+ * copy until the process ends).  The call allocates and frees nothing.
+ *   - Shapes with plc_workspace_bytes(dims) > PLC_STATIC_SCRATCH_BYTES are refused with PLC_ERR_SCRATCH
+ *     before anything is enqueued (48 MiB covers 1.6e8 KV components per call, e.g. L=32, H=8, d=128,
+ *     n=4096).
+ *   - The first call on a device looks the buffer's address up (hipGetSymbolAddress with that device
+ *     current) and must be made outside stream capture; PLC_ERR_HIP if the lookup fails.
+ *   - All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU (different
+ *     streams, or different threads) race.  Calls that follow each other on one stream do not: every part
+ *     of the buffer a kernel reads was written earlier in the same call, so nothing carries over from
+ *     the call before, whatever its shape.
+ */
+#define PLC_STATIC_SCRATCH_BYTES (48u << 20)
+int plc_predict_residual_noalloc(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                 const float *probs, const void *act_k, const void *act_v,
+                                 uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                                 uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
+                                 uint32_t *status, void *stream);
 
 /*
  * Per-stream symbol statistics for the entropy coder ("standard source

@@ -10,6 +10,7 @@ extern "C" const char *plc_strerror(int code) {
     case PLC_ERR_CAPACITY: return "output list too small";
     case PLC_ERR_CORRUPT: return "coded stream failed its integrity check";
     case PLC_ERR_HIP: return "HIP launch failed";
+    case PLC_ERR_SCRATCH: return "shape needs more scratch than the library's static buffer holds";
     default: return "unknown plc status";
   }
 }

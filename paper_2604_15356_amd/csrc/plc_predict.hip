@@ -10,6 +10,8 @@
 // organised purely around wide coalesced accesses: one thread owns one
 // 16-byte chunk (8 components) of one K or V row, and issues all of its
 // k + 1 loads before the first use.
+#include <mutex>
+
 #include "plc_device.h"
 
 namespace plc {
@@ -786,6 +788,52 @@ extern "C" int plc_predict_residual(const plc_dims *dims, const void *cand_k, co
                                     size_t ws_bytes, uint32_t *status, void *stream) {
   return encode_floats(dims, cand_k, cand_v, probs, nullptr, nullptr, 0.0f, PLC_TRACE_PREDICT, act_k, act_v, symbols, esc_vals,
                        esc_cap, esc_cnt, esc_off, pred_out, ws, ws_bytes, status, stream);
+}
+
+// ---------------------------------------------------------------------------
+// plc_predict_residual for callers that cannot allocate: the workspace is a buffer of the library's own
+// ---------------------------------------------------------------------------
+// Device memory that lives in the library's code object, one copy per GPU, held until the process ends.
+// Host code never uses the array's name as an address: the address on a device is looked up once, with
+// that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[PLC_STATIC_SCRATCH_BYTES];
+
+namespace plc {
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch`, or null if the runtime cannot name it.
+void *static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+}  // namespace plc
+
+extern "C" int plc_predict_residual_noalloc(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                            const float *probs, const void *act_k, const void *act_v,
+                                            uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                                            uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
+                                            uint32_t *status, void *stream) {
+  Plan p;
+  if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
+  if (p.total > (size_t)PLC_STATIC_SCRATCH_BYTES) return PLC_ERR_SCRATCH;
+  void *ws = static_scratch();
+  if (!ws) return PLC_ERR_HIP;
+  // Every word of the workspace that a kernel reads has been written earlier in the same call (weights,
+  // per-tile counts, their prefix sums, the staged escapes up to each tile's count), so nothing of the
+  // previous call's contents needs clearing.
+  return encode_floats(dims, cand_k, cand_v, probs, nullptr, nullptr, 0.0f, PLC_TRACE_PREDICT, act_k, act_v, symbols,
+                       esc_vals, esc_cap, esc_cnt, esc_off, pred_out, ws, p.total, status, stream);
 }
 
 extern "C" int plc_predict_residual_cond(const plc_dims *dims, const void *cand_k, const void *cand_v,

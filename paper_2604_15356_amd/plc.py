@@ -16,11 +16,12 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libplc.so")
 
-PLC_OK, PLC_ERR_INVALID, PLC_ERR_CAPACITY, PLC_ERR_CORRUPT, PLC_ERR_HIP = 0, 1, 2, 3, 4
+PLC_OK, PLC_ERR_INVALID, PLC_ERR_CAPACITY, PLC_ERR_CORRUPT, PLC_ERR_HIP, PLC_ERR_SCRATCH = 0, 1, 2, 3, 4, 5
+STATIC_SCRATCH_BYTES = 48 << 20
 PLC_ESCAPE = 255
 
 EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_stream",
-           "plc_predict_residual", "plc_histogram", "plc_build_freq", "plc_rans_encode",
+           "plc_predict_residual", "plc_predict_residual_noalloc", "plc_histogram", "plc_build_freq", "plc_rans_encode",
            "plc_rans_decode", "plc_reconstruct", "plc_rans_decode_reconstruct", "plc_rans_decode_reconstruct_cond",
            "plc_rans_decode_reconstruct_adapt",
            "plc_trace_kernel_events",
@@ -73,6 +74,7 @@ def lib() -> C.CDLL:
         L.plc_units_per_stream.restype = i64
         L.plc_units_per_stream.argtypes = [i64, i32]
         L.plc_predict_residual.argtypes = [dp, p, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_predict_residual_noalloc.argtypes = [dp, p, p, p, p, p, p, p, u64, p, p, p, p, p]
         L.plc_histogram.argtypes = [p, i64, i64, p, p]
         L.plc_build_freq.argtypes = [p, i64, p, p, p, p]
         L.plc_rans_encode.argtypes = [p, i64, i64, i32, p, p, p, p, u64, p, p, p]
@@ -184,6 +186,18 @@ def plc_predict_residual(dims, cand_k, cand_v, probs, act_k, act_v, symbols, esc
         _contig(esc_cnt, torch.int32), _contig(esc_off, torch.int64), _contig(pred_out, torch.float32),
         _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
     _check(rc, "plc_predict_residual")
+
+
+def plc_predict_residual_noalloc(dims, cand_k, cand_v, probs, act_k, act_v, symbols, esc_vals, esc_cnt,
+                                 esc_off, status, pred_out=None):
+    """plc_predict_residual with the library's own static workspace (no ws argument)."""
+    rc = lib().plc_predict_residual_noalloc(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _ptr(act_k, torch.float16), _ptr(act_v, torch.float16),
+        _contig(symbols, torch.uint8), _contig(esc_vals, None), esc_vals.numel(),
+        _contig(esc_cnt, torch.int32), _contig(esc_off, torch.int64), _contig(pred_out, torch.float32),
+        _contig(status, torch.int32), _stream())
+    _check(rc, "plc_predict_residual_noalloc")
 
 
 def plc_histogram(symbols, n_streams, syms_per_stream, counts):

@@ -176,6 +176,20 @@ def test_bad_strides_pointers_and_sizes_are_rejected():
     assert L.plc_surprisal_thresholds(3.0, 3.9, 4, None) == 1
 
 
+def test_noalloc_entry_point_refuses_shapes_beyond_its_static_buffer():
+    """Host-side refusals of plc_predict_residual_noalloc come before any GPU call."""
+    L = plc.lib()
+    p = C.c_void_p(4096)
+    long_ctx = plc.make_dims(1, 32, 8, 32768, 4, 128, 0.02)
+    assert plc.plc_workspace_bytes(long_ctx) > plc.STATIC_SCRATCH_BYTES
+    assert L.plc_predict_residual_noalloc(C.byref(long_ctx), p, p, p, p, p, p, p, 0, p, p, None, p, None) == plc.PLC_ERR_SCRATCH
+    bad = plc.make_dims(1, 2, 2, 16, 0, 64, 0.02)
+    assert L.plc_predict_residual_noalloc(C.byref(bad), p, p, p, p, p, p, p, 0, p, p, None, p, None) == plc.PLC_ERR_INVALID
+    assert plc.strerror(plc.PLC_ERR_SCRATCH) != plc.strerror(99)
+    llama = plc.make_dims(1, 32, 8, 4096, 8, 128, 0.02)
+    assert plc.plc_workspace_bytes(llama) <= plc.STATIC_SCRATCH_BYTES
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(plc, "_lib", None)
     monkeypatch.setattr(plc, "LIB_PATH", str(tmp_path / "nope.so"))
