@@ -96,8 +96,8 @@ int64_t plc_units_per_stream(int64_t syms_per_stream, int32_t chunk_syms);
  *               multiply-add, j ascending from 0 (Def. "Predicted KV vector"
  *               restricted to the top k);
  *   residual    r = act - pred (Def. "KV residual");
- *   quantise    q = round-half-even(r / delta) (Sec. 7.2, point 1: "quantize
- *               and write R_i"); symbol q+127 if |q| <= qmax and r/delta is
+ *   quantise    q = round-half-even(r / delta) (Sec. 7.2, point 1: the residual
+ *               is what gets quantised and stored); symbol q+127 if |q| <= qmax and r/delta is
  *               finite, else 255 with the raw fp16 of `act` appended to the
  *               stream's escape list.
  * One probability row serves every layer, head, K and V of a position.
@@ -146,8 +146,10 @@ int plc_predict_residual_noalloc(const plc_dims *dims, const void *cand_k, const
                                  uint32_t *status, void *stream);
 
 /*
- * Per-stream symbol statistics for the entropy coder ("standard source
- * coding" of the residuals, proof of Prop. "Layer orthogonality", Sec. 6.1).
+ * Per-stream symbol statistics for the entropy coder (the paper only asks
+ * for a source code of the residuals near their entropy, proof of Prop. "Layer
+ * orthogonality", Sec. 6.1, and names no coder; statistics, table and
+ * bitstream are this library's own format, defined here).
  *   symbols  u8 [n_streams, syms_per_stream] contiguous.
  *   counts   out, u32 [n_streams, 256]; overwritten.  syms_per_stream < 2^32.
  */
@@ -156,7 +158,8 @@ int plc_histogram(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_st
 
 /*
  * Counts -> integer frequency table on the 2^12 scale, integer arithmetic
- * only.  With C the inclusive running count and T the total,
+ * only (the paper is silent on the coder's tables; this normalisation is the
+ * format's own).  With C the inclusive running count and T the total,
  *   f[s] = floor(C[s] * 4096 / T) - floor(C[s-1] * 4096 / T);
  * then, for s ascending, every symbol that occurs but got f[s] = 0 takes one
  * unit from the currently largest frequency (lowest symbol on ties).
@@ -168,7 +171,9 @@ int plc_build_freq(const uint32_t *counts, int64_t n_streams, uint16_t *freq, ui
                    uint32_t *status, void *stream);
 
 /*
- * rANS encoder.  For each unit, with x = 2^16 in all 32 lanes initially and
+ * rANS encoder (the paper fixes no entropy coder, see plc_histogram; every
+ * constant and the word order below are the format's own).  For each unit,
+ * with x = 2^16 in all 32 lanes initially and
  * for t from the unit's last symbol down to its first (lane = t mod 32):
  *   if (x >> 20) >= f[sym]:  append (x & 0xffff) to the unit's words, x >>= 16
  *   x = (x / f[sym]) * 4096 + (x % f[sym]) + cum[sym]
@@ -189,7 +194,8 @@ int plc_rans_encode(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_
                     uint32_t *n_words, uint32_t *status, void *stream);
 
 /*
- * rANS decoder, the exact inverse.  For each unit, x = states, ptr = n_words,
+ * rANS decoder, the exact inverse (same remark: the format's own definition,
+ * not the paper's).  For each unit, x = states, ptr = n_words,
  * and for t from the unit's first symbol to its last (lane = t mod 32):
  *   slot = x & 4095;  sym = the s with cum[s] <= slot < cum[s+1]
  *   x = f[sym] * (x >> 12) + slot - cum[sym]
@@ -205,10 +211,10 @@ int plc_rans_decode(const uint16_t *freq, const uint32_t *states, const uint16_t
                     uint8_t *symbols, uint32_t *status, void *stream);
 
 /*
- * Decode side, floating-point part (Sec. 7.2, point 2: "dequantize R_i; add
- * back the prediction, recomputed identically"; Prop. "Three-layer
- * composition", correctness: the error of the recovered KV is the quantiser's
- * error on the residual).  The prediction is computed exactly as in
+ * Decode side, floating-point part (Sec. 7.2, point 2: the stored residual is
+ * dequantised and added to a prediction that the reader forms exactly as the
+ * writer did; Prop. "Three-layer composition", correctness: the error of the
+ * recovered KV is the quantiser's error on the residual).  The prediction is computed exactly as in
  * plc_predict_residual; then x = fma((float)(sym - 127), delta, pred), rounded
  * to fp16 (nearest even).  An escape symbol takes the next raw fp16 of its
  * stream's escape list instead.
@@ -475,14 +481,14 @@ int plc_reconstruct_linear(const plc_dims *dims, const void *ebar, int32_t m, co
  * Sec. 7.3, "Trie-Based Prefix Index": the structure in front of this path that finds, for a new
  * session, the stored session whose KV cache it can be coded against: a trie over token sequences
  * with insert, best-match lookup and evict, each linear in the prefix length.  All arguments are
- * HOST pointers; nothing here touches the GPU; a trie is not thread-safe.  Readings: the trie is
- * "pruned at nodes with probability below a threshold": a prefix is stored only down to the last
- * token at which its surprisal sum stays <= max_bits (= -log2 of that threshold); the best match is
- * the stored prefix with the longest common prefix with the query ("follow the path of the query
- * until it diverges from all stored paths"), for which the trie metric of Def. "PLT trie metric"
- * d_T = -log2 P(common prefix) is returned (the text's "maximizing d_T" and "maximizing the
- * probability of the longest common prefix" contradict each other; the traversal it describes is
- * what is implemented).
+ * HOST pointers; nothing here touches the GPU; a trie is not thread-safe.  Readings: Sec. 7.3 prunes
+ * the trie where a node's probability falls under a threshold, taken here as: a prefix is stored only
+ * down to the last token at which its surprisal sum stays <= max_bits (= -log2 of that threshold); the
+ * best match is the stored prefix with the longest common prefix with the query (the walk down the
+ * query's path to the point where no stored path continues, which is the traversal the section gives),
+ * for which the trie metric of Def. "PLT trie metric", d_T = -log2 P(common prefix), is returned (the
+ * section states the objective once as the largest d_T and once as the most probable common prefix,
+ * which contradict each other; the traversal it describes is what is implemented).
  *
  *   tokens  i32 [n];  bits  fp32 [n], nullable: surprisal -log2 P(token | path) of each token, >= 0.
  *   id      caller's handle of a stored prefix, >= 0, unique.

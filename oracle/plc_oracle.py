@@ -2,7 +2,8 @@
 
 TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
 benchmark's CPU-baseline leg.  Nothing in the product package may import it.
-All arithmetic lives in the C file; this module only marshals numpy arrays.
+All of the method's arithmetic lives in the C file; this module only marshals numpy arrays
+(its one sum, coded_bits, is storage accounting: it adds up the sizes of the coded artefacts).
 """
 from __future__ import annotations
 

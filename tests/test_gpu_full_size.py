@@ -345,44 +345,51 @@ def test_linear_predictor_full_size(oracle):
     codec.decode_linear(w.probs_full, w.embed_t, w.A, w.bias_k, w.bias_v, out_k, out_v)
     codec.check_status("linear predictor, full size")
     assert torch.equal(codec.dec_symbols, coded.symbols)
+    from oracle import plc_oracle_linear as OL
     rng = np.random.default_rng(5)
-    # expected embedding: sampled rows in fp64
-    Et = w.embed_t.cpu().numpy().astype(np.float64)
-    for r in rng.integers(0, w.S * w.n, 6):
-        want = (w.probs_full[r].cpu().numpy().astype(np.float64) @ Et.T).astype(np.float16)
+    # expected embedding: sampled rows through the oracle
+    rows = np.sort(rng.integers(0, w.S * w.n, 6))
+    want_rows = OL.expected_embedding(w.probs_full[rows].cpu().numpy(), w.embed_t.cpu().numpy())
+    for r, want in zip(rows, want_rows):
         got = codec.ebar[r].cpu().numpy()
         ulp = np.spacing(np.maximum(np.abs(want), np.float16(2.0 ** -14))).astype(np.float64)
         assert (np.abs(got.astype(np.float64) - want.astype(np.float64)) <= ulp).all()
         assert (got.view(np.uint16) != want.view(np.uint16)).mean() < 0.05
-    del Et
-    # prediction / symbols: sampled rows from the device's expected embedding
+    # prediction / symbols / reconstruction: sampled (layer, head, position) through the oracle, which is fed the
+    # device's expected embedding (the matrix cores add in their own order: no bit-exact mirror of Ebar)
     sym = coded.symbols.reshape(w.S, w.L, w.H, w.n, 2, w.d)
     delta = float(np.float32(w.delta))
     n_diff = 0
     for _ in range(48):
-        l, h, c, i = int(rng.integers(w.L)), int(rng.integers(w.H)), int(rng.integers(2)), int(rng.integers(w.n))
-        a_row = w.A[l, h, c].cpu().numpy().astype(np.float64)                       # [d, m]
-        eb = codec.ebar[i].cpu().numpy().astype(np.float64)                         # [m]
-        bias = (w.bias_v if c else w.bias_k)[0, l, h, i].cpu().numpy().astype(np.float64)
-        act = (w.act_v if c else w.act_k)[0, l, h, i].cpu().numpy()
-        pred = bias + a_row @ eb
-        u = (act.astype(np.float64) - pred) / delta
-        q = np.rint(u)
-        want = np.where(np.abs(q) > 127, 255, q + 127).astype(np.int64)
-        got = sym[0, l, h, i, c].cpu().numpy().astype(np.int64)
-        tau = (w.m + 4) * 2.0 ** -24 * (np.abs(a_row) @ np.abs(eb) + 8.0) / delta
+        l, h, i = int(rng.integers(w.L)), int(rng.integers(w.H)), int(rng.integers(w.n))
+        cut = lambda t: t[0:1, l:l + 1, h:h + 1, i:i + 1].cpu().numpy()              # [1, 1, 1, 1, d]
+        eb = codec.ebar[i].cpu().numpy().reshape(1, 1, w.m)
+        A = w.A[l:l + 1, h:h + 1].cpu().numpy()                                       # [1, 1, 2, d, m]
+        ref = OL.predict_residual(eb, A, cut(w.bias_k), cut(w.bias_v), cut(w.act_k), cut(w.act_v), w.delta)
+        want = ref["symbols"].reshape(2, w.d).astype(np.int64)
+        u = ref["u"].reshape(2, w.d)
+        got = sym[0, l, h, i].cpu().numpy().astype(np.int64)                           # [2, d]
+        # fp32 accumulation bound of each component's sum, in steps of Delta
+        mag = np.abs(A[0, 0].astype(np.float64)) @ np.abs(eb[0, 0].astype(np.float64))  # [2, d]
+        tau = (w.m + 4) * 2.0 ** -24 * (mag + 8.0) / delta
         differ = got != want
         near = np.abs(u - np.floor(u) - 0.5) < tau
         one = (np.abs(got - want) == 1) | (got == 255) | (want == 255)
         assert (differ <= (near & one)).all()
         n_diff += int(differ.sum())
-        out = (out_v if c else out_k)[0, l, h, i].cpu().numpy()
-        keep = got != 255
-        xhat = (pred + (got - 127.0) * delta)
-        # one fp16 step of the output plus the fp32 accumulation bound of the prediction (tau is in steps of Delta)
-        assert (np.abs(out.astype(np.float64) - xhat) <= np.maximum(np.abs(xhat), 2.0 ** -14) * 2.0 ** -10 + tau * delta)[keep].all()
-        assert np.array_equal(out.view(np.uint16)[~keep], act.view(np.uint16)[~keep])
-    print(f"  near-ties on sampled rows: {n_diff} of {48 * w.d}", flush=True)
+        # the oracle's reconstruction from the device's symbols (escapes: the actual values, as the lists hold them)
+        act2 = np.stack([cut(w.act_k).reshape(w.d), cut(w.act_v).reshape(w.d)]).view(np.uint16)
+        rk, rv = OL.reconstruct(eb, A, cut(w.bias_k), cut(w.bias_v), got.astype(np.uint8).reshape(1, 2 * w.d),
+                                act2[got == 255], w.delta)
+        for c, (outp, want_out) in enumerate(((out_k, rk), (out_v, rv))):
+            out = outp[0, l, h, i].cpu().numpy()
+            wo = want_out.reshape(w.d)
+            keep = got[c] != 255
+            ulp = np.maximum(np.abs(wo.astype(np.float64)), 2.0 ** -14) * 2.0 ** -10
+            # one fp16 step of the output plus the fp32 accumulation bound of the prediction
+            assert (np.abs(out.astype(np.float64) - wo.astype(np.float64)) <= ulp + tau[c] * delta)[keep].all()
+            assert np.array_equal(out.view(np.uint16)[~keep], wo.view(np.uint16)[~keep])
+    print(f"  near-ties on sampled rows: {n_diff} of {48 * 2 * w.d}", flush=True)
     assert n_diff <= 3
     # error bound on everything
     esc = sym == 255
