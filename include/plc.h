@@ -123,6 +123,19 @@ int plc_predict_residual(const plc_dims *dims, const void *cand_k, const void *c
                          void *ws, size_t ws_bytes, uint32_t *status, void *stream);
 
 /*
+ * plc_predict_residual and plc_histogram in one pass: the same outputs as plc_predict_residual, plus
+ *   counts   out, u32 [S*L*H, 256]; overwritten with what plc_histogram would count on `symbols`
+ * taken while the symbols are produced (per-workgroup histograms in LDS, added to `counts` with integer
+ * atomics: the result does not depend on the order), so that the symbols need not be read back for the
+ * statistics.  Everything else as in plc_predict_residual.
+ */
+int plc_predict_residual_hist(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                              const float *probs, const void *act_k, const void *act_v,
+                              uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                              uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out, uint32_t *counts,
+                              void *ws, size_t ws_bytes, uint32_t *status, void *stream);
+
+/*
  * plc_predict_residual for callers that cannot allocate device memory or have a workspace handed to
  * them: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, kernels and results, bit for bit, but the workspace is a buffer inside the library itself

@@ -91,10 +91,16 @@ class KVDeltaCodec:
         self.idx_n_words = torch.empty(S, dtype=torch.int32, device=dev)
 
     # -- single steps -------------------------------------------------------------------
-    def predict_residual(self, cand_k, cand_v, probs, act_k, act_v):
-        plc.plc_predict_residual(self.dims, cand_k, cand_v, probs, act_k, act_v, self.symbols,
-                                 self.esc_vals, self.esc_cnt, self.esc_off, self.ws, self.status,
-                                 pred_out=self.pred)
+    def predict_residual(self, cand_k, cand_v, probs, act_k, act_v, with_counts=False):
+        """with_counts: also leave the symbols' per-stream counts in self.counts (no histogram call needed after)."""
+        if with_counts:
+            plc.plc_predict_residual_hist(self.dims, cand_k, cand_v, probs, act_k, act_v, self.symbols,
+                                          self.esc_vals, self.esc_cnt, self.esc_off, self.counts, self.ws,
+                                          self.status, pred_out=self.pred)
+        else:
+            plc.plc_predict_residual(self.dims, cand_k, cand_v, probs, act_k, act_v, self.symbols,
+                                     self.esc_vals, self.esc_cnt, self.esc_off, self.ws, self.status,
+                                     pred_out=self.pred)
 
     def histogram(self, symbols=None):
         plc.plc_histogram(self.symbols if symbols is None else symbols, self.n_streams, self.N, self.counts)
@@ -119,9 +125,12 @@ class KVDeltaCodec:
                             self.esc_vals, self.esc_off, out_k, out_v, self.ws, self.status)
 
     # -- whole directions ---------------------------------------------------------------
-    def encode(self, cand_k, cand_v, probs, act_k, act_v) -> Coded:
-        self.predict_residual(cand_k, cand_v, probs, act_k, act_v)
-        self.histogram()
+    def encode(self, cand_k, cand_v, probs, act_k, act_v, fused_counts=True) -> Coded:
+        """fused_counts: the symbol statistics are taken inside the prediction pass (the results are the same
+        either way); False makes the plc_histogram call instead."""
+        self.predict_residual(cand_k, cand_v, probs, act_k, act_v, with_counts=fused_counts)
+        if not fused_counts:
+            self.histogram()
         self.build_freq()
         self.rans_encode()
         return self.coded()
@@ -261,3 +270,95 @@ class KVDeltaCodec:
         if code != plc.PLC_OK:
             self.status.zero_()
             raise plc.PlcError(code, where)
+
+
+class GroupedCodec:
+    """The weighted-mean path over a cache with thousands of streams, coded as independent groups of whole
+    sessions (or, inside one session, of whole layers), each group a KVDeltaCodec of its own with its own
+    buffers and artefacts.  Nothing is computed here: the class slices the caller's tensors into the groups'
+    views and orders the same libplc calls on two HIP streams, so that the entropy coding of one group
+    (integer work, bound by instruction issue and LDS) runs beside the prediction pass of the next (bound by
+    HBM): the caller's current stream carries the prediction passes, a side stream of default priority the
+    statistics, tables and rANS encoders; decode calls alternate between the two.  Streams are independent
+    units from the first step to the last, so a group's artefacts are exactly those a codec over that slice
+    alone would produce."""
+
+    def __init__(self, S, L, H, n, k, d, delta, qmax=127, groups=8, device="cuda", cand_stride=None,
+                 act_stride=None, **kw):
+        self.device = torch.device(device)
+        self.S, self.L, self.H, self.n, self.k, self.d = S, L, H, n, k, d
+        self.N = 2 * n * d
+        self.n_streams = S * L * H
+        # a group: sessions [s0, s1) whole, or layers [l0, l1) of session s0
+        self.slices = []
+        groups = max(1, int(groups))
+        if S >= groups:
+            for g in range(groups):
+                s0, s1 = S * g // groups, S * (g + 1) // groups
+                self.slices.append((s0, s1, 0, L))
+        else:
+            per = max(1, min(L, (groups + S - 1) // S))
+            for s in range(S):
+                for g in range(per):
+                    l0, l1 = L * g // per, L * (g + 1) // per
+                    self.slices.append((s, s + 1, l0, l1))
+        self.codecs = [KVDeltaCodec(s1 - s0, l1 - l0, H, n, k, d, delta, qmax, device=device,
+                                    cand_stride=cand_stride, act_stride=act_stride, **kw)
+                       for s0, s1, l0, l1 in self.slices]
+        self.n_units = sum(c.n_units for c in self.codecs)
+        self.side = torch.cuda.Stream(device=self.device)            # default priority
+        self.events = [torch.cuda.Event() for _ in self.codecs]
+        self.hook = None        # optional callable(group index), called before a group's calls are enqueued
+
+    def _views(self, i, *tensors):
+        s0, s1, l0, l1 = self.slices[i]
+        return [t[s0:s1, l0:l1] for t in tensors]
+
+    def encode(self, cand_k, cand_v, probs, act_k, act_v, overlap=True):
+        main = torch.cuda.current_stream()
+        side = self.side if overlap else main
+        if overlap:
+            side.wait_stream(main)
+        for i, c in enumerate(self.codecs):
+            ck, cv, ak, av = self._views(i, cand_k, cand_v, act_k, act_v)
+            p = probs[self.slices[i][0]:self.slices[i][1]]
+            if self.hook:
+                self.hook(i)
+            c.predict_residual(ck, cv, p, ak, av, with_counts=True)
+            if overlap:
+                self.events[i].record(main)
+                side.wait_event(self.events[i])
+            with torch.cuda.stream(side):
+                c.build_freq()
+                c.rans_encode()
+        if overlap:
+            main.wait_stream(side)
+        return [c.coded() for c in self.codecs]
+
+    def decode(self, cand_k, cand_v, probs, out_k, out_v, fused=True, overlap=True):
+        main = torch.cuda.current_stream()
+        if overlap:
+            self.side.wait_stream(main)
+        for i, c in enumerate(self.codecs):
+            ck, cv, ok, ov = self._views(i, cand_k, cand_v, out_k, out_v)
+            p = probs[self.slices[i][0]:self.slices[i][1]]
+            if self.hook:
+                self.hook(i)
+            with torch.cuda.stream(self.side if (overlap and i % 2) else main):
+                c.decode(ck, cv, p, ok, ov, fused=fused)
+        if overlap:
+            main.wait_stream(self.side)
+
+    def check_status(self, where="plc"):
+        for c in self.codecs:
+            c.check_status(where)
+
+    # what the accounting needs, summed over the groups
+    def total_words(self):
+        return sum(int(c.n_words.to(torch.int64).sum()) for c in self.codecs)
+
+    def total_escapes(self):
+        return sum(int(c.esc_cnt.to(torch.int64).sum()) for c in self.codecs)
+
+    def roundtrip_exact(self):
+        return all(bool(torch.equal(c.dec_symbols, c.symbols)) for c in self.codecs)

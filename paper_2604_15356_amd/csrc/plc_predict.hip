@@ -35,6 +35,7 @@ struct CodecArgs {
   uint64_t esc_len;               // decode
   const uint64_t *esc_off;        // decode
   float *pred_out;                // encode, nullable
+  uint32_t *counts;               // encode, nullable: [n_streams, 256] symbol counts taken on the way
   uint32_t *tile_cnt;             // [n_streams * tiles_per_stream] escapes per tile
   uint16_t *esc_stage;            // encode: [n_tiles, kEscStage] escapes of each tile in symbol order
   const uint32_t *tile_off;       // decode: exclusive prefix of tile_cnt inside a stream
@@ -231,6 +232,78 @@ __global__ __launch_bounds__(kBlock) void predict_residual_kernel(const CodecArg
     const uint32_t pos = prefix + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
     stage_escapes(a.esc_stage + (int64_t)blockIdx.x * kEscStage, pos, esc_bits, av);
   }
+}
+
+// The same pass with the symbol statistics taken on the way (plc_predict_residual_hist): a workgroup counts
+// every symbol it produces in a histogram in LDS (one copy per wavefront; LDS atomics, a few hundred cycles per
+// tile against the ~4000 the tile's bytes take to arrive) and at the end adds its non-empty bins to the
+// stream's counts with global atomics -- integer adds, so the result does not depend on the order.  The
+// symbols are then not read back for a histogram pass of their own (1 byte per component and a launch).
+// One tile per workgroup, as in the kernel above, measured best (64 sessions: the call 28.3 -> 28.4 ms against
+// 2.3 ms for the histogram pass it replaces; Llama shape 0.84 -> 0.88 against 0.08): walking several tiles in
+// one workgroup saves global atomics but puts a barrier between the tiles' loads (4 tiles: 29.6 and 0.94 ms).
+// Only where a stream is so long that thousands of workgroups in flight add to the same 256 counters do two
+// tiles per workgroup pay (32,768 positions, 4096 tiles per stream: 4.8 -> 4.4 ms).
+constexpr int kHistLongStream = 1024;  // tiles per stream from which on a workgroup takes two
+
+template <int K>
+__global__ __launch_bounds__(kBlock) void predict_residual_hist_kernel(const CodecArgs a, uint32_t *__restrict__ counts,
+                                                                       uint32_t wgs_per_stream, uint32_t tiles_per_wg) {
+  __shared__ uint32_t hist[kBlock / 64][256];
+  __shared__ uint32_t wave_cnt[2][kBlock / 64];
+  const uint32_t stream = blockIdx.x / wgs_per_stream;
+  const uint32_t first_tile = (blockIdx.x - stream * wgs_per_stream) * tiles_per_wg;
+  const int wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int w = 0; w < kBlock / 64; ++w) hist[w][threadIdx.x] = 0u;
+  __syncthreads();
+  uint32_t *myhist = hist[wave];
+#pragma unroll 1
+  for (uint32_t t = 0; t < tiles_per_wg; ++t) {
+    const uint32_t tile = first_tile + t;
+    if (tile >= a.tiles_per_stream) break;  // uniform
+    const int64_t g = (int64_t)stream * a.tiles_per_stream + tile;  // the tile's place in the per-tile arrays
+    const Coord q = locate_chunk(a, stream, tile, threadIdx.x);
+    uint32_t n_esc = 0, esc_bits = 0;
+    uint4 av = make_uint4(0u, 0u, 0u, 0u);
+    if (q.valid) {
+      const uint16_t *cand = (q.c ? a.cand_v : a.cand_k) + q.cand;
+      const uint16_t *act = (q.c ? a.act_v : a.act_k) + q.act;
+      av = load16_stream(act);
+      float pred[kChunk];
+      predict8<K>(cand, a.cs[4], a.weights + q.w, a.k, pred);
+      uint32_t packed[2];
+      quantise8(__builtin_bit_cast(half8, av), pred, a.delta, a.qmax, packed, &n_esc, &esc_bits);
+      store8_stream(a.symbols + q.sym, packed[0], packed[1]);
+      if (a.pred_out) {
+        float4 *po = reinterpret_cast<float4 *>(a.pred_out + q.sym);
+        po[0] = make_float4(pred[0], pred[1], pred[2], pred[3]);
+        po[1] = make_float4(pred[4], pred[5], pred[6], pred[7]);
+      }
+#pragma unroll
+      for (int e = 0; e < kChunk; ++e) atomicAdd(&myhist[(packed[e >> 2] >> (8 * (e & 3))) & 255u], 1u);
+    }
+    uint32_t wave_total = 0, prefix = 0;
+    if (__ballot(n_esc != 0) != 0) prefix = wave_escape_prefix(n_esc, &wave_total);  // uniform
+    uint32_t *cnt = wave_cnt[t & 1];  // two rows in turn: one barrier per tile is enough
+    if ((threadIdx.x & 63) == 0) cnt[wave] = wave_total;
+    __syncthreads();
+    const uint32_t c0 = cnt[0], c1 = cnt[1], c2 = cnt[2], c3 = cnt[3];
+    if (threadIdx.x == 0) a.tile_cnt[g] = c0 + c1 + c2 + c3;
+    if (n_esc) {
+      const uint32_t pos = prefix + (wave > 0 ? c0 : 0u) + (wave > 1 ? c1 : 0u) + (wave > 2 ? c2 : 0u);
+      stage_escapes(a.esc_stage + g * kEscStage, pos, esc_bits, av);
+    }
+  }
+  __syncthreads();
+  const uint32_t v = hist[0][threadIdx.x] + hist[1][threadIdx.x] + hist[2][threadIdx.x] + hist[3][threadIdx.x];
+  if (v) atomicAdd(&counts[(int64_t)stream * 256 + threadIdx.x], v);
+  static_assert(kBlock == 256, "one thread per bin");
+}
+
+__global__ __launch_bounds__(kBlock) void zero_counts_kernel(uint32_t *__restrict__ p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+  if (i < n) p[i] = 0u;
 }
 
 // Token-conditional encode.  A position whose token is a candidate reads 2 bytes per component of that
@@ -570,14 +643,32 @@ void dispatch_k(int k, const CodecArgs &a, unsigned grid, hipStream_t st) {
   }
 }
 
+// Unused dynamic LDS that caps the workgroups a compute unit holds.  Eight workgroups of the weighted-mean
+// kernels keep 8 x 256 x (k + 1) x 16 bytes of loads in flight per compute unit, more than HBM needs at k = 8,
+// and the extra only spreads the access stream: with six (24 KB each) the k = 8 kernels measured 2-4 % faster
+// (predict 0.842 -> 0.820 ms and 27.8 -> 26.7 ms, reconstruct 0.823 -> 0.788 ms on the Llama-shaped and the
+// 64-session configuration), with five or four no better, with three slower.  At k = 4 the prediction pass
+// gains from seven (3.95 -> 3.75 ms at 32,768 positions) and the reconstruction from none.
+unsigned occupancy_pad(int k, bool encode) {
+  if (k >= 8) return 24576u;
+  if (k >= 4 && encode) return 21000u;
+  return 0u;
+}
+
 template <int K>
 struct LaunchPredict {
   static void run(const CodecArgs &a, unsigned grid, hipStream_t st) {
     if (a.chosen) {
       hipLaunchKernelGGL(predict_residual_cond_kernel<K>, dim3((grid + kCondTiles - 1) / kCondTiles), dim3(kBlock), 0,
                          st, a, grid);
+    } else if (a.counts) {
+      const uint32_t T = a.tiles_per_stream > (uint32_t)kHistLongStream ? 2u : 1u;
+      const uint32_t pad = a.k >= 4 ? 24576u : 0u;  // measured best for this kernel at k = 4 and k = 8 alike
+      const uint32_t wgs = (a.tiles_per_stream + T - 1) / T;
+      hipLaunchKernelGGL(predict_residual_hist_kernel<K>, dim3((grid / a.tiles_per_stream) * wgs), dim3(kBlock),
+                         pad, st, a, a.counts, wgs, T);
     } else {
-      hipLaunchKernelGGL(predict_residual_kernel<K>, dim3(grid), dim3(kBlock), 0, st, a);
+      hipLaunchKernelGGL(predict_residual_kernel<K>, dim3(grid), dim3(kBlock), occupancy_pad(a.k, true), st, a);
     }
   }
 };
@@ -587,7 +678,7 @@ struct LaunchReconstruct {
     if (a.chosen) {
       hipLaunchKernelGGL((reconstruct_kernel<K, true>), dim3(grid), dim3(kBlock), 0, st, a);
     } else {
-      hipLaunchKernelGGL((reconstruct_kernel<K, false>), dim3(grid), dim3(kBlock), 0, st, a);
+      hipLaunchKernelGGL((reconstruct_kernel<K, false>), dim3(grid), dim3(kBlock), occupancy_pad(a.k, false), st, a);
     }
   }
 };
@@ -637,7 +728,7 @@ namespace {
 int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, const float *probs,
                   const int32_t *chosen, const uint8_t *bits, float range, int trace_id, const void *act_k, const void *act_v, uint8_t *symbols,
                   uint16_t *esc_vals, uint64_t esc_cap, uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out,
-                  void *ws, size_t ws_bytes, uint32_t *status, void *stream) {
+                  void *ws, size_t ws_bytes, uint32_t *status, void *stream, uint32_t *counts = nullptr) {
   Plan p;
   if (!make_plan(dims, &p)) return PLC_ERR_INVALID;
   if (!aligned(cand_k, 16) || !aligned(cand_v, 16) || !aligned(act_k, 16) || !aligned(act_v, 16))
@@ -661,11 +752,15 @@ int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
   a.chosen = chosen;
   a.bits = bits;
   a.range = range;
+  a.counts = counts;
   float *weights = const_cast<float *>(a.weights);
   uint32_t *tile_off = const_cast<uint32_t *>(a.tile_off);
 
   hipLaunchKernelGGL(weights_kernel, dim3((unsigned)((p.rows + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, probs,
                      weights, p.rows, dims->k, status);
+  if (counts)
+    hipLaunchKernelGGL(zero_counts_kernel, dim3((unsigned)((p.n_streams * 256 + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                       st, counts, p.n_streams * 256);
   {
     TraceScope trace(trace_id, st);
     dispatch_k<LaunchPredict>(dims->k, a, (unsigned)p.n_tiles, st);
@@ -818,6 +913,16 @@ void *static_scratch() {
 }
 }  // namespace
 }  // namespace plc
+
+extern "C" int plc_predict_residual_hist(const plc_dims *dims, const void *cand_k, const void *cand_v,
+                                         const float *probs, const void *act_k, const void *act_v,
+                                         uint8_t *symbols, uint16_t *esc_vals, uint64_t esc_cap,
+                                         uint32_t *esc_cnt, uint64_t *esc_off, float *pred_out, uint32_t *counts,
+                                         void *ws, size_t ws_bytes, uint32_t *status, void *stream) {
+  if (!aligned(counts, 4)) return PLC_ERR_INVALID;
+  return encode_floats(dims, cand_k, cand_v, probs, nullptr, nullptr, 0.0f, PLC_TRACE_PREDICT, act_k, act_v, symbols, esc_vals,
+                       esc_cap, esc_cnt, esc_off, pred_out, ws, ws_bytes, status, stream, counts);
+}
 
 extern "C" int plc_predict_residual_noalloc(const plc_dims *dims, const void *cand_k, const void *cand_v,
                                             const float *probs, const void *act_k, const void *act_v,

@@ -51,6 +51,7 @@ struct RansArgs {
   uint32_t *status;
   int64_t n_units, units_per_stream, syms_per_stream, unit_syms;
   uint32_t wgs_per_stream;
+  uint32_t pair_wgs_per_stream;  // rans_encode_pair_kernel with one table: workgroups per stream
   // one table per bit depth (the *_bucketed calls): symbol t of a stream uses table bits[...] - 1 of its position
   const uint8_t *bits;
   int32_t syms_per_pos, streams_per_session, n_tables;
@@ -446,6 +447,336 @@ __global__ __launch_bounds__(W * 64) void rans_encode_kernel(const RansArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// Encoder for many units: two units per wavefront
+// ---------------------------------------------------------------------------
+// With thousands of units in flight the kernel above is bound by instruction issue, not by latency (measured:
+// 83 cycles of a SIMD per step of a unit, the ~21 instructions of a step at 4 cycles each), and half of every
+// instruction's lanes only mirror the other half.  Here lanes 32-63 code a unit of their own: the step's
+// instructions are the same, only the word positions are per half -- a lane ranks itself inside its own
+// half of the compare's lane mask, and the list pointer is a per-lane value that advances by its half's
+// count.  The two units of a wavefront have the same length: two consecutive whole chunks of a stream (one
+// table), or two consecutive whole streams (TWO_TABLES); a unit without such a partner (an odd count, a
+// shorter last chunk) is coded by the lower half while the upper half shadows it and stores nothing.
+// Symbols and words are staged per half exactly as above.
+template <bool LONG, bool MASKED>
+__device__ __forceinline__ void enc2_step(uint32_t &x, const uint4 e, uint16_t *&wtop, uint16_t *scratch,
+                                          uint32_t &flags, uint32_t below, bool upper, bool on) {
+  bool emit = x > e.y;
+  if (MASKED) emit = emit && on;
+  const uint64_t m = __builtin_amdgcn_ballot_w64(emit);
+  const uint32_t mine = upper ? (uint32_t)(m >> 32) : (uint32_t)m;  // the emit mask of this lane's half
+  uint16_t *slot = wtop + __builtin_popcount(mine & below);
+  *(emit ? slot : scratch) = (uint16_t)x;
+  x = emit ? x >> 16 : x;
+  wtop += __builtin_popcount(mine);
+  const uint32_t t1 = __umulhi(e.x, x);
+  const uint32_t q = (LONG ? t1 + x : t1) >> (e.z >> 24);
+  const uint32_t xn = __umul24(q, e.z) + (x + e.w);
+  if (MASKED) {
+    x = on ? xn : x;
+    flags |= on ? e.w : 0u;
+  } else {
+    x = xn;
+    flags |= e.w;
+  }
+}
+
+template <bool LONG>
+__device__ __forceinline__ void enc2_step_pinned(uint32_t &x, const uint4 e, uint16_t *&wtop, uint16_t *scratch,
+                                                 uint32_t &flags, uint32_t below, bool upper) {
+  const uint64_t m = __builtin_amdgcn_uicmp(x, e.y, 34 /* unsigned > */);
+  const bool emit = x > e.y;
+  PLC_PIN();
+  const uint32_t x16 = x >> 16;
+  PLC_PIN();
+  const uint32_t mine = upper ? (uint32_t)(m >> 32) : (uint32_t)m;
+  PLC_PIN();
+  const uint32_t xr = emit ? x16 : x;
+  PLC_PIN();
+  const uint32_t under = mine & below;
+  PLC_PIN();
+  const uint32_t t1 = __umulhi(e.x, xr);
+  PLC_PIN();
+  const uint32_t rank = (uint32_t)__builtin_popcount(under);
+  PLC_PIN();
+  uint32_t q, xc;
+  if (LONG) {
+    q = (t1 + xr) >> (e.z >> 24);
+  } else {
+    q = t1 >> (e.z >> 24);
+  }
+  xc = xr + e.w;
+  PLC_PIN();
+  uint16_t *slot = wtop + rank;
+  PLC_PIN();
+  const uint32_t p = __umul24(q, e.z);
+  PLC_PIN();
+  slot = emit ? slot : scratch;
+  PLC_PIN();
+  wtop += __builtin_popcount(mine);
+  PLC_PIN();
+  *slot = (uint16_t)x;
+  PLC_PIN();
+  x = p + xc;
+  PLC_PIN();
+  flags |= e.w;
+}
+
+constexpr int kPairMaxWaves = 4;
+// SUPER = batches of symbols staged per round.  Four, as above, is the efficient size (a round's bookkeeping is
+// spread over 64 steps).  With whole streams a workgroup is one wavefront with two tables, and its LDS decides
+// how many are resident: 18.8 KB with four batches (eight per compute unit), 14.7 KB with two (eleven).  Two is
+// taken only where it lets every pair of streams be resident at once instead of leaving a second, mostly empty
+// round (5120 streams: 3.3 -> 2.5 ms); where there are several full rounds anyway the shorter rounds cost more
+// than the extra wavefronts gain (16,384 streams: 7.4 against 7.7 ms).
+template <int W, bool TWO_TABLES, int SUPER = 4>
+__global__ __launch_bounds__(W * 64) void rans_encode_pair_kernel(const RansArgs a) {
+  constexpr int kPairGroups = SUPER * kBatch;                  // groups per staging round
+  constexpr int kPairSymStage = kPairGroups * kLanes + 32;     // its symbols at any 16-byte misalignment
+  constexpr int kPairPieces = (kPairSymStage + 1023) / 1024;   // 16-byte pieces per lane and round
+  static_assert(!TWO_TABLES || W == 1, "whole streams: one pair of streams per workgroup");
+  __shared__ uint4 table[TWO_TABLES ? 2 : 1][256];
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[W][2][2][kPairSymStage];                // [half][buffer]
+  __shared__ __attribute__((aligned(16))) uint16_t word_stage[W][2][kBatchSyms + 8 + 64];       // list + carry + scratch slots
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5;
+  const bool upper = half != 0;
+
+  // ---- which units: unit[0] for lanes 0-31, unit[1] for lanes 32-63 (or none: the upper half then shadows unit[0])
+  int64_t stream[2], begin[2];
+  bool second;       // uniform: the upper half has a unit of its own
+  bool live = true;  // uniform: this wavefront has a unit at all
+  uint32_t len;
+  if (TWO_TABLES) {
+    stream[0] = 2 * (int64_t)blockIdx.x;
+    second = stream[0] + 1 < a.n_units;
+    stream[1] = second ? stream[0] + 1 : stream[0];
+    begin[0] = begin[1] = 0;
+    len = (uint32_t)a.syms_per_stream;
+  } else {
+    const int64_t st = blockIdx.x / a.pair_wgs_per_stream;
+    const int64_t slot = (int64_t)(blockIdx.x - st * a.pair_wgs_per_stream) * W + wave;
+    const int64_t n_full = a.syms_per_stream / a.unit_syms;  // chunks of full length
+    const int64_t n_pairs = n_full / 2;
+    int64_t chunk0;
+    if (slot < n_pairs) {
+      chunk0 = 2 * slot, second = true;
+    } else if ((n_full & 1) && slot == n_pairs) {
+      chunk0 = n_full - 1, second = false;                   // the odd full chunk
+    } else {
+      chunk0 = n_full, second = false;                       // the shorter last chunk
+      live = slot == n_pairs + (n_full & 1) && n_full < a.units_per_stream;
+    }
+    stream[0] = stream[1] = st;
+    begin[0] = chunk0 * a.unit_syms;
+    begin[1] = second ? begin[0] + a.unit_syms : begin[0];
+    const int64_t rest = a.syms_per_stream - begin[0];
+    len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
+  }
+
+  bool long_form = false;
+  {  // table entries: every wavefront scans the frequencies; entry 4*lane + r is built by wavefront (4*lane + r) mod W
+    uint32_t f[TWO_TABLES ? 2 : 1][4], cum[TWO_TABLES ? 2 : 1];
+#pragma unroll
+    for (int t = 0; t < (TWO_TABLES ? 2 : 1); ++t) {
+      const uint32_t total = load_freq4(a.freq + stream[t] * 256, lane, f[t], &cum[t]);
+      if (total != kScale && threadIdx.x == 0) raise(a.status, PLC_ERR_INVALID);
+      long_form = long_form || __ballot(f[t][0] > 2048u || f[t][1] > 2048u || f[t][2] > 2048u || f[t][3] > 2048u) != 0;
+    }
+#pragma unroll
+    for (int t = 0; t < (TWO_TABLES ? 2 : 1); ++t) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int s = lane * 4 + r;
+        if ((s & (W - 1)) == wave)
+          table[t][s] = long_form ? make_enc_entry<true>(f[t][r], cum[t]) : make_enc_entry<false>(f[t][r], cum[t]);
+        cum[t] += f[t][r];
+      }
+    }
+  }
+  __syncthreads();
+  if (!live) return;  // no workgroup barrier below
+
+  const int64_t unit[2] = {stream[0] * a.units_per_stream + begin[0] / a.unit_syms,
+                           stream[1] * a.units_per_stream + begin[1] / a.unit_syms};
+  const uint8_t *ubase[2] = {a.sym_in + stream[0] * a.syms_per_stream + begin[0],
+                             a.sym_in + stream[1] * a.syms_per_stream + begin[1]};
+  const uint32_t mis[2] = {(uint32_t)(reinterpret_cast<uintptr_t>(ubase[0]) & 15u),
+                           (uint32_t)(reinterpret_cast<uintptr_t>(ubase[1]) & 15u)};
+  const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
+  const uint32_t top_syms = len - (uint32_t)(G - 1) * kLanes;  // symbols in the last group, 1..32
+  uint16_t *wp[2] = {a.words_out + a.word_off[unit[0]], a.words_out + a.word_off[unit[1]]};
+  uint16_t *wstage = word_stage[wave][half];               // this lane's half's list
+  uint16_t *scratch = wstage + kBatchSyms + 8 + (lane & 31);
+  // (a shadowing upper half writes its words to its own LDS list and never to global memory)
+
+  const int rl = 31 - (lane & 31);  // rANS lane carried by this hardware lane
+  const uint32_t below = (1u << (lane & 31)) - 1u;
+  const bool top_active = (uint32_t)rl < top_syms;
+  const uint4 *mytable = table[TWO_TABLES ? half : 0];
+  uint32_t x = kLow, flags = 0;
+
+  // Symbol staging per half, as in the kernel above: a round's symbols are fetched as 16-byte pieces aligned
+  // in absolute address by all 64 lanes and placed so that symbol (group ghi-1-j, lane l) sits at
+  // mis + l + 32 * (kPairGroups - 1 - j).
+  auto stage_load = [&](int h, int32_t glo, int32_t ghi, uint4 v[kPairPieces], bool take[kPairPieces]) {
+    const int64_t lo = (int64_t)(glo > 0 ? glo : 0) * kLanes;
+    int64_t hi = (int64_t)(ghi > 0 ? ghi : 0) * kLanes;
+    hi = hi < (int64_t)len ? hi : (int64_t)len;
+#pragma unroll
+    for (int i = 0; i < kPairPieces; ++i) {
+      const int64_t off = lo - (int64_t)mis[h] + (int64_t)(lane + 64 * i) * 16;  // 16-byte aligned in absolute address
+      take[i] = ghi > 0 && off < hi;
+      if (take[i]) v[i] = load16_stream(ubase[h] + off);
+    }
+  };
+  auto stage_store = [&](int h, int buf, int32_t cnt, const uint4 v[kPairPieces], const bool take[kPairPieces]) {
+#pragma unroll
+    for (int i = 0; i < kPairPieces; ++i)
+      if (take[i])
+        *reinterpret_cast<uint4 *>(&sym_stage[wave][h][buf][(lane + 64 * i) * 16 + kLanes * (kPairGroups - cnt)]) = v[i];
+  };
+  // Word lists per half, as above: position p of a list stands for the word at 16-byte-aligned address
+  // (wp - pad) + vbase + p.
+  const uint32_t pad[2] = {(uint32_t)__builtin_amdgcn_readfirstlane((int)((reinterpret_cast<uintptr_t>(wp[0]) >> 1) & 7u)),
+                           (uint32_t)__builtin_amdgcn_readfirstlane((int)((reinterpret_cast<uintptr_t>(wp[1]) >> 1) & 7u))};
+  const uint32_t cap = a.word_cap < 0x7fffffffull ? (uint32_t)a.word_cap : 0x7fffffffu;  // a unit has < 2^31 symbols
+  uint32_t vbase[2] = {0u, 0u};          // multiples of 8
+  uint32_t fill[2] = {pad[0], pad[1]};   // positions of each list in use
+  const bool writes[2] = {true, second};
+  auto store_words = [&](int h, uint32_t first_pos, uint32_t n_pos) {  // word-by-word, with all checks
+    if (!writes[h]) return;
+    const uint16_t *list = word_stage[wave][h];
+    for (uint32_t p = first_pos + lane; p < first_pos + n_pos; p += 64) {
+      const uint32_t v = vbase[h] + p;
+      if (v >= pad[h] && v - pad[h] < cap) wp[h][v - pad[h]] = list[p];
+    }
+  };
+  auto drain = [&](int h, uint32_t new_fill) {  // new_fill uniform
+    uint16_t *list = word_stage[wave][h];
+    const uint32_t full = new_fill / 8;  // at most 65 pieces
+    const bool plain = vbase[h] >= pad[h] && vbase[h] + 8 * full - pad[h] <= cap;
+    if (plain) {
+      if (writes[h]) {
+        uint16_t *dst = wp[h] + (vbase[h] - pad[h]);  // 16-byte aligned
+        if ((uint32_t)lane < full)
+          *reinterpret_cast<uint4 *>(dst + 8 * lane) = *reinterpret_cast<const uint4 *>(list + 8 * lane);
+        if (full > 64 && lane == 0)
+          *reinterpret_cast<uint4 *>(dst + 8 * 64) = *reinterpret_cast<const uint4 *>(list + 8 * 64);
+      }
+    } else {
+      store_words(h, 0, 8 * full);
+    }
+    const uint32_t rest = new_fill - 8 * full;
+    uint16_t carry = 0;
+    if ((uint32_t)lane < rest) carry = list[8 * full + lane];
+    wave_sync();
+    if ((uint32_t)lane < rest) list[lane] = carry;
+    vbase[h] += 8 * full;
+    fill[h] = rest;
+  };
+  // after a batch: each half's new fill from its lanes' list pointer (uniform inside a half), both lists drained
+  auto drain_both = [&](uint16_t *wtop) {
+    const uint32_t mine = (uint32_t)(wtop - wstage);
+    const uint32_t f0 = (uint32_t)__builtin_amdgcn_readlane((int)mine, 0);
+    const uint32_t f1 = (uint32_t)__builtin_amdgcn_readlane((int)mine, 32);
+    wave_sync();
+    drain(0, f0);
+    drain(1, f1);
+    wave_sync();
+  };
+
+  int32_t ghi = G;
+  int32_t cnt_groups = G % kPairGroups ? G % kPairGroups : kPairGroups;
+  // groups of the first round that do not fill a batch (and the top group if it is ragged) run in a
+  // rolled loop with lane masking; every other batch is 16 full groups, fully unrolled
+  int32_t head_groups = cnt_groups % kBatch;
+  if (head_groups == 0 && top_syms < kLanes) head_groups = kBatch;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    uint4 v[kPairPieces];
+    bool take[kPairPieces];
+    stage_load(h, ghi - cnt_groups, ghi, v, take);
+    stage_store(h, 0, cnt_groups, v, take);
+  }
+  wave_sync();
+  int buf = 0;
+  while (ghi > 0) {
+    const int32_t glo = ghi - cnt_groups;
+    uint4 nv[2][kPairPieces];
+    bool ntake[2][kPairPieces];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) stage_load(h, glo - kPairGroups, glo, nv[h], ntake[h]);  // next round, in flight
+    const uint8_t *sb = &sym_stage[wave][half][buf][(upper ? mis[1] : mis[0]) + rl];
+    int32_t j0 = 0;
+    bool landed = false;
+    if (head_groups) {
+      uint16_t *wtop = wstage + (upper ? fill[1] : fill[0]);
+      for (int32_t j = 0; j < head_groups; ++j) {
+        const uint4 e = mytable[sb[kLanes * (kPairGroups - 1 - j)]];
+        if (long_form) {
+          enc2_step<true, true>(x, e, wtop, scratch, flags, below, upper, j != 0 || top_active);
+        } else {
+          enc2_step<false, true>(x, e, wtop, scratch, flags, below, upper, j != 0 || top_active);
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) stage_store(h, buf ^ 1, kPairGroups, nv[h], ntake[h]);
+      landed = true;
+      drain_both(wtop);
+      j0 = head_groups;
+    }
+    for (; j0 < cnt_groups; j0 += kBatch) {
+      const uint8_t *sbb = sb + kLanes * (kPairGroups - kBatch - j0);  // lowest group of this batch
+      uint32_t sy[kBatch];
+      uint16_t *wtop = wstage + (upper ? fill[1] : fill[0]);
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) sy[j] = sbb[kLanes * (kBatch - 1 - j)];
+      // table entries are fetched four groups ahead of the chain, so that their LDS time hides behind it
+      uint4 e[2][4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) e[0][j] = mytable[sy[j]];
+#pragma unroll
+      for (int qt = 0; qt < kBatch / 4; ++qt) {
+        if (qt + 1 < kBatch / 4) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) e[(qt + 1) & 1][j] = mytable[sy[4 * (qt + 1) + j]];
+        }
+        if (long_form) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) enc2_step_pinned<true>(x, e[qt & 1][j], wtop, scratch, flags, below, upper);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) enc2_step_pinned<false>(x, e[qt & 1][j], wtop, scratch, flags, below, upper);
+        }
+      }
+      if (!landed) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) stage_store(h, buf ^ 1, kPairGroups, nv[h], ntake[h]);
+        landed = true;
+      }
+      drain_both(wtop);
+    }
+    wave_sync();
+    buf ^= 1;
+    ghi = glo;
+    cnt_groups = kPairGroups;
+    head_groups = 0;
+  }
+  if (!upper || second) a.states_out[(upper ? unit[1] : unit[0]) * kLanes + rl] = x;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    store_words(h, 0, fill[h]);  // the incomplete last piece
+    const uint32_t n_words = vbase[h] + fill[h] - pad[h];
+    if (lane == 0 && writes[h]) {
+      a.n_words_out[unit[h]] = n_words;
+      if ((uint64_t)n_words > a.word_cap) raise(a.status, PLC_ERR_CAPACITY);
+    }
+  }
+  if ((!upper || second) && (flags & 0x80000000u)) raise(a.status, PLC_ERR_INVALID);  // a symbol with f = 0 occurred
+}
+
+// ---------------------------------------------------------------------------
 // Encoder for few, long units: three wavefronts per unit
 // ---------------------------------------------------------------------------
 // When there are no more units than compute units, time is the length of one unit's chain of steps,
@@ -472,6 +803,11 @@ constexpr int64_t kChainMaxUnits = 1024;  // the same bound for the decoder of w
 // The decoder with one table per depth holds one unit per compute unit (its tables take 128 KB of LDS): two
 // rounds of 256 are what it may take before the many-unit decoder is as fast.
 constexpr int64_t kDepthsMaxUnits = 512;
+// From this many streams on (more than two workgroups per compute unit) the decoder that reconstructs takes
+// its three-block ring where k <= 4 lets three workgroups share a compute unit.
+constexpr int64_t kComputeUnits = 256;  // MI355X
+constexpr int64_t kDenseStreams = 512;
+constexpr int kDenseMaxK = 6;  // up to here the kernel's registers (156 at k = 6) leave room for three wavefronts per SIMD
 
 template <bool LONG>
 __device__ __forceinline__ void pipe_step(uint32_t &x, const uint4 e) {
@@ -1027,7 +1363,7 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 // while the next batches are decoded: out = prediction over RK candidates + symbol * step (the arithmetic
 // of plc_reconstruct; COND: of plc_reconstruct_cond; ADAPT: of plc_reconstruct_adapt).  A batch is 512 symbols = 64 chunks of 8 components,
 // one chunk per lane.  The candidates and weights of a chunk do not depend on its symbols, so they are
-// requested kRecDepth batches ahead and are in registers when the symbols arrive.  The wavefront meets the
+// requested kRecDepth batches ahead (a template parameter) and are in registers when the symbols arrive.  The wavefront meets the
 // decoder at every batch barrier -- one "start" barrier, then one per batch, in step with the other
 // wavefronts of the workgroup -- through the bare instruction, which unlike __syncthreads does not first
 // wait for its outstanding loads.  Loads are issued by every lane in every batch (past the end of the stream
@@ -1037,9 +1373,9 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 // that count).
 //   stream, len, G   the unit's stream, its symbols and groups of 32
 //   sym_stage        the decoder's two symbol stages: batch b is in stage b mod 2 from its barrier to the next
-constexpr int kRecDepth = 3;
+constexpr int kRecDepthBase = 3;  // batches a request runs ahead of its symbols
 
-template <int RK, bool COND, bool ADAPT>
+template <int RK, bool COND, bool ADAPT, int kRecDepth>
 __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t stream, uint32_t len, int32_t G,
                                                     const uint8_t (&sym_stage)[2][2 * kBatchSyms], int lane) {
   static_assert(COND || !ADAPT, "the adaptive quantiser lives on the token-conditional path");
@@ -1093,9 +1429,12 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   // of a chunk is a running count plus a prefix over the lanes.  A chunk with escapes is not stored when
   // its symbols arrive: its raw values are requested from the stream's list, the chunk is held, and the
   // next time the same registers come round, kRecDepth batches later, the values that have arrived are
-  // put over its escaped components and the chunk is stored, once and whole.
+  // put over its escaped components and the chunk is stored, once and whole.  The registers hold up to
+  // kEscLate raw values per chunk; a batch in which some chunk has more (3e-5 of the chunks at the synthetic
+  // workloads' escape rates) fetches its raw values, waits for them and stores its escaped chunks at once.
+  constexpr int kEscLate = 2;
   uint32_t esc_bits[kRecDepth];  // which components of the chunk held for esc_dst await their raw value
-  uint32_t esc_raw[kRecDepth][kChunk];
+  uint32_t esc_raw[kRecDepth][kEscLate];
   u32x4 esc_held[kRecDepth];
   global_u32x4 esc_dst[kRecDepth];
   const uint64_t esc_base = r.esc_off[stream];
@@ -1180,20 +1519,22 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   };
   // the raw values that have arrived for the chunk held for `out`: over its escaped components, lowest
   // first (component e is half e & 1 of word e >> 1), then the chunk goes out
-  auto patch = [&](global_u32x4 out, uint32_t &bits, const uint32_t (&raw)[kChunk], u32x4 &held) {
+  // one raw value over the lowest component still marked in `bits`
+  auto put_raw = [](u32x4 &chunk, uint32_t &bits, uint32_t raw) {
+    const uint32_t e = (uint32_t)__builtin_ctz(bits);
+    bits &= bits - 1u;
+    const uint32_t shift = (e & 1u) * 16u, keep = ~(0xffffu << shift), value = (raw & 0xffffu) << shift;
+#pragma unroll
+    for (uint32_t word = 0; word < 4; ++word)
+      chunk[word] = (e >> 1) == word ? (chunk[word] & keep) | value : chunk[word];
+  };
+  auto patch = [&](global_u32x4 out, uint32_t &bits, const uint32_t (&raw)[kEscLate], u32x4 &held) {
     if (__ballot(bits != 0u) == 0) return;  // uniform
     const bool pending = bits != 0u;
 #pragma unroll
-    for (int i = 0; i < kChunk; ++i) {
+    for (int i = 0; i < kEscLate; ++i) {
       if (i > 0 && __ballot(bits != 0u) == 0) break;  // uniform; seldom more than one per chunk
-      if (bits) {
-        const uint32_t e = (uint32_t)__builtin_ctz(bits);
-        bits &= bits - 1u;
-        const uint32_t shift = (e & 1u) * 16u, keep = ~(0xffffu << shift), value = (raw[i] & 0xffffu) << shift;
-#pragma unroll
-        for (uint32_t word = 0; word < 4; ++word)
-          held[word] = (e >> 1) == word ? (held[word] & keep) | value : held[word];
-      }
+      if (bits) put_raw(held, bits, raw[i]);
     }
     if (pending) __builtin_nontemporal_store(held, out);
   };
@@ -1212,7 +1553,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   // One batch: join its barrier, take its symbols from the stage, finish the chunk, request the chunk
   // of the batch kRecDepth later into the registers just freed.
   auto turn = [&](uint4(&c)[RK], float(&w)[RK], global_u32x4 &out, bool &ok, uint32_t &bits,
-                  uint32_t(&raw)[kChunk], u32x4 &held, global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
+                  uint32_t(&raw)[kEscLate], u32x4 &held, global_u32x4 &late, int32_t &pick_nx, int32_t &pick_us, bool &mean,
                   uint32_t &depth_nx, uint32_t &depth_us, int32_t b, bool whole) {
     // (the scheduler would otherwise start on the predictions of all kRecDepth batches at the top of a
     // pass, and so wait there for requests that have only just gone out)
@@ -1249,8 +1590,6 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
       // bit 7 of byte e to bit e
       const uint32_t mx = ((hx >> 7) * 0x00204081u) >> 21 & 0xfu, my = ((hy >> 7) * 0x00204081u) >> 21 & 0xfu;
       bits = has ? (mx | (my << 4)) : 0u;
-      held = __builtin_bit_cast(u32x4, v);
-      late = out;
       const uint32_t n_esc = (uint32_t)__builtin_popcount(bits);
       const bool several = __ballot(n_esc > 1u) != 0;  // uniform; seldom
       uint32_t total, before;
@@ -1262,15 +1601,35 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
       }
       const uint64_t src = esc_base + esc_seen + before;
       esc_seen += total;
+      if (several && __ballot(n_esc > (uint32_t)kEscLate) != 0) {  // uniform; rare: fetch, wait, store now
+        u32x4 now = __builtin_bit_cast(u32x4, v);
 #pragma unroll
-      for (int i = 0; i < kChunk; ++i) {
-        if (i > 0 && (!several || __ballot(n_esc > (uint32_t)i) == 0)) break;  // uniform
-        if (n_esc > (uint32_t)i) {
-          if (src + i < r.esc_len) {
-            raw[i] = r.esc_in[src + i];
-          } else {
-            raise(a.status, PLC_ERR_CORRUPT);
-            raw[i] = 0u;
+        for (int i = 0; i < kChunk; ++i) {
+          if (__ballot(bits != 0u) == 0) break;  // uniform
+          if (bits) {
+            uint32_t value = 0u;
+            if (src + i < r.esc_len) {
+              value = r.esc_in[src + i];
+            } else {
+              raise(a.status, PLC_ERR_CORRUPT);
+            }
+            put_raw(now, bits, value);
+          }
+        }
+        if (has) __builtin_nontemporal_store(now, out);  // bits is 0 again: nothing is held
+      } else {
+        held = __builtin_bit_cast(u32x4, v);
+        late = out;
+#pragma unroll
+        for (int i = 0; i < kEscLate; ++i) {
+          if (i > 0 && (!several || __ballot(n_esc > (uint32_t)i) == 0)) break;  // uniform
+          if (n_esc > (uint32_t)i) {
+            if (src + i < r.esc_len) {
+              raw[i] = r.esc_in[src + i];
+            } else {
+              raise(a.status, PLC_ERR_CORRUPT);
+              raw[i] = 0u;
+            }
           }
         }
       }
@@ -1318,7 +1677,14 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
 // xc = v << 4 if the lane renormalised and v >> 12 if not (ready long before the entry arrives), so
 // that f * (x >> 12) + slot - cum = f * (xc + w4) + slot - cum = f * xc + .y: one multiply-add, whose
 // 24-bit multiplicand ignores the symbol in the top byte of .x.
-constexpr int kRing2Entries = kRingWords + kRingMirror;
+// The ring holds RB blocks of 512 words.  Four let the helper leave its newest block on its way for a batch
+// (below); three are what the decoder strictly needs -- the block of the pointer, the one below it, and the
+// one being staged for the batch after -- and bring the workgroup's LDS from 56.6 to 52.5 KB, so that a
+// compute unit holds three workgroups instead of two where the registers allow it (k <= 6).  That is the
+// variant for thousands of streams, where units in flight count for more than the helper's wait: 9.1 -> 7.9 ms
+// on 5120 streams with k = 4.  (With k = 8 and 16,384 streams the kernel is bound by HBM at 5.4 TB/s whatever
+// the workgroups per compute unit or the depth of the reconstruction's requests: two, three or four batches
+// ahead, two or three workgroups, all within 0.1 % of one another.)
 
 template <bool MASKED>
 __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uint2 *tab, uint32_t &q,
@@ -1360,9 +1726,11 @@ __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uin
 //
 // RK > 0 adds a third wavefront that reconstructs the KV components of each batch while the next batches are
 // decoded (reconstruct_batches above).
-template <int RK, bool COND>
+template <int RK, bool COND, int RB = 4>
 __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const RansArgs a) {
-  __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing2Entries];  // slot table, then the ring
+  static_assert(RB == 3 || RB == 4, "ring blocks");
+  constexpr uint32_t kRing = RB * kBlockWords;  // words the ring holds: word i sits at kRing - 1 - i mod kRing
+  __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing + kRingMirror];  // slot table, then the ring
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
   __shared__ uint32_t fc[256];
   __shared__ int32_t ptr_pub;
@@ -1425,7 +1793,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
 
   if constexpr (RK > 0) {
     if (wave == 2) {
-      reconstruct_batches<RK, COND, false>(a, stream, len, G, sym_stage, lane);
+      reconstruct_batches<RK, COND, false, kRecDepthBase>(a, stream, len, G, sym_stage, lane);
       return;
     }
   }
@@ -1442,7 +1810,8 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
     // bits multiplied in.
     auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
       if (take) {
-        const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
+        // ring position of the piece's last word (blk >= 0 here)
+        const uint32_t pos = (RB - 1u - (uint32_t)blk % RB) * kBlockWords + (uint32_t)(kBlockWords - 8 - lane * 8);
         const uint32_t w[8] = {v.x & 0xffffu, v.x >> 16, v.y & 0xffffu, v.y >> 16,
                                v.z & 0xffffu, v.z >> 16, v.w & 0xffffu, v.w >> 16};
         uint2 en[8];
@@ -1456,7 +1825,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
         if (pos < (uint32_t)kRingMirror) {
 #pragma unroll
           for (int i = 0; i < 8; i += 2)
-            *reinterpret_cast<uint4 *>(&ring[kRingWords + pos + i]) =
+            *reinterpret_cast<uint4 *>(&ring[kRing + pos + i]) =
                 make_uint4(en[i].x, en[i].y, en[i + 1].x, en[i + 1].y);
         }
       }
@@ -1491,11 +1860,15 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
     // A batch consumes at most one block of words.  While batch b runs, the pointer p_b it started from is
     // known here: the words down to p_b - 3 blocks are requested and those down to p_(b-1) - 3 blocks, at
     // or below p_b - 2 blocks, are in the ring -- batch b + 1 reads no further down than that.
-    stage_down_to(hi - 3 * kBlockWords, false);
+    // With three blocks the words are staged two blocks below the pointer and none is left on its way: the
+    // block written while batch b runs then takes the slot of the block three above it, which lies wholly
+    // above the pointer batch b started from.
+    constexpr int kBelow = (RB == 4 ? 3 : 2) * kBlockWords;
+    stage_down_to(hi - kBelow, false);
     __syncthreads();  // barrier "start"
     int32_t ptr_before = hi;  // the pointer as it stood before the batch now running
     for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
-      stage_down_to(ptr_before - 3 * kBlockWords, true);
+      stage_down_to(ptr_before - kBelow, RB == 4);
       __syncthreads();  // barrier of this batch: its symbols are in the stage, the pointer is published
       ptr_before = ptr_pub;  // read at once: the decoder writes it again only at the end of its next batch
       const bool tail = g0 >= g_tail;
@@ -1533,7 +1906,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
     const bool tail = g0 >= g_tail;
     const int32_t cnt_groups = tail ? tail_groups : kBatch;
     uint8_t *sb = &sym_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
-    const uint32_t q0 = (uint32_t)(-ptr) & (kRingWords - 1);
+    const uint32_t q0 = kRing - 1u - (uint32_t)(ptr - 1) % kRing;  // ring position of the top word (uniform)
     uint32_t q = q0;
     if (tail) {
       for (int32_t j = 0; j < cnt_groups; ++j)
@@ -1683,7 +2056,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(cons
 
   if constexpr (RK > 0) {  // the wavefront that reconstructs, as in the kernel above
     if (wave == 2) {
-      reconstruct_batches<RK, true, true>(a, stream, len, G, sym_stage, lane);
+      reconstruct_batches<RK, true, true, kRecDepthBase>(a, stream, len, G, sym_stage, lane);
       return;
     }
   }
@@ -1933,8 +2306,29 @@ int encode_impl(const uint8_t *symbols, int64_t n_streams, int64_t syms_per_stre
       } else {
         hipLaunchKernelGGL(rans_encode_pipe_kernel<false>, dim3((unsigned)a.n_units), dim3(192), 0, st, a);
       }
-    } else {
+    } else if (a.bits) {
       dispatch_waves<LaunchEncode>(waves, a, (unsigned)(n_streams * a.wgs_per_stream), st);
+    } else if (a.units_per_stream == 1) {
+      // many whole streams: two streams per wavefront, one wavefront per workgroup
+      const int64_t pairs = (a.n_units + 1) / 2;
+      if (pairs > 8 * kComputeUnits && pairs <= 11 * kComputeUnits) {  // all resident at once with the smaller stages
+        hipLaunchKernelGGL((rans_encode_pair_kernel<1, true, 2>), dim3((unsigned)pairs), dim3(64), 0, st, a);
+      } else {
+        hipLaunchKernelGGL((rans_encode_pair_kernel<1, true, 4>), dim3((unsigned)pairs), dim3(64), 0, st, a);
+      }
+    } else {
+      // chunks: two chunks of full length per wavefront; an odd one and a shorter last chunk take a wavefront each
+      const int64_t n_full = a.syms_per_stream / a.unit_syms;
+      const int64_t slots = n_full / 2 + (n_full & 1) + (n_full < a.units_per_stream ? 1 : 0);
+      int w = 1;
+      while (w < kPairMaxWaves && 2 * w <= slots) w *= 2;
+      a.pair_wgs_per_stream = (uint32_t)((slots + w - 1) / w);
+      const unsigned grid = (unsigned)(n_streams * a.pair_wgs_per_stream);  // at most the grid checked above
+      switch (w) {
+        case 1: hipLaunchKernelGGL((rans_encode_pair_kernel<1, false>), dim3(grid), dim3(64), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((rans_encode_pair_kernel<2, false>), dim3(grid), dim3(128), 0, st, a); break;
+        default: hipLaunchKernelGGL((rans_encode_pair_kernel<4, false>), dim3(grid), dim3(256), 0, st, a); break;
+      }
     }
   }
   return launch_status();
@@ -2024,6 +2418,8 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
       hipLaunchKernelGGL(rans_decode_depths_kernel<K>, grid, block, lds, st, a);                 \
     } else if (recon.chosen) {                                                                   \
       hipLaunchKernelGGL((rans_decode_chain_kernel<K, true>), grid, block, 0, st, a);            \
+    } else if (K <= kDenseMaxK && n_streams > kDenseStreams) {                                   \
+      hipLaunchKernelGGL((rans_decode_chain_kernel<(K <= kDenseMaxK ? K : 1), false, 3>), grid, block, 0, st, a); \
     } else {                                                                                     \
       hipLaunchKernelGGL((rans_decode_chain_kernel<K, false>), grid, block, 0, st, a);           \
     }                                                                                            \

@@ -21,7 +21,7 @@ STATIC_SCRATCH_BYTES = 48 << 20
 PLC_ESCAPE = 255
 
 EXPORTS = ("plc_version", "plc_strerror", "plc_workspace_bytes", "plc_units_per_stream",
-           "plc_predict_residual", "plc_predict_residual_noalloc", "plc_histogram", "plc_build_freq", "plc_rans_encode",
+           "plc_predict_residual", "plc_predict_residual_hist", "plc_predict_residual_noalloc", "plc_histogram", "plc_build_freq", "plc_rans_encode",
            "plc_rans_decode", "plc_reconstruct", "plc_rans_decode_reconstruct", "plc_rans_decode_reconstruct_cond",
            "plc_rans_decode_reconstruct_adapt",
            "plc_trace_kernel_events",
@@ -74,6 +74,7 @@ def lib() -> C.CDLL:
         L.plc_units_per_stream.restype = i64
         L.plc_units_per_stream.argtypes = [i64, i32]
         L.plc_predict_residual.argtypes = [dp, p, p, p, p, p, p, p, u64, p, p, p, p, sz, p, p]
+        L.plc_predict_residual_hist.argtypes = [dp, p, p, p, p, p, p, p, u64, p, p, p, p, p, sz, p, p]
         L.plc_predict_residual_noalloc.argtypes = [dp, p, p, p, p, p, p, p, u64, p, p, p, p, p]
         L.plc_histogram.argtypes = [p, i64, i64, p, p]
         L.plc_build_freq.argtypes = [p, i64, p, p, p, p]
@@ -186,6 +187,18 @@ def plc_predict_residual(dims, cand_k, cand_v, probs, act_k, act_v, symbols, esc
         _contig(esc_cnt, torch.int32), _contig(esc_off, torch.int64), _contig(pred_out, torch.float32),
         _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
     _check(rc, "plc_predict_residual")
+
+
+def plc_predict_residual_hist(dims, cand_k, cand_v, probs, act_k, act_v, symbols, esc_vals, esc_cnt,
+                              esc_off, counts, ws, status, pred_out=None):
+    """plc_predict_residual that also leaves the symbols' per-stream counts (int32 [streams, 256]) in `counts`."""
+    rc = lib().plc_predict_residual_hist(
+        C.byref(dims), _ptr(cand_k, torch.float16), _ptr(cand_v, torch.float16),
+        _contig(probs, torch.float32), _ptr(act_k, torch.float16), _ptr(act_v, torch.float16),
+        _contig(symbols, torch.uint8), _contig(esc_vals, None), esc_vals.numel(),
+        _contig(esc_cnt, torch.int32), _contig(esc_off, torch.int64), _contig(pred_out, torch.float32),
+        _contig(counts, torch.int32), _contig(ws, torch.uint8), ws.numel(), _contig(status, torch.int32), _stream())
+    _check(rc, "plc_predict_residual_hist")
 
 
 def plc_predict_residual_noalloc(dims, cand_k, cand_v, probs, act_k, act_v, symbols, esc_vals, esc_cnt,

@@ -49,6 +49,10 @@ CASES = {
     # more streams than the whole-stream encoder and decoder kernels take (1024): the many-unit kernels with one
     # wavefront per workgroup code them, and the one-kernel decode runs in several rounds of workgroups
     "many_streams": ("tiny", dict(S=2, L=20, H=32, n=9, k=4, d=24, seed=24), "lhnkd", True),
+    # more than two workgroups per compute unit with k <= 4: the one-kernel decode takes its three-block word ring,
+    # which these streams wrap a dozen times, from word lists at changing offsets inside a 1 KiB line; escapes are
+    # frequent enough that chunks with more than two of them occur
+    "dense_streams_k3": ("tiny", dict(S=1, L=20, H=30, n=161, k=3, d=64, sigma=0.9, seed=25), "lhnkd", True),
 }
 
 
@@ -195,6 +199,8 @@ def test_special_values_escape_bit_exactly(oracle, dev):
 BYTE_CASES = [(600, 1000, "gauss"),        # several hundred whole-stream units: the three-wavefront encoder, the chain decoder
               (1500, 1000, "gauss"),       # more whole-stream units than those kernels take: the many-unit kernels, one
                                            # wavefront per workgroup (the shape of the 70B-shaped and 64-session runs)
+              (1025, 700, "two"),          # an odd number of them: the last wavefront of the two-streams-per-wavefront
+                                           # encoder has a single stream, and many tables hold a frequency above 2048
               (1, 1, "gauss"), (3, 5, "gauss"), (2, 33, "uniform"), (5, 1000, "gauss"), (2, 4097, "two"),
               (3, 70001, "gauss"), (2, 200000, "constant"), (4, 131072, "uniform"), (1, 262144 + 17, "gauss")]
 
@@ -560,3 +566,51 @@ def test_one_call_decode_equals_two_calls_on_random_shapes(dev):
         codec.check_status("decode_cond in two calls")
         for a, b in zip(ones, twos):
             assert np.array_equal(u16(a), u16(b)), f"trial {trial} (token-conditional)"
+
+
+@pytest.mark.parametrize("S,L,groups,layout", [(5, 2, 3, "lhnkd"), (1, 6, 4, "lnkhd"), (2, 5, 4, "lhnkd")])
+def test_grouped_codec_matches_oracle(oracle, dev, S, L, groups, layout):
+    """The cache coded as independent groups of sessions (or of layers inside a session), the groups'
+    entropy coding on a second HIP stream beside the next group's prediction pass: every stream's symbols,
+    escapes, table, states and words are the oracle's, and the decoded cache is the oracle's reconstruction."""
+    from paper_2604_15356_amd.codec import GroupedCodec
+    O = oracle
+    w = make_workload("tiny", device=dev, layout=layout, random_rows=True,
+                      overrides=dict(S=S, L=L, H=3, n=150, k=5, d=40, sigma=0.4, seed=300 + S))
+    gc = GroupedCodec(w.S, w.L, w.H, w.n, w.k, w.d, w.delta, w.qmax, groups=groups, device=dev,
+                      cand_stride=w.cand_k.stride()[:5], act_stride=w.act_k.stride()[:4], esc_frac=1.0)
+    print(f"  S{S} L{L} {layout}: groups {gc.slices}", flush=True)
+    assert len(gc.codecs) > 1
+    ref = _oracle_encode(O, w, O.F32)
+    sym_ref = ref["symbols"].reshape(w.S, w.L, w.H, -1)
+    freq_ref, _ = O.build_freq(O.histogram(ref["symbols"]))
+    enc_ref = O.rans_encode(ref["symbols"], freq_ref)
+    rk, rv = O.reconstruct(oracle_dims(O, w), storage_np(w.cand_k), storage_np(w.cand_v), w.probs.cpu().numpy(),
+                           ref["symbols"], ref["esc_vals"], ref["esc_off"], mode=O.F32)
+    out_k, out_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+    for overlap in (True, False):
+        for _ in range(2):                      # twice: the second pass finds the first one's artefacts in place
+            coded = gc.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, overlap=overlap)
+        out_k.zero_(), out_v.zero_()
+        gc.decode(w.cand_k, w.cand_v, w.probs, out_k, out_v, overlap=overlap)
+        torch.cuda.synchronize()
+        gc.check_status("grouped")
+        for (s0, s1, l0, l1), c, art in zip(gc.slices, gc.codecs, coded):
+            ids = np.arange(w.S * w.L * w.H).reshape(w.S, w.L, w.H)[s0:s1, l0:l1].ravel()     # the group's streams
+            assert np.array_equal(u8(art.symbols), sym_ref[s0:s1, l0:l1].reshape(len(ids), -1))
+            assert np.array_equal(u16(art.freq), freq_ref[ids])
+            assert np.array_equal(u32(art.states), enc_ref["states"][ids])
+            assert np.array_equal(u32(art.n_words), enc_ref["n_words"][ids])
+            assert np.array_equal(u32(art.esc_cnt), ref["esc_cnt"][ids])
+            words, esc = u16(art.words), u16(art.esc_vals)
+            at = 0
+            for j, st in enumerate(ids):
+                nw, o = int(enc_ref["n_words"][st]), int(enc_ref["word_off"][st])
+                assert np.array_equal(words[j * c.word_cap:j * c.word_cap + nw], enc_ref["words"][o:o + nw])
+                ne, eo = int(ref["esc_cnt"][st]), int(ref["esc_off"][st])
+                assert np.array_equal(esc[at:at + ne], ref["esc_vals"][eo:eo + ne])
+                at += ne
+            assert torch.equal(c.dec_symbols, c.symbols)
+        assert np.array_equal(u16(out_k).ravel(), rk) and np.array_equal(u16(out_v).ravel(), rv)
+    assert gc.roundtrip_exact() and gc.total_words() == int(enc_ref["n_words"].sum())
+    assert gc.total_escapes() == int(ref["esc_cnt"].sum())
