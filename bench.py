@@ -522,7 +522,7 @@ def side_paths(run, args, plc, torch, result):
         for _ in range(args.warmup):
             step3()
         torch.cuda.synchronize()
-        one_kernel3 = one_kernel and w.n_streams <= 2048     # the one-call decode's own bound on this path
+        one_kernel3 = one_kernel and (w.n_streams <= 2048 or w.k <= 4)     # the one-call decode's own bound on this path
         timer3 = KernelTimer(plc, torch, args.steps, conditional=True, fused=one_kernel3)
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -298,8 +298,9 @@ int plc_reconstruct_cond(const plc_dims *dims, const void *cand_k, const void *c
 
 /* plc_rans_decode followed by plc_reconstruct_cond as one call, the way
  * plc_rans_decode_reconstruct stands for plc_rans_decode and plc_reconstruct:
- * same results, and under the same conditions -- here also: at most 2048
- * streams, beyond which the two calls are the faster -- one kernel, whose
+ * same results, and under the same conditions -- here also: with more than
+ * four candidates at most 2048 streams, beyond which the two calls are the
+ * faster -- one kernel, whose
  * reconstructing wavefront fetches each position's chosen index a round before
  * it requests that candidate (all k of them where a position has none).
  * chosen must be in place on `stream` (plc_index_decode) before the call. */

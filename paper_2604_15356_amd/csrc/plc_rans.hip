@@ -2363,14 +2363,16 @@ int decode_impl(const uint16_t *freq, const uint32_t *states, const uint16_t *wo
 
 bool decode_fused_supported(int64_t n_streams, int64_t syms_per_stream, int k, bool cond, bool per_depth) {
   // Candidates that fit the registers of one wavefront kRecDepth batches deep, and whole chunks.  As to
-  // the number of streams: 512 workgroups run at a time, and a round takes its chain's time or the HBM time
-  // of its reconstruction, whichever is longer.  With the weighted mean the two are of a size, so the kernel
-  // beats the many-unit decoder followed by the reconstruction kernel however many rounds there are (5120
-  // streams: 9.1 against 10.9 ms; 16,384 streams with k = 8: 32 against 42 ms).  The token-conditional
-  // reconstruction moves a quarter of the bytes, so there is little to hide and from some eight rounds on
-  // the many-unit decoder's shorter total wins (5120 streams: 8.2 against 6.6 ms): four rounds at most.
-  // With one table per depth a round is 256 workgroups, and the bound of that decoder applies.
-  const int64_t most = per_depth ? kDepthsMaxUnits : cond ? 2048 : INT64_MAX;
+  // the number of streams: two or three workgroups per compute unit run at a time, and a round takes its
+  // chain's time or the HBM time of its reconstruction, whichever is longer.  With the weighted mean the two
+  // are of a size, so the kernel beats the many-unit decoder followed by the reconstruction kernel however
+  // many rounds there are (5120 streams: 7.9 against 10.9 ms; 16,384 streams with k = 8: 31 against 42 ms).
+  // The token-conditional reconstruction moves a quarter of the bytes, so there is little to hide: with
+  // k <= 4, where three workgroups share a compute unit, the kernel still wins (5120 streams: 7.0 against
+  // 7.9 ms); with more candidates (two workgroups) the many-unit decoder's shorter total wins from some eight
+  // rounds on (16,384 streams, k = 8: 28.4 against 22.5 ms): 2048 streams at most.  With one table per depth a
+  // round is 256 workgroups, and the bound of that decoder applies.
+  const int64_t most = per_depth ? kDepthsMaxUnits : (cond && k > 4) ? 2048 : INT64_MAX;
   return n_streams >= 1 && n_streams <= most && k >= 1 && k <= 8 && syms_per_stream >= kChunk &&
          syms_per_stream % kChunk == 0;
 }
@@ -2416,6 +2418,8 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<K>),   \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
       hipLaunchKernelGGL(rans_decode_depths_kernel<K>, grid, block, lds, st, a);                 \
+    } else if (recon.chosen && K <= 4 && n_streams > kDenseStreams) {                            \
+      hipLaunchKernelGGL((rans_decode_chain_kernel<(K <= 4 ? K : 1), true, 3>), grid, block, 0, st, a); \
     } else if (recon.chosen) {                                                                   \
       hipLaunchKernelGGL((rans_decode_chain_kernel<K, true>), grid, block, 0, st, a);            \
     } else if (K <= kDenseMaxK && n_streams > kDenseStreams) {                                   \

@@ -41,9 +41,12 @@ CASES = {
     "three_sessions": ("tiny", dict(S=3, L=1, H=2, n=100, seed=28), "lhnkd", True, 0.15),
     # the generator's own misses (fresh vectors where the token is none of the k = 20 candidates)
     "k20_with_misses": ("miss20", dict(L=1, H=2, n=300, seed=29), "lhnkd", False, 0.0),
-    # more streams than the one-kernel decode takes on this path (2048): the single call then runs the
+    # more streams than the one-kernel decode takes on this path with more than four candidates (2048): the single call then runs the
     # many-unit entropy decoder, one wavefront per workgroup, followed by the reconstruction kernel
-    "many_streams": ("tiny", dict(S=3, L=24, H=32, n=7, k=4, d=16, seed=30), "lhnkd", True, 0.2),
+    "many_streams_k5": ("tiny", dict(S=3, L=24, H=32, n=7, k=5, d=16, seed=30), "lhnkd", True, 0.2),
+    # with k <= 4 the single call keeps its one-kernel form at any number of streams, three workgroups per compute
+    # unit on a three-block word ring that these streams wrap a dozen times
+    "dense_streams_k4": ("tiny", dict(S=1, L=20, H=30, n=161, k=4, d=64, seed=32), "lhnkd", True, 0.2),
 }
 
 
