@@ -201,6 +201,8 @@ BYTE_CASES = [(600, 1000, "gauss"),        # several hundred whole-stream units:
                                            # wavefront per workgroup (the shape of the 70B-shaped and 64-session runs)
               (1025, 700, "two"),          # an odd number of them: the last wavefront of the two-streams-per-wavefront
                                            # encoder has a single stream, and many tables hold a frequency above 2048
+              (3, 8192, "gauss"),          # with chunks of 4096: exactly one pair of chunks per stream
+              (2, 20580, "gauss"),         # five full chunks and a short one: four waves of decoder units per workgroup
               (1, 1, "gauss"), (3, 5, "gauss"), (2, 33, "uniform"), (5, 1000, "gauss"), (2, 4097, "two"),
               (3, 70001, "gauss"), (2, 200000, "constant"), (4, 131072, "uniform"), (1, 262144 + 17, "gauss")]
 
@@ -614,3 +616,27 @@ def test_grouped_codec_matches_oracle(oracle, dev, S, L, groups, layout):
         assert np.array_equal(u16(out_k).ravel(), rk) and np.array_equal(u16(out_v).ravel(), rv)
     assert gc.roundtrip_exact() and gc.total_words() == int(enc_ref["n_words"].sum())
     assert gc.total_escapes() == int(ref["esc_cnt"].sum())
+
+
+def test_statistics_inside_the_prediction_pass_equal_the_histogram_call(oracle, dev):
+    """plc_predict_residual_hist against plc_predict_residual + plc_histogram and against the oracle's counts, on
+    streams long enough (more than 1024 tiles) that a workgroup of the counting pass takes two tiles, with an odd
+    number of tiles, and on short ragged ones."""
+    O = oracle
+    for ov in (dict(S=1, L=1, H=2, n=8200, k=2, d=128, seed=61), dict(S=2, L=1, H=3, n=37, k=5, d=24, sigma=0.8, seed=62)):
+        w = make_workload("tiny", device=dev, overrides=ov, random_rows=True)
+        print(f"  S{w.S} L{w.L} H{w.H} n{w.n} k{w.k} d{w.d}: {(2 * w.n * w.d + 2047) // 2048} tiles per stream", flush=True)
+        codec = codec_for(w, esc_frac=1.0)
+        a = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, fused_counts=True)
+        codec.check_status("counting pass")
+        first = [t.clone() for t in (a.symbols, a.counts, a.freq, a.esc_cnt, a.esc_off, a.states, a.n_words)]
+        esc1 = a.esc_vals[:int(a.esc_cnt.sum())].clone()
+        codec.counts.fill_(-1)
+        b = codec.encode(w.cand_k, w.cand_v, w.probs, w.act_k, w.act_v, fused_counts=False)
+        codec.check_status("separate histogram")
+        for x, y in zip(first, (b.symbols, b.counts, b.freq, b.esc_cnt, b.esc_off, b.states, b.n_words)):
+            assert torch.equal(x, y)
+        assert torch.equal(esc1, b.esc_vals[:int(b.esc_cnt.sum())])
+        ref = _oracle_encode(O, w, O.F32)
+        assert np.array_equal(u8(a.symbols), ref["symbols"])
+        assert np.array_equal(u32(first[1]), O.histogram(ref["symbols"]))
