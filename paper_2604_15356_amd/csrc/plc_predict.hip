@@ -447,27 +447,10 @@ __global__ __launch_bounds__(kBlock) void scan_streams_kernel(const uint32_t *__
   if (threadIdx.x == 0 && carry > esc_cap) raise(status, PLC_ERR_CAPACITY);
 }
 
-// Move every tile's escapes from its staging row to their place in the stream's list; one wavefront
-// per tile.  A tile that overflowed its staging row is gathered again from its symbols and the actual
-// values, 64 chunks at a time.
-__global__ __launch_bounds__(kBlock) void compact_escapes_kernel(const CodecArgs a, uint16_t *__restrict__ esc_vals,
-                                                                 uint64_t esc_cap,
-                                                                 const uint64_t *__restrict__ esc_off,
-                                                                 int64_t n_tiles, bool staged) {
-  const int lane = threadIdx.x & 63;
-  const int64_t t = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-  if (t >= n_tiles) return;
-  const uint32_t cnt = a.tile_cnt[t];
-  if (cnt == 0) return;  // uniform per wavefront
-  const uint32_t stream = (uint32_t)(t / a.tiles_per_stream);
-  const uint32_t tile = (uint32_t)(t - (int64_t)stream * a.tiles_per_stream);
-  uint64_t dst = esc_off[stream] + a.tile_off[t];
-  if (staged && cnt <= (uint32_t)kEscStage) {
-    const uint16_t *row = a.esc_stage + t * kEscStage;
-    for (uint32_t i = lane; i < cnt; i += 64)
-      if (dst + i < esc_cap) esc_vals[dst + i] = row[i];
-    return;
-  }
+// One wavefront gathers the escapes of one tile again from its symbols and the actual values, 64 chunks at
+// a time, and writes them from dst on; for a tile whose staging row overflowed, or that has none.
+__device__ __forceinline__ void regather_tile(const CodecArgs &a, uint16_t *__restrict__ esc_vals, uint64_t esc_cap,
+                                              uint32_t stream, uint32_t tile, uint64_t dst, int lane) {
   for (int round = 0; round < kBlock / 64; ++round) {
     const Coord q = locate_chunk(a, stream, tile, (uint32_t)(round * 64 + lane));
     uint2 sv = make_uint2(0u, 0u);
@@ -491,6 +474,62 @@ __global__ __launch_bounds__(kBlock) void compact_escapes_kernel(const CodecArgs
     }
     dst += wave_total;
   }
+}
+
+// Escapes of every tile from the symbols to their place in the stream's list, where no staging rows were
+// written (symbols that some other pass produced); one wavefront per tile.
+__global__ __launch_bounds__(kBlock) void gather_escapes_kernel(const CodecArgs a, uint16_t *__restrict__ esc_vals,
+                                                                uint64_t esc_cap,
+                                                                const uint64_t *__restrict__ esc_off,
+                                                                int64_t n_tiles) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t = (int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+  if (t >= n_tiles) return;
+  if (a.tile_cnt[t] == 0) return;  // uniform per wavefront
+  const uint32_t stream = (uint32_t)(t / a.tiles_per_stream);
+  const uint32_t tile = (uint32_t)(t - (int64_t)stream * a.tiles_per_stream);
+  regather_tile(a, esc_vals, esc_cap, stream, tile, esc_off[stream] + a.tile_off[t], lane);
+}
+
+// Move every tile's escapes from its staging row to their place in the stream's list.  A wavefront takes
+// 64 tiles in a row, a lane looks up the count and the destination of one of them, and the wavefront then
+// copies the rows one after the other (a row holds at most two wavefronts' worth).  A tile that overflowed
+// its row is gathered again from the symbols.
+__global__ __launch_bounds__(kBlock) void compact_escapes_kernel(const CodecArgs a, uint16_t *__restrict__ esc_vals,
+                                                                 uint64_t esc_cap,
+                                                                 const uint64_t *__restrict__ esc_off,
+                                                                 int64_t n_tiles) {
+  const int lane = threadIdx.x & 63;
+  const int64_t t0 = ((int64_t)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)) * 64;
+  if (t0 >= n_tiles) return;
+  const int64_t t = t0 + lane;
+  uint32_t cnt = 0, stream = 0;
+  uint64_t dst = 0;
+  if (t < n_tiles) {
+    cnt = a.tile_cnt[t];
+    if (cnt) {
+      stream = (uint32_t)(t / a.tiles_per_stream);
+      dst = esc_off[stream] + a.tile_off[t];
+    }
+  }
+  uint64_t todo = __ballot(cnt != 0);
+  while (todo) {  // uniform
+    const int j = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    const uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)cnt, j);
+    const uint64_t d = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)dst, j) |
+                       (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(dst >> 32), j) << 32;
+    if (c <= (uint32_t)kEscStage) {
+      const uint16_t *row = a.esc_stage + (t0 + j) * kEscStage;
+#pragma unroll
+      for (uint32_t i = (uint32_t)lane; i < (uint32_t)kEscStage; i += 64)
+        if (i < c && d + i < esc_cap) esc_vals[d + i] = row[i];
+    } else {
+      const uint32_t s = (uint32_t)__builtin_amdgcn_readlane((int)stream, j);
+      regather_tile(a, esc_vals, esc_cap, s, (uint32_t)(t0 + j - (int64_t)s * a.tiles_per_stream), d, lane);
+    }
+  }
+  static_assert(kEscStage == 128, "two passes of a wavefront over a staging row");
 }
 
 // ---------------------------------------------------------------------------
@@ -769,8 +808,8 @@ int encode_floats(const plc_dims *dims, const void *cand_k, const void *cand_v, 
                      (uint32_t)p.tiles_per_stream, esc_cnt);
   hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
                      status);
-  hipLaunchKernelGGL(compact_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))),
-                     dim3(kBlock), 0, st, a, esc_vals, esc_cap, esc_off, p.n_tiles, true);
+  hipLaunchKernelGGL(compact_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+                     a, esc_vals, esc_cap, esc_off, p.n_tiles);
   return launch_status();
 }
 
@@ -843,8 +882,8 @@ int plc::gather_escapes(const plc_dims *dims, const void *act_k, const void *act
                      (uint32_t)p.tiles_per_stream, esc_cnt);
   hipLaunchKernelGGL(scan_streams_kernel, dim3(1), dim3(kBlock), 0, st, esc_cnt, esc_off, p.n_streams, esc_cap,
                      status);
-  hipLaunchKernelGGL(compact_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))),
-                     dim3(kBlock), 0, st, a, esc_vals, esc_cap, esc_off, p.n_tiles, false);
+  hipLaunchKernelGGL(gather_escapes_kernel, dim3((unsigned)((p.n_tiles + kBlock / 64 - 1) / (kBlock / 64))),
+                     dim3(kBlock), 0, st, a, esc_vals, esc_cap, esc_off, p.n_tiles);
   return launch_status();
 }
 
