@@ -62,9 +62,11 @@ struct RansArgs {
 // Offset (in table entries of `stride` each) of the table that the 32 symbols from unit-relative group g on use.
 __device__ __forceinline__ uint32_t group_table(const RansArgs &a, int64_t stream, int64_t begin, int32_t g,
                                                 uint32_t stride, bool *bad) {
-  const int64_t pos = (begin + (int64_t)g * kLanes) / a.syms_per_pos;
-  const int64_t n_pos = a.syms_per_stream / a.syms_per_pos;
-  int b = a.bits[(stream / a.streams_per_session) * n_pos + pos];
+  // (a stream has fewer than 2^31 symbols and there are fewer than 2^31 streams: 32-bit divisions)
+  const uint32_t spp = (uint32_t)a.syms_per_pos;
+  const uint32_t pos = (uint32_t)(begin + (int64_t)g * kLanes) / spp;
+  const uint32_t n_pos = (uint32_t)a.syms_per_stream / spp;
+  int b = a.bits[(int64_t)((uint32_t)stream / (uint32_t)a.streams_per_session) * n_pos + pos];
   if (b < 1 || b > a.n_tables) {
     *bad = true;
     b = 1;
@@ -92,6 +94,16 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// A workgroup barrier that orders LDS traffic only: what the wavefront wrote to LDS is there when the others
+// pass, and its global loads and stores stay in flight (__syncthreads waits for those too, and a store to HBM
+// takes the better part of a microsecond to be acknowledged).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0), vmcnt and expcnt left alone
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
 }
 
 // ---------------------------------------------------------------------------
@@ -1372,10 +1384,11 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 // stores that escapes add are issued only where there are escapes and cost at most their own number in
 // that count).
 //   stream, len, G   the unit's stream, its symbols and groups of 32
-//   sym_stage        the decoder's two symbol stages: batch b is in stage b mod 2 from its barrier to the next
+//   sym_stage        the two symbol stages: batch b is in stage b mod 2 from its barrier to the next (kLate = 1:
+//                    from the barrier after its own, where the symbols pass through another wavefront first)
 constexpr int kRecDepthBase = 3;  // batches a request runs ahead of its symbols
 
-template <int RK, bool COND, bool ADAPT, int kRecDepth>
+template <int RK, bool COND, bool ADAPT, int kRecDepth, int kLate = 0>
 __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t stream, uint32_t len, int32_t G,
                                                     const uint8_t (&sym_stage)[2][2 * kBatchSyms], int lane) {
   static_assert(COND || !ADAPT, "the adaptive quantiser lives on the token-conditional path");
@@ -1548,6 +1561,11 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();  // barrier "start"
   asm volatile("" ::: "memory");
+  if constexpr (kLate > 0) {  // the first batch's own barrier: its symbols come one barrier later
+    static_assert(kLate == 1, "one barrier behind");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
   const int32_t n_batches = (G + kBatch - 1) / kBatch;
   const int32_t n_full = (int32_t)(n_chunks / 64u);  // batches all of whose chunks exist
   // One batch: join its barrier, take its symbols from the stage, finish the chunk, request the chunk
@@ -1559,7 +1577,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
     // pass, and so wait there for requests that have only just gone out)
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();  // barrier of batch b: its symbols are in the stage
+    __builtin_amdgcn_s_barrier();  // barrier of batch b (kLate: the one after): its symbols are in the stage
     asm volatile("" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);
     const uint2 sv = *reinterpret_cast<const uint2 *>(&sym_stage[b & 1][lane * kChunk]);
@@ -1935,72 +1953,112 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
 // ---------------------------------------------------------------------------
 // Decoder for streams coded as one unit with one table per bit depth
 // ---------------------------------------------------------------------------
-// The table changes from position to position, so a ring entry cannot carry the slot-table entry its word
-// will select (it would need to know the step that consumes it), and a step keeps two LDS round trips:
-// the ring, then the table.  What the kernel above teaches still applies: few dependent instructions
-// between the round trips, and everything that is not the recurrence on a helper wavefront.
-//   slot tables   per depth, 8 bytes per slot: .x = f | sym << 24, .y = slot - cum   (32 KB each)
-//   ring          4 bytes per word w: (w & 0xfff) * 8 | (w >> 12) << 16 -- the byte offset of the word's
-//                 slot in a table, and the four bits the state takes from it
-//   state         x >> 12 with the word's top bits already in; f * (x >> 12) + slot - cum is one
-//                 multiply-add on the entry's arrival
-//   step          multiply-add, compare, rank, shift | ring read | mask-or-in the next table's offset,
-//                 select | table read: six dependent instructions and two round trips
-// The helper stages the words, looks up the table of each group of the next batch, and moves the symbols
-// out; one workgroup barrier per batch, as above.
-constexpr uint32_t kDepthTableBytes = kScale * sizeof(uint2);
+// The table changes from position to position, so when a word is staged the step that will consume it, and
+// with it the table its slot will be looked up in, is not known.  There are at most PLC_MAX_BITS tables,
+// though: the wavefront that stages a word looks its slot up in every one of them, and the ring holds one
+// entry per word and table.  A step then has the one LDS round trip of the kernel above -- the ring entry of
+// the next group's table for a lane that renormalises, that table's slot entry for a lane that does not, one
+// read at an address chosen per lane.  For four rings and four tables to fit, an entry is 4 bytes and leaves
+// the symbol out:
+//   slot tables   per depth, 4 bytes per slot: f | (slot - cum) << 16                       (16 KB each)
+//   rings         per depth, 4 bytes per word w: f | (f * (w >> 12) + slot - cum) << 16 with the slot
+//                 w & 0xfff looked up in that depth's table (at most 4096 * 15 + 4095 = 2^16 - 1)
+//   state         xh = x >> 12 without the bits the word supplies, as above: f * xh + (entry >> 16)
+//   symbols       a step hands on where its entry was read from, as a 16-bit index of 4-byte words; the
+//                 helper turns a batch of these into slots (a table word is its slot; a ring word names a
+//                 word of the raw ring beside the rings, whose low 12 bits are the slot) and the slots into
+//                 symbols through a 4 KB table per depth, while the next batch is decoded, and moves them out
+//   step          multiply | add (each takes its half of the entry), compare, rank, select, shift | read:
+//                 six dependent instructions and one round trip
+// A lone wavefront issues one instruction every four cycles whatever its kind, so the step is as long as its
+// instructions are many: the decoder's uniform operands are formed once per batch, and whatever else can be
+// is left to the helper (handing on the slot itself, read by the decoder from the raw ring behind its entry,
+// was tried: three more instructions a step, 2.4 against 2.1 ms on the Llama shape).  The helper stages the
+// words, tells the decoder each batch's tables (16 tables in a word, two batches before they are needed; the
+// depths come from global memory and are asked for a batch before that, their range looked at when they are
+// used), turns the batch's entries' places into symbols and moves them out; it leaves a batch's barrier
+// without waiting for its stores to be acknowledged.  With candidates a third wavefront reconstructs; it takes
+// a batch's symbols from the helper, one barrier later than in the kernel above, and every wavefront joins one
+// more barrier at the end.
+constexpr uint32_t kDepthTableBytes = kScale * sizeof(uint32_t);
+constexpr uint32_t kDepthRingSlots = kRingWords + kRingMirror;
+constexpr uint32_t kDepthRingBytes = kDepthRingSlots * sizeof(uint32_t);
+constexpr uint32_t kDepthRawBytes = kDepthRingSlots * sizeof(uint16_t);
+constexpr uint32_t kDepthSymBytes = kScale;
+static_assert(kDepthTableBytes % 16 == 0 && kDepthRingBytes % 16 == 0 && kDepthRawBytes % 16 == 0, "16-byte stores");
+// dynamic LDS of the kernel: the slot tables, the rings, the raw ring, the symbol tables
+inline size_t depths_lds_bytes(int n_tables) {
+  return (size_t)n_tables * (kDepthTableBytes + kDepthRingBytes + kDepthSymBytes) + kDepthRawBytes;
+}
+constexpr int depths_threads(int rk) { return rk ? 192 : 128; }
+static_assert(PLC_MAX_BITS * (kDepthTableBytes + kDepthRingBytes) / 4 <= 65536, "a word of the tables and rings in 16 bits");
 
+// LDS of the kernel in 4-byte words.  tw is the first word of the next group's slot table, ring_at the word
+// of that group's ring where the top word sits (both uniform; ring_at in a vector register), ring_after the
+// first word of the ring the step after this one reads: ring_at for that step is formed here, behind the read,
+// like everything else a step can do before its entry has arrived.  `at` is the word the entry in hand was
+// read from; it is what a step hands on for its symbol.
 template <bool MASKED>
-__device__ __forceinline__ void dec_depth_step(uint32_t &xh, uint2 &e, uint32_t &at, const char *tabs,
-                                               const uint32_t *ring, uint32_t &q, uint8_t *sym_slot,
-                                               uint32_t next_table, uint32_t low16, bool on) {
-  const uint32_t xn = __umul24(e.x, xh) + e.y;  // f * (x >> 12) + slot - cum
+__device__ __forceinline__ void dec_depth_step(uint32_t &xh, uint32_t &e, uint32_t &at, const uint32_t *lds_words,
+                                               uint32_t &q, uint32_t &ring_at, uint16_t *code_slot, uint32_t tw,
+                                               uint32_t ring_after, uint32_t slot_mask, bool on) {
+  // f * (x >> 12) + slot - cum; product and sum kept apart so that each takes its half of the entry through
+  // the instruction's own operand select instead of a mask and a shift in front of a fused multiply-add
+  uint32_t fx = __umul24(e & 0xffffu, xh);
+  asm volatile("" : "+v"(fx));
+  const uint32_t xn = fx + (e >> 16);
   uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
   bool need = xn < kLow;
   if (MASKED) {
     need = need && on;
     m32 = (uint32_t)__builtin_amdgcn_ballot_w64(need);
   }
-  const uint32_t r = ring[__builtin_amdgcn_mbcnt_lo(m32, q)];  // the rank-th word from the top
-  __builtin_amdgcn_sched_barrier(0);                           // what does not need it is issued in its shadow
-  const uint32_t at_stay = (((xn & (kScale - 1)) << 3) | next_table);
-  const uint32_t xh_stay = xn >> kScaleBits, xh_base = xn << 4;
+  // ring entry of the rank-th word from the top, or slot-table entry of xn (tables start at multiples of 4096 words)
+  uint32_t idx_ring = __builtin_amdgcn_mbcnt_lo(m32, ring_at);
+  uint32_t idx_slot = (xn & slot_mask) | tw;  // (the mask in a register: and-or is one instruction then)
+  asm volatile("" : "+v"(idx_ring), "+v"(idx_slot));  // both in registers: the choice is one select, not a branch
+  const uint32_t at_next = need ? idx_ring : idx_slot;
+  const uint32_t en = lds_words[at_next];
+  __builtin_amdgcn_sched_barrier(0);  // what follows is issued in the shadow of the read
   q += (uint32_t)__builtin_popcount(m32);
-  if (!MASKED || on) *sym_slot = (uint8_t)(e.x >> 24);
-  __builtin_amdgcn_sched_barrier(0);
-  const uint32_t at_word = (r & low16) | next_table;
-  const uint32_t at_next = need ? at_word : at_stay;
-  const uint2 en = *reinterpret_cast<const uint2 *>(tabs + at_next);
-  const uint32_t xh_next = need ? (xh_base | (r >> 16)) : xh_stay;
+  ring_at = ring_after + q;
+  asm volatile("" : "+v"(ring_at));
+  const uint32_t next = need ? (xn << 4) : (xn >> kScaleBits);
   if (!MASKED || on) {
-    xh = xh_next;
+    *code_slot = (uint16_t)at;
+    xh = next;
     e = en;
     at = at_next;
   }
+  __builtin_amdgcn_sched_barrier(0);  // all of it before the entry is waited for
 }
 
 template <int RK>
-__global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(const RansArgs a) {
-  extern __shared__ __attribute__((aligned(16))) char depth_lds[];  // n_tables slot tables, then the ring
-  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
+__global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(const RansArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char depth_lds[];  // see depths_lds_bytes
+  __shared__ __attribute__((aligned(16))) uint16_t code_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];    // symbols, for the reconstruction
   __shared__ uint32_t fc[256];
-  __shared__ uint32_t table_of_group[2][kBatch];  // byte offset of the table of groups g0 + 1 .. g0 + 16
+  __shared__ uint32_t tables_of_batch[4];  // batch b mod 4: the tables of groups 16 b + 1 .. 16 b + 16, two bits each
   __shared__ uint32_t first_table;
   __shared__ int32_t ptr_pub;
   __shared__ uint32_t tables_ok;
-  constexpr int kThreads = RK ? 192 : 128;
+  constexpr int kThreads = depths_threads(RK);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const bool helper = wave == 1;
   const int64_t stream = blockIdx.x / a.wgs_per_stream;
   const int64_t chunk = blockIdx.x - stream * a.wgs_per_stream;
-  uint2 *tabs2 = reinterpret_cast<uint2 *>(depth_lds);
-  uint32_t *ring = reinterpret_cast<uint32_t *>(depth_lds + (size_t)a.n_tables * kDepthTableBytes);
+  const uint32_t ring_off = (uint32_t)a.n_tables * kDepthTableBytes;
+  const uint32_t raw_off = ring_off + (uint32_t)a.n_tables * kDepthRingBytes;
+  const uint32_t symtab_off = raw_off + kDepthRawBytes;
   bool bad = false;
 
-  // slot tables, one after the other; an all-zero table (a depth the stream does not use) stays zero
+  // slot and symbol tables, one depth after the other; an all-zero table (a depth the stream does not use)
+  // stays zero
   if (threadIdx.x == 0) tables_ok = 1u;
   __syncthreads();
+  uint32_t used = 0;  // uniform: bit t set when table t is one
   for (int t = 0; t < a.n_tables; ++t) {
     uint32_t f[4], cum;
     const uint32_t total = load_freq4(a.freq + (stream * a.n_tables + t) * 256, lane, f, &cum);
@@ -2013,19 +2071,24 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(cons
       }
     }
     __syncthreads();
-    uint2 *tt = tabs2 + (size_t)t * kScale;
+    uint32_t *tt = reinterpret_cast<uint32_t *>(depth_lds + (size_t)t * kDepthTableBytes);
+    uint8_t *ts = reinterpret_cast<uint8_t *>(depth_lds + symtab_off + (size_t)t * kDepthSymBytes);
     if (total == kScale) {
+      used |= 1u << t;
       for (int sy = 0; sy < 256; ++sy) {
         const uint32_t v = fc[sy];
         const uint32_t fs = v & 0xffffu, cs = v >> 16;
-        for (uint32_t o = threadIdx.x; o < fs; o += kThreads) tt[cs + o] = make_uint2(fs | ((uint32_t)sy << 24), o);
+        for (uint32_t o = threadIdx.x; o < fs; o += kThreads) {
+          tt[cs + o] = fs | (o << 16);
+          ts[cs + o] = (uint8_t)sy;
+        }
       }
     } else {
-      for (uint32_t o = threadIdx.x; o < (uint32_t)kScale; o += kThreads) tt[o] = make_uint2(0u, 0u);
+      for (uint32_t o = threadIdx.x; o < (uint32_t)kScale; o += kThreads) tt[o] = 0u, ts[o] = 0;
     }
     __syncthreads();
   }
-  if (!tables_ok) {  // not a table: nothing can be decoded (uniform: both wavefronts leave)
+  if (!tables_ok) {  // not a table: nothing can be decoded (uniform: every wavefront leaves)
     if (threadIdx.x == 0) raise(a.status, PLC_ERR_CORRUPT);
     return;
   }
@@ -2034,14 +2097,12 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(cons
   const int64_t begin = chunk * a.unit_syms;
   const int64_t rest = a.syms_per_stream - begin;
   const uint32_t len = (uint32_t)(rest < a.unit_syms ? rest : a.unit_syms);
-  uint8_t *ubase = a.sym_out + stream * a.syms_per_stream + begin;
-  const bool out_aligned = (reinterpret_cast<uintptr_t>(ubase) & 15u) == 0;
   const int32_t G = (int32_t)((len + kLanes - 1) / kLanes);
   const uint32_t top_syms = len - (uint32_t)(G - 1) * kLanes;
 
   const uint64_t off = a.word_off[unit];
   const uint32_t n = a.n_words_in[unit];
-  if (off > a.words_len || (uint64_t)n > a.words_len - off) {  // uniform: both wavefronts leave
+  if (off > a.words_len || (uint64_t)n > a.words_len - off) {  // uniform: every wavefront leaves
     if (threadIdx.x == 0) raise(a.status, PLC_ERR_CORRUPT);
     return;
   }
@@ -2054,32 +2115,50 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(cons
   if (tail_groups == 0 && top_syms < kLanes) tail_groups = kBatch;
   const int32_t g_tail = G - tail_groups;
 
-  if constexpr (RK > 0) {  // the wavefront that reconstructs, as in the kernel above
+  if constexpr (RK > 0) {  // the wavefront that reconstructs, one barrier behind the decoder's batch
     if (wave == 2) {
-      reconstruct_batches<RK, true, true, kRecDepthBase>(a, stream, len, G, sym_stage, lane);
+      reconstruct_batches<RK, true, true, kRecDepthBase, 1>(a, stream, len, G, sym_stage, lane);
       return;
     }
   }
 
   if (helper) {
     bool bad_depth = false;
+    uint8_t *ubase = a.sym_out + stream * a.syms_per_stream + begin;
+    const bool out_aligned = (reinterpret_cast<uintptr_t>(ubase) & 7u) == 0;
     auto block_load = [&](int32_t blk, uint4 &v) -> bool {
       const int32_t first = blk * kBlockWords + lane * 8;
       const bool take = blk >= 0 && hi > lo && first + 8 > lo && first < hi;
       if (take) v = *reinterpret_cast<const uint4 *>(aligned_base + first);
       return take;
     };
-    auto entry = [](uint32_t w) { return ((w & (kScale - 1)) << 3) | ((w >> kScaleBits) << 16); };
-    auto block_store = [&](int32_t blk, bool take, const uint4 &v) {  // word i goes to ring position (~i) mod 2048
+    // word i goes to ring position (~i) mod 2048: the lane's eight words, last one first
+    auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
       if (take) {
         const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
-        const uint4 r0 = make_uint4(entry(v.w >> 16), entry(v.w & 0xffffu), entry(v.z >> 16), entry(v.z & 0xffffu));
-        const uint4 r1 = make_uint4(entry(v.y >> 16), entry(v.y & 0xffffu), entry(v.x >> 16), entry(v.x & 0xffffu));
-        *reinterpret_cast<uint4 *>(&ring[pos]) = r0;
-        *reinterpret_cast<uint4 *>(&ring[pos + 4]) = r1;
-        if (pos < (uint32_t)kRingMirror) {
-          *reinterpret_cast<uint4 *>(&ring[kRingWords + pos]) = r0;
-          *reinterpret_cast<uint4 *>(&ring[kRingWords + pos + 4]) = r1;
+        const uint32_t w[8] = {v.w >> 16, v.w & 0xffffu, v.z >> 16, v.z & 0xffffu,
+                               v.y >> 16, v.y & 0xffffu, v.x >> 16, v.x & 0xffffu};
+        const uint4 rw = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
+        char *raw = depth_lds + raw_off;
+        *reinterpret_cast<uint4 *>(raw + pos * 2) = rw;
+        if (pos < (uint32_t)kRingMirror) *reinterpret_cast<uint4 *>(raw + (kRingWords + pos) * 2) = rw;
+        for (int t = 0; t < a.n_tables; ++t) {  // uniform
+          if (!((used >> t) & 1u)) continue;    // a depth without a table is never looked up
+          const uint32_t *tt = reinterpret_cast<const uint32_t *>(depth_lds + (size_t)t * kDepthTableBytes);
+          uint32_t en[8];
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const uint32_t s = tt[w[i] & (kScale - 1)];
+            en[i] = s + (__umul24(s & 0xffffu, w[i] >> kScaleBits) << 16);
+          }
+          uint32_t *ring = reinterpret_cast<uint32_t *>(depth_lds + ring_off + (size_t)t * kDepthRingBytes);
+          const uint4 r0 = make_uint4(en[0], en[1], en[2], en[3]), r1 = make_uint4(en[4], en[5], en[6], en[7]);
+          *reinterpret_cast<uint4 *>(&ring[pos]) = r0;
+          *reinterpret_cast<uint4 *>(&ring[pos + 4]) = r1;
+          if (pos < (uint32_t)kRingMirror) {
+            *reinterpret_cast<uint4 *>(&ring[kRingWords + pos]) = r0;
+            *reinterpret_cast<uint4 *>(&ring[kRingWords + pos + 4]) = r1;
+          }
         }
       }
     };
@@ -2108,39 +2187,91 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(cons
         }
       }
     };
-    // tables of groups g0 + 1 .. g0 + 16 (past the last group: the first table, whose entry is never used)
-    auto tables_for = [&](int32_t g0, int buf) {
-      if (lane < kBatch) {
-        const int32_t g = g0 + 1 + lane;
-        table_of_group[buf][lane] = g < G ? group_table(a, stream, begin, g, kDepthTableBytes, &bad_depth) : 0u;
+    // Tables of groups g0 + 1 .. g0 + 16, the ones the 16 steps of the batch at g0 look up (past the last
+    // group: the first table, whose entry is never used).  A depth is asked for here and looked at a batch
+    // later (in range or not included), when it is packed with the 15 others for the decoder.
+    static_assert(PLC_MAX_BITS <= 4 && kBatch == 16, "two bits per table, 16 tables in a word");
+    const uint32_t spp = (uint32_t)a.syms_per_pos;
+    const uint8_t *depth_row =
+        a.bits + (int64_t)((uint32_t)stream / (uint32_t)a.streams_per_session) * ((uint32_t)a.syms_per_stream / spp);
+    auto fetch_depths = [&](int32_t g0) -> uint32_t {
+      const int32_t g = g0 + 1 + (lane & (kBatch - 1));
+      return g < G ? depth_row[(uint32_t)(begin + (int64_t)g * kLanes) / spp] : 1u;
+    };
+    auto pack_tables = [&](uint32_t depth) -> uint32_t {  // lanes 0..15 hold a depth each
+      if (depth < 1u || depth > (uint32_t)a.n_tables) {
+        bad_depth = true;
+        depth = 1u;
       }
+      uint32_t v = (depth - 1u) << (2 * (lane & (kBatch - 1)));
+#pragma unroll
+      for (int off = 1; off < kBatch; off <<= 1) v |= __shfl_xor(v, off, 64);
+      return (uint32_t)__builtin_amdgcn_readfirstlane(v);
     };
     stage_down_to(hi - 3 * kBlockWords, false);
-    if (lane == 0) first_table = group_table(a, stream, begin, 0, kDepthTableBytes, &bad_depth);
-    tables_for(0, 0);
+    uint32_t t_first = group_table(a, stream, begin, 0, 1u, &bad_depth);  // table of the coming batch's first group
+    uint32_t tables_cur = pack_tables(fetch_depths(0)), tables_next = pack_tables(fetch_depths(kBatch));
+    if (lane == 0) {
+      first_table = t_first;
+      tables_of_batch[0] = tables_cur;
+      tables_of_batch[1] = tables_next;
+    }
+    uint32_t depth_ahead = fetch_depths(2 * kBatch);
     __syncthreads();  // barrier "start"
     int32_t ptr_before = hi;
     for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
       stage_down_to(ptr_before - 3 * kBlockWords, true);
-      tables_for(g0 + kBatch, ((g0 / kBatch) + 1) & 1);
-      __syncthreads();  // barrier of this batch
+      const uint32_t tables_after = pack_tables(depth_ahead);
+      if (lane == 0) tables_of_batch[((g0 / kBatch) + 2) & 3] = tables_after;
+      depth_ahead = fetch_depths(g0 + 3 * kBatch);
+      lds_barrier();  // barrier of this batch
       ptr_before = ptr_pub;
+      // the table of the group this lane's eight entries of the batch belong to: the one the step before
+      // looked up (for the batch's first group: the last of the batch before)
+      const uint32_t t_mine = (lane >> 2) == 0 ? t_first : (tables_cur >> (2 * ((lane >> 2) - 1))) & 3u;
+      t_first = tables_cur >> 30;
+      tables_cur = tables_next;
+      tables_next = tables_after;
       const bool tail = g0 >= g_tail;
       const int32_t cnt_groups = tail ? tail_groups : kBatch;
-      const uint8_t *stage = sym_stage[(g0 / kBatch) & 1];
+      const int buf = (g0 / kBatch) & 1;
       const uint32_t done = (uint32_t)g0 * kLanes;
       const uint32_t room = (uint32_t)cnt_groups * kLanes;
       const uint32_t nsym = (len - done) < room ? (len - done) : room;
-      if (out_aligned) {
-        const uint32_t full = nsym / 16;
-        if ((uint32_t)lane < full)
-          *reinterpret_cast<uint4 *>(ubase + done + lane * 16) = *reinterpret_cast<const uint4 *>(&stage[lane * 16]);
-        const uint32_t rest_at = full * 16 + (uint32_t)lane;
-        if (rest_at < nsym) ubase[done + rest_at] = stage[rest_at];
+      // where each entry was read from -> slot -> symbol, eight per lane
+      const uint4 cv = *reinterpret_cast<const uint4 *>(&code_stage[buf][lane * 8]);
+      const uint8_t *ts = reinterpret_cast<const uint8_t *>(depth_lds + symtab_off + (size_t)t_mine * kDepthSymBytes);
+      const uint16_t *raw = reinterpret_cast<const uint16_t *>(depth_lds + raw_off);
+      const uint32_t ring_word0 = ring_off / 4 + t_mine * kDepthRingSlots;  // of this group's ring
+      const uint32_t c[8] = {cv.x & 0xffffu, cv.x >> 16, cv.y & 0xffffu, cv.y >> 16,
+                             cv.z & 0xffffu, cv.z >> 16, cv.w & 0xffffu, cv.w >> 16};
+      // (every lane reads the raw ring, needed or not, and all eight reads are on their way before the first
+      // is used: two LDS round trips for the batch, not sixteen)
+      uint32_t word[8], sy[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        uint32_t p = c[i] - ring_word0;  // not a ring word, or a lane past the end of the stream: keep inside
+        p = p < kDepthRingSlots ? p : 0u;
+        word[i] = raw[p];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t slot_i = c[i] >= ring_off / 4 ? word[i] : c[i];
+        sy[i] = ts[slot_i & (kScale - 1)];
+      }
+      const uint2 sv = make_uint2(sy[0] | (sy[1] << 8) | (sy[2] << 16) | (sy[3] << 24),
+                                  sy[4] | (sy[5] << 8) | (sy[6] << 16) | (sy[7] << 24));
+      if constexpr (RK > 0) *reinterpret_cast<uint2 *>(&sym_stage[buf][lane * 8]) = sv;
+      const uint32_t mine = (uint32_t)lane * 8;
+      if (out_aligned && mine + 8 <= nsym) {
+        *reinterpret_cast<uint2 *>(ubase + done + mine) = sv;
       } else {
-        for (uint32_t i = lane; i < nsym; i += 64) ubase[done + i] = stage[i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          if (mine + i < nsym) ubase[done + mine + i] = (uint8_t)sy[i];
       }
     }
+    if constexpr (RK > 0) lds_barrier();  // the last batch's symbols are in the stage
     if (bad_depth) raise(a.status, PLC_ERR_INVALID);
     return;
   }
@@ -2150,29 +2281,44 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(cons
   const int rl = lane & (kLanes - 1);
   const bool top_active = (uint32_t)rl < top_syms;
   const uint32_t x0 = a.states_in[unit * kLanes + rl];
-  const uint32_t low16 = 0x7ff8u;  // a ring entry's slot offset; also keeps a stray entry inside a table
   int32_t ptr = hi;
   __syncthreads();  // barrier "start": the first words are staged, the first tables known
+  const uint32_t *lds_words = reinterpret_cast<const uint32_t *>(depth_lds);
+  uint32_t slot_mask = kScale - 1;
+  asm volatile("" : "+v"(slot_mask));
   uint32_t xh = x0 >> kScaleBits;
-  uint32_t at = ((x0 & (kScale - 1)) << 3) | first_table;
-  uint2 e = *reinterpret_cast<const uint2 *>(depth_lds + at);
+  uint32_t at = first_table * kScale + (x0 & (kScale - 1));
+  uint32_t e = lds_words[at];
+  uint32_t tables = (uint32_t)__builtin_amdgcn_readfirstlane(tables_of_batch[0]);
+  const uint32_t ring0 = ring_off / 4;
   for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
     const bool tail = g0 >= g_tail;
     const int32_t cnt_groups = tail ? tail_groups : kBatch;
-    const uint32_t *tg = table_of_group[(g0 / kBatch) & 1];
-    uint8_t *sb = &sym_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
+    const uint32_t tables_coming = tables_of_batch[((g0 / kBatch) + 1) & 3];  // asked for now, used after the barrier
+    uint16_t *sb = &code_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
     const uint32_t q0 = (uint32_t)(-ptr) & (kRingWords - 1);
     uint32_t q = q0;
+    uint32_t ring_at = ring0 + (tables & 3u) * kDepthRingSlots + q;
     if (tail) {
-      for (int32_t j = 0; j < cnt_groups; ++j)
-        dec_depth_step<true>(xh, e, at, depth_lds, ring, q, sb + kLanes * j,
-                             (uint32_t)__builtin_amdgcn_readfirstlane(tg[j]), low16, j != cnt_groups - 1 || top_active);
+      for (int32_t j = 0; j < cnt_groups; ++j) {
+        const uint32_t t = (tables >> (2 * j)) & 3u, t_after = j + 1 < kBatch ? (tables >> (2 * j + 2)) & 3u : 0u;
+        dec_depth_step<true>(xh, e, at, lds_words, q, ring_at, sb + kLanes * j, t * kScale,
+                             ring0 + t_after * kDepthRingSlots, slot_mask, j != cnt_groups - 1 || top_active);
+      }
     } else {
-      uint32_t nt[kBatch];
+      // every step's two uniform operands, formed before the first step (in scalar registers from here on)
+      uint32_t tw[kBatch], rw[kBatch + 1];
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) nt[j] = (uint32_t)__builtin_amdgcn_readfirstlane(tg[j]);
+      for (int j = 0; j < kBatch; ++j) {
+        const uint32_t t = (tables >> (2 * j)) & 3u;
+        tw[j] = t * kScale;
+        rw[j] = ring0 + t * kDepthRingSlots;
+        asm volatile("" : "+s"(tw[j]), "+s"(rw[j]));
+      }
+      rw[kBatch] = ring0;
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) dec_depth_step<false>(xh, e, at, depth_lds, ring, q, sb + kLanes * j, nt[j], low16, true);
+      for (int j = 0; j < kBatch; ++j)
+        dec_depth_step<false>(xh, e, at, lds_words, q, ring_at, sb + kLanes * j, tw[j], rw[j + 1], slot_mask, true);
     }
     ptr -= (int32_t)__builtin_amdgcn_readfirstlane(q - q0);
     if (ptr < lo) {
@@ -2181,9 +2327,19 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_depths_kernel(cons
     }
     if (lane == 0) ptr_pub = ptr;
     __syncthreads();  // barrier of this batch
+    tables = (uint32_t)__builtin_amdgcn_readfirstlane(tables_coming);
   }
-  // integrity: every word consumed, every lane back at the initial state (x >> 12 as carried, slot 0 in hand)
-  const bool home = xh == (kLow >> kScaleBits) && (at & (kDepthTableBytes - 1)) == 0;
+  if constexpr (RK > 0) __syncthreads();  // the helper's last batch of symbols, for the reconstruction
+  // integrity: every word consumed, every lane back at the initial state: x >> 12 as carried, and slot 0, which
+  // the place of the entry in hand tells (the helper stages nothing after the last batch's barrier)
+  uint32_t slot;
+  if (at >= ring0) {
+    const uint32_t p = (at - ring0) % kDepthRingSlots;
+    slot = reinterpret_cast<const uint16_t *>(depth_lds + raw_off)[p] & (kScale - 1);
+  } else {
+    slot = at & (kScale - 1);
+  }
+  const bool home = xh == (kLow >> kScaleBits) && slot == 0u;
   if (ptr != lo || (coder && !home)) bad = true;
   if (bad) raise(a.status, PLC_ERR_CORRUPT);
 }
@@ -2232,10 +2388,10 @@ struct LaunchDecode {
     // so take the variant with the shortest step.  With more units its 60 KB of LDS per workgroup would
     // cost more in occupancy than the shorter step gains.
     if (a.bits && W == 1 && a.n_units <= kDepthsMaxUnits) {
-      const size_t lds = (size_t)a.n_tables * kDepthTableBytes + (size_t)(kRingWords + kRingMirror) * sizeof(uint32_t);
+      const size_t lds = depths_lds_bytes(a.n_tables);
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<0>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      hipLaunchKernelGGL(rans_decode_depths_kernel<0>, dim3(grid), dim3(128), lds, st, a);
+      hipLaunchKernelGGL(rans_decode_depths_kernel<0>, dim3(grid), dim3(depths_threads(0)), lds, st, a);
     } else if (a.bits) {
       // (the split tables here too: 5 KB per depth instead of 16 lets three times the wavefronts in)
       const size_t lds = (size_t)a.n_tables * kCompactTable * sizeof(uint32_t);
@@ -2410,14 +2566,14 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
   {
     TraceScope trace(PLC_TRACE_RANS_DECODE, st);
     const dim3 grid((unsigned)n_streams), block(192);
-    const size_t lds = (size_t)a.n_tables * kDepthTableBytes + (size_t)(kRingWords + kRingMirror) * sizeof(uint32_t);
+    const size_t lds = depths_lds_bytes(a.n_tables);
     switch (recon.k) {
 #define PLC_CASE(K)                                                                              \
   case K:                                                                                        \
     if (recon.bits) {                                                                            \
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<K>),   \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
-      hipLaunchKernelGGL(rans_decode_depths_kernel<K>, grid, block, lds, st, a);                 \
+      hipLaunchKernelGGL(rans_decode_depths_kernel<K>, grid, dim3(depths_threads(K)), lds, st, a); \
     } else if (recon.chosen && K <= 4 && n_streams > kDenseStreams) {                            \
       hipLaunchKernelGGL((rans_decode_chain_kernel<(K <= 4 ? K : 1), true, 3>), grid, block, 0, st, a); \
     } else if (recon.chosen) {                                                                   \
