@@ -1705,7 +1705,7 @@ __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t s
 // ahead, two or three workgroups, all within 0.1 % of one another.)
 
 template <bool MASKED>
-__device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uint2 *tab, uint32_t &q,
+__device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uint2 *tab, uint32_t &ring_at,
                                                uint8_t *sym_slot, bool on) {
   const uint32_t xn = __umul24(e.x, xc) + e.y;  // f * (x >> 12) + slot - cum
   uint32_t m32 = (uint32_t)__builtin_amdgcn_uicmp(xn, kLow, 36 /* unsigned < */);
@@ -1716,12 +1716,15 @@ __device__ __forceinline__ void dec_chain_step(uint32_t &xc, uint2 &e, const uin
   }
   // ring entry of the rank-th word from the top (lane 0 is served first: the rank is the number of
   // renormalising lanes below this one), or slot-table entry of xn
-  uint32_t idx_ring = __builtin_amdgcn_mbcnt_lo(m32, (uint32_t)kScale + q);
+  uint32_t idx_ring = __builtin_amdgcn_mbcnt_lo(m32, ring_at);
   uint32_t idx_slot = xn & (kScale - 1);
   asm volatile("" : "+v"(idx_ring), "+v"(idx_slot));  // both in registers: the choice is one select, not a branch
   const uint2 en = tab[need ? idx_ring : idx_slot];
   __builtin_amdgcn_sched_barrier(0);  // what follows is issued in the shadow of the read
-  q += (uint32_t)__builtin_popcount(m32);
+  // (the entry of the top word, uniform, kept in a vector register where the rank is added to it: a count and
+  // an add per step)
+  ring_at += (uint32_t)__builtin_popcount(m32);
+  asm volatile("" : "+v"(ring_at));
   const uint32_t next = need ? (xn << 4) : (xn >> kScaleBits);
   if (!MASKED || on) {
     *sym_slot = (uint8_t)(e.x >> 24);
@@ -1925,15 +1928,16 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
     const int32_t cnt_groups = tail ? tail_groups : kBatch;
     uint8_t *sb = &sym_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
     const uint32_t q0 = kRing - 1u - (uint32_t)(ptr - 1) % kRing;  // ring position of the top word (uniform)
-    uint32_t q = q0;
+    uint32_t ring_at = (uint32_t)kScale + q0;  // its entry in tab
+    asm volatile("" : "+v"(ring_at));
     if (tail) {
       for (int32_t j = 0; j < cnt_groups; ++j)
-        dec_chain_step<true>(xc, e, tab, q, sb + kLanes * j, j != cnt_groups - 1 || top_active);
+        dec_chain_step<true>(xc, e, tab, ring_at, sb + kLanes * j, j != cnt_groups - 1 || top_active);
     } else {
 #pragma unroll
-      for (int j = 0; j < kBatch; ++j) dec_chain_step<false>(xc, e, tab, q, sb + kLanes * j, true);
+      for (int j = 0; j < kBatch; ++j) dec_chain_step<false>(xc, e, tab, ring_at, sb + kLanes * j, true);
     }
-    ptr -= (int32_t)__builtin_amdgcn_readfirstlane(q - q0);
+    ptr -= (int32_t)((uint32_t)__builtin_amdgcn_readfirstlane(ring_at) - (uint32_t)kScale - q0);
     if (ptr < lo) {  // ran out of words: the stream is damaged
       bad = true;
       ptr = lo;
@@ -1970,10 +1974,11 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
 //                 symbols through a 4 KB table per depth, while the next batch is decoded, and moves them out
 //   step          multiply | add (each takes its half of the entry), compare, rank, select, shift | read:
 //                 six dependent instructions and one round trip
-// A lone wavefront issues one instruction every four cycles whatever its kind, so the step is as long as its
-// instructions are many: the decoder's uniform operands are formed once per batch, and whatever else can be
-// is left to the helper (handing on the slot itself, read by the decoder from the raw ring behind its entry,
-// was tried: three more instructions a step, 2.4 against 2.1 ms on the Llama shape).  The helper stages the
+// What a step costs is its dependent chain -- the round trip and six vector instructions at about eight cycles
+// each, one more than the kernel above, whose entry needs no taking apart: 134 against 104 cycles a step with
+// the barrier's share -- so the decoder's uniform operands are formed once per batch, and whatever else can
+// be is left to the helper (handing on the slot itself, read by the decoder from the raw ring behind its
+// entry, was tried: 2.4 against 2.1 ms on the Llama shape).  The helper stages the
 // words, tells the decoder each batch's tables (16 tables in a word, two batches before they are needed; the
 // depths come from global memory and are asked for a batch before that, their range looked at when they are
 // used), turns the batch's entries' places into symbols and moves them out; it leaves a batch's barrier
@@ -1994,14 +1999,14 @@ constexpr int depths_threads(int rk) { return rk ? 192 : 128; }
 static_assert(PLC_MAX_BITS * (kDepthTableBytes + kDepthRingBytes) / 4 <= 65536, "a word of the tables and rings in 16 bits");
 
 // LDS of the kernel in 4-byte words.  tw is the first word of the next group's slot table, ring_at the word
-// of that group's ring where the top word sits (both uniform; ring_at in a vector register), ring_after the
-// first word of the ring the step after this one reads: ring_at for that step is formed here, behind the read,
-// like everything else a step can do before its entry has arrived.  `at` is the word the entry in hand was
-// read from; it is what a step hands on for its symbol.
+// of that group's ring where the top word sits (both uniform; ring_at in a vector register), ring_step how far
+// the ring that the step after this one reads lies behind this one's: ring_at for that step is formed here,
+// behind the read, like everything else a step can do before its entry has arrived.  `at` is the word the
+// entry in hand was read from; it is what a step hands on for its symbol.
 template <bool MASKED>
 __device__ __forceinline__ void dec_depth_step(uint32_t &xh, uint32_t &e, uint32_t &at, const uint32_t *lds_words,
-                                               uint32_t &q, uint32_t &ring_at, uint16_t *code_slot, uint32_t tw,
-                                               uint32_t ring_after, uint32_t slot_mask, bool on) {
+                                               uint32_t &ring_at, uint16_t *code_slot, uint32_t tw,
+                                               uint32_t ring_step, uint32_t slot_mask, bool on) {
   // f * (x >> 12) + slot - cum; product and sum kept apart so that each takes its half of the entry through
   // the instruction's own operand select instead of a mask and a shift in front of a fused multiply-add
   uint32_t fx = __umul24(e & 0xffffu, xh);
@@ -2020,8 +2025,7 @@ __device__ __forceinline__ void dec_depth_step(uint32_t &xh, uint32_t &e, uint32
   const uint32_t at_next = need ? idx_ring : idx_slot;
   const uint32_t en = lds_words[at_next];
   __builtin_amdgcn_sched_barrier(0);  // what follows is issued in the shadow of the read
-  q += (uint32_t)__builtin_popcount(m32);
-  ring_at = ring_after + q;
+  ring_at += (uint32_t)__builtin_popcount(m32) + ring_step;
   asm volatile("" : "+v"(ring_at));
   const uint32_t next = need ? (xn << 4) : (xn >> kScaleBits);
   if (!MASKED || on) {
@@ -2297,30 +2301,30 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
     const uint32_t tables_coming = tables_of_batch[((g0 / kBatch) + 1) & 3];  // asked for now, used after the barrier
     uint16_t *sb = &code_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
     const uint32_t q0 = (uint32_t)(-ptr) & (kRingWords - 1);
-    uint32_t q = q0;
-    uint32_t ring_at = ring0 + (tables & 3u) * kDepthRingSlots + q;
+    uint32_t ring_at = ring0 + (tables & 3u) * kDepthRingSlots + q0;
+    asm volatile("" : "+v"(ring_at));
     if (tail) {
       for (int32_t j = 0; j < cnt_groups; ++j) {
         const uint32_t t = (tables >> (2 * j)) & 3u, t_after = j + 1 < kBatch ? (tables >> (2 * j + 2)) & 3u : 0u;
-        dec_depth_step<true>(xh, e, at, lds_words, q, ring_at, sb + kLanes * j, t * kScale,
-                             ring0 + t_after * kDepthRingSlots, slot_mask, j != cnt_groups - 1 || top_active);
+        dec_depth_step<true>(xh, e, at, lds_words, ring_at, sb + kLanes * j, t * kScale,
+                             (t_after - t) * kDepthRingSlots, slot_mask, j != cnt_groups - 1 || top_active);
       }
     } else {
       // every step's two uniform operands, formed before the first step (in scalar registers from here on)
-      uint32_t tw[kBatch], rw[kBatch + 1];
+      uint32_t tw[kBatch], rs[kBatch];
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) {
-        const uint32_t t = (tables >> (2 * j)) & 3u;
+        const uint32_t t = (tables >> (2 * j)) & 3u, t_after = j + 1 < kBatch ? (tables >> (2 * j + 2)) & 3u : 0u;
         tw[j] = t * kScale;
-        rw[j] = ring0 + t * kDepthRingSlots;
-        asm volatile("" : "+s"(tw[j]), "+s"(rw[j]));
+        rs[j] = (t_after - t) * kDepthRingSlots;
+        asm volatile("" : "+s"(tw[j]), "+s"(rs[j]));
       }
-      rw[kBatch] = ring0;
 #pragma unroll
       for (int j = 0; j < kBatch; ++j)
-        dec_depth_step<false>(xh, e, at, lds_words, q, ring_at, sb + kLanes * j, tw[j], rw[j + 1], slot_mask, true);
+        dec_depth_step<false>(xh, e, at, lds_words, ring_at, sb + kLanes * j, tw[j], rs[j], slot_mask, true);
     }
-    ptr -= (int32_t)__builtin_amdgcn_readfirstlane(q - q0);
+    // the ring position is now the first ring's (table 0 stands in past the batch's last group) plus the words taken
+    ptr -= (int32_t)((uint32_t)__builtin_amdgcn_readfirstlane(ring_at) - ring0 - q0);
     if (ptr < lo) {
       bad = true;
       ptr = lo;
