@@ -172,6 +172,25 @@ def test_bucketed_byte_streams_bit_exact(oracle, dev):
         for unit in range(nu):
             o, k_ = unit * cap, int(enc["n_words"][unit])
             assert np.array_equal(wd[o:o + k_], enc["words"][o:o + k_]), f"unit {unit}"
+        if chunk == 0:
+            # The chain decoder with a ring per depth: a damaged word, then a damaged state, are reported (the
+            # walk ends at the stream's length whatever it reads); an undamaged decode after them is exact again.
+            words[woff[3] + 5] ^= 0x0a51
+            plc.plc_rans_decode_bucketed(freq, states, words, woff, nw, n_streams, N, chunk, spp, sps, bits, B, dec,
+                                         status)
+            assert int(status.item()) == plc.PLC_ERR_CORRUPT
+            words[woff[3] + 5] ^= 0x0a51
+            status.zero_()
+            states[11, 7] ^= 0x00010400
+            plc.plc_rans_decode_bucketed(freq, states, words, woff, nw, n_streams, N, chunk, spp, sps, bits, B, dec,
+                                         status)
+            assert int(status.item()) == plc.PLC_ERR_CORRUPT
+            states[11, 7] ^= 0x00010400
+            status.zero_()
+            dec.zero_()
+            plc.plc_rans_decode_bucketed(freq, states, words, woff, nw, n_streams, N, chunk, spp, sps, bits, B, dec,
+                                         status)
+            assert int(status.item()) == 0 and torch.equal(dec, sym)
     # a depth outside 1..n_tables is reported and nothing faults
     bad = bits.clone()
     bad[0, 5] = 7
