@@ -819,6 +819,7 @@ constexpr int64_t kDepthsMaxUnits = 512;
 // its three-block ring where k <= 4 lets three workgroups share a compute unit.
 constexpr int64_t kComputeUnits = 256;  // MI355X
 constexpr int64_t kDenseStreams = 512;
+constexpr int kCompactMaxK = 4;  // up to here four workgroups of the decoder with 4-byte entries fit a compute unit
 constexpr int kDenseMaxK = 6;  // up to here the kernel's registers (156 at k = 6) leave room for three wavefronts per SIMD
 
 template <bool LONG>
@@ -1388,9 +1389,9 @@ __global__ __launch_bounds__(W * 64) void rans_decode_kernel(const RansArgs a) {
 //                    from the barrier after its own, where the symbols pass through another wavefront first)
 constexpr int kRecDepthBase = 3;  // batches a request runs ahead of its symbols
 
-template <int RK, bool COND, bool ADAPT, int kRecDepth, int kLate = 0>
+template <int RK, bool COND, bool ADAPT, int kRecDepth, int kLate = 0, int kStageSyms = 2 * kBatchSyms>
 __device__ __forceinline__ void reconstruct_batches(const RansArgs &a, int64_t stream, uint32_t len, int32_t G,
-                                                    const uint8_t (&sym_stage)[2][2 * kBatchSyms], int lane) {
+                                                    const uint8_t (&sym_stage)[2][kStageSyms], int lane) {
   static_assert(COND || !ADAPT, "the adaptive quantiser lives on the token-conditional path");
   const ReconView &r = a.recon;
   const uint32_t lh = (uint32_t)(r.L * r.H);
@@ -1985,11 +1986,16 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
 // without waiting for its stores to be acknowledged.  With candidates a third wavefront reconstructs; it takes
 // a batch's symbols from the helper, one barrier later than in the kernel above, and every wavefront joins one
 // more barrier at the end.
+//
+// The same kernel with one table (MODE 1, and 2 with a chosen candidate per position) is the decoder that
+// reconstructs for thousands of streams with k <= 4: the 4-byte entries and the symbols' table bring a workgroup
+// to 39.2 KB of LDS, four to a compute unit instead of three with the 8-byte entries of the kernel above, and
+// what counts there is how many streams are in flight, not one step's length (5120 streams, k = 4: 7.9 -> 7.0 ms).
 constexpr uint32_t kDepthTableBytes = kScale * sizeof(uint32_t);
+constexpr uint32_t kDepthSymBytes = kScale;
 constexpr uint32_t kDepthRingSlots = kRingWords + kRingMirror;
 constexpr uint32_t kDepthRingBytes = kDepthRingSlots * sizeof(uint32_t);
 constexpr uint32_t kDepthRawBytes = kDepthRingSlots * sizeof(uint16_t);
-constexpr uint32_t kDepthSymBytes = kScale;
 static_assert(kDepthTableBytes % 16 == 0 && kDepthRingBytes % 16 == 0 && kDepthRawBytes % 16 == 0, "16-byte stores");
 // dynamic LDS of the kernel: the slot tables, the rings, the raw ring, the symbol tables
 inline size_t depths_lds_bytes(int n_tables) {
@@ -2037,15 +2043,22 @@ __device__ __forceinline__ void dec_depth_step(uint32_t &xh, uint32_t &e, uint32
   __builtin_amdgcn_sched_barrier(0);  // all of it before the entry is waited for
 }
 
-template <int RK>
+template <int RK, int MODE = 0>  // MODE 0: a table per depth; 1: one table; 2: one table and a chosen candidate
 __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(const RansArgs a) {
+  static_assert(MODE == 0 || RK > 0, "the one-table forms exist for the decoder that reconstructs");
+  constexpr int RB = 4;  // ring blocks
+  constexpr uint32_t kRing = kRingWords;
+  constexpr int32_t kBelow = 3 * kBlockWords;  // how far below the pointer the words are staged
+  const int n_tables = MODE ? 1 : a.n_tables;
   extern __shared__ __attribute__((aligned(16))) char depth_lds[];  // see depths_lds_bytes
-  __shared__ __attribute__((aligned(16))) uint16_t code_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
-  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];    // symbols, for the reconstruction
-  __shared__ uint32_t fc[256];
+  __shared__ __attribute__((aligned(16))) uint16_t code_stage[2][kBatchSyms];  // where the entries were read from
+  __shared__ uint16_t code_spare[kBatchSyms];                                  // the same from lanes 32..63, never read
+  __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][kBatchSyms];    // symbols, for the reconstruction
+  uint32_t *const fc = reinterpret_cast<uint32_t *>(&code_stage[0][0]);        // frequencies while the tables are built
+  static_assert(sizeof(code_stage) >= 256 * sizeof(uint32_t), "room for the frequencies");
   __shared__ uint32_t tables_of_batch[4];  // batch b mod 4: the tables of groups 16 b + 1 .. 16 b + 16, two bits each
   __shared__ uint32_t first_table;
-  __shared__ int32_t ptr_pub;
+  __shared__ int32_t ptr_pub[2];  // the word pointer after batch b, in slot b mod 2
   __shared__ uint32_t tables_ok;
   constexpr int kThreads = depths_threads(RK);
   const int lane = threadIdx.x & 63;
@@ -2053,8 +2066,8 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
   const bool helper = wave == 1;
   const int64_t stream = blockIdx.x / a.wgs_per_stream;
   const int64_t chunk = blockIdx.x - stream * a.wgs_per_stream;
-  const uint32_t ring_off = (uint32_t)a.n_tables * kDepthTableBytes;
-  const uint32_t raw_off = ring_off + (uint32_t)a.n_tables * kDepthRingBytes;
+  const uint32_t ring_off = (uint32_t)n_tables * kDepthTableBytes;
+  const uint32_t raw_off = ring_off + (uint32_t)n_tables * kDepthRingBytes;
   const uint32_t symtab_off = raw_off + kDepthRawBytes;
   bool bad = false;
 
@@ -2063,10 +2076,10 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
   if (threadIdx.x == 0) tables_ok = 1u;
   __syncthreads();
   uint32_t used = 0;  // uniform: bit t set when table t is one
-  for (int t = 0; t < a.n_tables; ++t) {
+  for (int t = 0; t < n_tables; ++t) {
     uint32_t f[4], cum;
-    const uint32_t total = load_freq4(a.freq + (stream * a.n_tables + t) * 256, lane, f, &cum);
-    if (total != kScale && total != 0 && threadIdx.x == 0) tables_ok = 0u;
+    const uint32_t total = load_freq4(a.freq + (stream * n_tables + t) * 256, lane, f, &cum);
+    if (total != kScale && (MODE || total != 0) && threadIdx.x == 0) tables_ok = 0u;
     if (wave == 0) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -2121,7 +2134,7 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
 
   if constexpr (RK > 0) {  // the wavefront that reconstructs, one barrier behind the decoder's batch
     if (wave == 2) {
-      reconstruct_batches<RK, true, true, kRecDepthBase, 1>(a, stream, len, G, sym_stage, lane);
+      reconstruct_batches<RK, MODE != 1, MODE == 0, kRecDepthBase, 1, kBatchSyms>(a, stream, len, G, sym_stage, lane);
       return;
     }
   }
@@ -2139,14 +2152,15 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
     // word i goes to ring position (~i) mod 2048: the lane's eight words, last one first
     auto block_store = [&](int32_t blk, bool take, const uint4 &v) {
       if (take) {
-        const uint32_t pos = (uint32_t)(~(blk * kBlockWords + lane * 8 + 7)) & (kRingWords - 1);  // of the last word
+        // word i sits at ring position kRing - 1 - i mod kRing; this is the lane's last word's
+        const uint32_t pos = (uint32_t)((RB - 1 - blk % RB) * kBlockWords + (kBlockWords - 8 - lane * 8));
         const uint32_t w[8] = {v.w >> 16, v.w & 0xffffu, v.z >> 16, v.z & 0xffffu,
                                v.y >> 16, v.y & 0xffffu, v.x >> 16, v.x & 0xffffu};
         const uint4 rw = make_uint4(w[0] | (w[1] << 16), w[2] | (w[3] << 16), w[4] | (w[5] << 16), w[6] | (w[7] << 16));
         char *raw = depth_lds + raw_off;
         *reinterpret_cast<uint4 *>(raw + pos * 2) = rw;
-        if (pos < (uint32_t)kRingMirror) *reinterpret_cast<uint4 *>(raw + (kRingWords + pos) * 2) = rw;
-        for (int t = 0; t < a.n_tables; ++t) {  // uniform
+        if (pos < (uint32_t)kRingMirror) *reinterpret_cast<uint4 *>(raw + (kRing + pos) * 2) = rw;
+        for (int t = 0; t < n_tables; ++t) {  // uniform
           if (!((used >> t) & 1u)) continue;    // a depth without a table is never looked up
           const uint32_t *tt = reinterpret_cast<const uint32_t *>(depth_lds + (size_t)t * kDepthTableBytes);
           uint32_t en[8];
@@ -2160,8 +2174,8 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
           *reinterpret_cast<uint4 *>(&ring[pos]) = r0;
           *reinterpret_cast<uint4 *>(&ring[pos + 4]) = r1;
           if (pos < (uint32_t)kRingMirror) {
-            *reinterpret_cast<uint4 *>(&ring[kRingWords + pos]) = r0;
-            *reinterpret_cast<uint4 *>(&ring[kRingWords + pos + 4]) = r1;
+            *reinterpret_cast<uint4 *>(&ring[kRing + pos]) = r0;
+            *reinterpret_cast<uint4 *>(&ring[kRing + pos + 4]) = r1;
           }
         }
       }
@@ -2195,9 +2209,10 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
     // group: the first table, whose entry is never used).  A depth is asked for here and looked at a batch
     // later (in range or not included), when it is packed with the 15 others for the decoder.
     static_assert(PLC_MAX_BITS <= 4 && kBatch == 16, "two bits per table, 16 tables in a word");
-    const uint32_t spp = (uint32_t)a.syms_per_pos;
+    const uint32_t spp = MODE ? 1u : (uint32_t)a.syms_per_pos;  // (one table: no depths, nothing below is reached)
     const uint8_t *depth_row =
-        a.bits + (int64_t)((uint32_t)stream / (uint32_t)a.streams_per_session) * ((uint32_t)a.syms_per_stream / spp);
+        MODE ? nullptr
+             : a.bits + (int64_t)((uint32_t)stream / (uint32_t)a.streams_per_session) * ((uint32_t)a.syms_per_stream / spp);
     auto fetch_depths = [&](int32_t g0) -> uint32_t {
       const int32_t g = g0 + 1 + (lane & (kBatch - 1));
       return g < G ? depth_row[(uint32_t)(begin + (int64_t)g * kLanes) / spp] : 1u;
@@ -2212,24 +2227,34 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
       for (int off = 1; off < kBatch; off <<= 1) v |= __shfl_xor(v, off, 64);
       return (uint32_t)__builtin_amdgcn_readfirstlane(v);
     };
-    stage_down_to(hi - 3 * kBlockWords, false);
-    uint32_t t_first = group_table(a, stream, begin, 0, 1u, &bad_depth);  // table of the coming batch's first group
-    uint32_t tables_cur = pack_tables(fetch_depths(0)), tables_next = pack_tables(fetch_depths(kBatch));
-    if (lane == 0) {
-      first_table = t_first;
-      tables_of_batch[0] = tables_cur;
-      tables_of_batch[1] = tables_next;
+    stage_down_to(hi - kBelow, false);
+    uint32_t t_first = 0, tables_cur = 0, tables_next = 0, depth_ahead = 1;
+    if constexpr (MODE == 0) {
+      t_first = group_table(a, stream, begin, 0, 1u, &bad_depth);  // table of the coming batch's first group
+      tables_cur = pack_tables(fetch_depths(0)), tables_next = pack_tables(fetch_depths(kBatch));
+      if (lane == 0) {
+        first_table = t_first;
+        tables_of_batch[0] = tables_cur;
+        tables_of_batch[1] = tables_next;
+      }
+      depth_ahead = fetch_depths(2 * kBatch);
     }
-    uint32_t depth_ahead = fetch_depths(2 * kBatch);
     __syncthreads();  // barrier "start"
     int32_t ptr_before = hi;
     for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
-      stage_down_to(ptr_before - 3 * kBlockWords, true);
-      const uint32_t tables_after = pack_tables(depth_ahead);
-      if (lane == 0) tables_of_batch[((g0 / kBatch) + 2) & 3] = tables_after;
-      depth_ahead = fetch_depths(g0 + 3 * kBatch);
+      stage_down_to(ptr_before - kBelow, true);
+      uint32_t tables_after = 0;
+      if constexpr (MODE == 0) {
+        tables_after = pack_tables(depth_ahead);
+        if (lane == 0) tables_of_batch[((g0 / kBatch) + 2) & 3] = tables_after;
+        depth_ahead = fetch_depths(g0 + 3 * kBatch);
+      }
       lds_barrier();  // barrier of this batch
-      ptr_before = ptr_pub;
+      // (The pointer has a slot per batch parity: this wavefront may still be waiting for its loads from global
+      // memory, which the barrier above does not wait for, when the decoder publishes the pointer after the next
+      // batch; read from a single slot it then stages a block too early, over words whose places are yet to be
+      // turned into symbols.)
+      ptr_before = ptr_pub[(g0 / kBatch) & 1];
       // the table of the group this lane's eight entries of the batch belong to: the one the step before
       // looked up (for the batch's first group: the last of the batch before)
       const uint32_t t_mine = (lane >> 2) == 0 ? t_first : (tables_cur >> (2 * ((lane >> 2) - 1))) & 3u;
@@ -2274,6 +2299,9 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
         for (int i = 0; i < 8; ++i)
           if (mine + i < nsym) ubase[done + mine + i] = (uint8_t)sy[i];
       }
+      // (the raw ring is read above as 16-bit words and written by the staging below as 16-byte vectors: the
+      // accesses are kept in this order whatever the compiler makes of their types)
+      asm volatile("" ::: "memory");
     }
     if constexpr (RK > 0) lds_barrier();  // the last batch's symbols are in the stage
     if (bad_depth) raise(a.status, PLC_ERR_INVALID);
@@ -2291,16 +2319,17 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
   uint32_t slot_mask = kScale - 1;
   asm volatile("" : "+v"(slot_mask));
   uint32_t xh = x0 >> kScaleBits;
-  uint32_t at = first_table * kScale + (x0 & (kScale - 1));
+  uint32_t at = (MODE ? 0u : first_table * kScale) + (x0 & (kScale - 1));
   uint32_t e = lds_words[at];
-  uint32_t tables = (uint32_t)__builtin_amdgcn_readfirstlane(tables_of_batch[0]);
+  uint32_t tables = MODE ? 0u : (uint32_t)__builtin_amdgcn_readfirstlane(tables_of_batch[0]);
   const uint32_t ring0 = ring_off / 4;
   for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
     const bool tail = g0 >= g_tail;
     const int32_t cnt_groups = tail ? tail_groups : kBatch;
-    const uint32_t tables_coming = tables_of_batch[((g0 / kBatch) + 1) & 3];  // asked for now, used after the barrier
-    uint16_t *sb = &code_stage[(g0 / kBatch) & 1][coder ? rl : kBatchSyms + rl];
-    const uint32_t q0 = (uint32_t)(-ptr) & (kRingWords - 1);
+    // (the next batch's tables: asked for now, used after the barrier)
+    const uint32_t tables_coming = MODE ? 0u : tables_of_batch[((g0 / kBatch) + 1) & 3];
+    uint16_t *sb = coder ? &code_stage[(g0 / kBatch) & 1][rl] : &code_spare[rl];
+    const uint32_t q0 = kRing - 1u - (uint32_t)(ptr - 1) % kRing;  // ring position of the top word (uniform)
     uint32_t ring_at = ring0 + (tables & 3u) * kDepthRingSlots + q0;
     asm volatile("" : "+v"(ring_at));
     if (tail) {
@@ -2323,15 +2352,18 @@ __global__ __launch_bounds__(depths_threads(RK)) void rans_decode_depths_kernel(
       for (int j = 0; j < kBatch; ++j)
         dec_depth_step<false>(xh, e, at, lds_words, ring_at, sb + kLanes * j, tw[j], rs[j], slot_mask, true);
     }
+    // (The entry in hand is handed on with the next batch's first step, and where it was read from is looked at
+    // a barrier after that.  If it is a ring word it is still there then: the block staged in between goes
+    // where a block above the pointer of a batch ago was, and the word is below that pointer.)
     // the ring position is now the first ring's (table 0 stands in past the batch's last group) plus the words taken
     ptr -= (int32_t)((uint32_t)__builtin_amdgcn_readfirstlane(ring_at) - ring0 - q0);
     if (ptr < lo) {
       bad = true;
       ptr = lo;
     }
-    if (lane == 0) ptr_pub = ptr;
+    if (lane == 0) ptr_pub[(g0 / kBatch) & 1] = ptr;
     __syncthreads();  // barrier of this batch
-    tables = (uint32_t)__builtin_amdgcn_readfirstlane(tables_coming);
+    tables = MODE ? 0u : (uint32_t)__builtin_amdgcn_readfirstlane(tables_coming);
   }
   if constexpr (RK > 0) __syncthreads();  // the helper's last batch of symbols, for the reconstruction
   // integrity: every word consumed, every lane back at the initial state: x >> 12 as carried, and slot 0, which
@@ -2578,8 +2610,13 @@ int rans_decode_fused(const uint16_t *freq, const uint32_t *states, const uint16
       (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&rans_decode_depths_kernel<K>),   \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);           \
       hipLaunchKernelGGL(rans_decode_depths_kernel<K>, grid, dim3(depths_threads(K)), lds, st, a); \
-    } else if (recon.chosen && K <= 4 && n_streams > kDenseStreams) {                            \
-      hipLaunchKernelGGL((rans_decode_chain_kernel<(K <= 4 ? K : 1), true, 3>), grid, block, 0, st, a); \
+    } else if (K <= kCompactMaxK && n_streams > kDenseStreams) {                                 \
+      const size_t lds1 = depths_lds_bytes(1);                                                \
+      if (recon.chosen) {                                                                        \
+        hipLaunchKernelGGL((rans_decode_depths_kernel<(K <= kCompactMaxK ? K : 1), 2>), grid, block, lds1, st, a); \
+      } else {                                                                                   \
+        hipLaunchKernelGGL((rans_decode_depths_kernel<(K <= kCompactMaxK ? K : 1), 1>), grid, block, lds1, st, a); \
+      }                                                                                          \
     } else if (recon.chosen) {                                                                   \
       hipLaunchKernelGGL((rans_decode_chain_kernel<K, true>), grid, block, 0, st, a);            \
     } else if (K <= kDenseMaxK && n_streams > kDenseStreams) {                                   \
