@@ -49,10 +49,12 @@ CASES = {
     # more streams than the whole-stream encoder and decoder kernels take (1024): the many-unit kernels with one
     # wavefront per workgroup code them, and the one-kernel decode runs in several rounds of workgroups
     "many_streams": ("tiny", dict(S=2, L=20, H=32, n=9, k=4, d=24, seed=24), "lhnkd", True),
-    # more than two workgroups per compute unit with k <= 4: the one-kernel decode takes its three-block word ring,
-    # which these streams wrap a dozen times, from word lists at changing offsets inside a 1 KiB line; escapes are
-    # frequent enough that chunks with more than two of them occur
+    # more than 512 streams with k <= 4: the one-kernel decode takes the form with 4-byte entries, four workgroups
+    # per compute unit; these streams wrap its word ring ten times, from word lists at changing offsets inside a
+    # 1 KiB line; escapes are frequent enough that chunks with more than two of them occur
     "dense_streams_k3": ("tiny", dict(S=1, L=20, H=30, n=161, k=3, d=64, sigma=0.9, seed=25), "lhnkd", True),
+    # the same with k = 6: the 8-byte entries on a three-block word ring, three workgroups per compute unit
+    "dense_streams_k6": ("tiny", dict(S=1, L=20, H=30, n=161, k=6, d=64, sigma=0.9, seed=26), "lhnkd", True),
 }
 
 
