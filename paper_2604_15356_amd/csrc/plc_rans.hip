@@ -1755,7 +1755,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
   __shared__ __attribute__((aligned(16))) uint2 tab[kScale + kRing + kRingMirror];  // slot table, then the ring
   __shared__ __attribute__((aligned(16))) uint8_t sym_stage[2][2 * kBatchSyms];  // second half: lanes 32..63
   __shared__ uint32_t fc[256];
-  __shared__ int32_t ptr_pub;
+  __shared__ int32_t ptr_pub[2];  // the word pointer after batch b, in slot b mod 2
   constexpr int kThreads = RK ? 192 : 128;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -1892,7 +1892,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
     for (int32_t g0 = 0; g0 < G; g0 += kBatch) {
       stage_down_to(ptr_before - kBelow, RB == 4);
       __syncthreads();  // barrier of this batch: its symbols are in the stage, the pointer is published
-      ptr_before = ptr_pub;  // read at once: the decoder writes it again only at the end of its next batch
+      ptr_before = ptr_pub[(g0 / kBatch) & 1];  // (its own slot: the decoder publishes the next one a batch later)
       const bool tail = g0 >= g_tail;
       const int32_t cnt_groups = tail ? tail_groups : kBatch;
       const uint8_t *stage = sym_stage[(g0 / kBatch) & 1];
@@ -1943,7 +1943,7 @@ __global__ __launch_bounds__(RK ? 192 : 128) void rans_decode_chain_kernel(const
       bad = true;
       ptr = lo;
     }
-    if (lane == 0) ptr_pub = ptr;
+    if (lane == 0) ptr_pub[(g0 / kBatch) & 1] = ptr;
     __syncthreads();  // barrier of this batch
   }
   // integrity: every word consumed, every lane back at the initial state: x >> 12 as carried, and the entry
