@@ -164,6 +164,19 @@ def test_other_configurations_full_size(oracle, name):
     codec.check_status(name)
     print(f"{name}: coded, checking", flush=True)
     assert torch.equal(codec.dec_symbols, coded.symbols)
+    # every stream, not only the sampled ones: the single decode call (one kernel that also reconstructs where the
+    # shape has one) against the two calls one after the other
+    free, _ = torch.cuda.mem_get_info()
+    if free > 2.2 * out_k.numel() * out_k.element_size() * 2:
+        two_k, two_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)
+        codec.dec_symbols.zero_()
+        codec.decode(w.cand_k, w.cand_v, w.probs, two_k, two_v, fused=False)
+        codec.check_status(name + ", two calls")
+        assert torch.equal(codec.dec_symbols, coded.symbols)
+        assert torch.equal(two_k.view(torch.int16), out_k.view(torch.int16))
+        assert torch.equal(two_v.view(torch.int16), out_v.view(torch.int16))
+        del two_k, two_v
+        print(f"{name}: one call and two calls agree on every stream", flush=True)
     freq = coded.freq.to(torch.int32) & 0xffff
     assert bool((freq.sum(1) == 4096).all())
     cnt = coded.esc_cnt.to(torch.int64)
