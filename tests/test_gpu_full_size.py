@@ -228,6 +228,14 @@ def test_token_conditional_full_size(oracle, name, chunk):
     codec.check_status("token-conditional, full size")
     assert np.array_equal(codec.dec_chosen.cpu().numpy(), ch)
     assert torch.equal(codec.dec_symbols, coded.symbols)
+    two_k, two_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)      # the two calls, on every stream
+    codec.dec_symbols.zero_()
+    codec.decode_cond(w.cand_k, w.cand_v, w.probs, two_k, two_v, fused=False)
+    codec.check_status("token-conditional, two calls")
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    assert torch.equal(two_k.view(torch.int16), out_k.view(torch.int16))
+    assert torch.equal(two_v.view(torch.int16), out_v.view(torch.int16))
+    del two_k, two_v
     probs = w.probs.cpu().numpy()
     ienc = O.index_encode(probs, ch, word_cap=codec.idx_word_cap)
     assert np.array_equal(u32(coded.idx_states), ienc["states"])
@@ -304,6 +312,14 @@ def test_surprisal_adaptive_full_size(oracle):
     bits = O.surprisal_bits(probs, ch, thr_oracle)
     assert np.array_equal(codec.dec_bits.cpu().numpy(), bits)
     assert torch.equal(codec.dec_symbols, coded.symbols)
+    two_k, two_v = torch.zeros_like(w.act_k), torch.zeros_like(w.act_v)      # the two calls, on every stream
+    codec.dec_symbols.zero_()
+    codec.decode_adapt(w.cand_k, w.cand_v, w.probs, two_k, two_v, thr, step_range, fused=False)
+    codec.check_status("surprisal-adaptive, two calls")
+    assert torch.equal(codec.dec_symbols, coded.symbols)
+    assert torch.equal(two_k.view(torch.int16), out_k.view(torch.int16))
+    assert torch.equal(two_v.view(torch.int16), out_v.view(torch.int16))
+    del two_k, two_v
     dm = O.make_dims(1, 1, 1, w.n, w.k, w.d, w.delta, w.qmax)
     spp, B = 2 * w.d, plc.MAX_BITS
     words = u16(coded.words)
