@@ -205,11 +205,12 @@ def test_other_configurations_full_size(oracle, name):
 
 # --------------------------------------------------------------------------- token-conditional path, full size
 
-@pytest.mark.parametrize("name,chunk", [("llama8b", 0), ("llama8b", 4096), ("miss20", 0)])
+@pytest.mark.parametrize("name,chunk", [("llama8b", 0), ("llama8b", 4096), ("miss20", 0), ("70b", 0)])
 def test_token_conditional_full_size(oracle, name, chunk):
     """The Llama-shaped configuration through the token-conditional path as bench.py runs it (true
-    candidate given, whole streams or 4096-symbol units); one position in 16 is declared a miss so that
-    both kinds of prediction occur.  Sampled streams bit for bit against the oracle, the index stream
+    candidate given, whole streams or 4096-symbol units), and the 70B-shaped one (5120 streams with k = 4: the
+    one-kernel decode in its form for many streams, five rounds of workgroups); one position in 16 is declared a
+    miss so that both kinds of prediction occur.  Sampled streams bit for bit against the oracle, the index stream
     completely, properties on everything."""
     if not torch.cuda.is_available():
         pytest.skip("needs a GPU")
