@@ -322,11 +322,15 @@ def time_run(run, args, plc, torch, calibrate=False):
         while dw < 8 and 2 * dw <= ups:
             dw *= 2
         enc_name, dec_name = f"rans_encode_pair_kernel<{pw}, false, 4>", f"rans_decode_kernel<{dw}, false, true>"
-    ring = 3 if (w.k <= 6 and streams_per_launch > 512) else 4
+    dense = streams_per_launch > 512
+    if dense and w.k <= 4:              # 4-byte entries, four workgroups per compute unit
+        fused_name = f"rans_decode_depths_kernel<{w.k}, 1>"
+    else:                               # three-block word ring for k = 5, 6 and many streams
+        fused_name = f"rans_decode_chain_kernel<{w.k}, false, {3 if (dense and w.k <= 6) else 4}>"
     symbol = {"predict_residual": f"predict_residual_hist_kernel<{w.k}>" if run.fused_counts else
               f"predict_residual_kernel<{w.k}>", "reconstruct": f"reconstruct_kernel<{w.k}, false>",
               "histogram": "histogram_kernel", "rans_encode": enc_name, "rans_decode": dec_name,
-              "rans_decode_reconstruct": f"rans_decode_chain_kernel<{w.k}, false, {ring}>"}
+              "rans_decode_reconstruct": fused_name}
     dom_name = max(ms, key=lambda nm: ms[nm] * L)
     dom = kernels[dom_name]
     plain = run.layout == "lhnkd" and not args.sessions and run.chunk_syms == 0
