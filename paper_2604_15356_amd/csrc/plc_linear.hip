@@ -246,10 +246,11 @@ struct DirectShape {
   static constexpr int kPairBytes = 2 * 1024 + 128;                   // two blocks and the padding
   static constexpr int kBytesX = kBlocksX / 2 * kPairBytes, kBufBytes = (kBlocksX + kBlocksY) / 2 * kPairBytes;
   static constexpr size_t kLdsBytes = (size_t)kBuffers * kBufBytes;
-  // The loads of a slice are issued from the barrier on: with three buffers spread over three K steps, with
-  // two buffers all in the first one (the slice is needed at the next barrier).
-  static constexpr int kLoadSteps = NB_ == 2 ? 1 : 3;
-  static constexpr int kLoadsPerSlot = (kLoads + kLoadSteps * FM_ - 1) / (kLoadSteps * FM_);
+  // The loads of a slice are issued from the barrier on, spread over this many K steps: three with three
+  // buffers; with two buffers (the slice is needed at the next barrier) one where the contraction is long and
+  // two where it is short (timed: K = 4096 gains 3-4 % from the second step, K = 50,000 loses 2 %).
+  static constexpr int load_steps(bool long_k) { return NB_ == 3 ? 3 : long_k ? 1 : 2; }
+  static constexpr int loads_per_slot(bool long_k) { return (kLoads + load_steps(long_k) * FM_ - 1) / (load_steps(long_k) * FM_); }
   static_assert(NB_ == 2 || NB_ == 3, "ring of two or three buffers");
   static_assert(kLoads * kWaves == kBlocksX + kBlocksY, "whole loads per wavefront");
   static_assert((NB_ - 1) * kLoads < 64, "the loads in flight fit the counter");
@@ -361,6 +362,7 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _
   //                   (requests spread evenly over the step, all in front of the first product, or every
   //                   load pinned behind a product of its own were 1 to 8 % behind it there).
   constexpr int kHalf = (FM + FN + 1) / 2;
+  constexpr int kLoadSteps = Shape::load_steps(kLongK), kLoadsPerSlot = Shape::loads_per_slot(kLongK);
   static_assert(FM >= 2 && FM * FN >= 2 + FM, "a step's products carry its fragment requests and FM loads");
 #define PLC_REQUEST_FRAGS(set, base, ks, e0, e1)                                                                  \
   _Pragma("unroll") for (int e = (e0); e < (e1); ++e) {                                                           \
@@ -374,9 +376,9 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _
   // slice in buffer `from` and, as the order-th step after the barrier (order < 0: none), its share of the
   // loads of slice fill_slice
 #define PLC_LOADS(order, a, fill_slice)                                                                 \
-  if ((order) >= 0 && (order) < Shape::kLoadSteps) {                                                    \
-    _Pragma("unroll") for (int i = 0; i < Shape::kLoadsPerSlot; ++i) {                                  \
-      const int idx = ((order)*FM + (a)) * Shape::kLoadsPerSlot + i;                                    \
+  if ((order) >= 0 && (order) < kLoadSteps) {                                                           \
+    _Pragma("unroll") for (int i = 0; i < kLoadsPerSlot; ++i) {                                         \
+      const int idx = ((order)*FM + (a)) * kLoadsPerSlot + i;                                           \
       if (idx < Shape::kLoads) request(idx, k_of(fill_slice), width_of(fill_slice), (fill_slice) % NB); \
     }                                                                                                   \
   }
