@@ -699,6 +699,31 @@ def linear_path(args, plc, torch, result, chunk_syms):
         for got, want in ((lo_k, lw.act_k), (lo_v, lw.act_v)):
             diff = (got[0, l_].float() - want[0, l_].float()).abs()
             err5 = max(err5, float(torch.nan_to_num(diff, nan=0.0, posinf=0.0).max()))
+    # Context, not part of the step: the first contraction with the vocabulary padded to a multiple of 64
+    # tokens (zero probabilities), which makes every row's pitch a whole number of 128-byte lines.
+    V64 = (lw.V + 63) // 64 * 64
+    padded = None
+    if V64 != lw.V:
+        p64 = torch.zeros((rows5, V64), dtype=torch.float16, device=dev)
+        e64 = torch.zeros((lw.m, V64), dtype=torch.float16, device=dev)
+        p64[:, :lw.V].copy_(lw.probs_full.reshape(rows5, lw.V))
+        e64[:, :lw.V].copy_(lw.embed_t)
+        eb64 = torch.empty((rows5, lw.m), dtype=torch.float16, device=dev)
+        for _ in range(2):
+            plc.plc_expected_embedding(p64, e64, eb64)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(lin_steps):
+            plc.plc_expected_embedding(p64, e64, eb64)
+        ev1.record()
+        torch.cuda.synchronize()
+        ms64 = ev0.elapsed_time(ev1) / lin_steps
+        eb = torch.empty_like(eb64)
+        plc.plc_expected_embedding(lw.probs_full.reshape(rows5, lw.V), lw.embed_t, eb)
+        tf64 = flops["expected_embedding"] / (ms64 * 1e-3) / 1e12    # the useful flops: the padding adds none
+        padded = dict(V=V64, ms=round(ms64, 4), TFLOPs=round(tf64, 1), frac_mfma=round(tf64 / MFMA_PEAK_TFLOPS, 4),
+                      same_result=bool(torch.equal(eb, eb64)))
+        del p64, e64, eb64, eb
     dom5 = k5["predict_linear"]
     result["linear_predictor"] = {
         "workload": f"S={lw.S} L={lw.L} H={lw.H} d={lw.d} n={lw.n} m={lw.m} V={lw.V}", "steps": lin_steps,
@@ -711,10 +736,12 @@ def linear_path(args, plc, torch, result, chunk_syms):
         "escape_rate": round(esc5 / E5, 6),
         "roundtrip_symbols_exact": bool(torch.equal(codec5.dec_symbols, codec5.symbols)),
         "max_abs_reconstruction_error": round(err5, 6),
+        "expected_embedding_padded_vocabulary": padded,
     }
     log(f"  linear predictor: step {result['linear_predictor']['ms_per_step']} ms ({result['linear_predictor']['value']} GB/s); "
         + ", ".join(f"{k} {v['ms']} ms = {v['TFLOPs']} TFLOP/s ({100 * v['frac_mfma']:.1f} % of fp16 MFMA peak)"
-                    for k, v in k5.items()))
+                    for k, v in k5.items())
+        + (f"; expected embedding with the vocabulary padded to {padded['V']}: {padded['ms']} ms = {padded['TFLOPs']} TFLOP/s" if padded else ""))
     del codec5, lw, lo_k, lo_v
     torch.cuda.empty_cache()
 

@@ -247,10 +247,10 @@ struct DirectShape {
   static constexpr int kBytesX = kBlocksX / 2 * kPairBytes, kBufBytes = (kBlocksX + kBlocksY) / 2 * kPairBytes;
   static constexpr size_t kLdsBytes = (size_t)kBuffers * kBufBytes;
   // The loads of a slice are issued from the barrier on, spread over this many K steps: three with three
-  // buffers; with two buffers (the slice is needed at the next barrier) one where the contraction is long and
-  // two where it is short (timed: K = 4096 gains 3-4 % from the second step, K = 50,000 loses 2 %).
-  static constexpr int load_steps(bool long_k) { return NB_ == 3 ? 3 : long_k ? 1 : 2; }
-  static constexpr int loads_per_slot(bool long_k) { return (kLoads + load_steps(long_k) * FM_ - 1) / (load_steps(long_k) * FM_); }
+  // buffers, two with two (the slice is needed at the next barrier; timed against one step: 2-6 % faster at
+  // every K from 4096 to 50,048; four steps are 5-9 % slower).
+  static constexpr int kLoadSteps = NB_ == 3 ? 3 : 2;
+  static constexpr int kLoadsPerSlot = (kLoads + kLoadSteps * FM_ - 1) / (kLoadSteps * FM_);
   static_assert(NB_ == 2 || NB_ == 3, "ring of two or three buffers");
   static_assert(kLoads * kWaves == kBlocksX + kBlocksY, "whole loads per wavefront");
   static_assert((NB_ - 1) * kLoads < 64, "the loads in flight fit the counter");
@@ -272,7 +272,7 @@ __device__ __forceinline__ void wait_loads_and_barrier() {
   asm volatile("" ::: "memory");
 }
 
-template <class Shape, class Epilogue, bool kLongK>
+template <class Shape, class Epilogue>
 __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _Float16 *__restrict__ X,
                                                                          const _Float16 *__restrict__ Y,
                                                                          int64_t x_batch_stride, int64_t y_batch_stride,
@@ -347,23 +347,15 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _
     for (int j = 0; j < Shape::kLoads; ++j) request(j, k_of(t), width_of(t), t);
   wait_loads_and_barrier<(NB - 1) * Shape::kLoads>();
 
-  // A K step has FM slots of FN products and requests the fragments of the next K step early enough that
-  // the wait in front of a step's first products covers no young request; it may also issue loads of the
-  // slice a whole ring ahead.  Two placements, chosen by the length of the contraction (both timed on
-  // 4096 x 4096 outputs, K = 4096 ... 50,048, and on the second contraction's shape):
-  //   kLongK = false  half of the fragment requests and a slot's loads right after the first slot's products,
-  //                   the other half before the second slot's, later loads in front of their slot; fences
-  //                   keep the memory instructions out of the runs of products.  Ahead by 2 to 5 % where K is
-  //                   4096 or 16,384.
-  //   kLongK = true   half of the requests behind the step's first product, half behind the second, then
-  //                   one load behind each of the next FM products, the rest where the instruction
-  //                   scheduler finds room; PLC_STEP_ORDER states this to the scheduler (groups of: matrix
-  //                   0x008, LDS read 0x100, memory read 0x020).  Ahead by 3 to 5 % where K is about 50,000
-  //                   (requests spread evenly over the step, all in front of the first product, or every
-  //                   load pinned behind a product of its own were 1 to 8 % behind it there).
+  // A K step has FM slots of FN products.  The fragments of the next K step are requested around the first
+  // slot's products -- half of them right after, half before the second slot's -- so that they are several
+  // slots old when the next step starts, and the wait in front of a step's first products covers no request
+  // younger than that.  A slot may also issue loads of the slice a whole ring ahead.  Fences keep the memory
+  // instructions out of the runs of products.  (Handing the order to the instruction scheduler as a sequence
+  // of groups instead -- requests behind the step's first two products, a load behind each of the next --
+  // was timed too: it mixes the products of neighbouring steps and waits for requests it has just made.)
   constexpr int kHalf = (FM + FN + 1) / 2;
-  constexpr int kLoadSteps = Shape::load_steps(kLongK), kLoadsPerSlot = Shape::loads_per_slot(kLongK);
-  static_assert(FM >= 2 && FM * FN >= 2 + FM, "a step's products carry its fragment requests and FM loads");
+  static_assert(FM >= 2, "two slots carry the fragment requests");
 #define PLC_REQUEST_FRAGS(set, base, ks, e0, e1)                                                                  \
   _Pragma("unroll") for (int e = (e0); e < (e1); ++e) {                                                           \
     if (e < FN)                                                                                                   \
@@ -376,26 +368,13 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _
   // slice in buffer `from` and, as the order-th step after the barrier (order < 0: none), its share of the
   // loads of slice fill_slice
 #define PLC_LOADS(order, a, fill_slice)                                                                 \
-  if ((order) >= 0 && (order) < kLoadSteps) {                                                           \
-    _Pragma("unroll") for (int i = 0; i < kLoadsPerSlot; ++i) {                                         \
-      const int idx = ((order)*FM + (a)) * kLoadsPerSlot + i;                                           \
+  if ((order) >= 0 && (order) < Shape::kLoadSteps) {                                                    \
+    _Pragma("unroll") for (int i = 0; i < Shape::kLoadsPerSlot; ++i) {                                  \
+      const int idx = ((order)*FM + (a)) * Shape::kLoadsPerSlot + i;                                    \
       if (idx < Shape::kLoads) request(idx, k_of(fill_slice), width_of(fill_slice), (fill_slice) % NB); \
     }                                                                                                   \
   }
-#define PLC_STEP_ORDER                                                                                  \
-  if (kLongK) {                                                                                         \
-    _Pragma("unroll") for (int i = 0; i < 2; ++i) {                                                     \
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
-      __builtin_amdgcn_sched_group_barrier(0x100, kHalf, 0);                                            \
-    }                                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                                    \
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                                \
-      __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                                \
-    }                                                                                                   \
-    __builtin_amdgcn_sched_group_barrier(0x008, FM * FN - 2 - FM, 0);                                   \
-  }
 #define PLC_KSTEP(ks, from, ks_next, order, fill_slice)                                                 \
-  PLC_STEP_ORDER                                                                                        \
   _Pragma("unroll") for (int a = 0; a < FM; ++a) {                                                      \
     if (a == 1) {                                                                                       \
       PLC_REQUEST_FRAGS(((ks) + 1) & 1, from, ks_next, kHalf, FM + FN);                                 \
@@ -403,10 +382,10 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _
     if (a > 0) {                                                                                        \
       PLC_LOADS(order, a, fill_slice);                                                                  \
     }                                                                                                   \
-    if (!kLongK) __builtin_amdgcn_sched_barrier(0);                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
     _Pragma("unroll") for (int b = 0; b < FN; ++b) acc[a][b] =                                          \
         __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[(ks)&1][a], fb[(ks)&1][b], acc[a][b], 0, 0, 0);       \
-    if (!kLongK) __builtin_amdgcn_sched_barrier(0);                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                                  \
     if (a == 0) {                                                                                       \
       PLC_REQUEST_FRAGS(((ks) + 1) & 1, from, ks_next, 0, kHalf);                                       \
       PLC_LOADS(order, a, fill_slice);                                                                  \
@@ -434,7 +413,6 @@ __global__ __launch_bounds__(Shape::kThreads) void gemm_nt_direct_kernel(const _
     PLC_KSTEP(3, nxt, 0, -1, 0);
   }
 #undef PLC_KSTEP
-#undef PLC_STEP_ORDER
 #undef PLC_LOADS
 #undef PLC_REQUEST_FRAGS
   // nothing may still be writing this workgroup's LDS when it ends
@@ -540,22 +518,15 @@ void launch_shape(int64_t M, int64_t N, int batches, hipStream_t st, const _Floa
                      xdiv, ymod, K, tiles_n, ep);
 }
 
-constexpr int kLongContraction = 32768;  // from here on the kernel places its requests the kLongK way
-
 template <class Shape, class Epilogue>
 void launch_direct(int64_t M, int64_t N, int batches, hipStream_t st, const _Float16 *X, const _Float16 *Y, int64_t xs,
                    int64_t ys, int32_t xdiv, int32_t ymod, int K, const Epilogue &ep) {
   const int tiles_n = (int)(N / Shape::kTileN);
   const dim3 grid((unsigned)((M / Shape::kTileM) * tiles_n), (unsigned)batches);
-  auto launch = [&](auto kernel) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)Shape::kLdsBytes);
-    hipLaunchKernelGGL(kernel, grid, dim3(Shape::kThreads), Shape::kLdsBytes, st, X, Y, xs, ys, xdiv, ymod, K, tiles_n, ep);
-  };
-  if (K >= kLongContraction)
-    launch(&gemm_nt_direct_kernel<Shape, Epilogue, true>);
-  else
-    launch(&gemm_nt_direct_kernel<Shape, Epilogue, false>);
+  (void)hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_nt_direct_kernel<Shape, Epilogue>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)Shape::kLdsBytes);
+  hipLaunchKernelGGL((gemm_nt_direct_kernel<Shape, Epilogue>), grid, dim3(Shape::kThreads), Shape::kLdsBytes, st, X, Y, xs,
+                     ys, xdiv, ymod, K, tiles_n, ep);
 }
 
 template <class Epilogue>
