@@ -75,6 +75,8 @@ def parse():
                          "table per depth) on the token-conditional path")
     ap.add_argument("--no-linear", action="store_true",
                     help="skip the linear-embedding predictor (two fp16 contractions on the matrix cores)")
+    ap.add_argument("--no-padded-vocabulary", action="store_true",
+                    help="linear predictor: skip the extra timing of the first contraction with the vocabulary padded to a multiple of 64")
     ap.add_argument("--two-call-decode", action="store_true",
                     help="decode with plc_rans_decode then plc_reconstruct instead of the single call that "
                          "reconstructs inside the entropy decoder")
@@ -703,7 +705,7 @@ def linear_path(args, plc, torch, result, chunk_syms):
     # tokens (zero probabilities), which makes every row's pitch a whole number of 128-byte lines.
     V64 = (lw.V + 63) // 64 * 64
     padded = None
-    if V64 != lw.V:
+    if V64 != lw.V and not args.no_padded_vocabulary:
         p64 = torch.zeros((rows5, V64), dtype=torch.float16, device=dev)
         e64 = torch.zeros((lw.m, V64), dtype=torch.float16, device=dev)
         p64[:, :lw.V].copy_(lw.probs_full.reshape(rows5, lw.V))
